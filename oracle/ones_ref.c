@@ -1,0 +1,516 @@
+/*
+ * CPU oracle for one generation of the ONES evolutionary search (arXiv 2108.03645,
+ * Section 3.2: population of candidate schedules, refresh / uniform crossover /
+ * uniform mutation, scoring with the "smallest remaining utilisation" objective
+ * Eq. 3 with T = Y/X of Eq. 5, selection of the best K).
+ *
+ * TEST INFRASTRUCTURE ONLY.  Plain scalar loops in the order the method states them;
+ * no blocking, fusion or reordering.  Build: gcc -O2 -ffp-contract=off -fopenmp.
+ *
+ * Encoding.  The paper's schedule maps (job, GPU) to a local batch (Eq. 1); the
+ * objective only needs the global batch B_j and GPU count c_j (Eq. 2, Eq. 3), so a
+ * genome here is one gene per job: B_j = 0 (the job waits, Section 3 "B_j = c_j = 0")
+ * or a power of two inside the job's window [bmin_j, bmax_j] (bmax_j is the limit R_j
+ * of Section 3.2.2).  GPU count c = ceil(B / per-GPU max batch); local batches equal.
+ * Inside this file a gene is its exponent g = log2 B, or WAIT.
+ */
+#include "ones_ref.h"
+
+#include <math.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+#define WAIT (-1)
+#define LANES 64
+#define MAX_SLOTS 2048
+#define MAX_POPULATION (1 << 20)
+#define MAX_GPUS (1 << 20)
+#define MAX_PARAM 1e100
+
+typedef struct {
+  int     active;
+  int     lo, hi, mu;      /* log2 of bmin, bmax, per-GPU max batch */
+  double  a, cc, d, Y;
+  int64_t id;
+} slot_t;
+
+struct ones_ref_ctx {
+  int      G, Jn, Jp, R, P, K;
+  uint32_t key[2];
+  uint32_t T_mut, T_x;
+  slot_t  *tab;            /* Jp entries */
+  int32_t *genes[2];       /* [P][Jp] batch sizes, ping-pong */
+  double  *fit;            /* [P] */
+  int32_t *sel;            /* [K] */
+  int      cur;
+  int64_t  t;              /* generation counter; 0 = initial population */
+};
+
+static int g_threads = 1;
+void ones_ref_set_threads(int n) { g_threads = n < 1 ? 1 : n; }
+int  ones_ref_get_threads(void) { return g_threads; }
+
+int ones_ref_padded_jobs(int32_t n_slots) {
+  int n = n_slots < 1 ? 1 : n_slots;
+  return LANES * ((n + LANES - 1) / LANES);
+}
+
+/* ------------------------------------------------------------------ RNG ---------- */
+/* Philox4x32-10 (Salmon, Moraes, Dror, Shaw, SC'11): ten rounds; each round multiplies
+ * counter words 0 and 2 by two fixed constants, the high halves are xored with words
+ * 1 and 3 and the round key, the low halves move to words 1 and 3; the key is bumped
+ * by two Weyl constants between rounds. */
+void ones_ref_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]) {
+  uint32_t x0 = ctr[0], x1 = ctr[1], x2 = ctr[2], x3 = ctr[3];
+  uint32_t k0 = key[0], k1 = key[1];
+  for (int round = 0; round < 10; ++round) {
+    uint64_t p0 = (uint64_t)0xD2511F53u * x0;
+    uint64_t p1 = (uint64_t)0xCD9E8D57u * x2;
+    uint32_t y0 = (uint32_t)(p1 >> 32) ^ x1 ^ k0;
+    uint32_t y1 = (uint32_t)p1;
+    uint32_t y2 = (uint32_t)(p0 >> 32) ^ x3 ^ k1;
+    uint32_t y3 = (uint32_t)p0;
+    x0 = y0; x1 = y1; x2 = y2; x3 = y3;
+    k0 += 0x9E3779B9u;
+    k1 += 0xBB67AE85u;
+  }
+  out[0] = x0; out[1] = x1; out[2] = x2; out[3] = x3;
+}
+
+static uint32_t bounded(uint32_t w, uint32_t n) { return (uint32_t)(((uint64_t)w * n) >> 32); }
+
+/* per-candidate draw: ranks of the two parents among the survivors, repair rotation */
+static void candidate_draw(const ones_ref_ctx *c, uint32_t p, uint32_t t,
+                           uint32_t *ra, uint32_t *rb, uint32_t *r) {
+  uint32_t ctr[4] = {0xFFFFFFFFu, p, t, 0u}, w[4];
+  ones_ref_philox4x32_10(ctr, c->key, w);
+  *ra = bounded(w[0], (uint32_t)c->K);
+  *rb = bounded(w[1], (uint32_t)c->K);
+  *r  = bounded(w[2], (uint32_t)c->Jp);
+}
+
+/* one 32-bit word per (candidate, generation, job): job j lives in column j mod 64,
+ * row j div 64; four consecutive rows of a column share one Philox block */
+static uint32_t gene_word(const ones_ref_ctx *c, uint32_t p, uint32_t t, int j) {
+  int l = j % LANES, i = j / LANES;
+  uint32_t ctr[4] = {(uint32_t)((i / 4) * LANES + l), p, t, 0u}, w[4];
+  ones_ref_philox4x32_10(ctr, c->key, w);
+  return w[i % 4];
+}
+
+/* ------------------------------------------------------------- job table --------- */
+static int ilog2_exact(int32_t v) {           /* -1 unless v is a power of two */
+  if (v <= 0 || (v & (v - 1)) != 0) return -1;
+  int e = 0;
+  while ((1 << e) != v) ++e;
+  return e;
+}
+
+static int check_config(const ones_ref_config *cfg) {
+  if (!cfg) return ONES_REF_E_INVALID_ARG;
+  if (cfg->n_gpus < 0 || cfg->n_gpus > MAX_GPUS) return ONES_REF_E_INVALID_ARG;
+  if (cfg->n_slots < 0 || cfg->n_slots > MAX_SLOTS) return ONES_REF_E_INVALID_ARG;
+  if (cfg->population <= 0 || cfg->population % 4 != 0 || cfg->population > MAX_POPULATION)
+    return ONES_REF_E_INVALID_ARG;
+  if (!(cfg->mutation_rate >= 0.0 && cfg->mutation_rate <= 1.0)) return ONES_REF_E_INVALID_ARG;
+  if (!(cfg->crossover_rate >= 0.0 && cfg->crossover_rate <= 1.0)) return ONES_REF_E_INVALID_ARG;
+  return ONES_REF_OK;
+}
+
+static int check_param(double v) {
+  if (!isfinite(v)) return ONES_REF_E_NONFINITE;
+  if (v < 0.0) return ONES_REF_E_INVALID_ARG;
+  if (v > MAX_PARAM) return ONES_REF_E_BOUNDS;
+  return ONES_REF_OK;
+}
+
+/* fills tab[0..Jp); slots that are empty or beyond n_slots become inactive */
+static int build_table(int Jn, int Jp, const ones_ref_jobs *jobs, slot_t *tab) {
+  memset(tab, 0, sizeof(slot_t) * (size_t)Jp);
+  if (Jn > 0) {
+    if (!jobs || !jobs->job_id || !jobs->active || !jobs->bmin || !jobs->bmax ||
+        !jobs->gpu_max_batch || !jobs->a || !jobs->c || !jobs->d || !jobs->remaining)
+      return ONES_REF_E_INVALID_ARG;
+  }
+  for (int j = 0; j < Jn; ++j) {
+    slot_t *s = &tab[j];
+    s->id = jobs->job_id[j];
+    if (!jobs->active[j]) continue;
+    int lo = ilog2_exact(jobs->bmin[j]), hi = ilog2_exact(jobs->bmax[j]);
+    int mu = ilog2_exact(jobs->gpu_max_batch[j]);
+    if (lo < 0 || hi < 0 || mu < 0) return ONES_REF_E_NOT_POW2;
+    if (lo > hi || hi > 30 || hi - mu > 20) return ONES_REF_E_BOUNDS;
+    int rc;
+    if ((rc = check_param(jobs->a[j])) || (rc = check_param(jobs->c[j])) ||
+        (rc = check_param(jobs->d[j])) || (rc = check_param(jobs->remaining[j])))
+      return rc;
+    s->active = 1; s->lo = lo; s->hi = hi; s->mu = mu;
+    s->a = jobs->a[j]; s->cc = jobs->c[j]; s->d = jobs->d[j]; s->Y = jobs->remaining[j];
+  }
+  return ONES_REF_OK;
+}
+
+static uint32_t rate_threshold(double rate) {   /* min(2^32-1, floor(rate * 2^32)) */
+  double v = floor(rate * 4294967296.0);
+  return v >= 4294967295.0 ? 0xFFFFFFFFu : (uint32_t)v;
+}
+
+/* --------------------------------------------------------- gene helpers ---------- */
+static int64_t gpus_of(int g, int mu) {           /* c(g): ceil(2^g / 2^mu), 0 if waiting */
+  if (g == WAIT) return 0;
+  return (int64_t)1 << (g > mu ? g - mu : 0);
+}
+static int32_t batch_of(int g) { return g == WAIT ? 0 : (int32_t)1 << g; }
+static int exponent_of(int32_t batch) { return batch == 0 ? WAIT : ilog2_exact(batch); }
+static int imin(int x, int y) { return x < y ? x : y; }
+static int imax(int x, int y) { return x > y ? x : y; }
+
+/* uniform draw over {WAIT, lo..hi} from k in [0, hi-lo+2) */
+static int gene_from_draw(const slot_t *s, uint32_t k) {
+  if (!s->active || k == 0) return WAIT;
+  return s->lo + (int)k - 1;
+}
+
+/* ------------------------------------------------------------- repair ------------ */
+/* The paper's refresh (Section 3.2.2): (1) drop finished jobs, (2) scale down to the
+ * limit R_j, (3) make room when capacity is exceeded (Eq. 4: a GPU hosts one worker),
+ * then fill idle GPUs by resuming waiting jobs or scaling up running ones until no
+ * single step fits.  Jobs are visited in a fixed order rotated by r. */
+static int repair(const slot_t *tab, int Jp, int R, int64_t G, int *g, uint32_t r) {
+  int order[MAX_SLOTS];
+  for (int j = 0; j < Jp; ++j) {
+    int sigma = (j % LANES) * R + (j / LANES);
+    int pi = (sigma + Jp - (int)r) % Jp;
+    order[pi] = j;
+  }
+  /* 1. clamp: empty slot waits; a running job is pulled inside its window */
+  for (int j = 0; j < Jp; ++j) {
+    if (!tab[j].active) g[j] = WAIT;
+    else if (g[j] != WAIT) g[j] = imin(imax(g[j], tab[j].lo), tab[j].hi);
+  }
+  /* 2. lift: a larger batch that needs no extra GPU */
+  for (int j = 0; j < Jp; ++j)
+    if (g[j] != WAIT) g[j] = imax(g[j], imin(tab[j].mu, tab[j].hi));
+  /* 3. admit: prefix sum of GPU counts in visiting order; beyond capacity -> wait */
+  int64_t Q = 0;
+  for (int pos = 0; pos < Jp; ++pos) {
+    int j = order[pos];
+    if (g[j] == WAIT) continue;
+    Q += gpus_of(g[j], tab[j].mu);
+    if (Q > G) g[j] = WAIT;
+  }
+  /* 4. fill */
+  int rounds = 0;
+  for (;;) {
+    int64_t used = 0;
+    for (int j = 0; j < Jp; ++j) used += gpus_of(g[j], tab[j].mu);
+    int64_t idle = G - used;
+    int     target[MAX_SLOTS];
+    int64_t cost[MAX_SLOTS];
+    int any = 0;
+    for (int j = 0; j < Jp; ++j) {
+      const slot_t *s = &tab[j];
+      target[j] = WAIT; cost[j] = -1;              /* no proposal */
+      if (!s->active) continue;
+      if (g[j] == WAIT) {
+        target[j] = imax(s->lo, imin(s->mu, s->hi));
+        cost[j] = gpus_of(target[j], s->mu);
+      } else if (g[j] < s->hi) {
+        target[j] = g[j] + 1;
+        cost[j] = gpus_of(target[j], s->mu) - gpus_of(g[j], s->mu);
+      }
+      if (cost[j] >= 0 && cost[j] > idle) { target[j] = WAIT; cost[j] = -1; } /* not participating */
+      if (cost[j] >= 0) any = 1;
+    }
+    if (!any) break;
+    ++rounds;
+    Q = 0;
+    for (int pos = 0; pos < Jp; ++pos) {
+      int j = order[pos];
+      if (cost[j] < 0) continue;
+      Q += cost[j];
+      if (Q <= idle) g[j] = target[j];
+    }
+  }
+  return rounds;
+}
+
+/* -------------------------------------------------------------- score ------------ */
+/* Eq. 3 with Eq. 5: sum over running jobs of T_j * c_j, T_j = Y_j / X_j, throughput
+ * X_j = B_j / t_j, iteration time t(b,g) = a*b/g + c*log2(g) + d with b/g the local
+ * batch.  T_j*c_j = Y_j * t_j / (B_j/c_j).  Fixed summation order: column sums over the
+ * rows top to bottom, then a xor-butterfly over the 64 columns. */
+static double score(const slot_t *tab, int R, const int *g) {
+  double part[LANES], next[LANES];
+  for (int l = 0; l < LANES; ++l) {
+    double acc = 0.0;
+    for (int i = 0; i < R; ++i) {
+      int j = l + LANES * i;
+      double term = 0.0;
+      if (g[j] != WAIT) {
+        const slot_t *s = &tab[j];
+        double bf = (double)((int64_t)1 << imin(g[j], s->mu));   /* local batch */
+        double lg = (double)imax(0, g[j] - s->mu);               /* log2(GPU count) */
+        double prod_a = s->a * bf;
+        double prod_c = s->cc * lg;
+        double t = (prod_a + prod_c) + s->d;
+        double yt = s->Y * t;
+        term = yt / bf;
+      }
+      acc = acc + term;
+    }
+    part[l] = acc;
+  }
+  for (int s = 32; s >= 1; s >>= 1) {
+    for (int l = 0; l < LANES; ++l) next[l] = part[l] + part[l ^ s];
+    memcpy(part, next, sizeof(part));
+  }
+  return part[0];
+}
+
+/* ------------------------------------------------------------- select ------------ */
+typedef struct { double f; int32_t idx; } keyed_t;
+static int keyed_cmp(const void *x, const void *y) {
+  const keyed_t *u = (const keyed_t *)x, *v = (const keyed_t *)y;
+  if (u->f < v->f) return -1;
+  if (u->f > v->f) return 1;
+  return (u->idx > v->idx) - (u->idx < v->idx);
+}
+/* the K = P/4 slots with the smallest (fitness, slot index), in that order */
+void ones_ref_select(const double *fit, int32_t population, int32_t *sel) {
+  keyed_t *k = (keyed_t *)malloc(sizeof(keyed_t) * (size_t)population);
+  for (int32_t p = 0; p < population; ++p) { k[p].f = fit[p]; k[p].idx = p; }
+  qsort(k, (size_t)population, sizeof(keyed_t), keyed_cmp);
+  for (int32_t i = 0; i < population / 4; ++i) sel[i] = k[i].idx;
+  free(k);
+}
+
+/* ------------------------------------------------------------ compose ------------ */
+/* Genome of pool slot p of generation t, before repair, read from the previous
+ * generation through its survivor list.  Pool = K refreshed survivors, K parent pairs
+ * giving 2K crossover children, K mutants (Section 3.2.2). */
+static void compose(const ones_ref_ctx *c, const int32_t *prev, uint32_t t, int p, int *g,
+                    uint32_t *r_out, int *pa_out, int *pb_out) {
+  const int K = c->K, Jp = c->Jp;
+  uint32_t ra, rb, r;
+  candidate_draw(c, (uint32_t)p, t, &ra, &rb, &r);     /* rotation: always the slot's own */
+  *r_out = r;
+  *pa_out = *pb_out = -1;
+  if (p < K) {                                          /* refreshed survivor */
+    const int32_t *src = prev + (size_t)c->sel[p] * Jp;
+    for (int j = 0; j < Jp; ++j) g[j] = exponent_of(src[j]);
+    *pa_out = c->sel[p];
+  } else if (p < 3 * K) {                               /* uniform crossover */
+    int q = (p - K) / 2, side = (p - K) % 2, p0 = K + 2 * q;
+    uint32_t unused;
+    candidate_draw(c, (uint32_t)p0, t, &ra, &rb, &unused);   /* both children share parents */
+    const int32_t *A = prev + (size_t)c->sel[ra] * Jp;
+    const int32_t *B = prev + (size_t)c->sel[rb] * Jp;
+    for (int j = 0; j < Jp; ++j) {
+      int swap = gene_word(c, (uint32_t)p0, t, j) < c->T_x;
+      int from_b = side == 0 ? swap : !swap;            /* the children are complementary */
+      g[j] = exponent_of(from_b ? B[j] : A[j]);
+    }
+    *pa_out = c->sel[ra]; *pb_out = c->sel[rb];
+  } else {                                              /* uniform mutation */
+    const int32_t *A = prev + (size_t)c->sel[ra] * Jp;
+    for (int j = 0; j < Jp; ++j) {
+      uint32_t w = gene_word(c, (uint32_t)p, t, j);
+      const slot_t *s = &c->tab[j];
+      if (w < c->T_mut) {
+        uint32_t n = (uint32_t)(s->hi - s->lo + 2);
+        uint32_t k = ((w & 0xFFFFu) * n) >> 16;         /* k = 0: the job is pre-empted */
+        g[j] = gene_from_draw(s, k);
+      } else {
+        g[j] = exponent_of(A[j]);
+      }
+    }
+    *pa_out = c->sel[ra];
+  }
+}
+
+static void initial_genome(const ones_ref_ctx *c, int p, int *g, uint32_t *r_out) {
+  uint32_t ra, rb;
+  candidate_draw(c, (uint32_t)p, 0u, &ra, &rb, r_out);
+  for (int j = 0; j < c->Jp; ++j) {
+    const slot_t *s = &c->tab[j];
+    uint32_t n = (uint32_t)(s->hi - s->lo + 2);
+    g[j] = gene_from_draw(s, bounded(gene_word(c, (uint32_t)p, 0u, j), n));
+  }
+}
+
+static void finish_slot(ones_ref_ctx *c, int32_t *dst, int p, int *g, uint32_t r) {
+  repair(c->tab, c->Jp, c->R, c->G, g, r);
+  c->fit[p] = score(c->tab, c->R, g);
+  int32_t *row = dst + (size_t)p * c->Jp;
+  for (int j = 0; j < c->Jp; ++j) row[j] = batch_of(g[j]);
+}
+
+/* ------------------------------------------------------------- public ------------ */
+int ones_ref_init(ones_ref_ctx **out, const ones_ref_config *cfg, const ones_ref_jobs *jobs) {
+  if (!out) return ONES_REF_E_INVALID_ARG;
+  int rc = check_config(cfg);
+  if (rc) return rc;
+  ones_ref_ctx *c = (ones_ref_ctx *)calloc(1, sizeof(*c));
+  c->G = cfg->n_gpus; c->Jn = cfg->n_slots; c->Jp = ones_ref_padded_jobs(cfg->n_slots);
+  c->R = c->Jp / LANES; c->P = cfg->population; c->K = c->P / 4;
+  c->key[0] = (uint32_t)cfg->seed; c->key[1] = (uint32_t)(cfg->seed >> 32);
+  c->T_mut = rate_threshold(cfg->mutation_rate);
+  c->T_x = rate_threshold(cfg->crossover_rate);
+  c->tab = (slot_t *)malloc(sizeof(slot_t) * (size_t)c->Jp);
+  rc = build_table(c->Jn, c->Jp, jobs, c->tab);
+  if (rc) { free(c->tab); free(c); return rc; }
+  size_t n = (size_t)c->P * c->Jp;
+  c->genes[0] = (int32_t *)calloc(n, sizeof(int32_t));
+  c->genes[1] = (int32_t *)calloc(n, sizeof(int32_t));
+  c->fit = (double *)calloc((size_t)c->P, sizeof(double));
+  c->sel = (int32_t *)calloc((size_t)c->K, sizeof(int32_t));
+  c->cur = 0; c->t = 0;
+  /* initial population: random genomes, repaired, scored, ranked */
+#pragma omp parallel for num_threads(g_threads) schedule(static)
+  for (int p = 0; p < c->P; ++p) {
+    int g[MAX_SLOTS]; uint32_t r;
+    initial_genome(c, p, g, &r);
+    finish_slot(c, c->genes[0], p, g, r);
+  }
+  ones_ref_select(c->fit, c->P, c->sel);
+  *out = c;
+  return ONES_REF_OK;
+}
+
+int ones_ref_set_jobs(ones_ref_ctx *c, const ones_ref_jobs *jobs) {
+  if (!c) return ONES_REF_E_INVALID_ARG;
+  slot_t *tab = (slot_t *)malloc(sizeof(slot_t) * (size_t)c->Jp);
+  int rc = build_table(c->Jn, c->Jp, jobs, tab);
+  if (rc) { free(tab); return rc; }
+  /* a slot that changed hands starts from "waiting" in every candidate */
+  for (int j = 0; j < c->Jn; ++j) {
+    if (tab[j].id == c->tab[j].id) continue;
+    for (int p = 0; p < c->P; ++p) c->genes[c->cur][(size_t)p * c->Jp + j] = 0;
+  }
+  free(c->tab);
+  c->tab = tab;
+  return ONES_REF_OK;
+}
+
+int ones_ref_generation(ones_ref_ctx *c, int32_t n_generations) {
+  if (!c || n_generations < 0) return ONES_REF_E_INVALID_ARG;
+  if (c->t + n_generations > 0xFFFFFFFFll) return ONES_REF_E_INVALID_ARG;
+  for (int32_t it = 0; it < n_generations; ++it) {
+    const int32_t *prev = c->genes[c->cur];
+    int32_t *next = c->genes[c->cur ^ 1];
+    uint32_t t = (uint32_t)(c->t + 1);
+#pragma omp parallel for num_threads(g_threads) schedule(static)
+    for (int p = 0; p < c->P; ++p) {
+      int g[MAX_SLOTS], pa, pb; uint32_t r;
+      compose(c, prev, t, p, g, &r, &pa, &pb);
+      finish_slot(c, next, p, g, r);
+    }
+    ones_ref_select(c->fit, c->P, c->sel);
+    c->cur ^= 1;
+    c->t += 1;
+  }
+  return ONES_REF_OK;
+}
+
+int ones_ref_best(ones_ref_ctx *c, int32_t *batch_out, int32_t *gpus_out, double *fitness_out) {
+  if (!c) return ONES_REF_E_INVALID_ARG;
+  int best = c->sel[0];                                 /* smallest score wins (Alg. 1) */
+  const int32_t *row = c->genes[c->cur] + (size_t)best * c->Jp;
+  for (int j = 0; j < c->Jn; ++j) {
+    if (batch_out) batch_out[j] = row[j];
+    if (gpus_out) gpus_out[j] = (int32_t)gpus_of(exponent_of(row[j]), c->tab[j].mu);
+  }
+  if (fitness_out) *fitness_out = c->fit[best];
+  return ONES_REF_OK;
+}
+
+int ones_ref_export(ones_ref_ctx *c, int32_t *genes, double *fit, int32_t *sel, int64_t *generation) {
+  if (!c) return ONES_REF_E_INVALID_ARG;
+  if (genes) memcpy(genes, c->genes[c->cur], sizeof(int32_t) * (size_t)c->P * c->Jp);
+  if (fit) memcpy(fit, c->fit, sizeof(double) * (size_t)c->P);
+  if (sel) memcpy(sel, c->sel, sizeof(int32_t) * (size_t)c->K);
+  if (generation) *generation = c->t;
+  return ONES_REF_OK;
+}
+
+void ones_ref_destroy(ones_ref_ctx *c) {
+  if (!c) return;
+  free(c->tab); free(c->genes[0]); free(c->genes[1]); free(c->fit); free(c->sel); free(c);
+}
+
+int ones_ref_compose_slot(ones_ref_ctx *c, int32_t p, int32_t *genes_out, uint32_t *r_out,
+                          int32_t *parent_a_out, int32_t *parent_b_out) {
+  if (!c || p < 0 || p >= c->P || !genes_out) return ONES_REF_E_INVALID_ARG;
+  int g[MAX_SLOTS], pa, pb; uint32_t r;
+  compose(c, c->genes[c->cur], (uint32_t)(c->t + 1), p, g, &r, &pa, &pb);
+  for (int j = 0; j < c->Jp; ++j) genes_out[j] = batch_of(g[j]);
+  if (r_out) *r_out = r;
+  if (parent_a_out) *parent_a_out = pa;
+  if (parent_b_out) *parent_b_out = pb;
+  return ONES_REF_OK;
+}
+
+/* single-genome entry points for the pins */
+int ones_ref_initial_genome(const ones_ref_config *cfg, const ones_ref_jobs *jobs, int32_t p,
+                            int32_t *genes_out, uint32_t *r_out) {
+  int rc = check_config(cfg);
+  if (rc) return rc;
+  if (p < 0 || p >= cfg->population || !genes_out) return ONES_REF_E_INVALID_ARG;
+  ones_ref_ctx c;
+  memset(&c, 0, sizeof(c));
+  c.Jn = cfg->n_slots; c.Jp = ones_ref_padded_jobs(cfg->n_slots); c.R = c.Jp / LANES;
+  c.P = cfg->population; c.K = c.P / 4;
+  c.key[0] = (uint32_t)cfg->seed; c.key[1] = (uint32_t)(cfg->seed >> 32);
+  slot_t tab[MAX_SLOTS]; int g[MAX_SLOTS]; uint32_t r;
+  if ((rc = build_table(c.Jn, c.Jp, jobs, tab))) return rc;
+  c.tab = tab;
+  initial_genome(&c, p, g, &r);
+  for (int j = 0; j < c.Jn; ++j) genes_out[j] = batch_of(g[j]);
+  if (r_out) *r_out = r;
+  return ONES_REF_OK;
+}
+
+static int load_genome(const slot_t *tab, int Jn, int Jp, const int32_t *genes, int *g) {
+  (void)tab;
+  for (int j = 0; j < Jp; ++j) {
+    int32_t b = j < Jn ? genes[j] : 0;
+    if (b < 0) return ONES_REF_E_INVALID_ARG;
+    int e = exponent_of(b);
+    if (b != 0 && e < 0) return ONES_REF_E_NOT_POW2;
+    g[j] = e;
+  }
+  return ONES_REF_OK;
+}
+
+int ones_ref_repair_genome(const ones_ref_config *cfg, const ones_ref_jobs *jobs,
+                           int32_t *genes, uint32_t r, int32_t *fill_rounds_out) {
+  int rc = check_config(cfg);
+  if (rc) return rc;
+  int Jn = cfg->n_slots, Jp = ones_ref_padded_jobs(Jn);
+  if ((int64_t)r >= Jp || !genes) return ONES_REF_E_INVALID_ARG;
+  slot_t tab[MAX_SLOTS]; int g[MAX_SLOTS];
+  if ((rc = build_table(Jn, Jp, jobs, tab))) return rc;
+  if ((rc = load_genome(tab, Jn, Jp, genes, g))) return rc;
+  int rounds = repair(tab, Jp, Jp / LANES, cfg->n_gpus, g, r);
+  for (int j = 0; j < Jn; ++j) genes[j] = batch_of(g[j]);
+  if (fill_rounds_out) *fill_rounds_out = rounds;
+  return ONES_REF_OK;
+}
+
+int ones_ref_score_genome(const ones_ref_config *cfg, const ones_ref_jobs *jobs,
+                          const int32_t *genes, double *fitness_out) {
+  int rc = check_config(cfg);
+  if (rc) return rc;
+  int Jn = cfg->n_slots, Jp = ones_ref_padded_jobs(Jn);
+  if (!genes || !fitness_out) return ONES_REF_E_INVALID_ARG;
+  slot_t tab[MAX_SLOTS]; int g[MAX_SLOTS];
+  if ((rc = build_table(Jn, Jp, jobs, tab))) return rc;
+  if ((rc = load_genome(tab, Jn, Jp, genes, g))) return rc;
+  for (int j = 0; j < Jp; ++j) if (!tab[j].active) g[j] = WAIT;
+  *fitness_out = score(tab, Jp / LANES, g);
+  return ONES_REF_OK;
+}

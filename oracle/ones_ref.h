@@ -1,0 +1,89 @@
+/*
+ * CPU oracle for one generation of the ONES evolutionary search (arXiv 2108.03645,
+ * Section 3.2).  TEST INFRASTRUCTURE ONLY: plain, slow, scalar C; it exists to check
+ * the GPU library and to be timed as a CPU baseline.  It shares no code, header,
+ * table or constant with the GPU library and must never be called from it.
+ *
+ * Parity status of each function (what pins it, other than itself):
+ *   ones_ref_philox4x32_10 : published known-answer vectors + a big-integer Python
+ *                            transcription of the SC'11 definition.
+ *   ones_ref_repair_genome : hand-worked example, Eq. 4 capacity, maximality,
+ *                            idempotence, closed-form special cases, brute force.
+ *   ones_ref_score_genome  : hand values, exact rational recomputation of
+ *                            Eq. 3 / Eq. 5, monotonicity.
+ *   ones_ref_select        : numpy lexsort on (fitness, index).
+ *   compose (crossover, mutation, init): complementarity of children, coin
+ *                            frequencies, chi-square on redraws and parent ranks,
+ *                            theta = chi = 0 and chi = 1 special cases.
+ *   scheduling quality against the paper's JCT numbers: parity unpinned (the paper's
+ *                            trace, jobs and comparison schedulers do not exist here).
+ */
+#ifndef ONES_REF_H
+#define ONES_REF_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct ones_ref_ctx ones_ref_ctx;
+
+typedef struct {
+  int32_t  n_gpus;         /* |C| of Table 1 */
+  int32_t  n_slots;        /* job slots Jn */
+  int32_t  population;     /* pool size P = 4K (K elites + 2K children + K mutants) */
+  uint64_t seed;
+  double   mutation_rate;  /* theta, Section 3.2.2 "Uniform mutation" */
+  double   crossover_rate; /* per-gene swap probability of the uniform crossover */
+} ones_ref_config;
+
+typedef struct {           /* arrays of length n_slots, host memory */
+  const int64_t *job_id;
+  const uint8_t *active;
+  const int32_t *bmin, *bmax, *gpu_max_batch;
+  const double  *a, *c, *d;
+  const double  *remaining;
+} ones_ref_jobs;
+
+enum {
+  ONES_REF_OK = 0,
+  ONES_REF_E_INVALID_ARG = -1,
+  ONES_REF_E_NOT_POW2 = -2,
+  ONES_REF_E_BOUNDS = -3,
+  ONES_REF_E_NONFINITE = -4
+};
+
+/* whole-search entry points, same call sequence as the GPU library */
+int  ones_ref_init(ones_ref_ctx **out, const ones_ref_config *cfg, const ones_ref_jobs *jobs);
+int  ones_ref_set_jobs(ones_ref_ctx *ctx, const ones_ref_jobs *jobs);
+int  ones_ref_generation(ones_ref_ctx *ctx, int32_t n_generations);
+int  ones_ref_best(ones_ref_ctx *ctx, int32_t *batch_out, int32_t *gpus_out, double *fitness_out);
+int  ones_ref_export(ones_ref_ctx *ctx, int32_t *genes, double *fit, int32_t *sel, int64_t *generation);
+void ones_ref_destroy(ones_ref_ctx *ctx);
+int  ones_ref_padded_jobs(int32_t n_slots);     /* Jp = 64*ceil(max(n,1)/64) */
+void ones_ref_set_threads(int n);               /* candidates split over n OpenMP threads */
+int  ones_ref_get_threads(void);
+
+/* single steps, exposed so that tests can pin them one at a time */
+void ones_ref_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]);
+/* genes: n_slots int32 batch sizes (0 or a power of two), repaired in place with
+ * rotation r in [0,Jp); fill_rounds_out (may be NULL) receives the number of fill rounds */
+int  ones_ref_repair_genome(const ones_ref_config *cfg, const ones_ref_jobs *jobs,
+                            int32_t *genes, uint32_t r, int32_t *fill_rounds_out);
+int  ones_ref_score_genome(const ones_ref_config *cfg, const ones_ref_jobs *jobs,
+                           const int32_t *genes, double *fitness_out);
+void ones_ref_select(const double *fit, int32_t population, int32_t *sel /* population/4 */);
+/* the genome slot p of generation t+1 would hold BEFORE repair, and its rotation */
+int  ones_ref_compose_slot(ones_ref_ctx *ctx, int32_t p, int32_t *genes_out, uint32_t *r_out,
+                           int32_t *parent_a_out, int32_t *parent_b_out);
+
+/* the random genome slot p of the initial population holds BEFORE repair (n_slots genes) */
+int  ones_ref_initial_genome(const ones_ref_config *cfg, const ones_ref_jobs *jobs, int32_t p,
+                             int32_t *genes_out, uint32_t *r_out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

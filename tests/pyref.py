@@ -1,0 +1,164 @@
+"""Independent, slow Python checks used to pin the C oracle: a big-integer Philox, an exact
+rational evaluation of the cluster objective, a batch-size-domain capacity repair written
+sequentially, and the invariant checker.  Nothing here is shared with oracle/ or the GPU
+library; everything works on global batch sizes B (not exponents) and uses ceil-division."""
+from __future__ import annotations
+
+from fractions import Fraction
+from types import SimpleNamespace
+
+import numpy as np
+
+M32 = (1 << 32) - 1
+
+
+def philox4x32_10(ctr, key):
+    """Philox4x32-10 after Salmon et al. (SC'11), with Python integers."""
+    x = [int(v) for v in ctr]
+    k = [int(v) for v in key]
+    for _ in range(10):
+        p0 = 0xD2511F53 * x[0]
+        p1 = 0xCD9E8D57 * x[2]
+        x = [(p1 >> 32) ^ x[1] ^ k[0], p1 & M32, (p0 >> 32) ^ x[3] ^ k[1], p0 & M32]
+        k = [(k[0] + 0x9E3779B9) & M32, (k[1] + 0xBB67AE85) & M32]
+    return x
+
+
+def make_jobs(n, **kw):
+    """Job table with defaults: active, window [32,1024], m=256, a=1e-3, c=0.02, d=0.01, Y=1e6."""
+    d = dict(job_id=np.arange(1, n + 1, dtype=np.int64), active=np.ones(n, np.uint8),
+             bmin=np.full(n, 32, np.int32), bmax=np.full(n, 1024, np.int32),
+             gpu_max_batch=np.full(n, 256, np.int32), a=np.full(n, 1e-3), c=np.full(n, 0.02),
+             d=np.full(n, 0.01), remaining=np.full(n, 1e6))
+    for k, v in kw.items():
+        d[k] = np.asarray(v, dtype=d[k].dtype) if np.ndim(v) else np.full(n, v, d[k].dtype)
+    return SimpleNamespace(**d)
+
+
+def random_jobs(rng, n, inactive_frac=0.1):
+    lo = rng.integers(4, 13, n)
+    hi = np.array([rng.integers(l, 13) for l in lo]) if n else np.zeros(0, np.int64)
+    m = rng.choice(np.array([64, 128, 256, 512]), n)
+    return make_jobs(n, active=(rng.random(n) >= inactive_frac).astype(np.uint8),
+                     bmin=1 << lo, bmax=1 << hi, gpu_max_batch=m,
+                     a=rng.lognormal(-7, 0.5, n), c=rng.uniform(0.01, 0.05, n),
+                     d=rng.uniform(0.005, 0.02, n), remaining=rng.uniform(1e5, 1e7, n))
+
+
+def random_genome(rng, jobs, wait_frac=0.3, wild=False):
+    n = len(jobs.bmin)
+    g = np.zeros(n, np.int32)
+    for j in range(n):
+        if rng.random() < wait_frac:
+            continue
+        if wild:                      # anywhere in [1, 2^14], also outside the window
+            g[j] = 1 << rng.integers(0, 15)
+        else:
+            lo, hi = int(jobs.bmin[j]).bit_length() - 1, int(jobs.bmax[j]).bit_length() - 1
+            g[j] = 1 << rng.integers(lo, hi + 1)
+    return g
+
+
+def gpus(b, m):
+    return 0 if b == 0 else -(-int(b) // int(m))
+
+
+def visiting_order(n, r):
+    """Jobs in the order the repair visits them: column-major over 64 columns, rotated by r."""
+    jp = 64 * max(1, -(-n // 64))
+    rows = jp // 64
+    return sorted(range(n), key=lambda j: (((j % 64) * rows + j // 64) - r) % jp)
+
+
+def start_batch(jobs, j):
+    """Batch a waiting job resumes with: the per-GPU max, pulled inside the window."""
+    return max(int(jobs.bmin[j]), min(int(jobs.gpu_max_batch[j]), int(jobs.bmax[j])))
+
+
+def proposal(jobs, j, b):
+    """(new batch, extra GPUs) of the single step job j may ask for, or None."""
+    if not jobs.active[j]:
+        return None
+    m = int(jobs.gpu_max_batch[j])
+    if b == 0:
+        nb = start_batch(jobs, j)
+        return nb, gpus(nb, m)
+    if b < int(jobs.bmax[j]):
+        return 2 * b, gpus(2 * b, m) - gpus(b, m)
+    return None
+
+
+def repair(G, jobs, genes, r):
+    """Sequential statement of the repair in the batch-size domain."""
+    n = len(genes)
+    B = [int(v) for v in genes]
+    order = visiting_order(n, r)
+    for j in range(n):
+        if not jobs.active[j]:
+            B[j] = 0
+        elif B[j]:
+            B[j] = min(max(B[j], int(jobs.bmin[j])), int(jobs.bmax[j]))
+            B[j] = max(B[j], min(int(jobs.gpu_max_batch[j]), int(jobs.bmax[j])))
+    total = 0
+    for j in order:                               # admission: keep the longest prefix that fits
+        total += gpus(B[j], jobs.gpu_max_batch[j])
+        if total > G:
+            B[j] = 0
+    rounds = 0
+    while True:
+        idle = G - sum(gpus(B[j], jobs.gpu_max_batch[j]) for j in range(n))
+        asks = []
+        for j in order:
+            pr = proposal(jobs, j, B[j])
+            if pr is not None and pr[1] <= idle:
+                asks.append((j, pr))
+        if not asks:
+            break
+        rounds += 1
+        spent = 0
+        for j, (nb, cost) in asks:                # first come first served, no skipping
+            spent += cost
+            if spent > idle:
+                break
+            B[j] = nb
+    return np.array(B, np.int32), rounds
+
+
+def check_invariants(G, jobs, genes):
+    """I1 window / inactive, I2 capacity (Eq. 4), I3 maximality.  Returns idle GPUs."""
+    n = len(genes)
+    used = 0
+    for j in range(n):
+        b = int(genes[j])
+        if not jobs.active[j]:
+            assert b == 0, f"inactive slot {j} runs"
+            continue
+        if b:
+            assert b & (b - 1) == 0 and jobs.bmin[j] <= b <= jobs.bmax[j], (j, b)
+            # a running job never sits below the free (no extra GPU) batch
+            assert b >= min(int(jobs.gpu_max_batch[j]), int(jobs.bmax[j])), (j, b)
+        used += gpus(b, jobs.gpu_max_batch[j])
+    assert used <= G, f"capacity exceeded: {used} > {G}"
+    idle = G - used
+    for j in range(n):
+        pr = proposal(jobs, j, int(genes[j]))
+        assert pr is None or pr[1] > idle, f"job {j} could still take {pr} with {idle} idle"
+    return idle
+
+
+def exact_objective(jobs, genes):
+    """Sum over running jobs of T_j * c_j in exact rational arithmetic, following the chain
+    t = a*B/g + c*log2(g) + d, X = B/t, T = Y/X literally (g = ceil(B/m))."""
+    total = Fraction(0)
+    for j, b in enumerate(genes):
+        b = int(b)
+        if b == 0 or not jobs.active[j]:
+            continue
+        g = gpus(b, jobs.gpu_max_batch[j])
+        log2g = g.bit_length() - 1
+        assert 1 << log2g == g
+        t = Fraction(float(jobs.a[j])) * b / g + Fraction(float(jobs.c[j])) * log2g + Fraction(float(jobs.d[j]))
+        X = Fraction(b) / t
+        T = Fraction(float(jobs.remaining[j])) / X
+        total += T * g
+    return total
