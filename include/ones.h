@@ -1,0 +1,126 @@
+/*
+ * libones - one generation of the ONES evolutionary search on an AMD MI355X (gfx950).
+ *
+ * ONES (arXiv 2108.03645) schedules the batch size of every deep-learning job in a
+ * shared GPU cluster by evolving a population of candidate schedules (Section 3.2).
+ * This library runs that search on one GPU: the initial population, and per generation
+ * the refresh / uniform crossover / uniform mutation operators (Section 3.2.2), the
+ * repair of every candidate to the cluster's capacity (Eq. 4), the scoring with the
+ * "smallest remaining utilisation" objective sum_j T_j * c_j (Eq. 3 with T = Y/X,
+ * Eq. 5 / Eq. 8) and the selection of the best K candidates.
+ *
+ * Encoding.  A schedule is one gene per job slot: the job's global batch size B_j,
+ * either 0 (the job waits, "B_j = c_j = 0" of Section 3) or a power of two inside
+ * [bmin_j, bmax_j]; bmax_j is the batch-size limit R_j of Section 3.2.2.  The job then
+ * runs on c_j = ceil(B_j / gpu_max_batch_j) GPUs with equal local batches.  The pool
+ * holds P = 4K candidates: slots [0,K) the refreshed survivors in rank order, [K,3K)
+ * the children of K parent pairs, [3K,4K) K mutants.
+ *
+ * Conventions.  Every function returns ONES_OK (0) or a negative ONES_E_* code; nothing
+ * aborts or throws across this boundary and outputs are untouched on error.  All job
+ * arrays are HOST pointers owned by the caller and copied during the call.  The device
+ * workspace and the HIP stream are owned by the caller and must outlive the context;
+ * the library allocates no device memory.  A context must be used by one thread at a
+ * time.  Calls on the same context execute in order on the context's stream.
+ */
+#ifndef ONES_H
+#define ONES_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define ONES_MAX_SLOTS      2048      /* job slots per cluster                         */
+#define ONES_MAX_GPUS       1048576   /* cluster size |C|                              */
+#define ONES_MAX_POPULATION 1048576   /* pool size P                                   */
+#define ONES_MAX_PARAM      1e100     /* upper bound of a, c, d, remaining             */
+
+enum {
+  ONES_OK = 0,
+  ONES_E_INVALID_ARG = -1,         /* null pointer, negative or out-of-range scalar      */
+  ONES_E_NOT_POW2 = -2,            /* bmin / bmax / gpu_max_batch of an active slot      */
+  ONES_E_BOUNDS = -3,              /* bmin > bmax, bmax > 2^30, bmax/gpu_max_batch > 2^20,
+                                      or a model parameter above ONES_MAX_PARAM          */
+  ONES_E_NONFINITE = -4,           /* NaN or infinity in a, c, d or remaining            */
+  ONES_E_WORKSPACE_TOO_SMALL = -5, /* workspace_bytes < ones_workspace_bytes(cfg), or
+                                      the workspace pointer is not 256-byte aligned      */
+  ONES_E_HIP = -6                  /* a HIP call failed; ones_strerror names it          */
+};
+
+typedef struct ones_ctx ones_ctx;  /* opaque, host side; owns no device memory */
+
+/* The search problem (Table 1: the GPU set C, the population; Section 3.2.2: theta). */
+typedef struct {
+  int32_t  n_gpus;         /* |C|, 0..ONES_MAX_GPUS                                      */
+  int32_t  n_slots;        /* job slots, 0..ONES_MAX_SLOTS; fixed for the context        */
+  int32_t  population;     /* pool size P > 0, multiple of 4; K = P/4 survive            */
+  uint64_t seed;           /* key of the counter-based generator                         */
+  double   mutation_rate;  /* theta in [0,1]: each job of a mutant is redrawn with it    */
+  double   crossover_rate; /* in [0,1]: per-gene probability that the children swap      */
+} ones_config;
+
+/* The job set J, one entry per slot (structure of arrays, each of length n_slots).
+ * Values of an inactive slot other than job_id are ignored. */
+typedef struct {
+  const int64_t *job_id;        /* identity; a change resets the slot's genes to "waiting" */
+  const uint8_t *active;        /* 0 = empty slot                                          */
+  const int32_t *bmin;          /* smallest allowed global batch, power of two             */
+  const int32_t *bmax;          /* limit R_j, power of two, bmin <= bmax <= 2^30           */
+  const int32_t *gpu_max_batch; /* per-GPU max batch, power of two, bmax/it <= 2^20        */
+  const double  *a, *c, *d;     /* iteration time t(B,g) = a*B/g + c*log2(g) + d seconds,
+                                   each finite, in [0, ONES_MAX_PARAM]                     */
+  const double  *remaining;     /* Y_j, remaining samples (Eq. 5), same range              */
+} ones_jobs;
+
+/* Bytes of device memory ones_init needs for cfg; 0 if cfg is invalid. */
+size_t ones_workspace_bytes(const ones_config *cfg);
+
+/* Creates a context and the initial population G_0 (Section 3.2.2 "Initialization"):
+ * P random genomes, each gene uniform over {waiting, bmin..bmax}, repaired, scored and
+ * ranked.  d_workspace: DEVICE pointer, 256-byte aligned, workspace_bytes long.
+ * hip_stream: a hipStream_t (NULL = the default stream).  Synchronises the stream
+ * before returning.  *out is written only on success. */
+int ones_init(ones_ctx **out, const ones_config *cfg, const ones_jobs *jobs,
+              void *d_workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Replaces the job table between scheduling epochs (the "real-time job status" the
+ * refresh operator reads, Section 3.2.2).  Slots whose job_id changed are set to
+ * "waiting" in every candidate; nothing else happens until the next generation, whose
+ * repair projects every candidate, survivors included, onto the new table.  The
+ * generation counter keeps running.  Synchronises the stream. */
+int ones_set_jobs(ones_ctx *ctx, const ones_jobs *jobs);
+
+/* Runs n_generations >= 0 generations (compose, repair, score, select), asynchronously
+ * on the stream. */
+int ones_generation(ones_ctx *ctx, int32_t n_generations);
+
+/* The winner S* (Alg. 1: smallest score): global batch and GPU count per slot (HOST
+ * arrays of n_slots entries, either may be NULL) and its score.  Synchronises. */
+int ones_best(ones_ctx *ctx, int32_t *batch_out, int32_t *gpus_out, double *fitness_out);
+
+/* Copies the whole state to HOST arrays (any may be NULL): genes[P][Jp] batch sizes with
+ * Jp = ones_padded_jobs(n_slots), fit[P], sel[K] (survivor slots by ascending
+ * (fitness, slot)), generation counter.  For parity checks and checkpoints.  Synchronises. */
+int ones_export(ones_ctx *ctx, int32_t *genes, double *fit, int32_t *sel, int64_t *generation);
+
+/* Job slots padded to whole rows of 64 columns: 64 * ceil(max(n_slots,1) / 64). */
+int32_t ones_padded_jobs(int32_t n_slots);
+
+/* Measurement hook.  When enabled, every launch of the evolve and select kernels is
+ * bracketed by HIP events on the context's stream; ones_profile_read synchronises and
+ * returns the accumulated kernel time in milliseconds and the launch counts since the
+ * last ones_profile_enable call (any output may be NULL). */
+int ones_profile_enable(ones_ctx *ctx, int32_t on);
+int ones_profile_read(ones_ctx *ctx, double *evolve_ms, int64_t *evolve_launches,
+                      double *select_ms, int64_t *select_launches);
+
+void ones_destroy(ones_ctx *ctx);           /* NULL is allowed */
+const char *ones_strerror(int code);        /* static or thread-local storage */
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -1,0 +1,357 @@
+// Host side of libones: argument validation, workspace layout, launch sequencing.
+// The boundary is declared and documented in include/ones.h.
+#include "ones.h"
+#include "ones_device.h"
+
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+namespace {
+
+using namespace ones;
+
+thread_local char g_hip_msg[256] = "HIP call failed";
+
+int hip_fail(hipError_t e, const char *what) {
+  snprintf(g_hip_msg, sizeof(g_hip_msg), "HIP call failed: %s: %s", what, hipGetErrorString(e));
+  return ONES_E_HIP;
+}
+#define HIP_TRY(expr)                                         \
+  do {                                                        \
+    hipError_t e__ = (expr);                                  \
+    if (e__ != hipSuccess) return hip_fail(e__, #expr);       \
+  } while (0)
+
+size_t align_up(size_t v) { return (v + 255) & ~static_cast<size_t>(255); }
+
+struct Layout {
+  size_t genes[2], fit, sel, keys, idx, cstart, cmax, info, abl, cc, d, Y;
+  size_t rawinfo, changed, ra, rc, rd, rY, best_batch, best_gpus, best_fit, total;
+};
+
+Layout make_layout(uint32_t P, uint32_t Jp) {
+  Layout L;
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t at = off; off = align_up(off + bytes); return at; };
+  const size_t chunks = (P + kSortChunk - 1) / kSortChunk;
+  L.genes[0] = take(static_cast<size_t>(P) * Jp * 4);
+  L.genes[1] = take(static_cast<size_t>(P) * Jp * 4);
+  L.fit = take(static_cast<size_t>(P) * 8);
+  L.sel = take(static_cast<size_t>(P / 4) * 4);
+  L.keys = take(chunks * kSortChunk * 8);
+  L.idx = take(chunks * kSortChunk * 4);
+  L.cstart = take(Jp * 4); L.cmax = take(Jp * 4); L.info = take(Jp * 4);
+  L.abl = take(Jp * 8); L.cc = take(Jp * 8); L.d = take(Jp * 8); L.Y = take(Jp * 8);
+  L.rawinfo = take(Jp * 4); L.changed = take(Jp * 4);
+  L.ra = take(Jp * 8); L.rc = take(Jp * 8); L.rd = take(Jp * 8); L.rY = take(Jp * 8);
+  L.best_batch = take(Jp * 4); L.best_gpus = take(Jp * 4); L.best_fit = take(8);
+  L.total = off;
+  return L;
+}
+
+int check_config(const ones_config *cfg) {
+  if (!cfg) return ONES_E_INVALID_ARG;
+  if (cfg->n_gpus < 0 || cfg->n_gpus > ONES_MAX_GPUS) return ONES_E_INVALID_ARG;
+  if (cfg->n_slots < 0 || cfg->n_slots > ONES_MAX_SLOTS) return ONES_E_INVALID_ARG;
+  if (cfg->population <= 0 || cfg->population % 4 != 0 || cfg->population > ONES_MAX_POPULATION)
+    return ONES_E_INVALID_ARG;
+  if (!(cfg->mutation_rate >= 0.0 && cfg->mutation_rate <= 1.0)) return ONES_E_INVALID_ARG;
+  if (!(cfg->crossover_rate >= 0.0 && cfg->crossover_rate <= 1.0)) return ONES_E_INVALID_ARG;
+  return ONES_OK;
+}
+
+// A rate becomes a threshold on a uniform 32-bit word: min(2^32 - 1, floor(rate * 2^32)).
+uint32_t rate_threshold(double rate) {
+  const double v = std::floor(rate * 4294967296.0);
+  return v >= 4294967295.0 ? 0xFFFFFFFFu : static_cast<uint32_t>(v);
+}
+
+int log2_pow2(int32_t v) {           // -1 unless v is a power of two
+  if (v <= 0 || (v & (v - 1)) != 0) return -1;
+  return 31 - __builtin_clz(static_cast<uint32_t>(v));
+}
+
+int check_param(double v) {
+  if (!std::isfinite(v)) return ONES_E_NONFINITE;
+  if (v < 0.0) return ONES_E_INVALID_ARG;
+  if (v > ONES_MAX_PARAM) return ONES_E_BOUNDS;
+  return ONES_OK;
+}
+
+struct HostJobs {                     // validated, padded staging copy of a job table
+  std::vector<uint32_t> rawinfo;
+  std::vector<double> a, c, d, Y;
+  std::vector<int64_t> id;
+};
+
+int stage_jobs(int Jn, int Jp, const ones_jobs *jobs, HostJobs &h) {
+  h.rawinfo.assign(Jp, 0u);
+  h.a.assign(Jp, 0.0); h.c.assign(Jp, 0.0); h.d.assign(Jp, 0.0); h.Y.assign(Jp, 0.0);
+  h.id.assign(Jp, 0);
+  if (Jn > 0 && (!jobs || !jobs->job_id || !jobs->active || !jobs->bmin || !jobs->bmax ||
+                 !jobs->gpu_max_batch || !jobs->a || !jobs->c || !jobs->d || !jobs->remaining))
+    return ONES_E_INVALID_ARG;
+  for (int j = 0; j < Jn; ++j) {
+    h.id[j] = jobs->job_id[j];
+    if (!jobs->active[j]) continue;
+    const int lo = log2_pow2(jobs->bmin[j]), hi = log2_pow2(jobs->bmax[j]);
+    const int mu = log2_pow2(jobs->gpu_max_batch[j]);
+    if (lo < 0 || hi < 0 || mu < 0) return ONES_E_NOT_POW2;
+    if (lo > hi || hi > 30 || hi - mu > 20) return ONES_E_BOUNDS;
+    int rc;
+    if ((rc = check_param(jobs->a[j])) || (rc = check_param(jobs->c[j])) ||
+        (rc = check_param(jobs->d[j])) || (rc = check_param(jobs->remaining[j])))
+      return rc;
+    h.rawinfo[j] = static_cast<uint32_t>(lo) | (static_cast<uint32_t>(hi) << 5) |
+                   (static_cast<uint32_t>(mu) << 10) | (1u << 15);
+    h.a[j] = jobs->a[j]; h.c[j] = jobs->c[j]; h.d[j] = jobs->d[j]; h.Y[j] = jobs->remaining[j];
+  }
+  return ONES_OK;
+}
+
+struct EventPair { hipEvent_t start, stop; };
+
+}  // namespace
+
+struct ones_ctx {
+  ones_config cfg;
+  uint32_t P, K, Jn, Jp, R, G;
+  uint32_t T_mut, T_x;
+  hipStream_t stream;
+  char *ws;
+  Layout L;
+  int cur;                    // genome buffer holding the current generation
+  int64_t t;                  // generation counter
+  std::vector<int64_t> ids;   // job identity per slot, to detect slots that change hands
+  // measurement
+  bool profiling;
+  std::vector<EventPair> evolve_ev, select_ev;
+  size_t evolve_used, select_used;
+
+  template <typename T> T *at(size_t off) const { return reinterpret_cast<T *>(ws + off); }
+  JobTable table() const {
+    return JobTable{at<uint32_t>(L.cstart), at<uint32_t>(L.cmax), at<uint32_t>(L.info),
+                    at<double>(L.abl), at<double>(L.cc), at<double>(L.d), at<double>(L.Y)};
+  }
+};
+
+namespace {
+
+int upload_table(ones_ctx *c, const HostJobs &h, const std::vector<uint32_t> *changed) {
+  const size_t n4 = static_cast<size_t>(c->Jp) * 4, n8 = static_cast<size_t>(c->Jp) * 8;
+  HIP_TRY(hipMemcpyAsync(c->ws + c->L.rawinfo, h.rawinfo.data(), n4, hipMemcpyHostToDevice, c->stream));
+  HIP_TRY(hipMemcpyAsync(c->ws + c->L.ra, h.a.data(), n8, hipMemcpyHostToDevice, c->stream));
+  HIP_TRY(hipMemcpyAsync(c->ws + c->L.rc, h.c.data(), n8, hipMemcpyHostToDevice, c->stream));
+  HIP_TRY(hipMemcpyAsync(c->ws + c->L.rd, h.d.data(), n8, hipMemcpyHostToDevice, c->stream));
+  HIP_TRY(hipMemcpyAsync(c->ws + c->L.rY, h.Y.data(), n8, hipMemcpyHostToDevice, c->stream));
+  RawJobs raw{c->at<uint32_t>(c->L.rawinfo), c->at<double>(c->L.ra), c->at<double>(c->L.rc),
+              c->at<double>(c->L.rd), c->at<double>(c->L.rY)};
+  HIP_TRY(launch_prepare_table(raw, c->table(), c->Jp, c->stream));
+  if (changed) {
+    HIP_TRY(hipMemcpyAsync(c->ws + c->L.changed, changed->data(), n4, hipMemcpyHostToDevice, c->stream));
+    HIP_TRY(launch_reset_slots(c->at<int32_t>(c->L.genes[c->cur]), c->at<uint32_t>(c->L.changed), c->P, c->Jp,
+                               c->stream));
+  }
+  HIP_TRY(hipStreamSynchronize(c->stream));     // the staging vectors may go away now
+  return ONES_OK;
+}
+
+int timed(ones_ctx *c, std::vector<EventPair> &pool, size_t &used, bool begin) {
+  if (!c->profiling) return ONES_OK;
+  if (begin) {
+    if (used == pool.size()) {
+      EventPair e;
+      HIP_TRY(hipEventCreate(&e.start));
+      HIP_TRY(hipEventCreate(&e.stop));
+      pool.push_back(e);
+    }
+    HIP_TRY(hipEventRecord(pool[used].start, c->stream));
+  } else {
+    HIP_TRY(hipEventRecord(pool[used].stop, c->stream));
+    ++used;
+  }
+  return ONES_OK;
+}
+
+int run_generation(ones_ctx *c, uint32_t t) {
+  EvolveArgs a;
+  a.genes_old = c->at<int32_t>(c->L.genes[c->cur]);
+  a.genes_new = c->at<int32_t>(c->L.genes[t == 0 ? c->cur : c->cur ^ 1]);
+  a.sel = c->at<int32_t>(c->L.sel);
+  a.fit = c->at<double>(c->L.fit);
+  a.tab = c->table();
+  a.G = c->G; a.P = c->P; a.K = c->K; a.Jp = c->Jp;
+  a.key0 = static_cast<uint32_t>(c->cfg.seed);
+  a.key1 = static_cast<uint32_t>(c->cfg.seed >> 32);
+  a.t = t; a.T_mut = c->T_mut; a.T_x = c->T_x;
+  int rc;
+  if ((rc = timed(c, c->evolve_ev, c->evolve_used, true))) return rc;
+  HIP_TRY(launch_evolve(a, static_cast<int>(c->R), c->stream));
+  if ((rc = timed(c, c->evolve_ev, c->evolve_used, false))) return rc;
+  if ((rc = timed(c, c->select_ev, c->select_used, true))) return rc;
+  HIP_TRY(launch_select(a.fit, c->P, c->K, c->at<uint64_t>(c->L.keys), c->at<uint32_t>(c->L.idx),
+                        c->at<int32_t>(c->L.sel), c->stream));
+  if ((rc = timed(c, c->select_ev, c->select_used, false))) return rc;
+  if (t != 0) c->cur ^= 1;
+  return ONES_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int32_t ones_padded_jobs(int32_t n_slots) {
+  const int32_t n = n_slots < 1 ? 1 : n_slots;
+  return kLanes * ((n + kLanes - 1) / kLanes);
+}
+
+size_t ones_workspace_bytes(const ones_config *cfg) {
+  if (check_config(cfg) != ONES_OK) return 0;
+  return make_layout(static_cast<uint32_t>(cfg->population),
+                     static_cast<uint32_t>(ones_padded_jobs(cfg->n_slots))).total;
+}
+
+int ones_init(ones_ctx **out, const ones_config *cfg, const ones_jobs *jobs, void *d_workspace,
+              size_t workspace_bytes, void *hip_stream) {
+  if (!out) return ONES_E_INVALID_ARG;
+  int rc = check_config(cfg);
+  if (rc) return rc;
+  const int Jp = ones_padded_jobs(cfg->n_slots);
+  HostJobs h;
+  if ((rc = stage_jobs(cfg->n_slots, Jp, jobs, h))) return rc;
+  const Layout L = make_layout(static_cast<uint32_t>(cfg->population), static_cast<uint32_t>(Jp));
+  if (!d_workspace) return ONES_E_INVALID_ARG;
+  if (workspace_bytes < L.total || (reinterpret_cast<uintptr_t>(d_workspace) & 255u) != 0)
+    return ONES_E_WORKSPACE_TOO_SMALL;
+  ones_ctx *c = new (std::nothrow) ones_ctx();
+  if (!c) return ONES_E_INVALID_ARG;
+  c->cfg = *cfg;
+  c->P = static_cast<uint32_t>(cfg->population); c->K = c->P / 4;
+  c->Jn = static_cast<uint32_t>(cfg->n_slots); c->Jp = static_cast<uint32_t>(Jp); c->R = c->Jp / kLanes;
+  c->G = static_cast<uint32_t>(cfg->n_gpus);
+  c->T_mut = rate_threshold(cfg->mutation_rate);
+  c->T_x = rate_threshold(cfg->crossover_rate);
+  c->stream = static_cast<hipStream_t>(hip_stream);
+  c->ws = static_cast<char *>(d_workspace);
+  c->L = L;
+  c->cur = 0; c->t = 0;
+  c->ids = h.id;
+  c->profiling = false; c->evolve_used = c->select_used = 0;
+  if ((rc = upload_table(c, h, nullptr)) || (rc = run_generation(c, 0))) { ones_destroy(c); return rc; }
+  hipError_t e = hipStreamSynchronize(c->stream);
+  if (e != hipSuccess) { ones_destroy(c); return hip_fail(e, "hipStreamSynchronize"); }
+  *out = c;
+  return ONES_OK;
+}
+
+int ones_set_jobs(ones_ctx *c, const ones_jobs *jobs) {
+  if (!c) return ONES_E_INVALID_ARG;
+  HostJobs h;
+  int rc = stage_jobs(static_cast<int>(c->Jn), static_cast<int>(c->Jp), jobs, h);
+  if (rc) return rc;
+  std::vector<uint32_t> changed(c->Jp, 0u);
+  bool any = false;
+  for (uint32_t j = 0; j < c->Jn; ++j)
+    if (h.id[j] != c->ids[j]) { changed[j] = 1u; any = true; }
+  if ((rc = upload_table(c, h, any ? &changed : nullptr))) return rc;
+  c->ids = h.id;
+  return ONES_OK;
+}
+
+int ones_generation(ones_ctx *c, int32_t n_generations) {
+  if (!c || n_generations < 0) return ONES_E_INVALID_ARG;
+  if (c->t + n_generations > 0xFFFFFFFFll) return ONES_E_INVALID_ARG;
+  for (int32_t i = 0; i < n_generations; ++i) {
+    int rc = run_generation(c, static_cast<uint32_t>(c->t + 1));
+    if (rc) return rc;
+    c->t += 1;
+  }
+  return ONES_OK;
+}
+
+int ones_best(ones_ctx *c, int32_t *batch_out, int32_t *gpus_out, double *fitness_out) {
+  if (!c) return ONES_E_INVALID_ARG;
+  HIP_TRY(launch_best(c->at<int32_t>(c->L.genes[c->cur]), c->at<double>(c->L.fit), c->at<int32_t>(c->L.sel),
+                      c->at<uint32_t>(c->L.info), c->Jn, c->Jp, c->at<int32_t>(c->L.best_batch),
+                      c->at<int32_t>(c->L.best_gpus), c->at<double>(c->L.best_fit), c->stream));
+  std::vector<int32_t> b(c->Jn), g(c->Jn);
+  double f = 0.0;
+  if (c->Jn) {
+    HIP_TRY(hipMemcpyAsync(b.data(), c->ws + c->L.best_batch, c->Jn * 4, hipMemcpyDeviceToHost, c->stream));
+    HIP_TRY(hipMemcpyAsync(g.data(), c->ws + c->L.best_gpus, c->Jn * 4, hipMemcpyDeviceToHost, c->stream));
+  }
+  HIP_TRY(hipMemcpyAsync(&f, c->ws + c->L.best_fit, 8, hipMemcpyDeviceToHost, c->stream));
+  HIP_TRY(hipStreamSynchronize(c->stream));
+  if (batch_out && c->Jn) memcpy(batch_out, b.data(), c->Jn * 4);
+  if (gpus_out && c->Jn) memcpy(gpus_out, g.data(), c->Jn * 4);
+  if (fitness_out) *fitness_out = f;
+  return ONES_OK;
+}
+
+int ones_export(ones_ctx *c, int32_t *genes, double *fit, int32_t *sel, int64_t *generation) {
+  if (!c) return ONES_E_INVALID_ARG;
+  // outputs must stay untouched on error: stage, then copy
+  HIP_TRY(hipStreamSynchronize(c->stream));
+  if (genes)
+    HIP_TRY(hipMemcpy(genes, c->ws + c->L.genes[c->cur], static_cast<size_t>(c->P) * c->Jp * 4,
+                      hipMemcpyDeviceToHost));
+  if (fit) HIP_TRY(hipMemcpy(fit, c->ws + c->L.fit, static_cast<size_t>(c->P) * 8, hipMemcpyDeviceToHost));
+  if (sel) HIP_TRY(hipMemcpy(sel, c->ws + c->L.sel, static_cast<size_t>(c->K) * 4, hipMemcpyDeviceToHost));
+  if (generation) *generation = c->t;
+  return ONES_OK;
+}
+
+int ones_profile_enable(ones_ctx *c, int32_t on) {
+  if (!c) return ONES_E_INVALID_ARG;
+  HIP_TRY(hipStreamSynchronize(c->stream));
+  c->profiling = on != 0;
+  c->evolve_used = c->select_used = 0;
+  return ONES_OK;
+}
+
+int ones_profile_read(ones_ctx *c, double *evolve_ms, int64_t *evolve_launches, double *select_ms,
+                      int64_t *select_launches) {
+  if (!c) return ONES_E_INVALID_ARG;
+  HIP_TRY(hipStreamSynchronize(c->stream));
+  double em = 0.0, sm = 0.0;
+  for (size_t i = 0; i < c->evolve_used; ++i) {
+    float ms = 0.f;
+    HIP_TRY(hipEventElapsedTime(&ms, c->evolve_ev[i].start, c->evolve_ev[i].stop));
+    em += ms;
+  }
+  for (size_t i = 0; i < c->select_used; ++i) {
+    float ms = 0.f;
+    HIP_TRY(hipEventElapsedTime(&ms, c->select_ev[i].start, c->select_ev[i].stop));
+    sm += ms;
+  }
+  if (evolve_ms) *evolve_ms = em;
+  if (evolve_launches) *evolve_launches = static_cast<int64_t>(c->evolve_used);
+  if (select_ms) *select_ms = sm;
+  if (select_launches) *select_launches = static_cast<int64_t>(c->select_used);
+  return ONES_OK;
+}
+
+void ones_destroy(ones_ctx *c) {
+  if (!c) return;
+  for (auto &e : c->evolve_ev) { (void)hipEventDestroy(e.start); (void)hipEventDestroy(e.stop); }
+  for (auto &e : c->select_ev) { (void)hipEventDestroy(e.start); (void)hipEventDestroy(e.stop); }
+  delete c;
+}
+
+const char *ones_strerror(int code) {
+  switch (code) {
+    case ONES_OK: return "ok";
+    case ONES_E_INVALID_ARG: return "invalid argument";
+    case ONES_E_NOT_POW2: return "bmin, bmax and gpu_max_batch of an active slot must be powers of two";
+    case ONES_E_BOUNDS: return "batch window or model parameter out of bounds";
+    case ONES_E_NONFINITE: return "NaN or infinity in a job parameter";
+    case ONES_E_WORKSPACE_TOO_SMALL: return "workspace too small or not 256-byte aligned";
+    case ONES_E_HIP: return g_hip_msg;
+    default: return "unknown error code";
+  }
+}
+
+}  // extern "C"

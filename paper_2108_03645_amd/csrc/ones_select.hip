@@ -1,0 +1,172 @@
+// Selection of the best K candidates (arXiv 2108.03645, Section 3.2.2 "Selection"; Alg. 1:
+// the smallest score wins), plus the small table / readout kernels of libones.
+//
+// Order: ascending (score, pool slot).  A score is a non-negative fp64, so its bit pattern
+// read as an unsigned 64-bit integer orders the same way; ties fall to the smaller slot.
+#include "ones_device.h"
+
+#pragma clang fp contract(off)
+
+namespace ones {
+namespace {
+
+constexpr int kSortThreads = 1024;
+
+struct Key { uint64_t k; uint32_t i; };
+
+__device__ __forceinline__ bool key_less(uint64_t ka, uint32_t ia, uint64_t kb, uint32_t ib) {
+  return ka < kb || (ka == kb && ia < ib);
+}
+
+// Each workgroup sorts one chunk of n (power of two, <= kSortChunk) keys with a bitonic
+// network in LDS.  With a single chunk the survivors are written directly.
+__global__ __launch_bounds__(kSortThreads) void sort_chunks_kernel(const double *fit, uint32_t P, uint32_t K,
+                                                                  uint32_t n, uint64_t *keys, uint32_t *idx,
+                                                                  int32_t *sel, int single) {
+  __shared__ uint64_t sk[kSortChunk];
+  __shared__ uint32_t si[kSortChunk];
+  const uint32_t base = blockIdx.x * n;
+  for (uint32_t e = threadIdx.x; e < n; e += kSortThreads) {
+    const uint32_t p = base + e;
+    sk[e] = p < P ? static_cast<uint64_t>(__double_as_longlong(fit[p])) : ~0ull;   // padding sorts last
+    si[e] = p < P ? p : 0xFFFFFFFFu;
+  }
+  __syncthreads();
+  for (uint32_t k = 2; k <= n; k <<= 1) {
+    for (uint32_t j = k >> 1; j > 0; j >>= 1) {
+      for (uint32_t e = threadIdx.x; e < n / 2; e += kSortThreads) {
+        const uint32_t lo = ((e & ~(j - 1)) << 1) | (e & (j - 1));
+        const uint32_t hi = lo | j;
+        const bool up = (lo & k) == 0;
+        const uint64_t ka = sk[lo], kb = sk[hi];
+        const uint32_t ia = si[lo], ib = si[hi];
+        if (key_less(kb, ib, ka, ia) == up) {
+          sk[lo] = kb; si[lo] = ib;
+          sk[hi] = ka; si[hi] = ia;
+        }
+      }
+      __syncthreads();
+    }
+  }
+  if (single) {
+    for (uint32_t e = threadIdx.x; e < K; e += kSortThreads) sel[e] = static_cast<int32_t>(si[e]);
+  } else {
+    for (uint32_t e = threadIdx.x; e < n; e += kSortThreads) {
+      keys[base + e] = sk[e];
+      idx[base + e] = si[e];
+    }
+  }
+}
+
+// Global rank of every element = its position in its own sorted chunk + the number of
+// smaller elements in every other chunk (binary search).  Ranks below K are survivors.
+__global__ __launch_bounds__(256) void rank_kernel(const uint64_t *keys, const uint32_t *idx, uint32_t chunks,
+                                                  uint32_t K, int32_t *sel) {
+  const uint32_t e = blockIdx.x * blockDim.x + threadIdx.x;
+  if (e >= chunks * kSortChunk) return;
+  const uint32_t mine = e / kSortChunk, pos = e % kSortChunk;
+  const uint32_t id = idx[e];
+  if (pos >= K || id == 0xFFFFFFFFu) return;
+  const uint64_t key = keys[e];
+  uint32_t rank = pos;
+  for (uint32_t c = 0; c < chunks && rank < K; ++c) {
+    if (c == mine) continue;
+    const uint64_t *ck = keys + static_cast<size_t>(c) * kSortChunk;
+    const uint32_t *ci = idx + static_cast<size_t>(c) * kSortChunk;
+    uint32_t lo = 0, hi = kSortChunk;                 // count of chunk elements below (key, id)
+    while (lo < hi) {
+      const uint32_t mid = (lo + hi) >> 1;
+      if (key_less(ck[mid], ci[mid], key, id)) lo = mid + 1; else hi = mid;
+    }
+    rank += lo;
+  }
+  if (rank < K) sel[rank] = static_cast<int32_t>(id);
+}
+
+__global__ void prepare_table_kernel(RawJobs raw, JobTable tab, uint32_t Jp) {
+  const uint32_t j = blockIdx.x * blockDim.x + threadIdx.x;
+  if (j >= Jp) return;
+  const uint32_t w = raw.rawinfo[j];
+  const int lo = w & 31, hi = (w >> 5) & 31, mu = (w >> 10) & 31;
+  if (!((w >> 15) & 1u)) {
+    tab.cstart[j] = 0; tab.cmax[j] = 0; tab.info[j] = 0;
+    tab.abl[j] = 0.0; tab.cc[j] = 0.0; tab.d[j] = 0.0; tab.Y[j] = 0.0;
+    return;
+  }
+  const int bl = min(mu, hi);                       // log2 of the local batch of a running job
+  const int gstart = max(lo, bl);                   // batch a waiting job resumes with
+  tab.cstart[j] = 1u << max(0, gstart - mu);
+  tab.cmax[j] = 1u << max(0, hi - mu);
+  tab.info[j] = static_cast<uint32_t>(lo) | (static_cast<uint32_t>(hi - lo + 2) << 5) |
+                (static_cast<uint32_t>(mu) << 11) | (static_cast<uint32_t>(bl) << 16) | (1u << 21);
+  tab.abl[j] = raw.a[j] * static_cast<double>(1u << bl);
+  tab.cc[j] = raw.c[j];
+  tab.d[j] = raw.d[j];
+  tab.Y[j] = raw.Y[j];
+}
+
+__global__ void reset_slots_kernel(int32_t *genes, const uint32_t *changed, uint32_t P, uint32_t Jp) {
+  const size_t n = static_cast<size_t>(P) * Jp;
+  for (size_t e = blockIdx.x * static_cast<size_t>(blockDim.x) + threadIdx.x; e < n;
+       e += static_cast<size_t>(gridDim.x) * blockDim.x)
+    if (changed[e % Jp]) genes[e] = 0;
+}
+
+__global__ void best_kernel(const int32_t *genes, const double *fit, const int32_t *sel, const uint32_t *info,
+                            uint32_t Jn, uint32_t Jp, int32_t *batch_out, int32_t *gpus_out, double *fit_out) {
+  const uint32_t best = static_cast<uint32_t>(sel[0]);
+  const int32_t *row = genes + static_cast<size_t>(best) * Jp;
+  for (uint32_t j = threadIdx.x; j < Jn; j += blockDim.x) {
+    const uint32_t B = static_cast<uint32_t>(row[j]);
+    batch_out[j] = static_cast<int32_t>(B);
+    gpus_out[j] = static_cast<int32_t>(B ? max(1u, B >> info_mu(info[j])) : 0u);
+  }
+  if (threadIdx.x == 0) *fit_out = fit[best];
+}
+
+uint32_t next_pow2(uint32_t v) {
+  uint32_t n = 1;
+  while (n < v) n <<= 1;
+  return n;
+}
+
+}  // namespace
+
+hipError_t launch_prepare_table(const RawJobs &raw, const JobTable &tab, uint32_t Jp, hipStream_t s) {
+  hipLaunchKernelGGL(prepare_table_kernel, dim3((Jp + 255) / 256), dim3(256), 0, s, raw, tab, Jp);
+  return hipGetLastError();
+}
+
+hipError_t launch_reset_slots(int32_t *genes, const uint32_t *changed, uint32_t P, uint32_t Jp, hipStream_t s) {
+  const size_t n = static_cast<size_t>(P) * Jp;
+  const uint32_t blocks = static_cast<uint32_t>(std::min<size_t>((n + 255) / 256, 65536));
+  hipLaunchKernelGGL(reset_slots_kernel, dim3(blocks), dim3(256), 0, s, genes, changed, P, Jp);
+  return hipGetLastError();
+}
+
+hipError_t launch_select(const double *fit, uint32_t P, uint32_t K, uint64_t *keys, uint32_t *idx,
+                         int32_t *sel, hipStream_t s) {
+  if (P <= static_cast<uint32_t>(kSortChunk)) {
+    hipLaunchKernelGGL(sort_chunks_kernel, dim3(1), dim3(kSortThreads), 0, s, fit, P, K, next_pow2(P), keys, idx,
+                       sel, 1);
+    return hipGetLastError();
+  }
+  const uint32_t chunks = (P + kSortChunk - 1) / kSortChunk;
+  hipLaunchKernelGGL(sort_chunks_kernel, dim3(chunks), dim3(kSortThreads), 0, s, fit, P, K,
+                     static_cast<uint32_t>(kSortChunk), keys, idx, sel, 0);
+  hipError_t rc = hipGetLastError();
+  if (rc != hipSuccess) return rc;
+  const uint32_t n = chunks * kSortChunk;
+  hipLaunchKernelGGL(rank_kernel, dim3((n + 255) / 256), dim3(256), 0, s, keys, idx, chunks, K, sel);
+  return hipGetLastError();
+}
+
+hipError_t launch_best(const int32_t *genes, const double *fit, const int32_t *sel, const uint32_t *info,
+                       uint32_t Jn, uint32_t Jp, int32_t *batch_out, int32_t *gpus_out, double *fit_out,
+                       hipStream_t s) {
+  hipLaunchKernelGGL(best_kernel, dim3(1), dim3(256), 0, s, genes, fit, sel, info, Jn, Jp, batch_out, gpus_out,
+                     fit_out);
+  return hipGetLastError();
+}
+
+}  // namespace ones

@@ -1,0 +1,245 @@
+"""GPU parity: libones (HIP, through the C ABI) against the CPU oracle on the same seeded
+inputs.  Genomes and survivor lists must match bit for bit every generation; scores within
+1e-12 relative (they are expected to be bit-identical too, which is asserted separately)."""
+import sys
+from types import SimpleNamespace
+
+import numpy as np
+import pytest
+
+from paper_2108_03645_amd import workloads as W
+from pyref import make_jobs, random_jobs
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def ones():
+    from paper_2108_03645_amd import ones as binding
+    binding.load()           # fails loudly if the library is not built
+    return binding
+
+
+def cluster(n_gpus, n_slots, population, seed=0, theta=0.1, chi=0.5):
+    return SimpleNamespace(n_gpus=n_gpus, n_slots=n_slots, population=population, seed=seed,
+                           mutation_rate=theta, crossover_rate=chi)
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def assert_same_state(gpu, cpu, where):
+    g_genes, g_fit, g_sel, g_t = gpu.export()
+    c_genes, c_fit, c_sel, c_t = cpu.export()
+    assert g_t == c_t, where
+    bad = np.flatnonzero((g_genes != c_genes).any(axis=1))
+    assert bad.size == 0, f"{where}: genomes differ in {bad.size} slots, first {bad[:5]}"
+    rel = np.abs(g_fit - c_fit) / np.maximum(np.abs(c_fit), 1e-300)
+    assert rel.max() <= 1e-12 if rel.size else True, f"{where}: fitness off by {rel.max()}"
+    assert np.array_equal(g_sel, c_sel), f"{where}: survivor lists differ"
+    assert np.array_equal(g_fit.view(np.uint64), c_fit.view(np.uint64)), f"{where}: fitness bits differ"
+
+
+def run_pair(ones, ref, cl, jobs, generations, every=1, label=""):
+    say(f"[parity] {label}: G={cl.n_gpus} slots={cl.n_slots} P={cl.population} seed={cl.seed} gens={generations}")
+    gpu = ones.Search(cl, jobs)
+    cpu = ref.RefSearch(cl, jobs)
+    assert_same_state(gpu, cpu, f"{label} generation 0")
+    done = 0
+    while done < generations:
+        step = min(every, generations - done)
+        gpu.generation(step)
+        cpu.generation(step)
+        done += step
+        assert_same_state(gpu, cpu, f"{label} generation {done}")
+    gb, gg, gf = gpu.best()
+    cb, cg, cf = cpu.best()
+    assert gb.tolist() == cb.tolist() and gg.tolist() == cg.tolist() and gf == cf
+    gpu.close(); cpu.close()
+
+
+def test_tiny_every_generation(ones, ref):
+    cl, jobs = W.tiny()
+    run_pair(ones, ref, cl, jobs, cl.generations, 1, "tiny")
+
+
+def test_paper_scale(ones, ref):
+    cl, jobs = W.paper_scale()
+    run_pair(ones, ref, cl, jobs, cl.generations, 5, "paper_scale")
+
+
+@pytest.mark.parametrize("n_slots,n_gpus,pop,seed", [
+    (1, 3, 8, 1), (63, 40, 64, 2), (64, 64, 128, 3), (65, 100, 64, 4), (130, 90, 256, 5),
+    (300, 500, 128, 6), (448, 300, 64, 7), (700, 5000, 64, 8), (1000, 1500, 128, 9),
+    (1500, 800, 64, 10), (2048, 4096, 256, 11),
+])
+def test_ragged_shapes(ones, ref, n_slots, n_gpus, pop, seed):
+    """Row counts 1..32 including odd ones, a ragged last row, inactive slots, mixed
+    per-GPU batch sizes and windows."""
+    rng = np.random.default_rng(seed)
+    jobs = random_jobs(rng, n_slots)
+    run_pair(ones, ref, cluster(n_gpus, n_slots, pop, seed=seed * 7919), jobs, 4, 1,
+             f"ragged{n_slots}")
+
+
+@pytest.mark.parametrize("rows", list(range(1, 33)))
+def test_every_row_count(ones, ref, rows):
+    rng = np.random.default_rng(100 + rows)
+    n_slots = 64 * rows - int(rng.integers(0, 64))
+    jobs = random_jobs(rng, n_slots)
+    run_pair(ones, ref, cluster(int(n_slots * 1.3), n_slots, 32, seed=rows), jobs, 2, 1, f"rows{rows}")
+
+
+def test_large_reduced_population(ones, ref):
+    cl, jobs = W.large()
+    cl.population = 2048
+    run_pair(ones, ref, cl, jobs, 6, 2, "large/P=2048")
+
+
+def test_stress_reduced_population(ones, ref):
+    cl, jobs = W.stress(population=1024)
+    run_pair(ones, ref, cl, jobs, 4, 2, "stress/P=1024")
+
+
+def test_selection_across_sort_chunks(ones, ref):
+    """Pool larger than one LDS sort chunk, with massive score ties (few distinct genomes)."""
+    jobs = make_jobs(6, bmin=256, bmax=512)
+    run_pair(ones, ref, cluster(5, 6, 4096 * 3 + 8, seed=12), jobs, 3, 1, "ties/P=12296")
+
+
+@pytest.mark.parametrize("theta,chi", [(0.0, 0.0), (1.0, 1.0), (0.0, 1.0), (1.0, 0.5)])
+def test_rate_extremes(ones, ref, theta, chi):
+    rng = np.random.default_rng(21)
+    jobs = random_jobs(rng, 100)
+    run_pair(ones, ref, cluster(150, 100, 64, seed=5, theta=theta, chi=chi), jobs, 4, 1,
+             f"theta={theta} chi={chi}")
+
+
+def test_degenerate_clusters(ones, ref):
+    run_pair(ones, ref, cluster(8, 0, 16), make_jobs(0), 2, 1, "no slots")
+    run_pair(ones, ref, cluster(8, 10, 16), make_jobs(10, active=0), 2, 1, "all inactive")
+    run_pair(ones, ref, cluster(0, 10, 16), make_jobs(10), 2, 1, "no GPUs")
+    run_pair(ones, ref, cluster(1, 1, 4), make_jobs(1), 3, 1, "one job, one GPU, K=1")
+    run_pair(ones, ref, cluster(1 << 20, 70, 8), make_jobs(70, bmin=1, bmax=1 << 28, gpu_max_batch=256),
+             2, 1, "largest GPU counts")
+    run_pair(ones, ref, cluster(40, 90, 8), make_jobs(90, bmin=2048, bmax=4096, gpu_max_batch=64),
+             2, 1, "window above the per-GPU batch")
+    run_pair(ones, ref, cluster(40, 90, 8), make_jobs(90, bmin=1, bmax=16, gpu_max_batch=512),
+             2, 1, "window below the per-GPU batch")
+
+
+def test_online_sequence(ones, ref):
+    """Warm-started epochs: arrivals, completions, shrinking limits; both sides are driven by
+    their own best schedule through the same cluster simulation."""
+    sims = [W.OnlineSequence(epochs=40), W.OnlineSequence(epochs=40)]
+    cl = sims[0].cluster
+    cl.population = 512
+    say(f"[parity] online: P={cl.population} epochs=40 gens/epoch=5")
+    gpu = ones.Search(cl, sims[0].jobs)
+    cpu = ref.RefSearch(cl, sims[1].jobs)
+    for epoch in range(40):
+        gpu.generation(5); cpu.generation(5)
+        assert_same_state(gpu, cpu, f"online epoch {epoch}")
+        gb, gg, gf = gpu.best(); cb, cg, cf = cpu.best()
+        assert gb.tolist() == cb.tolist() and gg.tolist() == cg.tolist() and gf == cf
+        sims[0].advance(gb); sims[1].advance(cb)
+        assert sims[0].jobs.sha256() == sims[1].jobs.sha256()
+        gpu.set_jobs(sims[0].jobs); cpu.set_jobs(sims[1].jobs)
+        assert_same_state(gpu, cpu, f"online epoch {epoch} after set_jobs")
+    assert sims[0].completed > 0
+    gpu.close(); cpu.close()
+
+
+def test_set_jobs_rejects_bad_tables_and_keeps_state(ones, ref):
+    rng = np.random.default_rng(31)
+    jobs = random_jobs(rng, 64)
+    cl = cluster(64, 64, 64, seed=3)
+    gpu = ones.Search(cl, jobs); cpu = ref.RefSearch(cl, jobs)
+    gpu.generation(2); cpu.generation(2)
+    bad = SimpleNamespace(**{k: getattr(jobs, k).copy() for k in vars(jobs)})
+    live = int(np.flatnonzero(jobs.active)[0])
+    bad.bmin[live] = 48
+    with pytest.raises(ones.OnesError) as e:
+        gpu.set_jobs(bad)
+    assert e.value.code == -2
+    bad.bmin[live] = jobs.bmin[live]; bad.remaining[live] = float("nan")
+    with pytest.raises(ones.OnesError) as e:
+        gpu.set_jobs(bad)
+    assert e.value.code == -4
+    assert_same_state(gpu, cpu, "after rejected set_jobs")
+    gpu.generation(1); cpu.generation(1)
+    assert_same_state(gpu, cpu, "generation after rejected set_jobs")
+
+
+def test_init_rejects_bad_arguments(ones):
+    import torch
+    jobs = make_jobs(4)
+    with pytest.raises(ones.OnesError) as e:
+        ones.Search(cluster(4, 4, 18), jobs)
+    assert e.value.code == -1
+    with pytest.raises(ones.OnesError) as e:
+        ones.Search(cluster(4, 4, 16), make_jobs(4, bmin=64, bmax=32))
+    assert e.value.code == -3
+    # workspace too small / misaligned
+    import ctypes as C
+    cfg = ones.make_config(cluster(4, 4, 16))
+    js, keep = ones.make_jobs(jobs)
+    ws = torch.empty(1 << 20, dtype=torch.uint8, device="cuda:0")
+    h = C.c_void_p()
+    L = ones.load()
+    ptr = (ws.data_ptr() + 255) & ~255
+    assert L.ones_init(C.byref(h), C.byref(cfg), C.byref(js), C.c_void_p(ptr), 1024, None) == -5
+    assert L.ones_init(C.byref(h), C.byref(cfg), C.byref(js), C.c_void_p(ptr + 4), 1 << 19, None) == -5
+    assert h.value is None
+
+
+def test_two_contexts_and_a_side_stream(ones, ref):
+    import torch
+    rng = np.random.default_rng(41)
+    jobs = random_jobs(rng, 200)
+    cl1, cl2 = cluster(256, 200, 64, seed=1), cluster(256, 200, 64, seed=2)
+    side = torch.cuda.Stream()
+    a = ones.Search(cl1, jobs)
+    b = ones.Search(cl2, jobs, stream=side)
+    ca, cb = ref.RefSearch(cl1, jobs), ref.RefSearch(cl2, jobs)
+    for _ in range(3):
+        a.generation(1); b.generation(1); ca.generation(1); cb.generation(1)
+    assert_same_state(a, ca, "context a")
+    assert_same_state(b, cb, "context b (side stream)")
+
+
+def test_full_size_stress_matches_oracle(ones, ref):
+    """The benchmark's own launch configuration: 2048 jobs, pool 65536.  The oracle runs the
+    same three steps on all host threads (about 2 s per generation on 8 cores)."""
+    import os
+    cl, jobs = W.stress()
+    ref.set_threads(min(16, os.cpu_count() or 1))
+    try:
+        run_pair(ones, ref, cl, jobs, 2, 1, "stress full size")
+    finally:
+        ref.set_threads(1)
+
+
+def test_full_size_large_matches_oracle(ones, ref):
+    import os
+    cl, jobs = W.large()
+    ref.set_threads(min(16, os.cpu_count() or 1))
+    try:
+        run_pair(ones, ref, cl, jobs, 3, 1, "large full size")
+    finally:
+        ref.set_threads(1)
+
+
+def test_profile_hook_counts_launches(ones):
+    cl, jobs = W.paper_scale()
+    s = ones.Search(cl, jobs)
+    s.profile_enable(True)
+    s.generation(7)
+    prof = s.profile_read()
+    assert prof["evolve_launches"] == 7 and prof["select_launches"] == 7
+    assert prof["evolve_ms"] > 0 and prof["select_ms"] > 0
+    s.profile_enable(False)
+    s.generation(1)
+    assert s.profile_read()["evolve_launches"] == 0
