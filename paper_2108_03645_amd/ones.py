@@ -50,6 +50,10 @@ def load():
         return _lib
     if not os.path.exists(_LIB_PATH):
         raise OnesError(-100, f"{_LIB_PATH} is missing: build it with paper_2108_03645_amd/build.py")
+    # PyTorch bundles its own HIP runtime (same soname as ROCm's).  Import it first so that
+    # libones binds to the runtime that owns the workspace and the stream instead of
+    # bringing up a second one.
+    import torch  # noqa: F401
     L = C.CDLL(_LIB_PATH)
     L.ones_workspace_bytes.argtypes = [C.POINTER(ones_config)]
     L.ones_workspace_bytes.restype = C.c_size_t
