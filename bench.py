@@ -1,0 +1,133 @@
+#!/usr/bin/env python3
+"""Benchmark of the ONES evolutionary search on one MI355X.
+
+A step is one generation of the whole hot path (compose the pool from the survivors, repair
+every candidate to the cluster capacity, score it, select the best quarter) on the stress
+cluster: 4096 GPUs, 2048 jobs, pool of 65536 candidates.  Prints one JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload stress|large|paper_scale|tiny]
+"""
+from __future__ import annotations
+
+import argparse
+import hashlib
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published peak
+
+# HBM bytes per evolve launch on the stress workload from rocprofv3 --pmc FETCH_SIZE and
+# WRITE_SIZE (see profiles/), valid only for the kernel source with this hash.
+MEASURED_TRAFFIC = {"source_sha256": None, "bytes_per_launch": None}
+
+
+def evolve_source_hash() -> str:
+    h = hashlib.sha256()
+    for f in ("ones_evolve.hip", "ones_device.h"):
+        h.update(open(os.path.join(ROOT, "paper_2108_03645_amd", "csrc", f), "rb").read())
+    return h.hexdigest()
+
+
+def cpu_baseline(workload: str):
+    """The CPU oracle, as it stands, on a bounded sample of the same workload."""
+    from oracle import ones_ref
+    from paper_2108_03645_amd import workloads as W
+    threads = max(1, min(16, os.cpu_count() or 1))
+    if workload == "stress":
+        cl, jobs = W.stress()
+        gens, sample = 3, "stress cluster at full size (pool 65536), 3 generations after the initial population"
+    else:
+        cl, jobs = W.CONFIGS[workload]()
+        gens = max(1, min(cl.generations, int(2e8 / (cl.population * max(cl.n_slots, 1)))))
+        sample = f"{workload}, {gens} generations"
+    ones_ref.set_threads(threads)
+    s = ones_ref.RefSearch(cl, jobs)
+    t0 = time.perf_counter()
+    s.generation(gens)
+    dt = time.perf_counter() - t0
+    s.close()
+    ones_ref.set_threads(1)
+    active = int(jobs.active.sum())
+    return {"value": cl.population * active * gens / dt, "unit": "evals/s", "cores": threads,
+            "kind": "oracle", "sample": sample,
+            "generations_per_s": gens / dt, "seconds": dt}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=40)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="stress", choices=["stress", "large", "paper_scale", "tiny"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: the search runs on one GPU; --gpus above 1 is not supported "
+              "(the pool would shard by candidates, see DESIGN.md)", file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2108_03645_amd import ones, workloads as W
+
+    cl, jobs = W.CONFIGS[args.workload]()
+    active = int(jobs.active.sum())
+    jp = ones.padded_jobs(cl.n_slots)
+    torch.cuda.set_device(0)
+    search = ones.Search(cl, jobs, device="cuda:0")       # initial population, not timed
+    search.generation(args.warmup)
+    search.synchronize()
+    torch.cuda.synchronize()
+
+    search.profile_enable(True)
+    t0 = time.perf_counter()
+    search.generation(args.steps)
+    search.synchronize()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    prof = search.profile_read()
+    _, _, best_fit = search.best()
+
+    evolve_ms = prof["evolve_ms"] / max(1, prof["evolve_launches"])
+    select_ms = prof["select_ms"] / max(1, prof["select_launches"])
+    # algorithmic bytes of one evolve launch: every gene read once and written once (int32),
+    # one fp64 score per candidate
+    alg_bytes = cl.population * cl.n_slots * 8 + cl.population * 8
+    achieved = alg_bytes / (evolve_ms * 1e-3) / 1e9
+    traffic = None
+    if MEASURED_TRAFFIC["source_sha256"] == evolve_source_hash() and args.workload == "stress":
+        traffic = MEASURED_TRAFFIC["bytes_per_launch"]
+
+    out = {
+        "metric": "candidate-job fitness evals/sec",
+        "value": cl.population * active * args.steps / dt,
+        "unit": "evals/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": dt * 1e3 / args.steps,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "i32 genes, f64 fitness", "data": "synthetic",
+        "config": {"workload": args.workload, "n_gpus_cluster": cl.n_gpus, "jobs": active,
+                   "slots_padded": jp, "population": cl.population, "survivors": cl.population // 4,
+                   "mutation_rate": cl.mutation_rate, "crossover_rate": cl.crossover_rate,
+                   "seed": cl.seed, "jobs_sha256": jobs.sha256()[:16]},
+        "generations_per_s": args.steps / dt,
+        "best_fitness": best_fit,
+        "kernels": {"evolve_ms": evolve_ms, "select_ms": select_ms},
+        "roofline": {"bound": "hbm", "kernel": "evolve_kernel", "achieved": achieved, "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
+                     "algorithmic_bytes_per_launch": alg_bytes},
+    }
+    search.close()
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(args.workload)
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
