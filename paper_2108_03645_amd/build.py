@@ -10,23 +10,26 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB = os.path.join(HERE, "libones.so")
-SOURCES = ["ones_api.hip", "ones_evolve.hip", "ones_select.hip"]
+# (source, object, extra flags); the evolve kernel is built once per group of eight row counts
+UNITS = [("ones_api.hip", "ones_api.o", []), ("ones_select.hip", "ones_select.o", [])] + [
+    ("ones_evolve.hip", f"ones_evolve_{g}.o", [f"-DONES_ROW_GROUP={g}"]) for g in range(4)]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wall", "-Wno-unused-command-line-argument", f"-I{INCLUDE}", f"-I{CSRC}"]
 
 
-def _compile(src: str) -> str:
-    obj = os.path.join(CSRC, os.path.splitext(src)[0] + ".o")
-    subprocess.check_call([HIPCC, *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj])
+def _compile(unit) -> str:
+    src, obj, extra = unit
+    obj = os.path.join(CSRC, obj)
+    subprocess.check_call([HIPCC, *FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", obj])
     return obj
 
 
 def build(verbose: bool = True) -> str:
     """Compile every source and link the shared library; returns its path."""
-    with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
-        objs = list(ex.map(_compile, SOURCES))
+    with ThreadPoolExecutor(max_workers=min(8, len(UNITS))) as ex:
+        objs = list(ex.map(_compile, UNITS))
     subprocess.check_call([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", LIB])
     if verbose:
         print(f"built {LIB}", file=sys.stderr)

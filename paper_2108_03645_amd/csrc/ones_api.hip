@@ -28,7 +28,7 @@ int hip_fail(hipError_t e, const char *what) {
 size_t align_up(size_t v) { return (v + 255) & ~static_cast<size_t>(255); }
 
 struct Layout {
-  size_t genes[2], fit, sel, keys, idx, cstart, cmax, info, abl, cc, d, Y;
+  size_t genes[2], fit[2], sel, keys, idx, cstart, cmax, info, abl, cc, d, Y;
   size_t rawinfo, changed, ra, rc, rd, rY, best_batch, best_gpus, best_fit, total;
 };
 
@@ -39,7 +39,8 @@ Layout make_layout(uint32_t P, uint32_t Jp) {
   const size_t chunks = (P + kSortChunk - 1) / kSortChunk;
   L.genes[0] = take(static_cast<size_t>(P) * Jp * 4);
   L.genes[1] = take(static_cast<size_t>(P) * Jp * 4);
-  L.fit = take(static_cast<size_t>(P) * 8);
+  L.fit[0] = take(static_cast<size_t>(P) * 8);
+  L.fit[1] = take(static_cast<size_t>(P) * 8);
   L.sel = take(static_cast<size_t>(P / 4) * 4);
   L.keys = take(chunks * kSortChunk * 8);
   L.idx = take(chunks * kSortChunk * 4);
@@ -123,7 +124,9 @@ struct ones_ctx {
   hipStream_t stream;
   char *ws;
   Layout L;
-  int cur;                    // genome buffer holding the current generation
+  int cur;                    // genome / score buffer holding the current generation
+  bool table_changed;         // job table replaced since the current generation was computed
+  int n_cus;
   int64_t t;                  // generation counter
   std::vector<int64_t> ids;   // job identity per slot, to detect slots that change hands
   // measurement
@@ -179,9 +182,11 @@ int timed(ones_ctx *c, std::vector<EventPair> &pool, size_t &used, bool begin) {
 int run_generation(ones_ctx *c, uint32_t t) {
   EvolveArgs a;
   a.genes_old = c->at<int32_t>(c->L.genes[c->cur]);
-  a.genes_new = c->at<int32_t>(c->L.genes[t == 0 ? c->cur : c->cur ^ 1]);
+  const int next = t == 0 ? c->cur : c->cur ^ 1;
+  a.genes_new = c->at<int32_t>(c->L.genes[next]);
   a.sel = c->at<int32_t>(c->L.sel);
-  a.fit = c->at<double>(c->L.fit);
+  a.fit = c->at<double>(c->L.fit[next]);
+  a.fit_old = c->at<double>(c->L.fit[c->cur]);
   a.tab = c->table();
   a.G = c->G; a.P = c->P; a.K = c->K; a.Jp = c->Jp;
   a.key0 = static_cast<uint32_t>(c->cfg.seed);
@@ -189,13 +194,14 @@ int run_generation(ones_ctx *c, uint32_t t) {
   a.t = t; a.T_mut = c->T_mut; a.T_x = c->T_x;
   int rc;
   if ((rc = timed(c, c->evolve_ev, c->evolve_used, true))) return rc;
-  HIP_TRY(launch_evolve(a, static_cast<int>(c->R), c->stream));
+  HIP_TRY(launch_evolve(a, static_cast<int>(c->R), !c->table_changed, c->n_cus, c->stream));
   if ((rc = timed(c, c->evolve_ev, c->evolve_used, false))) return rc;
   if ((rc = timed(c, c->select_ev, c->select_used, true))) return rc;
   HIP_TRY(launch_select(a.fit, c->P, c->K, c->at<uint64_t>(c->L.keys), c->at<uint32_t>(c->L.idx),
                         c->at<int32_t>(c->L.sel), c->stream));
   if ((rc = timed(c, c->select_ev, c->select_used, false))) return rc;
-  if (t != 0) c->cur ^= 1;
+  c->cur = next;
+  c->table_changed = false;
   return ONES_OK;
 }
 
@@ -238,7 +244,16 @@ int ones_init(ones_ctx **out, const ones_config *cfg, const ones_jobs *jobs, voi
   c->ws = static_cast<char *>(d_workspace);
   c->L = L;
   c->cur = 0; c->t = 0;
+  c->table_changed = false;
   c->ids = h.id;
+  {
+    int dev = 0;
+    hipDeviceProp_t prop;
+    hipError_t e = hipGetDevice(&dev);
+    if (e == hipSuccess) e = hipGetDeviceProperties(&prop, dev);
+    if (e != hipSuccess) { delete c; return hip_fail(e, "hipGetDeviceProperties"); }
+    c->n_cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+  }
   c->profiling = false; c->evolve_used = c->select_used = 0;
   if ((rc = upload_table(c, h, nullptr)) || (rc = run_generation(c, 0))) { ones_destroy(c); return rc; }
   hipError_t e = hipStreamSynchronize(c->stream);
@@ -258,6 +273,7 @@ int ones_set_jobs(ones_ctx *c, const ones_jobs *jobs) {
     if (h.id[j] != c->ids[j]) { changed[j] = 1u; any = true; }
   if ((rc = upload_table(c, h, any ? &changed : nullptr))) return rc;
   c->ids = h.id;
+  c->table_changed = true;
   return ONES_OK;
 }
 
@@ -274,7 +290,7 @@ int ones_generation(ones_ctx *c, int32_t n_generations) {
 
 int ones_best(ones_ctx *c, int32_t *batch_out, int32_t *gpus_out, double *fitness_out) {
   if (!c) return ONES_E_INVALID_ARG;
-  HIP_TRY(launch_best(c->at<int32_t>(c->L.genes[c->cur]), c->at<double>(c->L.fit), c->at<int32_t>(c->L.sel),
+  HIP_TRY(launch_best(c->at<int32_t>(c->L.genes[c->cur]), c->at<double>(c->L.fit[c->cur]), c->at<int32_t>(c->L.sel),
                       c->at<uint32_t>(c->L.info), c->Jn, c->Jp, c->at<int32_t>(c->L.best_batch),
                       c->at<int32_t>(c->L.best_gpus), c->at<double>(c->L.best_fit), c->stream));
   std::vector<int32_t> b(c->Jn), g(c->Jn);
@@ -298,7 +314,7 @@ int ones_export(ones_ctx *c, int32_t *genes, double *fit, int32_t *sel, int64_t 
   if (genes)
     HIP_TRY(hipMemcpy(genes, c->ws + c->L.genes[c->cur], static_cast<size_t>(c->P) * c->Jp * 4,
                       hipMemcpyDeviceToHost));
-  if (fit) HIP_TRY(hipMemcpy(fit, c->ws + c->L.fit, static_cast<size_t>(c->P) * 8, hipMemcpyDeviceToHost));
+  if (fit) HIP_TRY(hipMemcpy(fit, c->ws + c->L.fit[c->cur], static_cast<size_t>(c->P) * 8, hipMemcpyDeviceToHost));
   if (sel) HIP_TRY(hipMemcpy(sel, c->ws + c->L.sel, static_cast<size_t>(c->K) * 4, hipMemcpyDeviceToHost));
   if (generation) *generation = c->t;
   return ONES_OK;

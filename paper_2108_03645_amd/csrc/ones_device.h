@@ -36,6 +36,7 @@ struct EvolveArgs {
   int32_t       *genes_new;   // [P][Jp]
   const int32_t *sel;         // [K] survivors of the previous generation, best first
   double        *fit;         // [P] scores of the new generation
+  const double  *fit_old;     // [P] scores of the previous generation
   JobTable       tab;
   uint32_t       G, P, K, Jp;
   uint32_t       key0, key1;  // seed
@@ -51,7 +52,20 @@ struct RawJobs {              // uploaded by the host after validation, [Jp] eac
 // launchers (each returns the hipGetLastError of its launch)
 hipError_t launch_prepare_table(const RawJobs &raw, const JobTable &tab, uint32_t Jp, hipStream_t s);
 hipError_t launch_reset_slots(int32_t *genes, const uint32_t *changed, uint32_t P, uint32_t Jp, hipStream_t s);
-hipError_t launch_evolve(const EvolveArgs &a, int rows, hipStream_t s);
+// same_table: the job table is the one the previous generation was repaired and scored with
+hipError_t launch_evolve_group0(const EvolveArgs &a, int rows, bool same_table, int n_cus, hipStream_t s);
+hipError_t launch_evolve_group1(const EvolveArgs &a, int rows, bool same_table, int n_cus, hipStream_t s);
+hipError_t launch_evolve_group2(const EvolveArgs &a, int rows, bool same_table, int n_cus, hipStream_t s);
+hipError_t launch_evolve_group3(const EvolveArgs &a, int rows, bool same_table, int n_cus, hipStream_t s);
+inline hipError_t launch_evolve(const EvolveArgs &a, int rows, bool same_table, int n_cus, hipStream_t s) {
+  switch ((rows - 1) / 8) {
+    case 0: return launch_evolve_group0(a, rows, same_table, n_cus, s);
+    case 1: return launch_evolve_group1(a, rows, same_table, n_cus, s);
+    case 2: return launch_evolve_group2(a, rows, same_table, n_cus, s);
+    case 3: return launch_evolve_group3(a, rows, same_table, n_cus, s);
+    default: return hipErrorInvalidValue;
+  }
+}
 hipError_t launch_select(const double *fit, uint32_t P, uint32_t K, uint64_t *keys, uint32_t *idx,
                          int32_t *sel, hipStream_t s);
 hipError_t launch_best(const int32_t *genes, const double *fit, const int32_t *sel, const uint32_t *info,

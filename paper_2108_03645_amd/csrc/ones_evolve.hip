@@ -5,14 +5,24 @@
 // wave composes the candidate from the survivors of the previous generation (refresh copy,
 // uniform crossover, uniform mutation), repairs it to the cluster capacity (refresh + fill
 // under Eq. 4), scores it (Eq. 3 with T = Y/X, Eq. 5) and writes genome and score.
+//
+// Workgroups are persistent: each stages the job table in LDS once and its waves then walk
+// the work items with a grid stride; waves never synchronise with each other after that.
 #include "ones_device.h"
 
+#include <algorithm>
 #include <utility>
 
 #pragma clang fp contract(off)   // every fp64 product and sum is rounded on its own
 
+#ifndef ONES_ROW_GROUP
+#error "compile with -DONES_ROW_GROUP=0..3"
+#endif
+
 namespace ones {
 namespace {
+
+constexpr int kGroupFirst = 8 * ONES_ROW_GROUP + 1;   // row counts kGroupFirst .. kGroupFirst + 7
 
 // ------------------------------------------------------------------ RNG ------------
 // Philox4x32-10 (Salmon, Moraes, Dror, Shaw, SC'11).
@@ -64,111 +74,155 @@ __device__ __forceinline__ void gene_words(const EvolveArgs &a, uint32_t p, int 
 }
 
 // --------------------------------------------------------- wave primitives ---------
-__device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t v, int lane) {
-#pragma unroll
-  for (int d = 1; d < kLanes; d <<= 1) {
-    const uint32_t up = __shfl_up(v, d, kLanes);
-    if (lane >= d) v += up;
-  }
+// DPP controls (gfx9): row_shr:n shifts within a row of 16 lanes, row_bcast:15 / :31 copy the
+// last lane of a row / of the lower half-wave into the following row(s).
+constexpr int kRowShr = 0x110, kRowBcast15 = 0x142, kRowBcast31 = 0x143;
+
+template <int Ctrl, int RowMask, bool Bound>
+__device__ __forceinline__ uint32_t dpp_or_zero(uint32_t v) {
+  return static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(v), Ctrl, RowMask, 0xF, Bound));
+}
+
+__device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t v) {
+  v += dpp_or_zero<kRowShr + 1, 0xF, true>(v);
+  v += dpp_or_zero<kRowShr + 2, 0xF, true>(v);
+  v += dpp_or_zero<kRowShr + 4, 0xF, true>(v);
+  v += dpp_or_zero<kRowShr + 8, 0xF, true>(v);
+  v += dpp_or_zero<kRowBcast15, 0xA, false>(v);
+  v += dpp_or_zero<kRowBcast31, 0xC, false>(v);
   return v;
 }
 
 __device__ __forceinline__ uint32_t wave_sum(uint32_t v) {
-#pragma unroll
-  for (int s = 32; s >= 1; s >>= 1) v += __shfl_xor(v, s, kLanes);
-  return v;
+  return __builtin_amdgcn_readlane(wave_inclusive_scan(v), kLanes - 1);
 }
 
-// ------------------------------------------------------------- per-lane state ------
-template <int R>
-struct Lane {
-  uint32_t cstart[R], cmax[R], info[R];
+// ------------------------------------------------------------- job table in LDS ----
+struct Smem {
+  uint2    *cc2;     // [Jp] {cstart, cmax}: GPUs a waiting job resumes with / at the limit R_j
+  uint32_t *info;    // [Jp]
+  double   *abl, *cc, *d, *Y;   // [Jp]
+  uint8_t  *stash;   // [waves][Jp] second crossover child while the first is repaired
 };
 
-template <int R>
-__device__ __forceinline__ void load_lane(const JobTable &tab, int lane, Lane<R> &L) {
+inline size_t smem_bytes(uint32_t Jp, int waves) {
+  return static_cast<size_t>(Jp) * (8 + 4 + 32) + static_cast<size_t>(waves) * Jp;
+}
+
+__device__ __forceinline__ Smem carve(unsigned char *base, uint32_t Jp) {
+  Smem s;
+  s.abl = reinterpret_cast<double *>(base);
+  s.cc = s.abl + Jp;
+  s.d = s.cc + Jp;
+  s.Y = s.d + Jp;
+  s.cc2 = reinterpret_cast<uint2 *>(s.Y + Jp);
+  s.info = reinterpret_cast<uint32_t *>(s.cc2 + Jp);
+  s.stash = reinterpret_cast<uint8_t *>(s.info + Jp);
+  return s;
+}
+
+__device__ __forceinline__ void stage_table(const JobTable &tab, const Smem &s, uint32_t Jp) {
+  for (uint32_t j = threadIdx.x; j < Jp; j += blockDim.x) {
+    s.cc2[j] = make_uint2(tab.cstart[j], tab.cmax[j]);
+    s.info[j] = tab.info[j];
+    s.abl[j] = tab.abl[j];
+    s.cc[j] = tab.cc[j];
+    s.d[j] = tab.d[j];
+    s.Y[j] = tab.Y[j];
+  }
+  __syncthreads();
+}
+
+// Global batch -> GPU count.  In general: clamp to the window and lift for free to the
+// per-GPU max batch, i.e. clamp(B >> mu, cstart, cmax) for a running job.  A gene written by
+// this kernel under the same job table is already of the form c << bl_exp.
+template <int R, bool kSameTable>
+__device__ __forceinline__ void gpus_from_batches(const Smem &s, int lane, uint32_t (&c)[R]) {
 #pragma unroll
   for (int i = 0; i < R; ++i) {
     const int j = lane + kLanes * i;
-    L.cstart[i] = tab.cstart[j];
-    L.cmax[i] = tab.cmax[j];
-    L.info[i] = tab.info[j];
+    const uint32_t w = s.info[j];
+    if (kSameTable) {
+      c[i] = c[i] >> info_blexp(w);
+    } else {
+      const uint2 k = s.cc2[j];
+      const uint32_t g = min(max(c[i] >> info_mu(w), k.x), k.y);
+      c[i] = c[i] ? g : 0u;
+    }
   }
 }
 
-// Global batch -> GPU count after clamp to the window and the free lift: a running job
-// holds clamp(B >> mu, cstart, cmax) GPUs; an empty slot has cstart = cmax = 0.
-__device__ __forceinline__ uint32_t gpus_from_batch(uint32_t B, uint32_t info, uint32_t cstart, uint32_t cmax) {
-  const uint32_t c = min(max(B >> info_mu(info), cstart), cmax);
-  return B ? c : 0u;
-}
-
-// Redraw of a gene from k in [0, n): 0 = the job is pre-empted, else 2^(lo + k - 1).
-__device__ __forceinline__ uint32_t batch_from_draw(uint32_t k, uint32_t info) {
-  return k ? (1u << (info_lo(info) + k - 1u)) : 0u;
-}
-
-// Accept the longest prefix, in the rotated visiting order, of the asks v whose running
-// sum stays within limit.  Visiting order: column-major (a lane's rows are consecutive),
-// starting at lane lr, row ir, wrapping.  ok bit i is set iff row i's prefix fits; a row
-// with v = 0 does not matter.  Returns the sum of the accepted asks (wave-uniform).
+// Accept the longest prefix, in the rotated visiting order, of the asks v whose running sum
+// stays within limit.  Visiting order: column-major (a lane's rows are consecutive), starting
+// at lane lr, row ir, wrapping.  got[i] = v[i] if accepted else 0; returns the accepted sum.
 template <int R>
 __device__ __forceinline__ uint32_t accept_prefix(const uint32_t (&v)[R], uint32_t limit, uint32_t lr,
-                                                  uint32_t ir, int lane, uint32_t &ok) {
+                                                  uint32_t ir, int lane, uint32_t (&got)[R]) {
   uint32_t run = 0, pre = 0;
 #pragma unroll
   for (int i = 0; i < R; ++i) {
     pre = (static_cast<uint32_t>(i) == ir) ? run : pre;   // sum of the lane's rows above ir
     run += v[i];
   }
-  const uint32_t incl = wave_inclusive_scan(run, lane);
+  const uint32_t incl = wave_inclusive_scan(run);
   const uint32_t excl = incl - run;
   const uint32_t total = __builtin_amdgcn_readlane(incl, kLanes - 1);
-  const uint32_t base = __builtin_amdgcn_readlane(excl + pre, lr);   // asks visited "last" (before the start)
-  const uint32_t off_hi = excl - base;            // rows at or after the start
-  const uint32_t off_lo = excl + (total - base);  // rows before the start: visited after the wrap
-  const uint32_t irow = static_cast<uint32_t>(lane) > lr ? 0u : (static_cast<uint32_t>(lane) < lr ? R : ir);
+  if (total <= limit) {                            // everything fits: no second pass
+#pragma unroll
+    for (int i = 0; i < R; ++i) got[i] = v[i];
+    return total;
+  }
+  const uint32_t base = __builtin_amdgcn_readlane(excl + pre, lr);   // asks visited after the wrap
+  // A row's prefix is run_i + off; it fits iff run_i <= limit - off (0 when off exceeds the
+  // limit: then only rows without an ask "fit", which changes nothing).
+  const uint32_t off_hi = excl - base;             // rows at or after the start
+  const uint32_t off_lo = excl + (total - base);   // rows before the start, visited after the wrap
+  const bool after = static_cast<uint32_t>(lane) > lr;
+  const bool at = static_cast<uint32_t>(lane) == lr;
+  // off_hi of lane lr is -pre (mod 2^32): add pre to the threshold instead
+  const uint32_t thr_hi = at ? limit + pre : (off_hi <= limit ? limit - off_hi : 0u);
+  const uint32_t thr_lo = off_lo <= limit ? limit - off_lo : 0u;
   uint32_t acc = 0;
   run = 0;
-  ok = 0;
 #pragma unroll
   for (int i = 0; i < R; ++i) {
     run += v[i];
-    const uint32_t q = run + (static_cast<uint32_t>(i) >= irow ? off_hi : off_lo);
-    const bool fits = q <= limit;
-    ok |= fits ? (1u << i) : 0u;
-    acc += fits ? v[i] : 0u;
+    const bool hi = after | (at & (static_cast<uint32_t>(i) >= ir));
+    const uint32_t thr = hi ? thr_hi : thr_lo;
+    got[i] = run <= thr ? v[i] : 0u;
+    acc += got[i];
   }
-  return __builtin_amdgcn_readfirstlane(wave_sum(acc));
+  return wave_sum(acc);
 }
 
 // Refresh + fill (Section 3.2.2) on GPU counts c[]; clamp and lift already applied.
 template <int R>
-__device__ __forceinline__ void repair(uint32_t (&c)[R], const Lane<R> &L, uint32_t G, uint32_t r, int lane) {
+__device__ __forceinline__ void repair(uint32_t (&c)[R], const Smem &s, uint32_t G, uint32_t r, int lane) {
   const uint32_t lr = r / R, ir = r % R;
-  uint32_t ok;
+  uint32_t v[R];
   // admit: jobs beyond the capacity in visiting order wait (Eq. 4)
-  uint32_t used = accept_prefix<R>(c, G, lr, ir, lane, ok);
+  const uint32_t used = accept_prefix<R>(c, G, lr, ir, lane, v);
 #pragma unroll
-  for (int i = 0; i < R; ++i) c[i] = (ok >> i) & 1u ? c[i] : 0u;
-  // fill: a waiting job asks for cstart GPUs, a running one below its limit asks to double
+  for (int i = 0; i < R; ++i) c[i] = v[i];
+  // fill: a waiting job asks for cstart GPUs, a running one below its limit asks to double.
   // Every round accepts at least its first ask, and a job doubles at most 20 times, so
   // kMaxRows * 64 * 21 rounds always suffice; the bound and the got == 0 exit only make the
   // loop end whatever happens.
   uint32_t idle = G - used;
   for (int round = 0; round < kMaxRows * kLanes * 21 && idle > 0; ++round) {
-    uint32_t v[R];
     uint32_t any = 0;
 #pragma unroll
     for (int i = 0; i < R; ++i) {
-      const uint32_t cost = max(c[i], L.cstart[i]);
-      v[i] = (c[i] < L.cmax[i] && cost <= idle) ? cost : 0u;
+      const uint2 k = s.cc2[lane + kLanes * i];
+      const uint32_t cost = max(c[i], k.x);
+      v[i] = (c[i] < k.y && cost <= idle) ? cost : 0u;
       any |= v[i];
     }
     if (__ballot(any != 0) == 0) break;
-    const uint32_t got = accept_prefix<R>(v, idle, lr, ir, lane, ok);
+    uint32_t x[R];
+    const uint32_t got = accept_prefix<R>(v, idle, lr, ir, lane, x);
 #pragma unroll
-    for (int i = 0; i < R; ++i) c[i] += (ok >> i) & 1u ? v[i] : 0u;
+    for (int i = 0; i < R; ++i) c[i] += x[i];
     if (got == 0) break;
     idle -= got;
   }
@@ -177,31 +231,32 @@ __device__ __forceinline__ void repair(uint32_t (&c)[R], const Lane<R> &L, uint3
 // Eq. 3: sum over running jobs of T_j c_j = Y_j t_j / (local batch), t = a b + c log2(g) + d.
 // Summation order: a lane's rows top to bottom, then a xor butterfly 32,16,..,1 over lanes.
 template <int R>
-__device__ __forceinline__ double score(const uint32_t (&c)[R], const Lane<R> &L, const JobTable &tab, int lane) {
+__device__ __forceinline__ double score(const uint32_t (&c)[R], const Smem &s, int lane) {
   double acc = 0.0;
 #pragma unroll
   for (int i = 0; i < R; ++i) {
     const int j = lane + kLanes * i;
     const uint32_t ci = c[i];
     const double lg = static_cast<double>(31 - __clz(static_cast<int>(ci | 1u)));
-    const double inv_bl = __hiloint2double(static_cast<int>((1023u - info_blexp(L.info[i])) << 20), 0);
-    const double t = (tab.abl[j] + tab.cc[j] * lg) + tab.d[j];
-    const double term = (tab.Y[j] * t) * inv_bl;
+    const double inv_bl = __hiloint2double(static_cast<int>((1023u - info_blexp(s.info[j])) << 20), 0);
+    const double t = (s.abl[j] + s.cc[j] * lg) + s.d[j];
+    const double term = (s.Y[j] * t) * inv_bl;
     acc = acc + (ci ? term : 0.0);
   }
 #pragma unroll
-  for (int s = 32; s >= 1; s >>= 1) acc = acc + __shfl_xor(acc, s, kLanes);
+  for (int sft = 32; sft >= 1; sft >>= 1) acc = acc + __shfl_xor(acc, sft, kLanes);
   return acc;
 }
 
 template <int R>
-__device__ __forceinline__ void finish(const EvolveArgs &a, const Lane<R> &L, uint32_t p, uint32_t r,
+__device__ __forceinline__ void finish(const EvolveArgs &a, const Smem &s, uint32_t p, uint32_t r,
                                        uint32_t (&c)[R], int lane) {
-  repair<R>(c, L, a.G, r, lane);
-  const double f = score<R>(c, L, a.tab, lane);
+  repair<R>(c, s, a.G, r, lane);
+  const double f = score<R>(c, s, lane);
   int32_t *row = a.genes_new + static_cast<size_t>(p) * a.Jp;
 #pragma unroll
-  for (int i = 0; i < R; ++i) row[lane + kLanes * i] = static_cast<int32_t>(c[i] << info_blexp(L.info[i]));
+  for (int i = 0; i < R; ++i)
+    row[lane + kLanes * i] = static_cast<int32_t>(c[i] << info_blexp(s.info[lane + kLanes * i]));
   if (lane == 0) a.fit[p] = f;
 }
 
@@ -211,103 +266,160 @@ __device__ __forceinline__ void load_genes(const int32_t *row, int lane, uint32_
   for (int i = 0; i < R; ++i) B[i] = static_cast<uint32_t>(row[lane + kLanes * i]);
 }
 
+// Redraw of a gene from k in [0, n): 0 = the job is pre-empted, else 2^(lo + k - 1).
+__device__ __forceinline__ uint32_t batch_from_draw(uint32_t k, uint32_t info) {
+  return (k && info_active(info)) ? (1u << (info_lo(info) + k - 1u)) : 0u;
+}
+
 // ----------------------------------------------------------------- kernels ---------
-constexpr int kWavesPerBlock = 4;
+template <int R> struct Shape { static constexpr int kWaves = R > 16 ? 16 : (R > 4 ? 8 : 4); };
 
 // Initial population G_0: every gene uniform over {waiting, bmin..bmax}.
 template <int R>
-__global__ __launch_bounds__(kWavesPerBlock * kLanes) void init_kernel(EvolveArgs a) {
+__global__ __launch_bounds__(Shape<R>::kWaves *kLanes) void init_kernel(EvolveArgs a) {
+  extern __shared__ __align__(16) unsigned char smem_raw[];
+  const Smem s = carve(smem_raw, a.Jp);
+  stage_table(a.tab, s, a.Jp);
   const int lane = threadIdx.x & (kLanes - 1);
-  const uint32_t p = __builtin_amdgcn_readfirstlane(blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6));
-  if (p >= a.P) return;
-  Lane<R> L;
-  load_lane<R>(a.tab, lane, L);
-  const Draw dr = candidate_draw(a, p);
-  uint32_t w[R], c[R];
-  gene_words<R>(a, p, lane, w);
+  const uint32_t wave = __builtin_amdgcn_readfirstlane(blockIdx.x * Shape<R>::kWaves + (threadIdx.x >> 6));
+  const uint32_t stride = gridDim.x * Shape<R>::kWaves;
+  for (uint32_t p = wave; p < a.P; p += stride) {
+    const Draw dr = candidate_draw(a, p);
+    uint32_t c[R];
+    gene_words<R>(a, p, lane, c);
 #pragma unroll
-  for (int i = 0; i < R; ++i) {
-    const uint32_t B = info_active(L.info[i]) ? batch_from_draw(bounded(w[i], info_n(L.info[i])), L.info[i]) : 0u;
-    c[i] = gpus_from_batch(B, L.info[i], L.cstart[i], L.cmax[i]);
+    for (int i = 0; i < R; ++i) {
+      const uint32_t w = s.info[lane + kLanes * i];
+      c[i] = batch_from_draw(bounded(c[i], info_n(w)), w);
+    }
+    gpus_from_batches<R, false>(s, lane, c);
+    finish<R>(a, s, p, dr.r, c, lane);
   }
-  finish<R>(a, L, p, dr.r, c, lane);
 }
 
 // One generation.  Work items: K crossover pairs, K mutants, K refreshed survivors.
-template <int R>
-__global__ __launch_bounds__(kWavesPerBlock * kLanes) void evolve_kernel(EvolveArgs a) {
+// kSameTable: the job table has not changed since the previous generation was repaired and
+// scored, so a survivor is a fixed point of the repair (copy genome and score) and stored
+// genes need no clamp.
+template <int R, bool kSameTable>
+__global__ __launch_bounds__(Shape<R>::kWaves *kLanes) void evolve_kernel(EvolveArgs a) {
+  extern __shared__ __align__(16) unsigned char smem_raw[];
+  const Smem s = carve(smem_raw, a.Jp);
+  stage_table(a.tab, s, a.Jp);
   const int lane = threadIdx.x & (kLanes - 1);
-  const uint32_t item = __builtin_amdgcn_readfirstlane(blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6));
+  const uint32_t wave_in_block = threadIdx.x >> 6;
+  const uint32_t wave = __builtin_amdgcn_readfirstlane(blockIdx.x * Shape<R>::kWaves + wave_in_block);
+  const uint32_t stride = gridDim.x * Shape<R>::kWaves;
   const uint32_t K = a.K;
-  if (item >= 3 * K) return;
-  Lane<R> L;
-  load_lane<R>(a.tab, lane, L);
-  uint32_t c[R];
-  if (item < K) {
-    // uniform crossover: per gene the children swap their parents' genes with rate chi
-    const uint32_t p0 = K + 2 * item;
-    const Draw d0 = candidate_draw(a, p0);
-    const Draw d1 = candidate_draw(a, p0 + 1);
-    uint32_t A[R], B[R], w[R];
-    load_genes<R>(a.genes_old + static_cast<size_t>(a.sel[d0.ra]) * a.Jp, lane, A);
-    load_genes<R>(a.genes_old + static_cast<size_t>(a.sel[d0.rb]) * a.Jp, lane, B);
-    gene_words<R>(a, p0, lane, w);
+  uint8_t *stash = s.stash + static_cast<size_t>(wave_in_block) * a.Jp;
+  for (uint32_t item = wave; item < 3 * K; item += stride) {
+    uint32_t c[R];
+    if (item < K) {
+      // uniform crossover: per gene the children swap their parents' genes with rate chi
+      const uint32_t p0 = K + 2 * item;
+      const Draw d0 = candidate_draw(a, p0);
+      const Draw d1 = candidate_draw(a, p0 + 1);
+      uint32_t swap = 0;
+      {
+        uint32_t w[R];
+        gene_words<R>(a, p0, lane, w);
 #pragma unroll
-    for (int i = 0; i < R; ++i)
-      c[i] = gpus_from_batch(w[i] < a.T_x ? B[i] : A[i], L.info[i], L.cstart[i], L.cmax[i]);
-    finish<R>(a, L, p0, d0.r, c, lane);
+        for (int i = 0; i < R; ++i) swap |= (w[i] < a.T_x ? 1u : 0u) << i;
+      }
+      {
+        uint32_t B[R];
+        load_genes<R>(a.genes_old + static_cast<size_t>(a.sel[d0.ra]) * a.Jp, lane, c);
+        load_genes<R>(a.genes_old + static_cast<size_t>(a.sel[d0.rb]) * a.Jp, lane, B);
+        gpus_from_batches<R, kSameTable>(s, lane, c);
+        gpus_from_batches<R, kSameTable>(s, lane, B);
+        // second child goes to LDS as a 5-bit code (0 = waiting, k = 2^(k-1) GPUs)
 #pragma unroll
-    for (int i = 0; i < R; ++i)
-      c[i] = gpus_from_batch(w[i] < a.T_x ? A[i] : B[i], L.info[i], L.cstart[i], L.cmax[i]);
-    finish<R>(a, L, p0 + 1, d1.r, c, lane);
-  } else if (item < 2 * K) {
-    // uniform mutation: each job redrawn with rate theta (k = 0 pre-empts it)
-    const uint32_t p = 3 * K + (item - K);
-    const Draw d = candidate_draw(a, p);
-    uint32_t A[R], w[R];
-    load_genes<R>(a.genes_old + static_cast<size_t>(a.sel[d.ra]) * a.Jp, lane, A);
-    gene_words<R>(a, p, lane, w);
+        for (int i = 0; i < R; ++i) {
+          const bool sw = (swap >> i) & 1u;
+          const uint32_t second = sw ? c[i] : B[i];
+          c[i] = sw ? B[i] : c[i];
+          stash[lane + kLanes * i] = static_cast<uint8_t>(32 - __clz(static_cast<int>(second)));
+        }
+      }
+      finish<R>(a, s, p0, d0.r, c, lane);
 #pragma unroll
-    for (int i = 0; i < R; ++i) {
-      const uint32_t k = ((w[i] & 0xFFFFu) * info_n(L.info[i])) >> 16;
-      const uint32_t redrawn = info_active(L.info[i]) ? batch_from_draw(k, L.info[i]) : 0u;
-      c[i] = gpus_from_batch(w[i] < a.T_mut ? redrawn : A[i], L.info[i], L.cstart[i], L.cmax[i]);
+      for (int i = 0; i < R; ++i) c[i] = (1u << stash[lane + kLanes * i]) >> 1;
+      finish<R>(a, s, p0 + 1, d1.r, c, lane);
+    } else if (item < 2 * K) {
+      // uniform mutation: each job redrawn with rate theta (k = 0 pre-empts it)
+      const uint32_t p = 3 * K + (item - K);
+      const Draw d = candidate_draw(a, p);
+      load_genes<R>(a.genes_old + static_cast<size_t>(a.sel[d.ra]) * a.Jp, lane, c);
+      {
+        uint32_t w[R];
+        gene_words<R>(a, p, lane, w);
+#pragma unroll
+        for (int i = 0; i < R; ++i) {
+          const uint32_t word = s.info[lane + kLanes * i];
+          const uint32_t k = ((w[i] & 0xFFFFu) * info_n(word)) >> 16;
+          c[i] = w[i] < a.T_mut ? batch_from_draw(k, word) : c[i];
+        }
+      }
+      gpus_from_batches<R, false>(s, lane, c);
+      finish<R>(a, s, p, d.r, c, lane);
+    } else {
+      // refresh: the survivor of rank p, projected onto the current job table
+      const uint32_t p = item - 2 * K;
+      const uint32_t src = static_cast<uint32_t>(a.sel[p]);
+      load_genes<R>(a.genes_old + static_cast<size_t>(src) * a.Jp, lane, c);
+      if (kSameTable) {
+        int32_t *row = a.genes_new + static_cast<size_t>(p) * a.Jp;
+#pragma unroll
+        for (int i = 0; i < R; ++i) row[lane + kLanes * i] = static_cast<int32_t>(c[i]);
+        if (lane == 0) a.fit[p] = a.fit_old[src];
+      } else {
+        const Draw d = candidate_draw(a, p);
+        gpus_from_batches<R, false>(s, lane, c);
+        finish<R>(a, s, p, d.r, c, lane);
+      }
     }
-    finish<R>(a, L, p, d.r, c, lane);
-  } else {
-    // refresh: the survivor of rank p, projected onto the current job table
-    const uint32_t p = item - 2 * K;
-    const Draw d = candidate_draw(a, p);
-    uint32_t A[R];
-    load_genes<R>(a.genes_old + static_cast<size_t>(a.sel[p]) * a.Jp, lane, A);
-#pragma unroll
-    for (int i = 0; i < R; ++i) c[i] = gpus_from_batch(A[i], L.info[i], L.cstart[i], L.cmax[i]);
-    finish<R>(a, L, p, d.r, c, lane);
   }
 }
 
-template <int R>
-hipError_t launch_rows(const EvolveArgs &a, hipStream_t s) {
-  const uint32_t items = a.t == 0 ? a.P : 3 * a.K;
-  const uint32_t blocks = (items + kWavesPerBlock - 1) / kWavesPerBlock;
-  if (a.t == 0)
-    hipLaunchKernelGGL(init_kernel<R>, dim3(blocks), dim3(kWavesPerBlock * kLanes), 0, s, a);
-  else
-    hipLaunchKernelGGL(evolve_kernel<R>, dim3(blocks), dim3(kWavesPerBlock * kLanes), 0, s, a);
+template <typename Kernel>
+hipError_t launch_persistent(Kernel k, const EvolveArgs &a, int waves, uint32_t items, int n_cus, hipStream_t s) {
+  const size_t lds = smem_bytes(a.Jp, waves);
+  // as many workgroups as can be resident (LDS- and wave-limited), at most one wave per item
+  const size_t per_cu = std::max<size_t>(1, std::min<size_t>(160 * 1024 / lds, 32 / waves));
+  const uint32_t blocks = std::max<uint32_t>(1u, std::min<uint32_t>((items + waves - 1) / waves,
+                                                                    static_cast<uint32_t>(n_cus * per_cu)));
+  hipError_t rc = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                      static_cast<int>(lds));
+  if (rc != hipSuccess) return rc;
+  hipLaunchKernelGGL(k, dim3(blocks), dim3(waves * kLanes), lds, s, a);
   return hipGetLastError();
 }
 
+template <int R>
+hipError_t launch_rows(const EvolveArgs &a, bool same_table, int n_cus, hipStream_t s) {
+  constexpr int kWaves = Shape<R>::kWaves;
+  if (a.t == 0) return launch_persistent(init_kernel<R>, a, kWaves, a.P, n_cus, s);
+  if (same_table) return launch_persistent(evolve_kernel<R, true>, a, kWaves, 3 * a.K, n_cus, s);
+  return launch_persistent(evolve_kernel<R, false>, a, kWaves, 3 * a.K, n_cus, s);
+}
+
 template <int... Rs>
-hipError_t dispatch_rows(const EvolveArgs &a, int rows, hipStream_t s, std::integer_sequence<int, Rs...>) {
+hipError_t dispatch_rows(const EvolveArgs &a, int rows, bool same_table, int n_cus, hipStream_t s,
+                         std::integer_sequence<int, Rs...>) {
   hipError_t rc = hipErrorInvalidValue;
-  (void)((rows == Rs + 1 ? (rc = launch_rows<Rs + 1>(a, s), true) : false) || ...);
+  (void)((rows == kGroupFirst + Rs ? (rc = launch_rows<kGroupFirst + Rs>(a, same_table, n_cus, s), true) : false) || ...);
   return rc;
 }
 
 }  // namespace
 
-hipError_t launch_evolve(const EvolveArgs &a, int rows, hipStream_t s) {
-  return dispatch_rows(a, rows, s, std::make_integer_sequence<int, kMaxRows>{});
+// This file is compiled once per group of eight row counts (-DONES_ROW_GROUP=0..3) so that
+// the 32 instantiations build in parallel.
+#define ONES_CONCAT2(x, y) x##y
+#define ONES_CONCAT(x, y) ONES_CONCAT2(x, y)
+hipError_t ONES_CONCAT(launch_evolve_group, ONES_ROW_GROUP)(const EvolveArgs &a, int rows, bool same_table,
+                                                            int n_cus, hipStream_t s) {
+  return dispatch_rows(a, rows, same_table, n_cus, s, std::make_integer_sequence<int, 8>{});
 }
 
 }  // namespace ones
