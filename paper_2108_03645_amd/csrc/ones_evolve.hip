@@ -24,6 +24,19 @@ namespace {
 
 constexpr int kGroupFirst = 8 * ONES_ROW_GROUP + 1;   // row counts kGroupFirst .. kGroupFirst + 7
 
+// Keeps the instruction scheduler from interleaving two phases of a work item, or too many
+// rows of one loop, which would keep all their registers live at once.
+__device__ __forceinline__ void phase_fence() {
+  asm volatile("" ::: "memory");        // loads stay on their side of the fence in the optimiser
+  __builtin_amdgcn_sched_barrier(0);    // ... and in the instruction scheduler
+}
+__device__ __forceinline__ void fence_every(int i, int n) { if (i % n == n - 1) phase_fence(); }
+// The lane number, re-materialised so that nothing derived from it (LDS addresses, the first
+// Philox round) is hoisted out of the work-item loop and kept live, or spilled, across it.
+// Forces x to be computed before the following fence (its producers cannot sink below it).
+template <typename T> __device__ __forceinline__ void pin(T &x) { asm volatile("" : "+v"(x)); }
+__device__ __forceinline__ int opaque(int v) { asm volatile("" : "+v"(v)); return v; }
+
 // ------------------------------------------------------------------ RNG ------------
 // Philox4x32-10 (Salmon, Moraes, Dror, Shaw, SC'11).
 struct Words { uint32_t w[4]; };
@@ -70,6 +83,7 @@ __device__ __forceinline__ void gene_words(const EvolveArgs &a, uint32_t p, int 
 #pragma unroll
     for (int k = 0; k < 4; ++k)
       if (4 * q + k < R) w[4 * q + k] = x.w[k];
+    fence_every(q, 2);
   }
 }
 
@@ -149,15 +163,17 @@ __device__ __forceinline__ void gpus_from_batches(const Smem &s, int lane, uint3
       const uint32_t g = min(max(c[i] >> info_mu(w), k.x), k.y);
       c[i] = c[i] ? g : 0u;
     }
+    fence_every(i, 8);
   }
 }
 
 // Accept the longest prefix, in the rotated visiting order, of the asks v whose running sum
 // stays within limit.  Visiting order: column-major (a lane's rows are consecutive), starting
-// at lane lr, row ir, wrapping.  got[i] = v[i] if accepted else 0; returns the accepted sum.
+// at lane lr, row ir, wrapping.  On return v[i] is unchanged if accepted, else 0; returns the
+// accepted sum (wave-uniform).
 template <int R>
-__device__ __forceinline__ uint32_t accept_prefix(const uint32_t (&v)[R], uint32_t limit, uint32_t lr,
-                                                  uint32_t ir, int lane, uint32_t (&got)[R]) {
+__device__ __forceinline__ uint32_t accept_prefix(uint32_t (&v)[R], uint32_t limit, uint32_t lr, uint32_t ir,
+                                                  int lane) {
   uint32_t run = 0, pre = 0;
 #pragma unroll
   for (int i = 0; i < R; ++i) {
@@ -167,11 +183,7 @@ __device__ __forceinline__ uint32_t accept_prefix(const uint32_t (&v)[R], uint32
   const uint32_t incl = wave_inclusive_scan(run);
   const uint32_t excl = incl - run;
   const uint32_t total = __builtin_amdgcn_readlane(incl, kLanes - 1);
-  if (total <= limit) {                            // everything fits: no second pass
-#pragma unroll
-    for (int i = 0; i < R; ++i) got[i] = v[i];
-    return total;
-  }
+  if (total <= limit) return total;                // everything fits: no second pass
   const uint32_t base = __builtin_amdgcn_readlane(excl + pre, lr);   // asks visited after the wrap
   // A row's prefix is run_i + off; it fits iff run_i <= limit - off (0 when off exceeds the
   // limit: then only rows without an ask "fit", which changes nothing).
@@ -189,8 +201,8 @@ __device__ __forceinline__ uint32_t accept_prefix(const uint32_t (&v)[R], uint32
     run += v[i];
     const bool hi = after | (at & (static_cast<uint32_t>(i) >= ir));
     const uint32_t thr = hi ? thr_hi : thr_lo;
-    got[i] = run <= thr ? v[i] : 0u;
-    acc += got[i];
+    v[i] = run <= thr ? v[i] : 0u;
+    acc += v[i];
   }
   return wave_sum(acc);
 }
@@ -199,17 +211,15 @@ __device__ __forceinline__ uint32_t accept_prefix(const uint32_t (&v)[R], uint32
 template <int R>
 __device__ __forceinline__ void repair(uint32_t (&c)[R], const Smem &s, uint32_t G, uint32_t r, int lane) {
   const uint32_t lr = r / R, ir = r % R;
-  uint32_t v[R];
   // admit: jobs beyond the capacity in visiting order wait (Eq. 4)
-  const uint32_t used = accept_prefix<R>(c, G, lr, ir, lane, v);
-#pragma unroll
-  for (int i = 0; i < R; ++i) c[i] = v[i];
+  const uint32_t used = accept_prefix<R>(c, G, lr, ir, lane);
   // fill: a waiting job asks for cstart GPUs, a running one below its limit asks to double.
   // Every round accepts at least its first ask, and a job doubles at most 20 times, so
   // kMaxRows * 64 * 21 rounds always suffice; the bound and the got == 0 exit only make the
   // loop end whatever happens.
   uint32_t idle = G - used;
   for (int round = 0; round < kMaxRows * kLanes * 21 && idle > 0; ++round) {
+    uint32_t v[R];
     uint32_t any = 0;
 #pragma unroll
     for (int i = 0; i < R; ++i) {
@@ -217,12 +227,12 @@ __device__ __forceinline__ void repair(uint32_t (&c)[R], const Smem &s, uint32_t
       const uint32_t cost = max(c[i], k.x);
       v[i] = (c[i] < k.y && cost <= idle) ? cost : 0u;
       any |= v[i];
+      if (i % 8 == 7) { pin(any); phase_fence(); }
     }
     if (__ballot(any != 0) == 0) break;
-    uint32_t x[R];
-    const uint32_t got = accept_prefix<R>(v, idle, lr, ir, lane, x);
+    const uint32_t got = accept_prefix<R>(v, idle, lr, ir, lane);
 #pragma unroll
-    for (int i = 0; i < R; ++i) c[i] += x[i];
+    for (int i = 0; i < R; ++i) c[i] += v[i];
     if (got == 0) break;
     idle -= got;
   }
@@ -242,6 +252,7 @@ __device__ __forceinline__ double score(const uint32_t (&c)[R], const Smem &s, i
     const double t = (s.abl[j] + s.cc[j] * lg) + s.d[j];
     const double term = (s.Y[j] * t) * inv_bl;
     acc = acc + (ci ? term : 0.0);
+    if (i % 4 == 3) { pin(acc); phase_fence(); }
   }
 #pragma unroll
   for (int sft = 32; sft >= 1; sft >>= 1) acc = acc + __shfl_xor(acc, sft, kLanes);
@@ -252,7 +263,9 @@ template <int R>
 __device__ __forceinline__ void finish(const EvolveArgs &a, const Smem &s, uint32_t p, uint32_t r,
                                        uint32_t (&c)[R], int lane) {
   repair<R>(c, s, a.G, r, lane);
+  phase_fence();
   const double f = score<R>(c, s, lane);
+  phase_fence();
   int32_t *row = a.genes_new + static_cast<size_t>(p) * a.Jp;
 #pragma unroll
   for (int i = 0; i < R; ++i)
@@ -268,11 +281,15 @@ __device__ __forceinline__ void load_genes(const int32_t *row, int lane, uint32_
 
 // Redraw of a gene from k in [0, n): 0 = the job is pre-empted, else 2^(lo + k - 1).
 __device__ __forceinline__ uint32_t batch_from_draw(uint32_t k, uint32_t info) {
-  return (k && info_active(info)) ? (1u << (info_lo(info) + k - 1u)) : 0u;
+  const uint32_t b = (info_active(info) << (info_lo(info) + k)) >> 1;   // k = 0 or empty slot -> 0
+  return k ? b : 0u;
 }
 
 // ----------------------------------------------------------------- kernels ---------
-template <int R> struct Shape { static constexpr int kWaves = R > 16 ? 16 : (R > 4 ? 8 : 4); };
+#ifndef ONES_WAVES_BIG
+#define ONES_WAVES_BIG 16
+#endif
+template <int R> struct Shape { static constexpr int kWaves = R > 16 ? ONES_WAVES_BIG : (R > 4 ? 8 : 4); };
 
 // Initial population G_0: every gene uniform over {waiting, bmin..bmax}.
 template <int R>
@@ -280,10 +297,11 @@ __global__ __launch_bounds__(Shape<R>::kWaves *kLanes) void init_kernel(EvolveAr
   extern __shared__ __align__(16) unsigned char smem_raw[];
   const Smem s = carve(smem_raw, a.Jp);
   stage_table(a.tab, s, a.Jp);
-  const int lane = threadIdx.x & (kLanes - 1);
+  const int lane0 = threadIdx.x & (kLanes - 1);
   const uint32_t wave = __builtin_amdgcn_readfirstlane(blockIdx.x * Shape<R>::kWaves + (threadIdx.x >> 6));
   const uint32_t stride = gridDim.x * Shape<R>::kWaves;
   for (uint32_t p = wave; p < a.P; p += stride) {
+    const int lane = opaque(lane0);
     const Draw dr = candidate_draw(a, p);
     uint32_t c[R];
     gene_words<R>(a, p, lane, c);
@@ -306,13 +324,14 @@ __global__ __launch_bounds__(Shape<R>::kWaves *kLanes) void evolve_kernel(Evolve
   extern __shared__ __align__(16) unsigned char smem_raw[];
   const Smem s = carve(smem_raw, a.Jp);
   stage_table(a.tab, s, a.Jp);
-  const int lane = threadIdx.x & (kLanes - 1);
+  const int lane0 = threadIdx.x & (kLanes - 1);
   const uint32_t wave_in_block = threadIdx.x >> 6;
   const uint32_t wave = __builtin_amdgcn_readfirstlane(blockIdx.x * Shape<R>::kWaves + wave_in_block);
   const uint32_t stride = gridDim.x * Shape<R>::kWaves;
   const uint32_t K = a.K;
   uint8_t *stash = s.stash + static_cast<size_t>(wave_in_block) * a.Jp;
   for (uint32_t item = wave; item < 3 * K; item += stride) {
+    const int lane = opaque(lane0);
     uint32_t c[R];
     if (item < K) {
       // uniform crossover: per gene the children swap their parents' genes with rate chi
@@ -326,6 +345,7 @@ __global__ __launch_bounds__(Shape<R>::kWaves *kLanes) void evolve_kernel(Evolve
 #pragma unroll
         for (int i = 0; i < R; ++i) swap |= (w[i] < a.T_x ? 1u : 0u) << i;
       }
+      phase_fence();
       {
         uint32_t B[R];
         load_genes<R>(a.genes_old + static_cast<size_t>(a.sel[d0.ra]) * a.Jp, lane, c);
@@ -341,7 +361,9 @@ __global__ __launch_bounds__(Shape<R>::kWaves *kLanes) void evolve_kernel(Evolve
           stash[lane + kLanes * i] = static_cast<uint8_t>(32 - __clz(static_cast<int>(second)));
         }
       }
+      phase_fence();
       finish<R>(a, s, p0, d0.r, c, lane);
+      phase_fence();
 #pragma unroll
       for (int i = 0; i < R; ++i) c[i] = (1u << stash[lane + kLanes * i]) >> 1;
       finish<R>(a, s, p0 + 1, d1.r, c, lane);
@@ -349,17 +371,22 @@ __global__ __launch_bounds__(Shape<R>::kWaves *kLanes) void evolve_kernel(Evolve
       // uniform mutation: each job redrawn with rate theta (k = 0 pre-empts it)
       const uint32_t p = 3 * K + (item - K);
       const Draw d = candidate_draw(a, p);
-      load_genes<R>(a.genes_old + static_cast<size_t>(a.sel[d.ra]) * a.Jp, lane, c);
       {
         uint32_t w[R];
         gene_words<R>(a, p, lane, w);
+        phase_fence();
+        load_genes<R>(a.genes_old + static_cast<size_t>(a.sel[d.ra]) * a.Jp, lane, c);
 #pragma unroll
         for (int i = 0; i < R; ++i) {
           const uint32_t word = s.info[lane + kLanes * i];
           const uint32_t k = ((w[i] & 0xFFFFu) * info_n(word)) >> 16;
-          c[i] = w[i] < a.T_mut ? batch_from_draw(k, word) : c[i];
+          const uint32_t redrawn = batch_from_draw(k, word);
+          const uint32_t pick = w[i] < a.T_mut ? 0xFFFFFFFFu : 0u;     // branch-free select
+          c[i] = (redrawn & pick) | (c[i] & ~pick);
+          fence_every(i, 8);
         }
       }
+      phase_fence();
       gpus_from_batches<R, false>(s, lane, c);
       finish<R>(a, s, p, d.r, c, lane);
     } else {
