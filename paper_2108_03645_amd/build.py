@@ -16,7 +16,8 @@ UNITS = [("ones_api.hip", "ones_api.o", []), ("ones_select.hip", "ones_select.o"
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-         "-Wall", "-Wno-unused-command-line-argument", f"-I{INCLUDE}", f"-I{CSRC}"]
+         "-Wall", "-Wno-unused-command-line-argument", f"-I{INCLUDE}", f"-I{CSRC}",
+         *os.environ.get("ONES_EXTRA_FLAGS", "").split()]
 
 
 def _compile(unit) -> str:

@@ -3,6 +3,7 @@
 #include "ones.h"
 #include "ones_device.h"
 
+#include <algorithm>
 #include <cmath>
 #include <cstdio>
 #include <cstring>
@@ -28,9 +29,22 @@ int hip_fail(hipError_t e, const char *what) {
 size_t align_up(size_t v) { return (v + 255) & ~static_cast<size_t>(255); }
 
 struct Layout {
-  size_t genes[2], fit[2], sel, keys, idx, cstart, cmax, info, abl, cc, d, Y;
+  size_t genes[2], fit[2], sel, keys, idx, split, thresh, bcount[2], bkeys, bidx, cstart, cmax, info, abl, cc, d, Y;
   size_t rawinfo, changed, ra, rc, rd, rY, best_batch, best_gpus, best_fit, total;
 };
+
+// Buckets: about 64 survivors each, at most kMaxBuckets; a bucket's storage can take every
+// child and mutant of the pool (3P/4), rounded up to a power of two for the sorting network.
+struct BucketPlan { uint32_t nb, seg; };
+BucketPlan bucket_plan(uint32_t P) {
+  if (P <= static_cast<uint32_t>(kSortChunk)) return BucketPlan{0, 0};
+  const uint32_t K = P / 4;
+  BucketPlan bp;
+  bp.nb = std::min<uint32_t>(kMaxBuckets, std::max<uint32_t>(1, K / 64));
+  bp.seg = 1;
+  while (bp.seg < 3 * K) bp.seg <<= 1;
+  return bp;
+}
 
 Layout make_layout(uint32_t P, uint32_t Jp) {
   Layout L;
@@ -44,6 +58,12 @@ Layout make_layout(uint32_t P, uint32_t Jp) {
   L.sel = take(static_cast<size_t>(P / 4) * 4);
   L.keys = take(chunks * kSortChunk * 8);
   L.idx = take(chunks * kSortChunk * 4);
+  // quantile buckets of the selection (pools larger than one sort chunk)
+  const BucketPlan bp = bucket_plan(P);
+  L.split = take(kMaxBuckets * 8); L.thresh = take(8);
+  L.bcount[0] = take(kMaxBuckets * 4); L.bcount[1] = take(kMaxBuckets * 4);
+  L.bkeys = take(static_cast<size_t>(bp.nb) * bp.seg * 8);
+  L.bidx = take(static_cast<size_t>(bp.nb) * bp.seg * 4);
   L.cstart = take(Jp * 4); L.cmax = take(Jp * 4); L.info = take(Jp * 4);
   L.abl = take(Jp * 8); L.cc = take(Jp * 8); L.d = take(Jp * 8); L.Y = take(Jp * 8);
   L.rawinfo = take(Jp * 4); L.changed = take(Jp * 4);
@@ -126,6 +146,8 @@ struct ones_ctx {
   Layout L;
   int cur;                    // genome / score buffer holding the current generation
   bool table_changed;         // job table replaced since the current generation was computed
+  BucketPlan bp;              // nb == 0: pool small enough for the single-chunk sort
+  int bucket_phase;           // which counter set the next bucketed generation fills
   int n_cus;
   int64_t t;                  // generation counter
   std::vector<int64_t> ids;   // job identity per slot, to detect slots that change hands
@@ -192,13 +214,33 @@ int run_generation(ones_ctx *c, uint32_t t) {
   a.key0 = static_cast<uint32_t>(c->cfg.seed);
   a.key1 = static_cast<uint32_t>(c->cfg.seed >> 32);
   a.t = t; a.T_mut = c->T_mut; a.T_x = c->T_x;
+  // quantile buckets: only when the survivors reappear unchanged (same table, not generation 0)
+  const bool same_table = t != 0 && !c->table_changed;
+  const bool buckets = same_table && c->bp.nb != 0;
+  a.bk.nb = buckets ? c->bp.nb : 0;
+  a.bk.seg = c->bp.seg;
+  a.bk.split = a.bk.split_next = c->at<uint64_t>(c->L.split);
+  a.bk.thresh = a.bk.thresh_next = c->at<uint64_t>(c->L.thresh);
+  a.bk.count = c->at<uint32_t>(c->L.bcount[c->bucket_phase]);
+  a.bk.keys = c->at<uint64_t>(c->L.bkeys);
+  a.bk.idx = c->at<uint32_t>(c->L.bidx);
   int rc;
   if ((rc = timed(c, c->evolve_ev, c->evolve_used, true))) return rc;
-  HIP_TRY(launch_evolve(a, static_cast<int>(c->R), !c->table_changed, c->n_cus, c->stream));
+  HIP_TRY(launch_evolve(a, static_cast<int>(c->R), same_table, c->n_cus, c->stream));
   if ((rc = timed(c, c->evolve_ev, c->evolve_used, false))) return rc;
   if ((rc = timed(c, c->select_ev, c->select_used, true))) return rc;
-  HIP_TRY(launch_select(a.fit, c->P, c->K, c->at<uint64_t>(c->L.keys), c->at<uint32_t>(c->L.idx),
-                        c->at<int32_t>(c->L.sel), c->stream));
+  if (buckets) {
+    HIP_TRY(launch_bucket_select(a.fit, a.bk, c->K, c->at<uint32_t>(c->L.bcount[c->bucket_phase ^ 1]),
+                                 c->at<int32_t>(c->L.sel), c->stream));
+    c->bucket_phase ^= 1;
+  } else {
+    HIP_TRY(launch_select(a.fit, c->P, c->K, c->at<uint64_t>(c->L.keys), c->at<uint32_t>(c->L.idx),
+                          c->at<int32_t>(c->L.sel), c->stream));
+    if (c->bp.nb != 0)   // splitters for the bucketed generations that follow; clears both counter sets
+      HIP_TRY(launch_splitters(a.fit, c->at<int32_t>(c->L.sel), c->K, c->bp.nb, c->at<uint64_t>(c->L.split),
+                               c->at<uint64_t>(c->L.thresh), c->at<uint32_t>(c->L.bcount[0]),
+                               c->at<uint32_t>(c->L.bcount[1]), c->stream));
+  }
   if ((rc = timed(c, c->select_ev, c->select_used, false))) return rc;
   c->cur = next;
   c->table_changed = false;
@@ -245,6 +287,8 @@ int ones_init(ones_ctx **out, const ones_config *cfg, const ones_jobs *jobs, voi
   c->L = L;
   c->cur = 0; c->t = 0;
   c->table_changed = false;
+  c->bp = bucket_plan(c->P);
+  c->bucket_phase = 0;
   c->ids = h.id;
   {
     int dev = 0;
@@ -371,3 +415,4 @@ const char *ones_strerror(int code) {
 }
 
 }  // extern "C"
+

@@ -9,7 +9,10 @@ namespace ones {
 
 constexpr int kLanes = 64;          // one candidate schedule per wave64, job columns across lanes
 constexpr int kMaxRows = 32;        // 2048 job slots / 64 columns
-constexpr int kSortChunk = 4096;    // keys sorted per workgroup in LDS
+#ifndef ONES_SORT_CHUNK
+#define ONES_SORT_CHUNK 4096
+#endif
+constexpr int kSortChunk = ONES_SORT_CHUNK;   // keys sorted per workgroup in LDS
 
 // Per-slot constants derived from the job table, structure of arrays over the padded
 // slots (column = slot mod 64, row = slot div 64).  A gene is handled on the device as
@@ -31,6 +34,21 @@ __host__ __device__ inline uint32_t info_mu(uint32_t w)     { return (w >> 11) &
 __host__ __device__ inline uint32_t info_blexp(uint32_t w)  { return (w >> 16) & 31u; }
 __host__ __device__ inline uint32_t info_active(uint32_t w) { return (w >> 21) & 1u; }
 
+// Quantile buckets of the selection (valid while the job table stays the same): children and
+// mutants that beat the K-th survivor are dropped into the bucket of the survivors they fall
+// between.  nb == 0 switches the mechanism off.
+constexpr int kMaxBuckets = 256;
+struct BucketArgs {
+  const uint64_t *split;      // [kMaxBuckets] score bits of survivor ranks c*K/nb, c = 1..nb-1, then +inf
+  const uint64_t *thresh;     // [1] score bits of the K-th survivor
+  uint32_t       *count;      // [nb] offspring per bucket, this generation
+  uint64_t       *keys;       // [nb][seg] score bits of the bucket's offspring
+  uint32_t       *idx;        // [nb][seg] their pool slots
+  uint64_t       *split_next; // splitters and threshold for the next generation (same arrays)
+  uint64_t       *thresh_next;
+  uint32_t        nb, seg;
+};
+
 struct EvolveArgs {
   const int32_t *genes_old;   // [P][Jp] previous generation (unused by the initial population)
   int32_t       *genes_new;   // [P][Jp]
@@ -42,6 +60,7 @@ struct EvolveArgs {
   uint32_t       key0, key1;  // seed
   uint32_t       t;           // generation counter (0 = initial population)
   uint32_t       T_mut, T_x;  // rate thresholds on a 32-bit word
+  BucketArgs     bk;
 };
 
 struct RawJobs {              // uploaded by the host after validation, [Jp] each
@@ -68,6 +87,10 @@ inline hipError_t launch_evolve(const EvolveArgs &a, int rows, bool same_table, 
 }
 hipError_t launch_select(const double *fit, uint32_t P, uint32_t K, uint64_t *keys, uint32_t *idx,
                          int32_t *sel, hipStream_t s);
+hipError_t launch_bucket_select(const double *fit, const BucketArgs &bk, uint32_t K, uint32_t *count_next,
+                                int32_t *sel, hipStream_t s);
+hipError_t launch_splitters(const double *fit, const int32_t *sel, uint32_t K, uint32_t nb, uint64_t *split,
+                            uint64_t *thresh, uint32_t *count0, uint32_t *count1, hipStream_t s);
 hipError_t launch_best(const int32_t *genes, const double *fit, const int32_t *sel, const uint32_t *info,
                        uint32_t Jn, uint32_t Jp, int32_t *batch_out, int32_t *gpus_out, double *fit_out,
                        hipStream_t s);

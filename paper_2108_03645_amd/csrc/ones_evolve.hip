@@ -116,11 +116,12 @@ struct Smem {
   uint2    *cc2;     // [Jp] {cstart, cmax}: GPUs a waiting job resumes with / at the limit R_j
   uint32_t *info;    // [Jp]
   double   *abl, *cc, *d, *Y;   // [Jp]
+  uint64_t *split;   // [kMaxBuckets] bucket splitters, then [1] the K-th survivor's score bits
   uint8_t  *stash;   // [waves][Jp] second crossover child while the first is repaired
 };
 
 inline size_t smem_bytes(uint32_t Jp, int waves) {
-  return static_cast<size_t>(Jp) * (8 + 4 + 32) + static_cast<size_t>(waves) * Jp;
+  return static_cast<size_t>(Jp) * (8 + 4 + 32) + (kMaxBuckets + 1) * 8 + static_cast<size_t>(waves) * Jp;
 }
 
 __device__ __forceinline__ Smem carve(unsigned char *base, uint32_t Jp) {
@@ -129,13 +130,18 @@ __device__ __forceinline__ Smem carve(unsigned char *base, uint32_t Jp) {
   s.cc = s.abl + Jp;
   s.d = s.cc + Jp;
   s.Y = s.d + Jp;
-  s.cc2 = reinterpret_cast<uint2 *>(s.Y + Jp);
+  s.split = reinterpret_cast<uint64_t *>(s.Y + Jp);
+  s.cc2 = reinterpret_cast<uint2 *>(s.split + kMaxBuckets + 1);
   s.info = reinterpret_cast<uint32_t *>(s.cc2 + Jp);
   s.stash = reinterpret_cast<uint8_t *>(s.info + Jp);
   return s;
 }
 
-__device__ __forceinline__ void stage_table(const JobTable &tab, const Smem &s, uint32_t Jp) {
+__device__ __forceinline__ void stage_table(const JobTable &tab, const BucketArgs &bk, const Smem &s, uint32_t Jp) {
+  if (bk.nb != 0) {
+    for (uint32_t q = threadIdx.x; q <= kMaxBuckets; q += blockDim.x)
+      s.split[q] = q < kMaxBuckets ? bk.split[q] : *bk.thresh;
+  }
   for (uint32_t j = threadIdx.x; j < Jp; j += blockDim.x) {
     s.cc2[j] = make_uint2(tab.cstart[j], tab.cmax[j]);
     s.info[j] = tab.info[j];
@@ -259,9 +265,32 @@ __device__ __forceinline__ double score(const uint32_t (&c)[R], const Smem &s, i
   return acc;
 }
 
+// A child or mutant that beats the K-th survivor joins the bucket of the survivors it falls
+// between: bucket = number of splitters <= its score.  Scores at or above the threshold
+// cannot be among the best K (the K survivors themselves are in the pool, in smaller slots).
+__device__ __forceinline__ void drop_in_bucket(const EvolveArgs &a, const Smem &s, uint32_t p, double f, int lane) {
+  const uint64_t raw = static_cast<uint64_t>(__double_as_longlong(f));
+  // the butterfly leaves the same sum in every lane; make that visible to the compiler
+  // (the builtin returns a signed int: widen through uint32_t, not by sign extension)
+  const uint32_t hi = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(raw >> 32)));
+  const uint32_t lo = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(raw)));
+  const uint64_t bits = (static_cast<uint64_t>(hi) << 32) | lo;
+  if (bits >= s.split[kMaxBuckets]) return;
+  uint32_t b = 0;
+#pragma unroll
+  for (int q = 0; q < kMaxBuckets / kLanes; ++q)
+    b += static_cast<uint32_t>(__popcll(__ballot(s.split[q * kLanes + lane] <= bits)));
+  if (lane == 0) {
+    const uint32_t slot = atomicAdd(&a.bk.count[b], 1u);
+    const size_t at = static_cast<size_t>(b) * a.bk.seg + slot;
+    a.bk.keys[at] = bits;
+    a.bk.idx[at] = p;
+  }
+}
+
 template <int R>
-__device__ __forceinline__ void finish(const EvolveArgs &a, const Smem &s, uint32_t p, uint32_t r,
-                                       uint32_t (&c)[R], int lane) {
+__device__ __forceinline__ double finish(const EvolveArgs &a, const Smem &s, uint32_t p, uint32_t r,
+                                         uint32_t (&c)[R], int lane) {
   repair<R>(c, s, a.G, r, lane);
   phase_fence();
   const double f = score<R>(c, s, lane);
@@ -271,6 +300,7 @@ __device__ __forceinline__ void finish(const EvolveArgs &a, const Smem &s, uint3
   for (int i = 0; i < R; ++i)
     row[lane + kLanes * i] = static_cast<int32_t>(c[i] << info_blexp(s.info[lane + kLanes * i]));
   if (lane == 0) a.fit[p] = f;
+  return f;
 }
 
 template <int R>
@@ -296,7 +326,7 @@ template <int R>
 __global__ __launch_bounds__(Shape<R>::kWaves *kLanes) void init_kernel(EvolveArgs a) {
   extern __shared__ __align__(16) unsigned char smem_raw[];
   const Smem s = carve(smem_raw, a.Jp);
-  stage_table(a.tab, s, a.Jp);
+  stage_table(a.tab, a.bk, s, a.Jp);
   const int lane0 = threadIdx.x & (kLanes - 1);
   const uint32_t wave = __builtin_amdgcn_readfirstlane(blockIdx.x * Shape<R>::kWaves + (threadIdx.x >> 6));
   const uint32_t stride = gridDim.x * Shape<R>::kWaves;
@@ -323,7 +353,7 @@ template <int R, bool kSameTable>
 __global__ __launch_bounds__(Shape<R>::kWaves *kLanes) void evolve_kernel(EvolveArgs a) {
   extern __shared__ __align__(16) unsigned char smem_raw[];
   const Smem s = carve(smem_raw, a.Jp);
-  stage_table(a.tab, s, a.Jp);
+  stage_table(a.tab, a.bk, s, a.Jp);
   const int lane0 = threadIdx.x & (kLanes - 1);
   const uint32_t wave_in_block = threadIdx.x >> 6;
   const uint32_t wave = __builtin_amdgcn_readfirstlane(blockIdx.x * Shape<R>::kWaves + wave_in_block);
@@ -362,11 +392,13 @@ __global__ __launch_bounds__(Shape<R>::kWaves *kLanes) void evolve_kernel(Evolve
         }
       }
       phase_fence();
-      finish<R>(a, s, p0, d0.r, c, lane);
+      const double f0 = finish<R>(a, s, p0, d0.r, c, lane);
+      if (kSameTable && a.bk.nb != 0) drop_in_bucket(a, s, p0, f0, lane);
       phase_fence();
 #pragma unroll
       for (int i = 0; i < R; ++i) c[i] = (1u << stash[lane + kLanes * i]) >> 1;
-      finish<R>(a, s, p0 + 1, d1.r, c, lane);
+      const double f1 = finish<R>(a, s, p0 + 1, d1.r, c, lane);
+      if (kSameTable && a.bk.nb != 0) drop_in_bucket(a, s, p0 + 1, f1, lane);
     } else if (item < 2 * K) {
       // uniform mutation: each job redrawn with rate theta (k = 0 pre-empts it)
       const uint32_t p = 3 * K + (item - K);
@@ -388,7 +420,8 @@ __global__ __launch_bounds__(Shape<R>::kWaves *kLanes) void evolve_kernel(Evolve
       }
       phase_fence();
       gpus_from_batches<R, false>(s, lane, c);
-      finish<R>(a, s, p, d.r, c, lane);
+      const double f = finish<R>(a, s, p, d.r, c, lane);
+      if (kSameTable && a.bk.nb != 0) drop_in_bucket(a, s, p, f, lane);
     } else {
       // refresh: the survivor of rank p, projected onto the current job table
       const uint32_t p = item - 2 * K;

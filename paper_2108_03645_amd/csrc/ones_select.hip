@@ -10,16 +10,42 @@
 namespace ones {
 namespace {
 
-constexpr int kSortThreads = 1024;
-
-struct Key { uint64_t k; uint32_t i; };
+constexpr int kSortThreads = kSortChunk / 2 > 1024 ? 1024 : kSortChunk / 2;
 
 __device__ __forceinline__ bool key_less(uint64_t ka, uint32_t ia, uint64_t kb, uint32_t ib) {
   return ka < kb || (ka == kb && ia < ib);
 }
 
-// Each workgroup sorts one chunk of n (power of two, <= kSortChunk) keys with a bitonic
-// network in LDS.  With a single chunk the survivors are written directly.
+// Bitonic sorting network over n (a power of two) keys by one workgroup, ascending
+// (score bits, slot).  Works on LDS or, for oversized inputs, on global memory.
+template <typename K64, typename I32>
+__device__ __forceinline__ void bitonic_sort(K64 *sk, I32 *si, uint32_t n) {
+  for (uint32_t k = 2; k <= n; k <<= 1) {
+    for (uint32_t j = k >> 1; j > 0; j >>= 1) {
+      for (uint32_t e = threadIdx.x; e < n / 2; e += blockDim.x) {
+        const uint32_t lo = ((e & ~(j - 1)) << 1) | (e & (j - 1));
+        const uint32_t hi = lo | j;
+        const bool up = (lo & k) == 0;
+        const uint64_t ka = sk[lo], kb = sk[hi];
+        const uint32_t ia = si[lo], ib = si[hi];
+        if (key_less(kb, ib, ka, ia) == up) {
+          sk[lo] = kb; si[lo] = ib;
+          sk[hi] = ka; si[hi] = ia;
+        }
+      }
+      __threadfence_block();
+      __syncthreads();
+    }
+  }
+}
+
+__device__ __forceinline__ uint32_t pow2_at_least(uint32_t v) {
+  return v <= 1 ? 1u : 1u << (32 - __clz(static_cast<int>(v - 1)));
+}
+
+// ---------------------------------------------------------------- general path -----
+// Each workgroup sorts one chunk of n (power of two, <= kSortChunk) keys in LDS.  With a
+// single chunk the survivors are written directly.
 __global__ __launch_bounds__(kSortThreads) void sort_chunks_kernel(const double *fit, uint32_t P, uint32_t K,
                                                                   uint32_t n, uint64_t *keys, uint32_t *idx,
                                                                   int32_t *sel, int single) {
@@ -32,22 +58,7 @@ __global__ __launch_bounds__(kSortThreads) void sort_chunks_kernel(const double 
     si[e] = p < P ? p : 0xFFFFFFFFu;
   }
   __syncthreads();
-  for (uint32_t k = 2; k <= n; k <<= 1) {
-    for (uint32_t j = k >> 1; j > 0; j >>= 1) {
-      for (uint32_t e = threadIdx.x; e < n / 2; e += kSortThreads) {
-        const uint32_t lo = ((e & ~(j - 1)) << 1) | (e & (j - 1));
-        const uint32_t hi = lo | j;
-        const bool up = (lo & k) == 0;
-        const uint64_t ka = sk[lo], kb = sk[hi];
-        const uint32_t ia = si[lo], ib = si[hi];
-        if (key_less(kb, ib, ka, ia) == up) {
-          sk[lo] = kb; si[lo] = ib;
-          sk[hi] = ka; si[hi] = ia;
-        }
-      }
-      __syncthreads();
-    }
-  }
+  bitonic_sort(sk, si, n);
   if (single) {
     for (uint32_t e = threadIdx.x; e < K; e += kSortThreads) sel[e] = static_cast<int32_t>(si[e]);
   } else {
@@ -81,6 +92,106 @@ __global__ __launch_bounds__(256) void rank_kernel(const uint64_t *keys, const u
     rank += lo;
   }
   if (rank < K) sel[rank] = static_cast<int32_t>(id);
+}
+
+// ----------------------------------------------------------- quantile buckets ------
+// While the job table stays the same, the K survivors reappear in the next pool with the same
+// scores, already in rank order (slots 0..K-1).  Their scores at ranks r_c = c*K/nb therefore
+// split the next pool into nb buckets that each hold K/nb survivors; the evolve kernel drops
+// every child or mutant that beats the K-th survivor into its bucket, and one workgroup per
+// bucket sorts those few and merges them with its survivors.  Buckets concatenate to the
+// global order.
+
+// Boundary rank of bucket c (c = 0..nb); bucket b owns survivor ranks [bound(b), bound(b+1)).
+__device__ __forceinline__ uint32_t bucket_bound(uint32_t c, uint32_t K, uint32_t nb) {
+  return static_cast<uint32_t>((static_cast<uint64_t>(c) * K) / nb);
+}
+
+// Records the next generation's splitters when an element lands on a boundary rank.
+__device__ __forceinline__ void note_rank(uint32_t g, uint64_t bits, uint32_t K, uint32_t nb, uint64_t *split,
+                                          uint64_t *thresh) {
+  if (g == K - 1) *thresh = bits;
+  const uint32_t c = static_cast<uint32_t>((static_cast<uint64_t>(g) * nb) / K);
+  if (c >= 1 && bucket_bound(c, K, nb) == g) split[c - 1] = bits;
+  if (c + 1 < nb && bucket_bound(c + 1, K, nb) == g) split[c] = bits;
+}
+
+constexpr int kBucketThreads = 256;
+constexpr int kBucketLds = 2048;      // offspring of one bucket that are sorted in LDS
+
+__global__ __launch_bounds__(kBucketThreads) void bucket_select_kernel(const double *fit, BucketArgs bk, uint32_t K,
+                                                                       uint32_t *count_next, int32_t *sel) {
+  __shared__ uint64_t sk[kBucketLds];
+  __shared__ uint32_t si[kBucketLds];
+  __shared__ uint32_t red[kBucketThreads];
+  const uint32_t b = blockIdx.x, nb = bk.nb, tid = threadIdx.x;
+  // offset of this bucket = its first survivor rank + all offspring of the buckets before it
+  uint32_t before = 0;
+  for (uint32_t c = tid; c < b; c += kBucketThreads) before += bk.count[c];
+  red[tid] = before;
+  __syncthreads();
+  for (uint32_t s = kBucketThreads / 2; s > 0; s >>= 1) {
+    if (tid < s) red[tid] += red[tid + s];
+    __syncthreads();
+  }
+  const uint32_t e0 = bucket_bound(b, K, nb), e1 = bucket_bound(b + 1, K, nb), ne = e1 - e0;
+  const uint32_t off = e0 + red[0];
+  const uint32_t n = bk.count[b];
+  uint64_t *gk = bk.keys + static_cast<size_t>(b) * bk.seg;
+  uint32_t *gi = bk.idx + static_cast<size_t>(b) * bk.seg;
+  const uint32_t n2 = pow2_at_least(n);
+  const bool in_lds = n2 <= static_cast<uint32_t>(kBucketLds);
+  if (off < K) {                                     // otherwise nothing of this bucket survives
+    if (in_lds) {
+      for (uint32_t e = tid; e < n2; e += kBucketThreads) {
+        sk[e] = e < n ? gk[e] : ~0ull;
+        si[e] = e < n ? gi[e] : 0xFFFFFFFFu;
+      }
+      __syncthreads();
+      bitonic_sort(sk, si, n2);
+    } else {                                         // oversized bucket: same network in global memory
+      for (uint32_t e = n + tid; e < n2; e += kBucketThreads) { gk[e] = ~0ull; gi[e] = 0xFFFFFFFFu; }
+      __threadfence_block();
+      __syncthreads();
+      bitonic_sort(gk, gi, n2);
+    }
+    // offspring i: rank = i + survivors with score <= its score (a survivor wins a tie: smaller slot)
+    for (uint32_t i = tid; i < n; i += kBucketThreads) {
+      const uint64_t key = in_lds ? sk[i] : gk[i];
+      const uint32_t id = in_lds ? si[i] : gi[i];
+      uint32_t lo = 0, hi = ne;
+      while (lo < hi) {
+        const uint32_t mid = (lo + hi) >> 1;
+        if (static_cast<uint64_t>(__double_as_longlong(fit[e0 + mid])) <= key) lo = mid + 1; else hi = mid;
+      }
+      const uint32_t g = off + i + lo;
+      if (g < K) { sel[g] = static_cast<int32_t>(id); note_rank(g, key, K, nb, bk.split_next, bk.thresh_next); }
+    }
+    // survivor e: rank = e + offspring with a strictly smaller score
+    for (uint32_t e = tid; e < ne; e += kBucketThreads) {
+      const uint64_t key = static_cast<uint64_t>(__double_as_longlong(fit[e0 + e]));
+      uint32_t lo = 0, hi = n;
+      while (lo < hi) {
+        const uint32_t mid = (lo + hi) >> 1;
+        if ((in_lds ? sk[mid] : gk[mid]) < key) lo = mid + 1; else hi = mid;
+      }
+      const uint32_t g = off + e + lo;
+      if (g < K) { sel[g] = static_cast<int32_t>(e0 + e); note_rank(g, key, K, nb, bk.split_next, bk.thresh_next); }
+    }
+  }
+  if (tid == 0) count_next[b] = 0;                   // the other counter set, for the next generation
+}
+
+// Splitters after a selection by the general path.
+__global__ void splitters_kernel(const double *fit, const int32_t *sel, uint32_t K, uint32_t nb, uint64_t *split,
+                                 uint64_t *thresh, uint32_t *count0, uint32_t *count1) {
+  const uint32_t c = blockIdx.x * blockDim.x + threadIdx.x;
+  if (c < 256) {
+    count0[c] = 0; count1[c] = 0;
+    split[c] = (c + 1 < nb) ? static_cast<uint64_t>(__double_as_longlong(fit[sel[bucket_bound(c + 1, K, nb)]]))
+                            : 0x7FF0000000000000ull;          // +infinity pads the table
+  }
+  if (c == 0) *thresh = static_cast<uint64_t>(__double_as_longlong(fit[sel[K - 1]]));
 }
 
 __global__ void prepare_table_kernel(RawJobs raw, JobTable tab, uint32_t Jp) {
@@ -158,6 +269,18 @@ hipError_t launch_select(const double *fit, uint32_t P, uint32_t K, uint64_t *ke
   if (rc != hipSuccess) return rc;
   const uint32_t n = chunks * kSortChunk;
   hipLaunchKernelGGL(rank_kernel, dim3((n + 255) / 256), dim3(256), 0, s, keys, idx, chunks, K, sel);
+  return hipGetLastError();
+}
+
+hipError_t launch_bucket_select(const double *fit, const BucketArgs &bk, uint32_t K, uint32_t *count_next,
+                                int32_t *sel, hipStream_t s) {
+  hipLaunchKernelGGL(bucket_select_kernel, dim3(bk.nb), dim3(kBucketThreads), 0, s, fit, bk, K, count_next, sel);
+  return hipGetLastError();
+}
+
+hipError_t launch_splitters(const double *fit, const int32_t *sel, uint32_t K, uint32_t nb, uint64_t *split,
+                            uint64_t *thresh, uint32_t *count0, uint32_t *count1, hipStream_t s) {
+  hipLaunchKernelGGL(splitters_kernel, dim3(1), dim3(256), 0, s, fit, sel, K, nb, split, thresh, count0, count1);
   return hipGetLastError();
 }
 
