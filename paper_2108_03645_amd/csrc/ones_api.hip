@@ -29,7 +29,7 @@ int hip_fail(hipError_t e, const char *what) {
 size_t align_up(size_t v) { return (v + 255) & ~static_cast<size_t>(255); }
 
 struct Layout {
-  size_t genes[2], fit[2], sel, keys, idx, split, thresh, bcount[2], bkeys, bidx, cstart, cmax, info, abl, cc, d, Y;
+  size_t genes[2], fit[2], sel, keys, idx, split, thresh, bcount[2], bkeys, bidx, cstart, cmax, info, abl, cc, d, Y, terms;
   size_t rawinfo, changed, ra, rc, rd, rY, best_batch, best_gpus, best_fit, total;
 };
 
@@ -66,6 +66,7 @@ Layout make_layout(uint32_t P, uint32_t Jp) {
   L.bidx = take(static_cast<size_t>(bp.nb) * bp.seg * 4);
   L.cstart = take(Jp * 4); L.cmax = take(Jp * 4); L.info = take(Jp * 4);
   L.abl = take(Jp * 8); L.cc = take(Jp * 8); L.d = take(Jp * 8); L.Y = take(Jp * 8);
+  L.terms = take(static_cast<size_t>(Jp) * kMaxTermEntries * 8);
   L.rawinfo = take(Jp * 4); L.changed = take(Jp * 4);
   L.ra = take(Jp * 8); L.rc = take(Jp * 8); L.rd = take(Jp * 8); L.rY = take(Jp * 8);
   L.best_batch = take(Jp * 4); L.best_gpus = take(Jp * 4); L.best_fit = take(8);
@@ -106,12 +107,14 @@ struct HostJobs {                     // validated, padded staging copy of a job
   std::vector<uint32_t> rawinfo;
   std::vector<double> a, c, d, Y;
   std::vector<int64_t> id;
+  uint32_t term_E = 2;                // waiting + GPU-count codes up to the largest bmax / gpu_max_batch
 };
 
 int stage_jobs(int Jn, int Jp, const ones_jobs *jobs, HostJobs &h) {
   h.rawinfo.assign(Jp, 0u);
   h.a.assign(Jp, 0.0); h.c.assign(Jp, 0.0); h.d.assign(Jp, 0.0); h.Y.assign(Jp, 0.0);
   h.id.assign(Jp, 0);
+  h.term_E = 2;
   if (Jn > 0 && (!jobs || !jobs->job_id || !jobs->active || !jobs->bmin || !jobs->bmax ||
                  !jobs->gpu_max_batch || !jobs->a || !jobs->c || !jobs->d || !jobs->remaining))
     return ONES_E_INVALID_ARG;
@@ -129,6 +132,7 @@ int stage_jobs(int Jn, int Jp, const ones_jobs *jobs, HostJobs &h) {
     h.rawinfo[j] = static_cast<uint32_t>(lo) | (static_cast<uint32_t>(hi) << 5) |
                    (static_cast<uint32_t>(mu) << 10) | (1u << 15);
     h.a[j] = jobs->a[j]; h.c[j] = jobs->c[j]; h.d[j] = jobs->d[j]; h.Y[j] = jobs->remaining[j];
+    h.term_E = std::max<uint32_t>(h.term_E, static_cast<uint32_t>(std::max(0, hi - mu)) + 2);
   }
   return ONES_OK;
 }
@@ -149,6 +153,7 @@ struct ones_ctx {
   BucketPlan bp;              // nb == 0: pool small enough for the single-chunk sort
   int bucket_phase;           // which counter set the next bucketed generation fills
   int n_cus;
+  uint32_t term_E;            // entries per job of the term table
   int64_t t;                  // generation counter
   std::vector<int64_t> ids;   // job identity per slot, to detect slots that change hands
   // measurement
@@ -159,7 +164,8 @@ struct ones_ctx {
   template <typename T> T *at(size_t off) const { return reinterpret_cast<T *>(ws + off); }
   JobTable table() const {
     return JobTable{at<uint32_t>(L.cstart), at<uint32_t>(L.cmax), at<uint32_t>(L.info),
-                    at<double>(L.abl), at<double>(L.cc), at<double>(L.d), at<double>(L.Y)};
+                    at<double>(L.abl), at<double>(L.cc), at<double>(L.d), at<double>(L.Y),
+                    at<double>(L.terms), term_E};
   }
 };
 
@@ -174,7 +180,9 @@ int upload_table(ones_ctx *c, const HostJobs &h, const std::vector<uint32_t> *ch
   HIP_TRY(hipMemcpyAsync(c->ws + c->L.rY, h.Y.data(), n8, hipMemcpyHostToDevice, c->stream));
   RawJobs raw{c->at<uint32_t>(c->L.rawinfo), c->at<double>(c->L.ra), c->at<double>(c->L.rc),
               c->at<double>(c->L.rd), c->at<double>(c->L.rY)};
+  c->term_E = h.term_E;
   HIP_TRY(launch_prepare_table(raw, c->table(), c->Jp, c->stream));
+  HIP_TRY(launch_build_terms(c->table(), c->Jp, c->stream));
   if (changed) {
     HIP_TRY(hipMemcpyAsync(c->ws + c->L.changed, changed->data(), n4, hipMemcpyHostToDevice, c->stream));
     HIP_TRY(launch_reset_slots(c->at<int32_t>(c->L.genes[c->cur]), c->at<uint32_t>(c->L.changed), c->P, c->Jp,

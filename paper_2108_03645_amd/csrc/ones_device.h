@@ -9,6 +9,7 @@ namespace ones {
 
 constexpr int kLanes = 64;          // one candidate schedule per wave64, job columns across lanes
 constexpr int kMaxRows = 32;        // 2048 job slots / 64 columns
+constexpr int kMaxTermEntries = 22; // waiting + GPU counts 2^0 .. 2^20
 #ifndef ONES_SORT_CHUNK
 #define ONES_SORT_CHUNK 4096
 #endif
@@ -26,6 +27,10 @@ struct JobTable {
   double   *cc;       // synchronisation cost per doubling of the GPU count
   double   *d;        // fixed cost per iteration
   double   *Y;        // remaining samples
+  // term table: T_j c_j of slot (row, lane) running on 2^(e-1) GPUs at [(row*term_E + e)*64 + lane],
+  // e = 0 (waiting, +0.0) .. term_E-1; the value the score formula gives, precomputed per table
+  double   *terms;
+  uint32_t  term_E;
 };
 
 __host__ __device__ inline uint32_t info_lo(uint32_t w)     { return w & 31u; }
@@ -60,6 +65,7 @@ struct EvolveArgs {
   uint32_t       key0, key1;  // seed
   uint32_t       t;           // generation counter (0 = initial population)
   uint32_t       T_mut, T_x;  // rate thresholds on a 32-bit word
+  uint32_t       term_lds;    // set by the launcher: entries per job of the term table in LDS, 0 = none
   BucketArgs     bk;
 };
 
@@ -70,6 +76,7 @@ struct RawJobs {              // uploaded by the host after validation, [Jp] eac
 
 // launchers (each returns the hipGetLastError of its launch)
 hipError_t launch_prepare_table(const RawJobs &raw, const JobTable &tab, uint32_t Jp, hipStream_t s);
+hipError_t launch_build_terms(const JobTable &tab, uint32_t Jp, hipStream_t s);
 hipError_t launch_reset_slots(int32_t *genes, const uint32_t *changed, uint32_t P, uint32_t Jp, hipStream_t s);
 // same_table: the job table is the one the previous generation was repaired and scored with
 hipError_t launch_evolve_group0(const EvolveArgs &a, int rows, bool same_table, int n_cus, hipStream_t s);

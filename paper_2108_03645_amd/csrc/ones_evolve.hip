@@ -23,6 +23,7 @@ namespace ones {
 namespace {
 
 constexpr int kGroupFirst = 8 * ONES_ROW_GROUP + 1;   // row counts kGroupFirst .. kGroupFirst + 7
+constexpr size_t kLdsBudget = 160 * 1024;             // LDS of one gfx950 compute unit
 
 // Keeps the instruction scheduler from interleaving two phases of a work item, or too many
 // rows of one loop, which would keep all their registers live at once.
@@ -115,29 +116,34 @@ __device__ __forceinline__ uint32_t wave_sum(uint32_t v) {
 struct Smem {
   uint2    *cc2;     // [Jp] {cstart, cmax}: GPUs a waiting job resumes with / at the limit R_j
   uint32_t *info;    // [Jp]
-  double   *abl, *cc, *d, *Y;   // [Jp]
+  double   *abl, *cc, *d, *Y;   // [Jp] model parameters (when the term table does not fit)
+  double   *terms;   // [R][E][64] T_j c_j of job (row, lane) at GPU-count code e, or null
   uint64_t *split;   // [kMaxBuckets] bucket splitters, then [1] the K-th survivor's score bits
   uint8_t  *stash;   // [waves][Jp] second crossover child while the first is repaired
 };
 
-inline size_t smem_bytes(uint32_t Jp, int waves) {
-  return static_cast<size_t>(Jp) * (8 + 4 + 32) + (kMaxBuckets + 1) * 8 + static_cast<size_t>(waves) * Jp;
+// E = entries per job of the term table kept in LDS, 0 = keep the four model parameters.
+inline size_t smem_bytes(uint32_t Jp, int waves, uint32_t E) {
+  return static_cast<size_t>(Jp) * (8 + 4 + (E ? 8 * E : 32)) + (kMaxBuckets + 1) * 8 +
+         static_cast<size_t>(waves) * Jp;
 }
 
-__device__ __forceinline__ Smem carve(unsigned char *base, uint32_t Jp) {
+__device__ __forceinline__ Smem carve(unsigned char *base, uint32_t Jp, uint32_t E) {
   Smem s;
   s.abl = reinterpret_cast<double *>(base);
   s.cc = s.abl + Jp;
   s.d = s.cc + Jp;
   s.Y = s.d + Jp;
-  s.split = reinterpret_cast<uint64_t *>(s.Y + Jp);
+  s.terms = E ? s.abl : nullptr;
+  s.split = reinterpret_cast<uint64_t *>(s.abl + static_cast<size_t>(Jp) * (E ? E : 4));
   s.cc2 = reinterpret_cast<uint2 *>(s.split + kMaxBuckets + 1);
   s.info = reinterpret_cast<uint32_t *>(s.cc2 + Jp);
   s.stash = reinterpret_cast<uint8_t *>(s.info + Jp);
   return s;
 }
 
-__device__ __forceinline__ void stage_table(const JobTable &tab, const BucketArgs &bk, const Smem &s, uint32_t Jp) {
+__device__ __forceinline__ void stage_table(const JobTable &tab, const BucketArgs &bk, const Smem &s, uint32_t Jp,
+                                            uint32_t E) {
   if (bk.nb != 0) {
     for (uint32_t q = threadIdx.x; q <= kMaxBuckets; q += blockDim.x)
       s.split[q] = q < kMaxBuckets ? bk.split[q] : *bk.thresh;
@@ -145,11 +151,15 @@ __device__ __forceinline__ void stage_table(const JobTable &tab, const BucketArg
   for (uint32_t j = threadIdx.x; j < Jp; j += blockDim.x) {
     s.cc2[j] = make_uint2(tab.cstart[j], tab.cmax[j]);
     s.info[j] = tab.info[j];
-    s.abl[j] = tab.abl[j];
-    s.cc[j] = tab.cc[j];
-    s.d[j] = tab.d[j];
-    s.Y[j] = tab.Y[j];
+    if (E == 0) {
+      s.abl[j] = tab.abl[j];
+      s.cc[j] = tab.cc[j];
+      s.d[j] = tab.d[j];
+      s.Y[j] = tab.Y[j];
+    }
   }
+  if (E != 0)
+    for (uint32_t q = threadIdx.x; q < Jp * E; q += blockDim.x) s.terms[q] = tab.terms[q];
   __syncthreads();
 }
 
@@ -247,8 +257,18 @@ __device__ __forceinline__ void repair(uint32_t (&c)[R], const Smem &s, uint32_t
 // Eq. 3: sum over running jobs of T_j c_j = Y_j t_j / (local batch), t = a b + c log2(g) + d.
 // Summation order: a lane's rows top to bottom, then a xor butterfly 32,16,..,1 over lanes.
 template <int R>
-__device__ __forceinline__ double score(const uint32_t (&c)[R], const Smem &s, int lane) {
+__device__ __forceinline__ double score(const uint32_t (&c)[R], const Smem &s, uint32_t E, int lane) {
   double acc = 0.0;
+  if (E != 0) {
+    // the job's term only depends on its GPU count c = 2^(code-1) (code 0: waiting), and the
+    // table holds exactly the value the formula below produces
+#pragma unroll
+    for (int i = 0; i < R; ++i) {
+      const uint32_t code = c[i] ? 32u - static_cast<uint32_t>(__clz(static_cast<int>(c[i]))) : 0u;
+      acc = acc + s.terms[(i * E + code) * kLanes + lane];
+      if (i % 8 == 7) { pin(acc); phase_fence(); }
+    }
+  } else
 #pragma unroll
   for (int i = 0; i < R; ++i) {
     const int j = lane + kLanes * i;
@@ -293,7 +313,7 @@ __device__ __forceinline__ double finish(const EvolveArgs &a, const Smem &s, uin
                                          uint32_t (&c)[R], int lane) {
   repair<R>(c, s, a.G, r, lane);
   phase_fence();
-  const double f = score<R>(c, s, lane);
+  const double f = score<R>(c, s, a.term_lds, lane);
   phase_fence();
   int32_t *row = a.genes_new + static_cast<size_t>(p) * a.Jp;
 #pragma unroll
@@ -325,8 +345,8 @@ template <int R> struct Shape { static constexpr int kWaves = R > 16 ? ONES_WAVE
 template <int R>
 __global__ __launch_bounds__(Shape<R>::kWaves *kLanes) void init_kernel(EvolveArgs a) {
   extern __shared__ __align__(16) unsigned char smem_raw[];
-  const Smem s = carve(smem_raw, a.Jp);
-  stage_table(a.tab, a.bk, s, a.Jp);
+  const Smem s = carve(smem_raw, a.Jp, a.term_lds);
+  stage_table(a.tab, a.bk, s, a.Jp, a.term_lds);
   const int lane0 = threadIdx.x & (kLanes - 1);
   const uint32_t wave = __builtin_amdgcn_readfirstlane(blockIdx.x * Shape<R>::kWaves + (threadIdx.x >> 6));
   const uint32_t stride = gridDim.x * Shape<R>::kWaves;
@@ -352,8 +372,8 @@ __global__ __launch_bounds__(Shape<R>::kWaves *kLanes) void init_kernel(EvolveAr
 template <int R, bool kSameTable>
 __global__ __launch_bounds__(Shape<R>::kWaves *kLanes) void evolve_kernel(EvolveArgs a) {
   extern __shared__ __align__(16) unsigned char smem_raw[];
-  const Smem s = carve(smem_raw, a.Jp);
-  stage_table(a.tab, a.bk, s, a.Jp);
+  const Smem s = carve(smem_raw, a.Jp, a.term_lds);
+  stage_table(a.tab, a.bk, s, a.Jp, a.term_lds);
   const int lane0 = threadIdx.x & (kLanes - 1);
   const uint32_t wave_in_block = threadIdx.x >> 6;
   const uint32_t wave = __builtin_amdgcn_readfirstlane(blockIdx.x * Shape<R>::kWaves + wave_in_block);
@@ -442,10 +462,12 @@ __global__ __launch_bounds__(Shape<R>::kWaves *kLanes) void evolve_kernel(Evolve
 }
 
 template <typename Kernel>
-hipError_t launch_persistent(Kernel k, const EvolveArgs &a, int waves, uint32_t items, int n_cus, hipStream_t s) {
-  const size_t lds = smem_bytes(a.Jp, waves);
+hipError_t launch_persistent(Kernel k, EvolveArgs a, int waves, uint32_t items, int n_cus, hipStream_t s) {
+  // the term table goes to LDS when it fits beside the rest
+  a.term_lds = (a.tab.term_E != 0 && smem_bytes(a.Jp, waves, a.tab.term_E) <= kLdsBudget) ? a.tab.term_E : 0u;
+  const size_t lds = smem_bytes(a.Jp, waves, a.term_lds);
   // as many workgroups as can be resident (LDS- and wave-limited), at most one wave per item
-  const size_t per_cu = std::max<size_t>(1, std::min<size_t>(160 * 1024 / lds, 32 / waves));
+  const size_t per_cu = std::max<size_t>(1, std::min<size_t>(kLdsBudget / lds, 32 / waves));
   const uint32_t blocks = std::max<uint32_t>(1u, std::min<uint32_t>((items + waves - 1) / waves,
                                                                     static_cast<uint32_t>(n_cus * per_cu)));
   hipError_t rc = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize,

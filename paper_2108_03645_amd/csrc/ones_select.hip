@@ -216,6 +216,24 @@ __global__ void prepare_table_kernel(RawJobs raw, JobTable tab, uint32_t Jp) {
   tab.Y[j] = raw.Y[j];
 }
 
+// Term table: the score formula evaluated once per (slot, GPU-count code), same operations in
+// the same order as the per-gene evaluation, so both give the same bits.
+__global__ void build_terms_kernel(JobTable tab, uint32_t Jp) {
+  const uint32_t q = blockIdx.x * blockDim.x + threadIdx.x;
+  const uint32_t E = tab.term_E;
+  if (q >= Jp * E) return;
+  const uint32_t lane = q % kLanes, e = (q / kLanes) % E, row = q / (kLanes * E);
+  const uint32_t j = row * kLanes + lane;
+  double term = 0.0;
+  if (e != 0) {
+    const double lg = static_cast<double>(e - 1);
+    const double inv_bl = __hiloint2double(static_cast<int>((1023u - info_blexp(tab.info[j])) << 20), 0);
+    const double t = (tab.abl[j] + tab.cc[j] * lg) + tab.d[j];
+    term = (tab.Y[j] * t) * inv_bl;
+  }
+  tab.terms[q] = term;
+}
+
 __global__ void reset_slots_kernel(int32_t *genes, const uint32_t *changed, uint32_t P, uint32_t Jp) {
   const size_t n = static_cast<size_t>(P) * Jp;
   for (size_t e = blockIdx.x * static_cast<size_t>(blockDim.x) + threadIdx.x; e < n;
@@ -245,6 +263,12 @@ uint32_t next_pow2(uint32_t v) {
 
 hipError_t launch_prepare_table(const RawJobs &raw, const JobTable &tab, uint32_t Jp, hipStream_t s) {
   hipLaunchKernelGGL(prepare_table_kernel, dim3((Jp + 255) / 256), dim3(256), 0, s, raw, tab, Jp);
+  return hipGetLastError();
+}
+
+hipError_t launch_build_terms(const JobTable &tab, uint32_t Jp, hipStream_t s) {
+  const uint32_t n = Jp * tab.term_E;
+  hipLaunchKernelGGL(build_terms_kernel, dim3((n + 255) / 256), dim3(256), 0, s, tab, Jp);
   return hipGetLastError();
 }
 
