@@ -66,6 +66,10 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="stress", choices=["stress", "large", "paper_scale", "tiny"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-events", action="store_true", help="do not bracket kernels with HIP events")
+    ap.add_argument("--copy-reference", action="store_true",
+                    help="also run plain device copies of 1 GiB (2 GiB of traffic each), the yardstick "
+                         "the rocprofv3 FETCH_SIZE / WRITE_SIZE counters are scaled by")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: the search runs on one GPU; --gpus above 1 is not supported "
@@ -84,7 +88,7 @@ def main() -> int:
     search.synchronize()
     torch.cuda.synchronize()
 
-    search.profile_enable(True)
+    search.profile_enable(0 if args.no_events else 4)     # events on every 4th generation
     t0 = time.perf_counter()
     search.generation(args.steps)
     search.synchronize()
@@ -93,6 +97,8 @@ def main() -> int:
     prof = search.profile_read()
     _, _, best_fit = search.best()
 
+    if args.no_events:
+        prof = {"evolve_ms": float("nan"), "evolve_launches": 1, "select_ms": float("nan"), "select_launches": 1}
     evolve_ms = prof["evolve_ms"] / max(1, prof["evolve_launches"])
     select_ms = prof["select_ms"] / max(1, prof["select_launches"])
     # algorithmic bytes of one evolve launch: every gene read once and written once (int32),
@@ -123,6 +129,13 @@ def main() -> int:
                      "algorithmic_bytes_per_launch": alg_bytes},
     }
     search.close()
+    if args.copy_reference:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda:0").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(args.workload)
     print(json.dumps(out))

@@ -109,11 +109,13 @@ int ones_export(ones_ctx *ctx, int32_t *genes, double *fit, int32_t *sel, int64_
 /* Job slots padded to whole rows of 64 columns: 64 * ceil(max(n_slots,1) / 64). */
 int32_t ones_padded_jobs(int32_t n_slots);
 
-/* Measurement hook.  When enabled, every launch of the evolve and select kernels is
- * bracketed by HIP events on the context's stream; ones_profile_read synchronises and
- * returns the accumulated kernel time in milliseconds and the launch counts since the
- * last ones_profile_enable call (any output may be NULL). */
-int ones_profile_enable(ones_ctx *ctx, int32_t on);
+/* Measurement hook.  With every = n > 0 the evolve and the select kernels of every n-th
+ * generation are bracketed by HIP events on the context's stream (n = 1: every generation;
+ * an event costs a few microseconds of stream time); every <= 0 switches it off.
+ * ones_profile_read synchronises and returns the accumulated kernel time in milliseconds
+ * and the number of bracketed launches since the last ones_profile_enable call (any output
+ * may be NULL). */
+int ones_profile_enable(ones_ctx *ctx, int32_t every);
 int ones_profile_read(ones_ctx *ctx, double *evolve_ms, int64_t *evolve_launches,
                       double *select_ms, int64_t *select_launches);
 

@@ -29,20 +29,24 @@ int hip_fail(hipError_t e, const char *what) {
 size_t align_up(size_t v) { return (v + 255) & ~static_cast<size_t>(255); }
 
 struct Layout {
-  size_t genes[2], fit[2], sel, keys, idx, split, thresh, bcount[2], bkeys, bidx, cstart, cmax, info, abl, cc, d, Y, terms;
+  size_t genes[2], fit[2], sel, keys, idx, split, thresh, bcount[2], bkeys, bidx, skeys, sidx, sbucket, pkeys, pidx, cstart, cmax, info, abl, cc, d, Y, terms;
   size_t rawinfo, changed, ra, rc, rd, rY, best_batch, best_gpus, best_fit, total;
 };
 
-// Buckets: about 64 survivors each, at most kMaxBuckets; a bucket's storage can take every
-// child and mutant of the pool (3P/4), rounded up to a power of two for the sorting network.
-struct BucketPlan { uint32_t nb, seg; };
+// Buckets: about 16 survivors each, at most kMaxBuckets.  A bucket stores eight times its fair
+// share of the 3P/4 children and mutants (at least 256, a power of two); the surplus goes to a
+// spill list that could hold all of them, and buckets too large for LDS are sorted in a scratch
+// pool of twice that size (each takes a power-of-two slice).
+struct BucketPlan { uint32_t nb, seg, spill, pool; };
+uint32_t pow2_at_least(uint32_t v) { uint32_t n = 1; while (n < v) n <<= 1; return n; }
 BucketPlan bucket_plan(uint32_t P) {
-  if (P <= static_cast<uint32_t>(kSortChunk)) return BucketPlan{0, 0};
+  if (P <= static_cast<uint32_t>(kSortChunk)) return BucketPlan{0, 0, 0, 0};
   const uint32_t K = P / 4;
   BucketPlan bp;
-  bp.nb = std::min<uint32_t>(kMaxBuckets, std::max<uint32_t>(1, K / 64));
-  bp.seg = 1;
-  while (bp.seg < 3 * K) bp.seg <<= 1;
+  bp.nb = std::min<uint32_t>(kMaxBuckets, std::max<uint32_t>(1, K / 16));
+  bp.spill = 3 * K;
+  bp.pool = 2 * pow2_at_least(3 * K);
+  bp.seg = std::min(pow2_at_least(std::max<uint32_t>(256, 8 * ((3 * K + bp.nb - 1) / bp.nb))), bp.pool / 2);
   return bp;
 }
 
@@ -61,9 +65,14 @@ Layout make_layout(uint32_t P, uint32_t Jp) {
   // quantile buckets of the selection (pools larger than one sort chunk)
   const BucketPlan bp = bucket_plan(P);
   L.split = take(kMaxBuckets * 8); L.thresh = take(8);
-  L.bcount[0] = take(kMaxBuckets * 4); L.bcount[1] = take(kMaxBuckets * 4);
+  L.bcount[0] = take(kBucketCounters * 4); L.bcount[1] = take(kBucketCounters * 4);
   L.bkeys = take(static_cast<size_t>(bp.nb) * bp.seg * 8);
   L.bidx = take(static_cast<size_t>(bp.nb) * bp.seg * 4);
+  L.skeys = take(static_cast<size_t>(bp.spill) * 8);
+  L.sidx = take(static_cast<size_t>(bp.spill) * 4);
+  L.sbucket = take(static_cast<size_t>(bp.spill) * 4);
+  L.pkeys = take(static_cast<size_t>(bp.pool) * 8);
+  L.pidx = take(static_cast<size_t>(bp.pool) * 4);
   L.cstart = take(Jp * 4); L.cmax = take(Jp * 4); L.info = take(Jp * 4);
   L.abl = take(Jp * 8); L.cc = take(Jp * 8); L.d = take(Jp * 8); L.Y = take(Jp * 8);
   L.terms = take(static_cast<size_t>(Jp) * kMaxTermEntries * 8);
@@ -158,6 +167,8 @@ struct ones_ctx {
   std::vector<int64_t> ids;   // job identity per slot, to detect slots that change hands
   // measurement
   bool profiling;
+  int profile_every;          // bracket the kernels of every profile_every-th generation
+  int64_t profile_tick;
   std::vector<EventPair> evolve_ev, select_ev;
   size_t evolve_used, select_used;
 
@@ -193,7 +204,7 @@ int upload_table(ones_ctx *c, const HostJobs &h, const std::vector<uint32_t> *ch
 }
 
 int timed(ones_ctx *c, std::vector<EventPair> &pool, size_t &used, bool begin) {
-  if (!c->profiling) return ONES_OK;
+  if (!c->profiling || c->profile_tick % c->profile_every != 0) return ONES_OK;
   if (begin) {
     if (used == pool.size()) {
       EventPair e;
@@ -232,6 +243,11 @@ int run_generation(ones_ctx *c, uint32_t t) {
   a.bk.count = c->at<uint32_t>(c->L.bcount[c->bucket_phase]);
   a.bk.keys = c->at<uint64_t>(c->L.bkeys);
   a.bk.idx = c->at<uint32_t>(c->L.bidx);
+  a.bk.spill_keys = c->at<uint64_t>(c->L.skeys);
+  a.bk.spill_idx = c->at<uint32_t>(c->L.sidx);
+  a.bk.spill_bucket = c->at<uint32_t>(c->L.sbucket);
+  a.bk.pool_keys = c->at<uint64_t>(c->L.pkeys);
+  a.bk.pool_idx = c->at<uint32_t>(c->L.pidx);
   int rc;
   if ((rc = timed(c, c->evolve_ev, c->evolve_used, true))) return rc;
   HIP_TRY(launch_evolve(a, static_cast<int>(c->R), same_table, c->n_cus, c->stream));
@@ -252,6 +268,7 @@ int run_generation(ones_ctx *c, uint32_t t) {
   if ((rc = timed(c, c->select_ev, c->select_used, false))) return rc;
   c->cur = next;
   c->table_changed = false;
+  c->profile_tick += 1;
   return ONES_OK;
 }
 
@@ -306,7 +323,7 @@ int ones_init(ones_ctx **out, const ones_config *cfg, const ones_jobs *jobs, voi
     if (e != hipSuccess) { delete c; return hip_fail(e, "hipGetDeviceProperties"); }
     c->n_cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
   }
-  c->profiling = false; c->evolve_used = c->select_used = 0;
+  c->profiling = false; c->profile_every = 1; c->profile_tick = 0; c->evolve_used = c->select_used = 0;
   if ((rc = upload_table(c, h, nullptr)) || (rc = run_generation(c, 0))) { ones_destroy(c); return rc; }
   hipError_t e = hipStreamSynchronize(c->stream);
   if (e != hipSuccess) { ones_destroy(c); return hip_fail(e, "hipStreamSynchronize"); }
@@ -375,7 +392,9 @@ int ones_export(ones_ctx *c, int32_t *genes, double *fit, int32_t *sel, int64_t 
 int ones_profile_enable(ones_ctx *c, int32_t on) {
   if (!c) return ONES_E_INVALID_ARG;
   HIP_TRY(hipStreamSynchronize(c->stream));
-  c->profiling = on != 0;
+  c->profiling = on > 0;
+  c->profile_every = on > 0 ? on : 1;
+  c->profile_tick = 0;
   c->evolve_used = c->select_used = 0;
   return ONES_OK;
 }

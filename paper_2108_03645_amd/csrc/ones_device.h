@@ -41,14 +41,24 @@ __host__ __device__ inline uint32_t info_active(uint32_t w) { return (w >> 21) &
 
 // Quantile buckets of the selection (valid while the job table stays the same): children and
 // mutants that beat the K-th survivor are dropped into the bucket of the survivors they fall
-// between.  nb == 0 switches the mechanism off.
-constexpr int kMaxBuckets = 256;
+// between.  nb == 0 switches the mechanism off.  A bucket stores up to seg offspring; the rare
+// surplus goes to one shared spill list, and a bucket too large for LDS is sorted in a slice of
+// a shared scratch pool.
+constexpr int kMaxBuckets = 1024;
+constexpr int kSpillCounter = kMaxBuckets;       // count[kSpillCounter]: records in the spill list
+constexpr int kPoolCounter = kMaxBuckets + 1;    // count[kPoolCounter]: scratch pool entries handed out
+constexpr int kBucketCounters = kMaxBuckets + 2;
 struct BucketArgs {
   const uint64_t *split;      // [kMaxBuckets] score bits of survivor ranks c*K/nb, c = 1..nb-1, then +inf
   const uint64_t *thresh;     // [1] score bits of the K-th survivor
-  uint32_t       *count;      // [nb] offspring per bucket, this generation
+  uint32_t       *count;      // [kBucketCounters] offspring per bucket (spilled ones included), this generation
   uint64_t       *keys;       // [nb][seg] score bits of the bucket's offspring
   uint32_t       *idx;        // [nb][seg] their pool slots
+  uint64_t       *spill_keys; // [3K] surplus offspring: score bits, slot, bucket
+  uint32_t       *spill_idx;
+  uint32_t       *spill_bucket;
+  uint64_t       *pool_keys;  // [pool] scratch for buckets that do not fit LDS
+  uint32_t       *pool_idx;
   uint64_t       *split_next; // splitters and threshold for the next generation (same arrays)
   uint64_t       *thresh_next;
   uint32_t        nb, seg;

@@ -190,33 +190,48 @@ __device__ __forceinline__ void gpus_from_batches(const Smem &s, int lane, uint3
 template <int R>
 __device__ __forceinline__ uint32_t accept_prefix(uint32_t (&v)[R], uint32_t limit, uint32_t lr, uint32_t ir,
                                                   int lane) {
-  uint32_t run = 0, pre = 0;
+  // first pass: lane totals, with the running sum noted after every eighth row
+  constexpr int kBlocks = (R + 7) / 8;
+  uint32_t run = 0, snap[kBlocks];
 #pragma unroll
   for (int i = 0; i < R; ++i) {
-    pre = (static_cast<uint32_t>(i) == ir) ? run : pre;   // sum of the lane's rows above ir
     run += v[i];
+    if (i % 8 == 7 || i == R - 1) snap[i / 8] = run;
   }
   const uint32_t incl = wave_inclusive_scan(run);
-  const uint32_t excl = incl - run;
   const uint32_t total = __builtin_amdgcn_readlane(incl, kLanes - 1);
   if (total <= limit) return total;                // everything fits: no second pass
+  const uint32_t excl = incl - run;
+  // pre = sum of the lane's rows above ir (only lane lr's value is used): the snapshot of the
+  // blocks before ir's block plus the rows of that block above ir.  ir is wave-uniform.
+  uint32_t pre = 0;
+#pragma unroll
+  for (int k = 0; k < kBlocks; ++k) {
+    if (ir / 8 == static_cast<uint32_t>(k)) {
+      if (k > 0) pre = snap[k - 1];
+#pragma unroll
+      for (int t = 0; t < 7; ++t)
+        if (8 * k + t < R && static_cast<uint32_t>(t) < ir % 8) pre += v[8 * k + t];
+    }
+  }
   const uint32_t base = __builtin_amdgcn_readlane(excl + pre, lr);   // asks visited after the wrap
   // A row's prefix is run_i + off; it fits iff run_i <= limit - off (0 when off exceeds the
   // limit: then only rows without an ask "fit", which changes nothing).
   const uint32_t off_hi = excl - base;             // rows at or after the start
   const uint32_t off_lo = excl + (total - base);   // rows before the start, visited after the wrap
-  const bool after = static_cast<uint32_t>(lane) > lr;
   const bool at = static_cast<uint32_t>(lane) == lr;
   // off_hi of lane lr is -pre (mod 2^32): add pre to the threshold instead
   const uint32_t thr_hi = at ? limit + pre : (off_hi <= limit ? limit - off_hi : 0u);
   const uint32_t thr_lo = off_lo <= limit ? limit - off_lo : 0u;
+  // first row of the lane that is visited before the wrap (a per-lane value on purpose, so
+  // that the row test below is one vector compare instead of a scalar mask per row)
+  const uint32_t first_hi = static_cast<uint32_t>(lane) > lr ? 0u : (at ? ir : static_cast<uint32_t>(R));
   uint32_t acc = 0;
   run = 0;
 #pragma unroll
   for (int i = 0; i < R; ++i) {
     run += v[i];
-    const bool hi = after | (at & (static_cast<uint32_t>(i) >= ir));
-    const uint32_t thr = hi ? thr_hi : thr_lo;
+    const uint32_t thr = static_cast<uint32_t>(i) >= first_hi ? thr_hi : thr_lo;
     v[i] = run <= thr ? v[i] : 0u;
     acc += v[i];
   }
@@ -297,14 +312,20 @@ __device__ __forceinline__ void drop_in_bucket(const EvolveArgs &a, const Smem &
   const uint64_t bits = (static_cast<uint64_t>(hi) << 32) | lo;
   if (bits >= s.split[kMaxBuckets]) return;
   uint32_t b = 0;
-#pragma unroll
-  for (int q = 0; q < kMaxBuckets / kLanes; ++q)
+  for (uint32_t q = 0; q * kLanes + 1 < a.bk.nb; ++q)      // splitters 0 .. nb-2, the rest is +inf
     b += static_cast<uint32_t>(__popcll(__ballot(s.split[q * kLanes + lane] <= bits)));
   if (lane == 0) {
     const uint32_t slot = atomicAdd(&a.bk.count[b], 1u);
-    const size_t at = static_cast<size_t>(b) * a.bk.seg + slot;
-    a.bk.keys[at] = bits;
-    a.bk.idx[at] = p;
+    if (slot < a.bk.seg) {
+      const size_t at = static_cast<size_t>(b) * a.bk.seg + slot;
+      a.bk.keys[at] = bits;
+      a.bk.idx[at] = p;
+    } else {                                               // bucket full: shared spill list
+      const uint32_t at = atomicAdd(&a.bk.count[kSpillCounter], 1u);
+      a.bk.spill_keys[at] = bits;
+      a.bk.spill_idx[at] = p;
+      a.bk.spill_bucket[at] = b;
+    }
   }
 }
 

@@ -104,93 +104,159 @@ __global__ __launch_bounds__(256) void rank_kernel(const uint64_t *keys, const u
 
 // Boundary rank of bucket c (c = 0..nb); bucket b owns survivor ranks [bound(b), bound(b+1)).
 __device__ __forceinline__ uint32_t bucket_bound(uint32_t c, uint32_t K, uint32_t nb) {
-  return static_cast<uint32_t>((static_cast<uint64_t>(c) * K) / nb);
+  return (c * K) / nb;          // c <= 1024, K <= 2^18: the product fits 32 bits
 }
 
 // Records the next generation's splitters when an element lands on a boundary rank.
 __device__ __forceinline__ void note_rank(uint32_t g, uint64_t bits, uint32_t K, uint32_t nb, uint64_t *split,
                                           uint64_t *thresh) {
   if (g == K - 1) *thresh = bits;
-  const uint32_t c = static_cast<uint32_t>((static_cast<uint64_t>(g) * nb) / K);
+  const uint32_t c = (g * nb) / K;                   // g < 2^20, nb <= 1024
   if (c >= 1 && bucket_bound(c, K, nb) == g) split[c - 1] = bits;
   if (c + 1 < nb && bucket_bound(c + 1, K, nb) == g) split[c] = bits;
 }
 
 constexpr int kBucketThreads = 256;
 constexpr int kBucketLds = 2048;      // offspring of one bucket that are sorted in LDS
+constexpr int kBucketCount = 64;      // up to here offspring are ranked by counting, not sorted
+constexpr int kBucketElites = 1025;   // survivors of one bucket: at most ceil(2^18 / 256) + 1
+
+__device__ __forceinline__ uint32_t wave_sum_u32(uint32_t v) {
+#pragma unroll
+  for (int s = 32; s >= 1; s >>= 1) v += __shfl_xor(v, s, kLanes);
+  return v;
+}
+
+// Ranks one bucket: offspring in (sk, si)[0..n) (padded with never-smaller keys up to npad, a
+// multiple of 8), survivors' score bits in ek[0..ne).  Writes the survivor list entries that
+// fall below K and notes the next generation's splitters.
+template <typename K64, typename I32>
+__device__ __forceinline__ void rank_bucket(K64 *sk, I32 *si, const uint64_t *ek, uint32_t n, uint32_t npad,
+                                            uint32_t ne, uint32_t e0, uint32_t off, bool sorted, uint32_t K,
+                                            const BucketArgs &bk, int32_t *sel) {
+  const uint32_t tid = threadIdx.x, nb = bk.nb;
+  // offspring i: rank = offspring before it + survivors with score <= its score (a survivor
+  // wins a tie: smaller slot)
+  for (uint32_t i = tid; i < n; i += kBucketThreads) {
+    const uint64_t key = sk[i];
+    const uint32_t id = si[i];
+    uint32_t below = i;
+    if (!sorted) {
+      below = 0;                                     // padding keys are never below a real one
+      for (uint32_t q = 0; q < npad; q += 8) {
+#pragma unroll
+        for (int u = 0; u < 8; ++u) below += key_less(sk[q + u], si[q + u], key, id) ? 1u : 0u;
+      }
+    }
+    uint32_t lo = 0, hi = ne;
+    while (lo < hi) {
+      const uint32_t mid = (lo + hi) >> 1;
+      if (ek[mid] <= key) lo = mid + 1; else hi = mid;
+    }
+    const uint32_t g = off + below + lo;
+    if (g < K) { sel[g] = static_cast<int32_t>(id); note_rank(g, key, K, nb, bk.split_next, bk.thresh_next); }
+  }
+  // survivor e: rank = e + offspring with a strictly smaller score
+  for (uint32_t e = tid; e < ne; e += kBucketThreads) {
+    const uint64_t key = ek[e];
+    uint32_t lo = 0;
+    if (!sorted) {
+      for (uint32_t q = 0; q < npad; q += 8) {
+#pragma unroll
+        for (int u = 0; u < 8; ++u) lo += sk[q + u] < key ? 1u : 0u;
+      }
+    } else {
+      uint32_t hi = n;
+      while (lo < hi) {
+        const uint32_t mid = (lo + hi) >> 1;
+        if (sk[mid] < key) lo = mid + 1; else hi = mid;
+      }
+    }
+    const uint32_t g = off + e + lo;
+    if (g < K) { sel[g] = static_cast<int32_t>(e0 + e); note_rank(g, key, K, nb, bk.split_next, bk.thresh_next); }
+  }
+}
+
+// Gathers the bucket's offspring (own storage, then its share of the spill list) into
+// (dk, di)[0..n) and pads up to npad.
+template <typename K64, typename I32>
+__device__ __forceinline__ void gather_bucket(K64 *dk, I32 *di, const BucketArgs &bk, uint32_t b, uint32_t n,
+                                              uint32_t npad, uint32_t *lds_counter) {
+  const uint32_t tid = threadIdx.x;
+  const uint32_t n_main = n < bk.seg ? n : bk.seg;
+  const uint64_t *gk = bk.keys + static_cast<size_t>(b) * bk.seg;
+  const uint32_t *gi = bk.idx + static_cast<size_t>(b) * bk.seg;
+  for (uint32_t e = tid; e < n_main; e += kBucketThreads) { dk[e] = gk[e]; di[e] = gi[e]; }
+  for (uint32_t e = n + tid; e < npad; e += kBucketThreads) { dk[e] = ~0ull; di[e] = 0xFFFFFFFFu; }
+  if (n > n_main) {
+    const uint32_t spilled = bk.count[kSpillCounter];
+    for (uint32_t q = tid; q < spilled; q += kBucketThreads) {
+      if (bk.spill_bucket[q] == b) {
+        const uint32_t at = n_main + atomicAdd(lds_counter, 1u);
+        dk[at] = bk.spill_keys[q];
+        di[at] = bk.spill_idx[q];
+      }
+    }
+  }
+  __threadfence_block();
+  __syncthreads();
+}
 
 __global__ __launch_bounds__(kBucketThreads) void bucket_select_kernel(const double *fit, BucketArgs bk, uint32_t K,
                                                                        uint32_t *count_next, int32_t *sel) {
   __shared__ uint64_t sk[kBucketLds];
   __shared__ uint32_t si[kBucketLds];
-  __shared__ uint32_t red[kBucketThreads];
+  __shared__ uint64_t ek[kBucketElites];
+  __shared__ uint32_t red[kBucketThreads / kLanes];
+  __shared__ uint32_t spill_cursor, pool_base;
   const uint32_t b = blockIdx.x, nb = bk.nb, tid = threadIdx.x;
   // offset of this bucket = its first survivor rank + all offspring of the buckets before it
   uint32_t before = 0;
   for (uint32_t c = tid; c < b; c += kBucketThreads) before += bk.count[c];
-  red[tid] = before;
-  __syncthreads();
-  for (uint32_t s = kBucketThreads / 2; s > 0; s >>= 1) {
-    if (tid < s) red[tid] += red[tid + s];
-    __syncthreads();
-  }
+  before = wave_sum_u32(before);
+  if ((tid & (kLanes - 1)) == 0) red[tid / kLanes] = before;
   const uint32_t e0 = bucket_bound(b, K, nb), e1 = bucket_bound(b + 1, K, nb), ne = e1 - e0;
-  const uint32_t off = e0 + red[0];
   const uint32_t n = bk.count[b];
-  uint64_t *gk = bk.keys + static_cast<size_t>(b) * bk.seg;
-  uint32_t *gi = bk.idx + static_cast<size_t>(b) * bk.seg;
   const uint32_t n2 = pow2_at_least(n);
-  const bool in_lds = n2 <= static_cast<uint32_t>(kBucketLds);
+  const uint32_t npad = n2 < 8 ? 8 : n2;             // counting loops run in steps of 8 over padding
+  const bool in_lds = npad <= static_cast<uint32_t>(kBucketLds);
+  for (uint32_t e = tid; e < ne; e += kBucketThreads)
+    ek[e] = static_cast<uint64_t>(__double_as_longlong(fit[e0 + e]));
+  if (tid == 0) {
+    spill_cursor = 0;
+    pool_base = in_lds ? 0u : atomicAdd(&bk.count[kPoolCounter], npad);   // a slice of the scratch pool
+  }
+  __syncthreads();
+  uint32_t off = e0;
+#pragma unroll
+  for (int w = 0; w < kBucketThreads / kLanes; ++w) off += red[w];
   if (off < K) {                                     // otherwise nothing of this bucket survives
     if (in_lds) {
-      for (uint32_t e = tid; e < n2; e += kBucketThreads) {
-        sk[e] = e < n ? gk[e] : ~0ull;
-        si[e] = e < n ? gi[e] : 0xFFFFFFFFu;
-      }
-      __syncthreads();
-      bitonic_sort(sk, si, n2);
+      gather_bucket(sk, si, bk, b, n, npad, &spill_cursor);
+      const bool sorted = n > static_cast<uint32_t>(kBucketCount);
+      if (sorted) bitonic_sort(sk, si, npad);
+      rank_bucket(sk, si, ek, n, npad, ne, e0, off, sorted, K, bk, sel);
     } else {                                         // oversized bucket: same network in global memory
-      for (uint32_t e = n + tid; e < n2; e += kBucketThreads) { gk[e] = ~0ull; gi[e] = 0xFFFFFFFFu; }
-      __threadfence_block();
-      __syncthreads();
-      bitonic_sort(gk, gi, n2);
-    }
-    // offspring i: rank = i + survivors with score <= its score (a survivor wins a tie: smaller slot)
-    for (uint32_t i = tid; i < n; i += kBucketThreads) {
-      const uint64_t key = in_lds ? sk[i] : gk[i];
-      const uint32_t id = in_lds ? si[i] : gi[i];
-      uint32_t lo = 0, hi = ne;
-      while (lo < hi) {
-        const uint32_t mid = (lo + hi) >> 1;
-        if (static_cast<uint64_t>(__double_as_longlong(fit[e0 + mid])) <= key) lo = mid + 1; else hi = mid;
-      }
-      const uint32_t g = off + i + lo;
-      if (g < K) { sel[g] = static_cast<int32_t>(id); note_rank(g, key, K, nb, bk.split_next, bk.thresh_next); }
-    }
-    // survivor e: rank = e + offspring with a strictly smaller score
-    for (uint32_t e = tid; e < ne; e += kBucketThreads) {
-      const uint64_t key = static_cast<uint64_t>(__double_as_longlong(fit[e0 + e]));
-      uint32_t lo = 0, hi = n;
-      while (lo < hi) {
-        const uint32_t mid = (lo + hi) >> 1;
-        if ((in_lds ? sk[mid] : gk[mid]) < key) lo = mid + 1; else hi = mid;
-      }
-      const uint32_t g = off + e + lo;
-      if (g < K) { sel[g] = static_cast<int32_t>(e0 + e); note_rank(g, key, K, nb, bk.split_next, bk.thresh_next); }
+      uint64_t *pk = bk.pool_keys + pool_base;
+      uint32_t *pi = bk.pool_idx + pool_base;
+      gather_bucket(pk, pi, bk, b, n, npad, &spill_cursor);
+      bitonic_sort(pk, pi, npad);
+      rank_bucket(pk, pi, ek, n, npad, ne, e0, off, true, K, bk, sel);
     }
   }
-  if (tid == 0) count_next[b] = 0;                   // the other counter set, for the next generation
+  // the other counter set, for the next generation
+  if (tid == 0) count_next[b] = 0;
+  if (b == 0 && tid < 2) count_next[kMaxBuckets + tid] = 0;
 }
 
 // Splitters after a selection by the general path.
 __global__ void splitters_kernel(const double *fit, const int32_t *sel, uint32_t K, uint32_t nb, uint64_t *split,
                                  uint64_t *thresh, uint32_t *count0, uint32_t *count1) {
   const uint32_t c = blockIdx.x * blockDim.x + threadIdx.x;
-  if (c < 256) {
-    count0[c] = 0; count1[c] = 0;
+  if (c < static_cast<uint32_t>(kBucketCounters)) { count0[c] = 0; count1[c] = 0; }
+  if (c < static_cast<uint32_t>(kMaxBuckets))
     split[c] = (c + 1 < nb) ? static_cast<uint64_t>(__double_as_longlong(fit[sel[bucket_bound(c + 1, K, nb)]]))
                             : 0x7FF0000000000000ull;          // +infinity pads the table
-  }
   if (c == 0) *thresh = static_cast<uint64_t>(__double_as_longlong(fit[sel[K - 1]]));
 }
 
@@ -304,7 +370,8 @@ hipError_t launch_bucket_select(const double *fit, const BucketArgs &bk, uint32_
 
 hipError_t launch_splitters(const double *fit, const int32_t *sel, uint32_t K, uint32_t nb, uint64_t *split,
                             uint64_t *thresh, uint32_t *count0, uint32_t *count1, hipStream_t s) {
-  hipLaunchKernelGGL(splitters_kernel, dim3(1), dim3(256), 0, s, fit, sel, K, nb, split, thresh, count0, count1);
+  hipLaunchKernelGGL(splitters_kernel, dim3((kBucketCounters + 255) / 256), dim3(256), 0, s, fit, sel, K, nb, split,
+                     thresh, count0, count1);
   return hipGetLastError();
 }
 

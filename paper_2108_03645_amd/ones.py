@@ -157,8 +157,9 @@ class Search:
                                       sel.ctypes.data, C.byref(t)))
         return g, fit, sel, t.value
 
-    def profile_enable(self, on: bool = True):
-        _check(load().ones_profile_enable(self._h, 1 if on else 0))
+    def profile_enable(self, every: int = 1):
+        """Bracket the kernels of every ``every``-th generation with HIP events (0 = off)."""
+        _check(load().ones_profile_enable(self._h, int(every)))
 
     def profile_read(self):
         em, sm = C.c_double(0.0), C.c_double(0.0)

@@ -103,10 +103,39 @@ def test_stress_reduced_population(ones, ref):
     run_pair(ones, ref, cl, jobs, 4, 2, "stress/P=1024")
 
 
-def test_selection_across_sort_chunks(ones, ref):
-    """Pool larger than one LDS sort chunk, with massive score ties (few distinct genomes)."""
-    jobs = make_jobs(6, bmin=256, bmax=512)
-    run_pair(ones, ref, cluster(5, 6, 4096 * 3 + 8, seed=12), jobs, 3, 1, "ties/P=12296")
+@pytest.mark.parametrize("pop,n_jobs,n_gpus", [(4096 * 3 + 8, 6, 5), (4100, 6, 5), (5000, 9, 7), (8192, 12, 9),
+                                               (20000, 5, 4)])
+def test_selection_with_massive_ties(ones, ref, pop, n_jobs, n_gpus):
+    """Pools larger than one LDS sort chunk with few distinct genomes, hence few distinct scores:
+    single buckets overflow into the spill list and the scratch pool."""
+    rng = np.random.default_rng(pop)
+    jobs = make_jobs(n_jobs, bmin=256, bmax=512, remaining=rng.uniform(1e5, 1e7, n_jobs))
+    run_pair(ones, ref, cluster(n_gpus, n_jobs, pop, seed=12), jobs, 4, 1, f"ties/P={pop}")
+
+
+@pytest.mark.parametrize("pop", [4100, 8192, 20000, 40004])
+def test_bucketed_selection_and_table_changes(ones, ref, pop):
+    """Pools above one sort chunk select through survivor-quantile buckets while the job table
+    stays the same and through the general sort right after it changed; alternate the two."""
+    rng = np.random.default_rng(pop)
+    jobs = random_jobs(rng, 130)
+    cl = cluster(180, 130, pop, seed=pop)
+    say(f"[parity] buckets: P={pop}")
+    gpu = ones.Search(cl, jobs); cpu = ref.RefSearch(cl, jobs)
+    ref.set_threads(8)
+    try:
+        for step in range(4):
+            gpu.generation(2); cpu.generation(2)
+            assert_same_state(gpu, cpu, f"buckets P={pop} step {step}")
+            jobs.remaining = jobs.remaining * rng.uniform(0.5, 1.0, 130)     # progress: new table
+            if step == 1:
+                jobs.job_id[7] += 1000; jobs.active[9] ^= 1
+            gpu.set_jobs(jobs); cpu.set_jobs(jobs)
+            gpu.generation(1); cpu.generation(1)
+            assert_same_state(gpu, cpu, f"buckets P={pop} step {step} after set_jobs")
+    finally:
+        ref.set_threads(1)
+    gpu.close(); cpu.close()
 
 
 @pytest.mark.parametrize("theta,chi", [(0.0, 0.0), (1.0, 1.0), (0.0, 1.0), (1.0, 0.5)])
@@ -235,11 +264,14 @@ def test_full_size_large_matches_oracle(ones, ref):
 def test_profile_hook_counts_launches(ones):
     cl, jobs = W.paper_scale()
     s = ones.Search(cl, jobs)
-    s.profile_enable(True)
+    s.profile_enable(1)
     s.generation(7)
     prof = s.profile_read()
     assert prof["evolve_launches"] == 7 and prof["select_launches"] == 7
     assert prof["evolve_ms"] > 0 and prof["select_ms"] > 0
-    s.profile_enable(False)
+    s.profile_enable(3)                       # generations 0, 3, 6 of the next 8
+    s.generation(8)
+    assert s.profile_read()["evolve_launches"] == 3
+    s.profile_enable(0)
     s.generation(1)
     assert s.profile_read()["evolve_launches"] == 0
