@@ -38,9 +38,10 @@ struct Layout {
 // spill list that could hold all of them, and buckets too large for LDS are sorted in a scratch
 // pool of twice that size (each takes a power-of-two slice).
 struct BucketPlan { uint32_t nb, seg, spill, pool; };
+constexpr uint32_t kMinBucketPool = 256;
 uint32_t pow2_at_least(uint32_t v) { uint32_t n = 1; while (n < v) n <<= 1; return n; }
 BucketPlan bucket_plan(uint32_t P) {
-  if (P <= static_cast<uint32_t>(kSortChunk)) return BucketPlan{0, 0, 0, 0};
+  if (P < kMinBucketPool) return BucketPlan{0, 0, 0, 0};      // tiny pools: one short sort is as fast
   const uint32_t K = P / 4;
   BucketPlan bp;
   bp.nb = std::min<uint32_t>(kMaxBuckets, std::max<uint32_t>(1, K / 16));
