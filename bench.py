@@ -24,7 +24,8 @@ HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published peak
 
 # HBM bytes per evolve launch on the stress workload from rocprofv3 --pmc FETCH_SIZE and
 # WRITE_SIZE (see profiles/), valid only for the kernel source with this hash.
-MEASURED_TRAFFIC = {"source_sha256": None, "bytes_per_launch": None}
+MEASURED_TRAFFIC = {"source_sha256": "0c65d0c95c087d05a5430f2b502a3628eb36446ac609956603920f3086299d3d",
+                    "bytes_per_launch": 1078776625}
 
 
 def evolve_source_hash() -> str:
