@@ -339,7 +339,8 @@ __device__ __forceinline__ double finish(const EvolveArgs &a, const Smem &s, uin
   int32_t *row = a.genes_new + static_cast<size_t>(p) * a.Jp;
 #pragma unroll
   for (int i = 0; i < R; ++i)
-    row[lane + kLanes * i] = static_cast<int32_t>(c[i] << info_blexp(s.info[lane + kLanes * i]));
+    __builtin_nontemporal_store(static_cast<int32_t>(c[i] << info_blexp(s.info[lane + kLanes * i])),
+                                &row[lane + kLanes * i]);
   if (lane == 0) a.fit[p] = f;
   return f;
 }
@@ -471,7 +472,7 @@ __global__ __launch_bounds__(Shape<R>::kWaves *kLanes) void evolve_kernel(Evolve
       if (kSameTable) {
         int32_t *row = a.genes_new + static_cast<size_t>(p) * a.Jp;
 #pragma unroll
-        for (int i = 0; i < R; ++i) row[lane + kLanes * i] = static_cast<int32_t>(c[i]);
+        for (int i = 0; i < R; ++i) __builtin_nontemporal_store(static_cast<int32_t>(c[i]), &row[lane + kLanes * i]);
         if (lane == 0) a.fit[p] = a.fit_old[src];
       } else {
         const Draw d = candidate_draw(a, p);
