@@ -29,7 +29,7 @@ int hip_fail(hipError_t e, const char *what) {
 size_t align_up(size_t v) { return (v + 255) & ~static_cast<size_t>(255); }
 
 struct Layout {
-  size_t genes[2], fit[2], sel, keys, idx, split, thresh, bcount[2], bkeys, bidx, skeys, sidx, sbucket, pkeys, pidx, cstart, cmax, info, abl, cc, d, Y, terms;
+  size_t genes, fit_row, row_of[2], parent_row[2], spare_row, occupied[2], sel, keys, idx, split, thresh, bcount[2], bkeys, bidx, skeys, sidx, sbucket, pkeys, pidx, cstart, cmax, info, abl, cc, d, Y, terms;
   size_t rawinfo, changed, ra, rc, rd, rY, best_batch, best_gpus, best_fit, total;
 };
 
@@ -56,10 +56,16 @@ Layout make_layout(uint32_t P, uint32_t Jp) {
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t at = off; off = align_up(off + bytes); return at; };
   const size_t chunks = (P + kSortChunk - 1) / kSortChunk;
-  L.genes[0] = take(static_cast<size_t>(P) * Jp * 4);
-  L.genes[1] = take(static_cast<size_t>(P) * Jp * 4);
-  L.fit[0] = take(static_cast<size_t>(P) * 8);
-  L.fit[1] = take(static_cast<size_t>(P) * 8);
+  const size_t rows = static_cast<size_t>(P) + P / 4;      // a pool of P slots lives in P + K physical rows
+  L.genes = take(rows * Jp * 4);
+  L.fit_row = take(rows * 8);
+  L.row_of[0] = take(static_cast<size_t>(P) * 4);
+  L.row_of[1] = take(static_cast<size_t>(P) * 4);
+  L.parent_row[0] = take(static_cast<size_t>(P / 4) * 4);
+  L.parent_row[1] = take(static_cast<size_t>(P / 4) * 4);
+  L.spare_row = take(static_cast<size_t>(P / 4) * 4);
+  L.occupied[0] = take((rows + 31) / 32 * 4);     // bitmaps of the rows the survivors keep
+  L.occupied[1] = take((rows + 31) / 32 * 4);
   L.sel = take(static_cast<size_t>(P / 4) * 4);
   L.keys = take(chunks * kSortChunk * 8);
   L.idx = take(chunks * kSortChunk * 4);
@@ -158,7 +164,7 @@ struct ones_ctx {
   hipStream_t stream;
   char *ws;
   Layout L;
-  int cur;                    // genome / score buffer holding the current generation
+  int cur;                    // which row_of array describes the current generation
   bool table_changed;         // job table replaced since the current generation was computed
   BucketPlan bp;              // nb == 0: pool small enough for the single-chunk sort
   int bucket_phase;           // which counter set the next bucketed generation fills
@@ -197,7 +203,8 @@ int upload_table(ones_ctx *c, const HostJobs &h, const std::vector<uint32_t> *ch
   HIP_TRY(launch_build_terms(c->table(), c->Jp, c->stream));
   if (changed) {
     HIP_TRY(hipMemcpyAsync(c->ws + c->L.changed, changed->data(), n4, hipMemcpyHostToDevice, c->stream));
-    HIP_TRY(launch_reset_slots(c->at<int32_t>(c->L.genes[c->cur]), c->at<uint32_t>(c->L.changed), c->P, c->Jp,
+    // every physical row, whether a candidate lives in it or not
+    HIP_TRY(launch_reset_slots(c->at<int32_t>(c->L.genes), c->at<uint32_t>(c->L.changed), c->P + c->K, c->Jp,
                                c->stream));
   }
   HIP_TRY(hipStreamSynchronize(c->stream));     // the staging vectors may go away now
@@ -223,12 +230,13 @@ int timed(ones_ctx *c, std::vector<EventPair> &pool, size_t &used, bool begin) {
 
 int run_generation(ones_ctx *c, uint32_t t) {
   EvolveArgs a;
-  a.genes_old = c->at<int32_t>(c->L.genes[c->cur]);
+  // generation 0 fills row_of[cur]; later generations fill the array the last compaction prepared
   const int next = t == 0 ? c->cur : c->cur ^ 1;
-  a.genes_new = c->at<int32_t>(c->L.genes[next]);
-  a.sel = c->at<int32_t>(c->L.sel);
-  a.fit = c->at<double>(c->L.fit[next]);
-  a.fit_old = c->at<double>(c->L.fit[c->cur]);
+  a.genes = c->at<int32_t>(c->L.genes);
+  a.fit_row = c->at<double>(c->L.fit_row);
+  a.parent_row = c->at<uint32_t>(c->L.parent_row[next]);
+  a.row_of = c->at<uint32_t>(c->L.row_of[next]);
+  a.spare_row = c->at<uint32_t>(c->L.spare_row);
   a.tab = c->table();
   a.G = c->G; a.P = c->P; a.K = c->K; a.Jp = c->Jp;
   a.key0 = static_cast<uint32_t>(c->cfg.seed);
@@ -249,23 +257,34 @@ int run_generation(ones_ctx *c, uint32_t t) {
   a.bk.spill_bucket = c->at<uint32_t>(c->L.sbucket);
   a.bk.pool_keys = c->at<uint64_t>(c->L.pkeys);
   a.bk.pool_idx = c->at<uint32_t>(c->L.pidx);
+  // the selection notes the rows the survivors keep: parents and first K slots of the next pool
+  RowPlan rp;
+  rp.row_of_cur = a.row_of;
+  rp.parent_next = c->at<uint32_t>(c->L.parent_row[next ^ 1]);
+  rp.row_of_next = c->at<uint32_t>(c->L.row_of[next ^ 1]);
+  rp.occupied = c->at<uint32_t>(c->L.occupied[next]);
   int rc;
   if ((rc = timed(c, c->evolve_ev, c->evolve_used, true))) return rc;
   HIP_TRY(launch_evolve(a, static_cast<int>(c->R), same_table, c->n_cus, c->stream));
   if ((rc = timed(c, c->evolve_ev, c->evolve_used, false))) return rc;
   if ((rc = timed(c, c->select_ev, c->select_used, true))) return rc;
   if (buckets) {
-    HIP_TRY(launch_bucket_select(a.fit, a.bk, c->K, c->at<uint32_t>(c->L.bcount[c->bucket_phase ^ 1]),
-                                 c->at<int32_t>(c->L.sel), c->stream));
+    HIP_TRY(launch_bucket_select(a.fit_row, a.parent_row, a.bk, rp, c->K,
+                                 c->at<uint32_t>(c->L.bcount[c->bucket_phase ^ 1]), c->at<int32_t>(c->L.sel),
+                                 c->stream));
     c->bucket_phase ^= 1;
   } else {
-    HIP_TRY(launch_select(a.fit, c->P, c->K, c->at<uint64_t>(c->L.keys), c->at<uint32_t>(c->L.idx),
+    HIP_TRY(launch_select(a.fit_row, rp, c->P, c->K, c->at<uint64_t>(c->L.keys), c->at<uint32_t>(c->L.idx),
                           c->at<int32_t>(c->L.sel), c->stream));
     if (c->bp.nb != 0)   // splitters for the bucketed generations that follow; clears both counter sets
-      HIP_TRY(launch_splitters(a.fit, c->at<int32_t>(c->L.sel), c->K, c->bp.nb, c->at<uint64_t>(c->L.split),
+      HIP_TRY(launch_splitters(a.fit_row, a.row_of, c->at<int32_t>(c->L.sel), c->K, c->bp.nb,
+                               c->at<uint64_t>(c->L.split),
                                c->at<uint64_t>(c->L.thresh), c->at<uint32_t>(c->L.bcount[0]),
                                c->at<uint32_t>(c->L.bcount[1]), c->stream));
   }
+  // survivors keep their rows; hand the free rows to the slots of the next pool
+  HIP_TRY(launch_free_rows(rp.occupied, c->at<uint32_t>(c->L.occupied[next ^ 1]), c->P, c->K, rp.row_of_next,
+                           c->at<uint32_t>(c->L.spare_row), c->stream));
   if ((rc = timed(c, c->select_ev, c->select_used, false))) return rc;
   c->cur = next;
   c->table_changed = false;
@@ -325,6 +344,12 @@ int ones_init(ones_ctx **out, const ones_config *cfg, const ones_jobs *jobs, voi
     c->n_cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
   }
   c->profiling = false; c->profile_every = 1; c->profile_tick = 0; c->evolve_used = c->select_used = 0;
+  {
+    const uint32_t words = (c->P + c->K + 31) / 32;
+    hipError_t e = launch_zero_words(c->at<uint32_t>(c->L.occupied[0]), words, c->stream);
+    if (e == hipSuccess) e = launch_zero_words(c->at<uint32_t>(c->L.occupied[1]), words, c->stream);
+    if (e != hipSuccess) { delete c; return hip_fail(e, "launch_zero_words"); }
+  }
   if ((rc = upload_table(c, h, nullptr)) || (rc = run_generation(c, 0))) { ones_destroy(c); return rc; }
   hipError_t e = hipStreamSynchronize(c->stream);
   if (e != hipSuccess) { ones_destroy(c); return hip_fail(e, "hipStreamSynchronize"); }
@@ -360,7 +385,8 @@ int ones_generation(ones_ctx *c, int32_t n_generations) {
 
 int ones_best(ones_ctx *c, int32_t *batch_out, int32_t *gpus_out, double *fitness_out) {
   if (!c) return ONES_E_INVALID_ARG;
-  HIP_TRY(launch_best(c->at<int32_t>(c->L.genes[c->cur]), c->at<double>(c->L.fit[c->cur]), c->at<int32_t>(c->L.sel),
+  HIP_TRY(launch_best(c->at<int32_t>(c->L.genes), c->at<double>(c->L.fit_row), c->at<uint32_t>(c->L.row_of[c->cur]),
+                      c->at<int32_t>(c->L.sel),
                       c->at<uint32_t>(c->L.info), c->Jn, c->Jp, c->at<int32_t>(c->L.best_batch),
                       c->at<int32_t>(c->L.best_gpus), c->at<double>(c->L.best_fit), c->stream));
   std::vector<int32_t> b(c->Jn), g(c->Jn);
@@ -379,13 +405,26 @@ int ones_best(ones_ctx *c, int32_t *batch_out, int32_t *gpus_out, double *fitnes
 
 int ones_export(ones_ctx *c, int32_t *genes, double *fit, int32_t *sel, int64_t *generation) {
   if (!c) return ONES_E_INVALID_ARG;
-  // outputs must stay untouched on error: stage, then copy
   HIP_TRY(hipStreamSynchronize(c->stream));
-  if (genes)
-    HIP_TRY(hipMemcpy(genes, c->ws + c->L.genes[c->cur], static_cast<size_t>(c->P) * c->Jp * 4,
-                      hipMemcpyDeviceToHost));
-  if (fit) HIP_TRY(hipMemcpy(fit, c->ws + c->L.fit[c->cur], static_cast<size_t>(c->P) * 8, hipMemcpyDeviceToHost));
+  // candidates live in physical rows: fetch the rows and put them in slot order on the host
+  const size_t rows = static_cast<size_t>(c->P) + c->K, Jp = c->Jp;
+  std::vector<uint32_t> row_of(c->P);
+  std::vector<int32_t> g;
+  std::vector<double> f;
+  HIP_TRY(hipMemcpy(row_of.data(), c->ws + c->L.row_of[c->cur], static_cast<size_t>(c->P) * 4, hipMemcpyDeviceToHost));
+  if (genes) {
+    g.resize(rows * Jp);
+    HIP_TRY(hipMemcpy(g.data(), c->ws + c->L.genes, rows * Jp * 4, hipMemcpyDeviceToHost));
+  }
+  if (fit) {
+    f.resize(rows);
+    HIP_TRY(hipMemcpy(f.data(), c->ws + c->L.fit_row, rows * 8, hipMemcpyDeviceToHost));
+  }
   if (sel) HIP_TRY(hipMemcpy(sel, c->ws + c->L.sel, static_cast<size_t>(c->K) * 4, hipMemcpyDeviceToHost));
+  for (uint32_t p = 0; p < c->P; ++p) {
+    if (genes) memcpy(genes + static_cast<size_t>(p) * Jp, g.data() + static_cast<size_t>(row_of[p]) * Jp, Jp * 4);
+    if (fit) fit[p] = f[row_of[p]];
+  }
   if (generation) *generation = c->t;
   return ONES_OK;
 }

@@ -64,12 +64,18 @@ struct BucketArgs {
   uint32_t        nb, seg;
 };
 
+// Genomes live in physical rows; a candidate keeps its row for as long as it survives, so a
+// survivor is never copied.  The pool of P slots uses P + K rows: while the job table stays
+// the same, the 3K children and mutants of a generation take rows freed by the candidates
+// that dropped out; after a table change the K refreshed survivors take the K spare rows.
 struct EvolveArgs {
-  const int32_t *genes_old;   // [P][Jp] previous generation (unused by the initial population)
-  int32_t       *genes_new;   // [P][Jp]
-  const int32_t *sel;         // [K] survivors of the previous generation, best first
-  double        *fit;         // [P] scores of the new generation
-  const double  *fit_old;     // [P] scores of the previous generation
+  int32_t        *genes;      // [P + K][Jp] genome rows (global batch sizes)
+  double         *fit_row;    // [P + K] score of the genome in each row
+  const uint32_t *parent_row; // [K] rows of the survivors, best first
+  uint32_t       *row_of;     // [P] row of every slot of the new pool, prefilled: survivors keep
+                              //     theirs, slot K + q takes the q-th free row; a refreshed
+                              //     survivor records its spare row here
+  const uint32_t *spare_row;  // [K] rows for refreshed survivors
   JobTable       tab;
   uint32_t       G, P, K, Jp;
   uint32_t       key0, key1;  // seed
@@ -77,6 +83,14 @@ struct EvolveArgs {
   uint32_t       T_mut, T_x;  // rate thresholds on a 32-bit word
   uint32_t       term_lds;    // set by the launcher: entries per job of the term table in LDS, 0 = none
   BucketArgs     bk;
+};
+
+// What a selection records besides the survivor list: the survivors keep their rows.
+struct RowPlan {
+  const uint32_t *row_of_cur;   // [P] row of every slot of the pool being ranked
+  uint32_t       *parent_next;  // [K] rows of the new survivors, best first
+  uint32_t       *row_of_next;  // [P] rows of the next pool; entries [0,K) are written here
+  uint32_t       *occupied;     // bitmap over the P + K rows, zero on entry; survivors' rows get set
 };
 
 struct RawJobs {              // uploaded by the host after validation, [Jp] each
@@ -102,13 +116,20 @@ inline hipError_t launch_evolve(const EvolveArgs &a, int rows, bool same_table, 
     default: return hipErrorInvalidValue;
   }
 }
-hipError_t launch_select(const double *fit, uint32_t P, uint32_t K, uint64_t *keys, uint32_t *idx,
-                         int32_t *sel, hipStream_t s);
-hipError_t launch_bucket_select(const double *fit, const BucketArgs &bk, uint32_t K, uint32_t *count_next,
-                                int32_t *sel, hipStream_t s);
-hipError_t launch_splitters(const double *fit, const int32_t *sel, uint32_t K, uint32_t nb, uint64_t *split,
-                            uint64_t *thresh, uint32_t *count0, uint32_t *count1, hipStream_t s);
-hipError_t launch_best(const int32_t *genes, const double *fit, const int32_t *sel, const uint32_t *info,
+hipError_t launch_select(const double *fit_row, const RowPlan &rp, uint32_t P, uint32_t K, uint64_t *keys,
+                         uint32_t *idx, int32_t *sel, hipStream_t s);
+// After a selection: hands the unoccupied rows, in ascending order, to slots K..P-1 of the next
+// pool and (the last K) to the spare list; clears the other bitmap for the next selection.
+hipError_t launch_free_rows(const uint32_t *occupied, uint32_t *occupied_other, uint32_t P, uint32_t K,
+                            uint32_t *row_of_next, uint32_t *spare_row, hipStream_t s);
+hipError_t launch_zero_words(uint32_t *words, uint32_t n, hipStream_t s);
+hipError_t launch_bucket_select(const double *fit_row, const uint32_t *parent_row, const BucketArgs &bk,
+                                const RowPlan &rp, uint32_t K, uint32_t *count_next, int32_t *sel, hipStream_t s);
+hipError_t launch_splitters(const double *fit_row, const uint32_t *row_of, const int32_t *sel, uint32_t K,
+                            uint32_t nb, uint64_t *split, uint64_t *thresh, uint32_t *count0, uint32_t *count1,
+                            hipStream_t s);
+hipError_t launch_best(const int32_t *genes, const double *fit_row, const uint32_t *row_of, const int32_t *sel,
+                       const uint32_t *info,
                        uint32_t Jn, uint32_t Jp, int32_t *batch_out, int32_t *gpus_out, double *fit_out,
                        hipStream_t s);
 

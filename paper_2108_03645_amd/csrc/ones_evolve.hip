@@ -330,18 +330,18 @@ __device__ __forceinline__ void drop_in_bucket(const EvolveArgs &a, const Smem &
 }
 
 template <int R>
-__device__ __forceinline__ double finish(const EvolveArgs &a, const Smem &s, uint32_t p, uint32_t r,
+__device__ __forceinline__ double finish(const EvolveArgs &a, const Smem &s, uint32_t dst_row, uint32_t r,
                                          uint32_t (&c)[R], int lane) {
   repair<R>(c, s, a.G, r, lane);
   phase_fence();
   const double f = score<R>(c, s, a.term_lds, lane);
   phase_fence();
-  int32_t *row = a.genes_new + static_cast<size_t>(p) * a.Jp;
+  int32_t *row = a.genes + static_cast<size_t>(dst_row) * a.Jp;
 #pragma unroll
   for (int i = 0; i < R; ++i)
     __builtin_nontemporal_store(static_cast<int32_t>(c[i] << info_blexp(s.info[lane + kLanes * i])),
                                 &row[lane + kLanes * i]);
-  if (lane == 0) a.fit[p] = f;
+  if (lane == 0) a.fit_row[dst_row] = f;
   return f;
 }
 
@@ -383,14 +383,15 @@ __global__ __launch_bounds__(Shape<R>::kWaves *kLanes) void init_kernel(EvolveAr
       c[i] = batch_from_draw(bounded(c[i], info_n(w)), w);
     }
     gpus_from_batches<R, false>(s, lane, c);
-    finish<R>(a, s, p, dr.r, c, lane);
+    finish<R>(a, s, p, dr.r, c, lane);                 // slot p starts in row p
+    if (lane == 0) a.row_of[p] = p;
   }
 }
 
-// One generation.  Work items: K crossover pairs, K mutants, K refreshed survivors.
-// kSameTable: the job table has not changed since the previous generation was repaired and
-// scored, so a survivor is a fixed point of the repair (copy genome and score) and stored
-// genes need no clamp.
+// One generation.  Work items: K crossover pairs, K mutants and, after a table change, the K
+// survivors to refresh.  kSameTable: the job table has not changed since the previous
+// generation was repaired and scored, so a survivor is a fixed point of the repair with the
+// same score: it stays in its row untouched, and stored genes need no clamp.
 template <int R, bool kSameTable>
 __global__ __launch_bounds__(Shape<R>::kWaves *kLanes) void evolve_kernel(EvolveArgs a) {
   extern __shared__ __align__(16) unsigned char smem_raw[];
@@ -402,7 +403,8 @@ __global__ __launch_bounds__(Shape<R>::kWaves *kLanes) void evolve_kernel(Evolve
   const uint32_t stride = gridDim.x * Shape<R>::kWaves;
   const uint32_t K = a.K;
   uint8_t *stash = s.stash + static_cast<size_t>(wave_in_block) * a.Jp;
-  for (uint32_t item = wave; item < 3 * K; item += stride) {
+  const uint32_t items = kSameTable ? 2 * K : 3 * K;
+  for (uint32_t item = wave; item < items; item += stride) {
     const int lane = opaque(lane0);
     uint32_t c[R];
     if (item < K) {
@@ -420,8 +422,8 @@ __global__ __launch_bounds__(Shape<R>::kWaves *kLanes) void evolve_kernel(Evolve
       phase_fence();
       {
         uint32_t B[R];
-        load_genes<R>(a.genes_old + static_cast<size_t>(a.sel[d0.ra]) * a.Jp, lane, c);
-        load_genes<R>(a.genes_old + static_cast<size_t>(a.sel[d0.rb]) * a.Jp, lane, B);
+        load_genes<R>(a.genes + static_cast<size_t>(a.parent_row[d0.ra]) * a.Jp, lane, c);
+        load_genes<R>(a.genes + static_cast<size_t>(a.parent_row[d0.rb]) * a.Jp, lane, B);
         gpus_from_batches<R, kSameTable>(s, lane, c);
         gpus_from_batches<R, kSameTable>(s, lane, B);
         // second child goes to LDS as a 5-bit code (0 = waiting, k = 2^(k-1) GPUs)
@@ -434,12 +436,12 @@ __global__ __launch_bounds__(Shape<R>::kWaves *kLanes) void evolve_kernel(Evolve
         }
       }
       phase_fence();
-      const double f0 = finish<R>(a, s, p0, d0.r, c, lane);
+      const double f0 = finish<R>(a, s, a.row_of[p0], d0.r, c, lane);
       if (kSameTable && a.bk.nb != 0) drop_in_bucket(a, s, p0, f0, lane);
       phase_fence();
 #pragma unroll
       for (int i = 0; i < R; ++i) c[i] = (1u << stash[lane + kLanes * i]) >> 1;
-      const double f1 = finish<R>(a, s, p0 + 1, d1.r, c, lane);
+      const double f1 = finish<R>(a, s, a.row_of[p0 + 1], d1.r, c, lane);
       if (kSameTable && a.bk.nb != 0) drop_in_bucket(a, s, p0 + 1, f1, lane);
     } else if (item < 2 * K) {
       // uniform mutation: each job redrawn with rate theta (k = 0 pre-empts it)
@@ -449,7 +451,7 @@ __global__ __launch_bounds__(Shape<R>::kWaves *kLanes) void evolve_kernel(Evolve
         uint32_t w[R];
         gene_words<R>(a, p, lane, w);
         phase_fence();
-        load_genes<R>(a.genes_old + static_cast<size_t>(a.sel[d.ra]) * a.Jp, lane, c);
+        load_genes<R>(a.genes + static_cast<size_t>(a.parent_row[d.ra]) * a.Jp, lane, c);
 #pragma unroll
         for (int i = 0; i < R; ++i) {
           const uint32_t word = s.info[lane + kLanes * i];
@@ -462,23 +464,18 @@ __global__ __launch_bounds__(Shape<R>::kWaves *kLanes) void evolve_kernel(Evolve
       }
       phase_fence();
       gpus_from_batches<R, false>(s, lane, c);
-      const double f = finish<R>(a, s, p, d.r, c, lane);
+      const double f = finish<R>(a, s, a.row_of[p], d.r, c, lane);
       if (kSameTable && a.bk.nb != 0) drop_in_bucket(a, s, p, f, lane);
     } else {
-      // refresh: the survivor of rank p, projected onto the current job table
+      // refresh: the survivor of rank p, projected onto the new job table, goes to a spare row
+      // (its old row is still being read as a parent by other waves)
       const uint32_t p = item - 2 * K;
-      const uint32_t src = static_cast<uint32_t>(a.sel[p]);
-      load_genes<R>(a.genes_old + static_cast<size_t>(src) * a.Jp, lane, c);
-      if (kSameTable) {
-        int32_t *row = a.genes_new + static_cast<size_t>(p) * a.Jp;
-#pragma unroll
-        for (int i = 0; i < R; ++i) __builtin_nontemporal_store(static_cast<int32_t>(c[i]), &row[lane + kLanes * i]);
-        if (lane == 0) a.fit[p] = a.fit_old[src];
-      } else {
-        const Draw d = candidate_draw(a, p);
-        gpus_from_batches<R, false>(s, lane, c);
-        finish<R>(a, s, p, d.r, c, lane);
-      }
+      const Draw d = candidate_draw(a, p);
+      load_genes<R>(a.genes + static_cast<size_t>(a.parent_row[p]) * a.Jp, lane, c);
+      gpus_from_batches<R, false>(s, lane, c);
+      const uint32_t dst = a.spare_row[p];
+      finish<R>(a, s, dst, d.r, c, lane);
+      if (lane == 0) a.row_of[p] = dst;
     }
   }
 }
@@ -503,7 +500,7 @@ template <int R>
 hipError_t launch_rows(const EvolveArgs &a, bool same_table, int n_cus, hipStream_t s) {
   constexpr int kWaves = Shape<R>::kWaves;
   if (a.t == 0) return launch_persistent(init_kernel<R>, a, kWaves, a.P, n_cus, s);
-  if (same_table) return launch_persistent(evolve_kernel<R, true>, a, kWaves, 3 * a.K, n_cus, s);
+  if (same_table) return launch_persistent(evolve_kernel<R, true>, a, kWaves, 2 * a.K, n_cus, s);
   return launch_persistent(evolve_kernel<R, false>, a, kWaves, 3 * a.K, n_cus, s);
 }
 

@@ -16,6 +16,14 @@ __device__ __forceinline__ bool key_less(uint64_t ka, uint32_t ia, uint64_t kb, 
   return ka < kb || (ka == kb && ia < ib);
 }
 
+// Slot id takes rank g < K: it survives in its row.
+__device__ __forceinline__ void keep_row(const RowPlan &rp, uint32_t g, uint32_t id) {
+  const uint32_t row = rp.row_of_cur[id];
+  rp.parent_next[g] = row;
+  rp.row_of_next[g] = row;
+  atomicOr(&rp.occupied[row / 32], 1u << (row % 32));
+}
+
 // Bitonic sorting network over n (a power of two) keys by one workgroup, ascending
 // (score bits, slot).  Works on LDS or, for oversized inputs, on global memory.
 template <typename K64, typename I32>
@@ -46,21 +54,25 @@ __device__ __forceinline__ uint32_t pow2_at_least(uint32_t v) {
 // ---------------------------------------------------------------- general path -----
 // Each workgroup sorts one chunk of n (power of two, <= kSortChunk) keys in LDS.  With a
 // single chunk the survivors are written directly.
-__global__ __launch_bounds__(kSortThreads) void sort_chunks_kernel(const double *fit, uint32_t P, uint32_t K,
-                                                                  uint32_t n, uint64_t *keys, uint32_t *idx,
-                                                                  int32_t *sel, int single) {
+__global__ __launch_bounds__(kSortThreads) void sort_chunks_kernel(const double *fit_row, RowPlan rp, uint32_t P,
+                                                                  uint32_t K, uint32_t n, uint64_t *keys,
+                                                                  uint32_t *idx, int32_t *sel, int single) {
+  const uint32_t *row_of = rp.row_of_cur;
   __shared__ uint64_t sk[kSortChunk];
   __shared__ uint32_t si[kSortChunk];
   const uint32_t base = blockIdx.x * n;
   for (uint32_t e = threadIdx.x; e < n; e += kSortThreads) {
     const uint32_t p = base + e;
-    sk[e] = p < P ? static_cast<uint64_t>(__double_as_longlong(fit[p])) : ~0ull;   // padding sorts last
+    sk[e] = p < P ? static_cast<uint64_t>(__double_as_longlong(fit_row[row_of[p]])) : ~0ull;   // padding sorts last
     si[e] = p < P ? p : 0xFFFFFFFFu;
   }
   __syncthreads();
   bitonic_sort(sk, si, n);
   if (single) {
-    for (uint32_t e = threadIdx.x; e < K; e += kSortThreads) sel[e] = static_cast<int32_t>(si[e]);
+    for (uint32_t e = threadIdx.x; e < K; e += kSortThreads) {
+      sel[e] = static_cast<int32_t>(si[e]);
+      keep_row(rp, e, si[e]);
+    }
   } else {
     for (uint32_t e = threadIdx.x; e < n; e += kSortThreads) {
       keys[base + e] = sk[e];
@@ -72,7 +84,7 @@ __global__ __launch_bounds__(kSortThreads) void sort_chunks_kernel(const double 
 // Global rank of every element = its position in its own sorted chunk + the number of
 // smaller elements in every other chunk (binary search).  Ranks below K are survivors.
 __global__ __launch_bounds__(256) void rank_kernel(const uint64_t *keys, const uint32_t *idx, uint32_t chunks,
-                                                  uint32_t K, int32_t *sel) {
+                                                  uint32_t K, RowPlan rp, int32_t *sel) {
   const uint32_t e = blockIdx.x * blockDim.x + threadIdx.x;
   if (e >= chunks * kSortChunk) return;
   const uint32_t mine = e / kSortChunk, pos = e % kSortChunk;
@@ -91,7 +103,10 @@ __global__ __launch_bounds__(256) void rank_kernel(const uint64_t *keys, const u
     }
     rank += lo;
   }
-  if (rank < K) sel[rank] = static_cast<int32_t>(id);
+  if (rank < K) {
+    sel[rank] = static_cast<int32_t>(id);
+    keep_row(rp, rank, id);
+  }
 }
 
 // ----------------------------------------------------------- quantile buckets ------
@@ -133,7 +148,7 @@ __device__ __forceinline__ uint32_t wave_sum_u32(uint32_t v) {
 template <typename K64, typename I32>
 __device__ __forceinline__ void rank_bucket(K64 *sk, I32 *si, const uint64_t *ek, uint32_t n, uint32_t npad,
                                             uint32_t ne, uint32_t e0, uint32_t off, bool sorted, uint32_t K,
-                                            const BucketArgs &bk, int32_t *sel) {
+                                            const BucketArgs &bk, const RowPlan &rp, int32_t *sel) {
   const uint32_t tid = threadIdx.x, nb = bk.nb;
   // offspring i: rank = offspring before it + survivors with score <= its score (a survivor
   // wins a tie: smaller slot)
@@ -154,7 +169,11 @@ __device__ __forceinline__ void rank_bucket(K64 *sk, I32 *si, const uint64_t *ek
       if (ek[mid] <= key) lo = mid + 1; else hi = mid;
     }
     const uint32_t g = off + below + lo;
-    if (g < K) { sel[g] = static_cast<int32_t>(id); note_rank(g, key, K, nb, bk.split_next, bk.thresh_next); }
+    if (g < K) {
+      sel[g] = static_cast<int32_t>(id);
+      keep_row(rp, g, id);
+      note_rank(g, key, K, nb, bk.split_next, bk.thresh_next);
+    }
   }
   // survivor e: rank = e + offspring with a strictly smaller score
   for (uint32_t e = tid; e < ne; e += kBucketThreads) {
@@ -173,7 +192,11 @@ __device__ __forceinline__ void rank_bucket(K64 *sk, I32 *si, const uint64_t *ek
       }
     }
     const uint32_t g = off + e + lo;
-    if (g < K) { sel[g] = static_cast<int32_t>(e0 + e); note_rank(g, key, K, nb, bk.split_next, bk.thresh_next); }
+    if (g < K) {
+      sel[g] = static_cast<int32_t>(e0 + e);
+      keep_row(rp, g, e0 + e);
+      note_rank(g, key, K, nb, bk.split_next, bk.thresh_next);
+    }
   }
 }
 
@@ -202,8 +225,10 @@ __device__ __forceinline__ void gather_bucket(K64 *dk, I32 *di, const BucketArgs
   __syncthreads();
 }
 
-__global__ __launch_bounds__(kBucketThreads) void bucket_select_kernel(const double *fit, BucketArgs bk, uint32_t K,
-                                                                       uint32_t *count_next, int32_t *sel) {
+__global__ __launch_bounds__(kBucketThreads) void bucket_select_kernel(const double *fit_row,
+                                                                       const uint32_t *parent_row, BucketArgs bk,
+                                                                       RowPlan rp, uint32_t K, uint32_t *count_next,
+                                                                       int32_t *sel) {
   __shared__ uint64_t sk[kBucketLds];
   __shared__ uint32_t si[kBucketLds];
   __shared__ uint64_t ek[kBucketElites];
@@ -221,7 +246,7 @@ __global__ __launch_bounds__(kBucketThreads) void bucket_select_kernel(const dou
   const uint32_t npad = n2 < 8 ? 8 : n2;             // counting loops run in steps of 8 over padding
   const bool in_lds = npad <= static_cast<uint32_t>(kBucketLds);
   for (uint32_t e = tid; e < ne; e += kBucketThreads)
-    ek[e] = static_cast<uint64_t>(__double_as_longlong(fit[e0 + e]));
+    ek[e] = static_cast<uint64_t>(__double_as_longlong(fit_row[parent_row[e0 + e]]));   // survivors stayed in their rows
   if (tid == 0) {
     spill_cursor = 0;
     pool_base = in_lds ? 0u : atomicAdd(&bk.count[kPoolCounter], npad);   // a slice of the scratch pool
@@ -235,13 +260,13 @@ __global__ __launch_bounds__(kBucketThreads) void bucket_select_kernel(const dou
       gather_bucket(sk, si, bk, b, n, npad, &spill_cursor);
       const bool sorted = n > static_cast<uint32_t>(kBucketCount);
       if (sorted) bitonic_sort(sk, si, npad);
-      rank_bucket(sk, si, ek, n, npad, ne, e0, off, sorted, K, bk, sel);
+      rank_bucket(sk, si, ek, n, npad, ne, e0, off, sorted, K, bk, rp, sel);
     } else {                                         // oversized bucket: same network in global memory
       uint64_t *pk = bk.pool_keys + pool_base;
       uint32_t *pi = bk.pool_idx + pool_base;
       gather_bucket(pk, pi, bk, b, n, npad, &spill_cursor);
       bitonic_sort(pk, pi, npad);
-      rank_bucket(pk, pi, ek, n, npad, ne, e0, off, true, K, bk, sel);
+      rank_bucket(pk, pi, ek, n, npad, ne, e0, off, true, K, bk, rp, sel);
     }
   }
   // the other counter set, for the next generation
@@ -249,15 +274,68 @@ __global__ __launch_bounds__(kBucketThreads) void bucket_select_kernel(const dou
   if (b == 0 && tid < 2) count_next[kMaxBuckets + tid] = 0;
 }
 
+// After a selection (which set the bits of the survivors' rows): every other row of the
+// P + K is free.  Free rows in ascending order: the first 3K go to the children and mutants of
+// the next pool (slots K..P-1), the last K are spares for survivors that must be refreshed
+// after a table change.  Each workgroup counts the free rows before its share of the bitmap by
+// itself (the bitmap is a few KB), so the workgroups need no synchronisation.
+constexpr int kFreeThreads = 256;
+__global__ __launch_bounds__(kFreeThreads) void free_rows_kernel(const uint32_t *occupied, uint32_t *occupied_other,
+                                                                uint32_t P, uint32_t K, uint32_t *row_of_next,
+                                                                uint32_t *spare_row) {
+  __shared__ uint32_t part[kFreeThreads];
+  const uint32_t tid = threadIdx.x, rows = P + K, words = (rows + 31) / 32;
+  const uint32_t w0 = blockIdx.x * kFreeThreads;                  // this workgroup: words w0 .. w0 + 255
+  auto free_bits_of = [&](uint32_t w) {
+    uint32_t f = ~occupied[w];
+    if (w == words - 1 && rows % 32 != 0) f &= (1u << (rows % 32)) - 1u;
+    return f;
+  };
+  uint32_t before = 0;
+  for (uint32_t w = tid; w < w0; w += kFreeThreads) before += __popc(free_bits_of(w));
+  const uint32_t mine = w0 + tid < words ? free_bits_of(w0 + tid) : 0u;
+  part[tid] = before;
+  __syncthreads();
+  for (uint32_t d = kFreeThreads / 2; d > 0; d >>= 1) {           // sum of `before` over the workgroup
+    if (tid < d) part[tid] += part[tid + d];
+    __syncthreads();
+  }
+  const uint32_t base = part[0];
+  __syncthreads();
+  part[tid] = __popc(mine);
+  __syncthreads();
+  for (uint32_t d = 1; d < kFreeThreads; d <<= 1) {               // inclusive scan of the word counts
+    const uint32_t add = tid >= d ? part[tid - d] : 0u;
+    __syncthreads();
+    part[tid] += add;
+    __syncthreads();
+  }
+  uint32_t q = base + part[tid] - __popc(mine);
+  uint32_t bits = mine;
+  while (bits) {
+    const uint32_t r = (w0 + tid) * 32 + (__ffs(static_cast<int>(bits)) - 1);
+    bits &= bits - 1;
+    if (q < 3 * K) row_of_next[K + q] = r; else spare_row[q - 3 * K] = r;
+    ++q;
+  }
+  if (w0 + tid < words) occupied_other[w0 + tid] = 0;             // ready for the next selection
+}
+
+__global__ void zero_words_kernel(uint32_t *words, uint32_t n) {
+  const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) words[i] = 0;
+}
+
 // Splitters after a selection by the general path.
-__global__ void splitters_kernel(const double *fit, const int32_t *sel, uint32_t K, uint32_t nb, uint64_t *split,
-                                 uint64_t *thresh, uint32_t *count0, uint32_t *count1) {
+__global__ void splitters_kernel(const double *fit_row, const uint32_t *row_of, const int32_t *sel, uint32_t K,
+                                 uint32_t nb, uint64_t *split, uint64_t *thresh, uint32_t *count0,
+                                 uint32_t *count1) {
   const uint32_t c = blockIdx.x * blockDim.x + threadIdx.x;
   if (c < static_cast<uint32_t>(kBucketCounters)) { count0[c] = 0; count1[c] = 0; }
   if (c < static_cast<uint32_t>(kMaxBuckets))
-    split[c] = (c + 1 < nb) ? static_cast<uint64_t>(__double_as_longlong(fit[sel[bucket_bound(c + 1, K, nb)]]))
+    split[c] = (c + 1 < nb) ? static_cast<uint64_t>(__double_as_longlong(fit_row[row_of[sel[bucket_bound(c + 1, K, nb)]]]))
                             : 0x7FF0000000000000ull;          // +infinity pads the table
-  if (c == 0) *thresh = static_cast<uint64_t>(__double_as_longlong(fit[sel[K - 1]]));
+  if (c == 0) *thresh = static_cast<uint64_t>(__double_as_longlong(fit_row[row_of[sel[K - 1]]]));
 }
 
 __global__ void prepare_table_kernel(RawJobs raw, JobTable tab, uint32_t Jp) {
@@ -307,16 +385,17 @@ __global__ void reset_slots_kernel(int32_t *genes, const uint32_t *changed, uint
     if (changed[e % Jp]) genes[e] = 0;
 }
 
-__global__ void best_kernel(const int32_t *genes, const double *fit, const int32_t *sel, const uint32_t *info,
-                            uint32_t Jn, uint32_t Jp, int32_t *batch_out, int32_t *gpus_out, double *fit_out) {
-  const uint32_t best = static_cast<uint32_t>(sel[0]);
+__global__ void best_kernel(const int32_t *genes, const double *fit_row, const uint32_t *row_of, const int32_t *sel,
+                            const uint32_t *info, uint32_t Jn, uint32_t Jp, int32_t *batch_out, int32_t *gpus_out,
+                            double *fit_out) {
+  const uint32_t best = row_of[sel[0]];
   const int32_t *row = genes + static_cast<size_t>(best) * Jp;
   for (uint32_t j = threadIdx.x; j < Jn; j += blockDim.x) {
     const uint32_t B = static_cast<uint32_t>(row[j]);
     batch_out[j] = static_cast<int32_t>(B);
     gpus_out[j] = static_cast<int32_t>(B ? max(1u, B >> info_mu(info[j])) : 0u);
   }
-  if (threadIdx.x == 0) *fit_out = fit[best];
+  if (threadIdx.x == 0) *fit_out = fit_row[best];
 }
 
 uint32_t next_pow2(uint32_t v) {
@@ -345,41 +424,56 @@ hipError_t launch_reset_slots(int32_t *genes, const uint32_t *changed, uint32_t 
   return hipGetLastError();
 }
 
-hipError_t launch_select(const double *fit, uint32_t P, uint32_t K, uint64_t *keys, uint32_t *idx,
-                         int32_t *sel, hipStream_t s) {
+hipError_t launch_free_rows(const uint32_t *occupied, uint32_t *occupied_other, uint32_t P, uint32_t K,
+                            uint32_t *row_of_next, uint32_t *spare_row, hipStream_t s) {
+  const uint32_t words = (P + K + 31) / 32;
+  hipLaunchKernelGGL(free_rows_kernel, dim3((words + kFreeThreads - 1) / kFreeThreads), dim3(kFreeThreads), 0, s,
+                     occupied, occupied_other, P, K, row_of_next, spare_row);
+  return hipGetLastError();
+}
+
+hipError_t launch_zero_words(uint32_t *words, uint32_t n, hipStream_t s) {
+  hipLaunchKernelGGL(zero_words_kernel, dim3((n + 255) / 256), dim3(256), 0, s, words, n);
+  return hipGetLastError();
+}
+
+hipError_t launch_select(const double *fit, const RowPlan &rp, uint32_t P, uint32_t K, uint64_t *keys,
+                         uint32_t *idx, int32_t *sel, hipStream_t s) {
   if (P <= static_cast<uint32_t>(kSortChunk)) {
-    hipLaunchKernelGGL(sort_chunks_kernel, dim3(1), dim3(kSortThreads), 0, s, fit, P, K, next_pow2(P), keys, idx,
-                       sel, 1);
+    hipLaunchKernelGGL(sort_chunks_kernel, dim3(1), dim3(kSortThreads), 0, s, fit, rp, P, K, next_pow2(P), keys,
+                       idx, sel, 1);
     return hipGetLastError();
   }
   const uint32_t chunks = (P + kSortChunk - 1) / kSortChunk;
-  hipLaunchKernelGGL(sort_chunks_kernel, dim3(chunks), dim3(kSortThreads), 0, s, fit, P, K,
+  hipLaunchKernelGGL(sort_chunks_kernel, dim3(chunks), dim3(kSortThreads), 0, s, fit, rp, P, K,
                      static_cast<uint32_t>(kSortChunk), keys, idx, sel, 0);
   hipError_t rc = hipGetLastError();
   if (rc != hipSuccess) return rc;
   const uint32_t n = chunks * kSortChunk;
-  hipLaunchKernelGGL(rank_kernel, dim3((n + 255) / 256), dim3(256), 0, s, keys, idx, chunks, K, sel);
+  hipLaunchKernelGGL(rank_kernel, dim3((n + 255) / 256), dim3(256), 0, s, keys, idx, chunks, K, rp, sel);
   return hipGetLastError();
 }
 
-hipError_t launch_bucket_select(const double *fit, const BucketArgs &bk, uint32_t K, uint32_t *count_next,
-                                int32_t *sel, hipStream_t s) {
-  hipLaunchKernelGGL(bucket_select_kernel, dim3(bk.nb), dim3(kBucketThreads), 0, s, fit, bk, K, count_next, sel);
+hipError_t launch_bucket_select(const double *fit_row, const uint32_t *parent_row, const BucketArgs &bk,
+                                const RowPlan &rp, uint32_t K, uint32_t *count_next, int32_t *sel, hipStream_t s) {
+  hipLaunchKernelGGL(bucket_select_kernel, dim3(bk.nb), dim3(kBucketThreads), 0, s, fit_row, parent_row, bk, rp, K,
+                     count_next, sel);
   return hipGetLastError();
 }
 
-hipError_t launch_splitters(const double *fit, const int32_t *sel, uint32_t K, uint32_t nb, uint64_t *split,
-                            uint64_t *thresh, uint32_t *count0, uint32_t *count1, hipStream_t s) {
-  hipLaunchKernelGGL(splitters_kernel, dim3((kBucketCounters + 255) / 256), dim3(256), 0, s, fit, sel, K, nb, split,
-                     thresh, count0, count1);
+hipError_t launch_splitters(const double *fit_row, const uint32_t *row_of, const int32_t *sel, uint32_t K,
+                            uint32_t nb, uint64_t *split, uint64_t *thresh, uint32_t *count0, uint32_t *count1,
+                            hipStream_t s) {
+  hipLaunchKernelGGL(splitters_kernel, dim3((kBucketCounters + 255) / 256), dim3(256), 0, s, fit_row, row_of, sel, K,
+                     nb, split, thresh, count0, count1);
   return hipGetLastError();
 }
 
-hipError_t launch_best(const int32_t *genes, const double *fit, const int32_t *sel, const uint32_t *info,
-                       uint32_t Jn, uint32_t Jp, int32_t *batch_out, int32_t *gpus_out, double *fit_out,
-                       hipStream_t s) {
-  hipLaunchKernelGGL(best_kernel, dim3(1), dim3(256), 0, s, genes, fit, sel, info, Jn, Jp, batch_out, gpus_out,
-                     fit_out);
+hipError_t launch_best(const int32_t *genes, const double *fit_row, const uint32_t *row_of, const int32_t *sel,
+                       const uint32_t *info, uint32_t Jn, uint32_t Jp, int32_t *batch_out, int32_t *gpus_out,
+                       double *fit_out, hipStream_t s) {
+  hipLaunchKernelGGL(best_kernel, dim3(1), dim3(256), 0, s, genes, fit_row, row_of, sel, info, Jn, Jp, batch_out,
+                     gpus_out, fit_out);
   return hipGetLastError();
 }
 
