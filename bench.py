@@ -24,8 +24,8 @@ HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published peak
 
 # HBM bytes per evolve launch on the stress workload from rocprofv3 --pmc FETCH_SIZE and
 # WRITE_SIZE (see profiles/), valid only for the kernel source with this hash.
-MEASURED_TRAFFIC = {"source_sha256": "0c65d0c95c087d05a5430f2b502a3628eb36446ac609956603920f3086299d3d",
-                    "bytes_per_launch": 1078776625}
+MEASURED_TRAFFIC = {"source_sha256": "67fb4912b7146c0c67e091a1bf98f1fe6bf98f9eed132181f196a20e5811346c",
+                    "bytes_per_launch": 802817165}
 
 
 def evolve_source_hash() -> str:
@@ -60,12 +60,54 @@ def cpu_baseline(workload: str):
             "generations_per_s": gens / dt, "seconds": dt}
 
 
+def online(args, torch, ones, W) -> int:
+    """The online sequence: every scheduling epoch replaces the job table (ones_set_jobs), runs
+    20 warm-started generations and reads the winner (ones_best), which drives the simulated
+    cluster.  A step is one epoch; --steps counts epochs."""
+    sim = W.OnlineSequence(epochs=args.steps + args.warmup)
+    cl = sim.cluster
+    torch.cuda.set_device(0)
+    search = ones.Search(cl, sim.jobs, device="cuda:0")
+    gens = cl.generations
+    t_set = t_gen = t_best = 0.0
+    evals = 0
+    for epoch in range(args.warmup + args.steps):
+        timed = epoch >= args.warmup
+        t0 = time.perf_counter()
+        search.generation(gens)
+        search.synchronize()
+        t1 = time.perf_counter()
+        batch, _, _ = search.best()
+        t2 = time.perf_counter()
+        sim.advance(batch)
+        t3 = time.perf_counter()
+        search.set_jobs(sim.jobs)
+        t4 = time.perf_counter()
+        if timed:
+            t_gen += t1 - t0; t_best += t2 - t1; t_set += t4 - t3
+            evals += cl.population * int(sim.jobs.active.sum()) * gens
+    dt = t_gen + t_best + t_set
+    out = {"metric": "candidate-job fitness evals/sec", "value": evals / dt, "unit": "evals/s", "n_gpus": 1,
+           "steps": args.steps, "warmup": args.warmup, "ms_per_step": dt * 1e3 / args.steps,
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+           "dtype": "i32 genes, f64 fitness", "data": "synthetic",
+           "config": {"workload": "online", "n_gpus_cluster": cl.n_gpus, "slots": cl.n_slots,
+                      "population": cl.population, "generations_per_epoch": gens, "seed": cl.seed,
+                      "jobs_completed": sim.completed},
+           "generations_per_s": gens * args.steps / dt,
+           "per_epoch_ms": {"generations": t_gen * 1e3 / args.steps, "ones_best": t_best * 1e3 / args.steps,
+                            "ones_set_jobs": t_set * 1e3 / args.steps}}
+    search.close()
+    print(json.dumps(out))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=40)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="stress", choices=["stress", "large", "paper_scale", "tiny"])
+    ap.add_argument("--workload", default="stress", choices=["stress", "large", "paper_scale", "tiny", "online"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-events", action="store_true", help="do not bracket kernels with HIP events")
     ap.add_argument("--copy-reference", action="store_true",
@@ -80,6 +122,8 @@ def main() -> int:
     import torch
     from paper_2108_03645_amd import ones, workloads as W
 
+    if args.workload == "online":
+        return online(args, torch, ones, W)
     cl, jobs = W.CONFIGS[args.workload]()
     active = int(jobs.active.sum())
     jp = ones.padded_jobs(cl.n_slots)
