@@ -29,7 +29,7 @@ int hip_fail(hipError_t e, const char *what) {
 size_t align_up(size_t v) { return (v + 255) & ~static_cast<size_t>(255); }
 
 struct Layout {
-  size_t genes, fit_row, row_of[2], parent_row[2], spare_row, occupied[2], sel, keys, idx, split, thresh, bcount[2], bkeys, bidx, skeys, sidx, sbucket, pkeys, pidx, cstart, cmax, info, abl, cc, d, Y, terms;
+  size_t genes, fit_row, row_of[2], parent_row[2], occupied[2], sel, keys, idx, split, thresh, bcount[2], bkeys, bidx, skeys, sidx, sbucket, pkeys, pidx, cstart, cmax, info, abl, cc, d, Y, terms;
   size_t rawinfo, changed, ra, rc, rd, rY, best_batch, best_gpus, best_fit, total;
 };
 
@@ -63,7 +63,6 @@ Layout make_layout(uint32_t P, uint32_t Jp) {
   L.row_of[1] = take(static_cast<size_t>(P) * 4);
   L.parent_row[0] = take(static_cast<size_t>(P / 4) * 4);
   L.parent_row[1] = take(static_cast<size_t>(P / 4) * 4);
-  L.spare_row = take(static_cast<size_t>(P / 4) * 4);
   L.occupied[0] = take((rows + 31) / 32 * 4);     // bitmaps of the rows the survivors keep
   L.occupied[1] = take((rows + 31) / 32 * 4);
   L.sel = take(static_cast<size_t>(P / 4) * 4);
@@ -230,13 +229,15 @@ int timed(ones_ctx *c, std::vector<EventPair> &pool, size_t &used, bool begin) {
 
 int run_generation(ones_ctx *c, uint32_t t) {
   EvolveArgs a;
-  // generation 0 fills row_of[cur]; later generations fill the array the last compaction prepared
+  // generation 0 fills row_of[cur]; later generations complete the array whose first K entries
+  // the last selection wrote
   const int next = t == 0 ? c->cur : c->cur ^ 1;
   a.genes = c->at<int32_t>(c->L.genes);
   a.fit_row = c->at<double>(c->L.fit_row);
   a.parent_row = c->at<uint32_t>(c->L.parent_row[next]);
   a.row_of = c->at<uint32_t>(c->L.row_of[next]);
-  a.spare_row = c->at<uint32_t>(c->L.spare_row);
+  a.occupied = c->at<uint32_t>(c->L.occupied[c->cur]);          // set by the last selection
+  a.occupied_other = c->at<uint32_t>(c->L.occupied[c->cur ^ 1]);
   a.tab = c->table();
   a.G = c->G; a.P = c->P; a.K = c->K; a.Jp = c->Jp;
   a.key0 = static_cast<uint32_t>(c->cfg.seed);
@@ -282,9 +283,6 @@ int run_generation(ones_ctx *c, uint32_t t) {
                                c->at<uint64_t>(c->L.thresh), c->at<uint32_t>(c->L.bcount[0]),
                                c->at<uint32_t>(c->L.bcount[1]), c->stream));
   }
-  // survivors keep their rows; hand the free rows to the slots of the next pool
-  HIP_TRY(launch_free_rows(rp.occupied, c->at<uint32_t>(c->L.occupied[next ^ 1]), c->P, c->K, rp.row_of_next,
-                           c->at<uint32_t>(c->L.spare_row), c->stream));
   if ((rc = timed(c, c->select_ev, c->select_used, false))) return rc;
   c->cur = next;
   c->table_changed = false;

@@ -48,6 +48,7 @@ constexpr int kMaxBuckets = 1024;
 constexpr int kSpillCounter = kMaxBuckets;       // count[kSpillCounter]: records in the spill list
 constexpr int kPoolCounter = kMaxBuckets + 1;    // count[kPoolCounter]: scratch pool entries handed out
 constexpr int kBucketCounters = kMaxBuckets + 2;
+constexpr int kRowGroupWords = 64;               // bitmap words per entry of the free-row index (one per lane)
 struct BucketArgs {
   const uint64_t *split;      // [kMaxBuckets] score bits of survivor ranks c*K/nb, c = 1..nb-1, then +inf
   const uint64_t *thresh;     // [1] score bits of the K-th survivor
@@ -65,17 +66,18 @@ struct BucketArgs {
 };
 
 // Genomes live in physical rows; a candidate keeps its row for as long as it survives, so a
-// survivor is never copied.  The pool of P slots uses P + K rows: while the job table stays
-// the same, the 3K children and mutants of a generation take rows freed by the candidates
-// that dropped out; after a table change the K refreshed survivors take the K spare rows.
+// survivor is never copied.  The pool of P slots uses P + K rows, K of them held by the
+// survivors (the selection marks them in a bitmap).  Of the P free rows in ascending order,
+// slot K + q of the new pool takes the q-th; a survivor that must be refreshed after a table
+// change (rank p) takes the (3K + p)-th.  The evolve kernel looks its rows up in the bitmap.
 struct EvolveArgs {
   int32_t        *genes;      // [P + K][Jp] genome rows (global batch sizes)
   double         *fit_row;    // [P + K] score of the genome in each row
   const uint32_t *parent_row; // [K] rows of the survivors, best first
-  uint32_t       *row_of;     // [P] row of every slot of the new pool, prefilled: survivors keep
-                              //     theirs, slot K + q takes the q-th free row; a refreshed
-                              //     survivor records its spare row here
-  const uint32_t *spare_row;  // [K] rows for refreshed survivors
+  uint32_t       *row_of;     // [P] row of every slot of the new pool: entries [0,K) prefilled
+                              //     (survivors keep their rows), the others written here
+  const uint32_t *occupied;   // bitmap over the P + K rows: the survivors' rows
+  uint32_t       *occupied_other;  // the other bitmap, cleared here for the coming selection
   JobTable       tab;
   uint32_t       G, P, K, Jp;
   uint32_t       key0, key1;  // seed
@@ -118,10 +120,6 @@ inline hipError_t launch_evolve(const EvolveArgs &a, int rows, bool same_table, 
 }
 hipError_t launch_select(const double *fit_row, const RowPlan &rp, uint32_t P, uint32_t K, uint64_t *keys,
                          uint32_t *idx, int32_t *sel, hipStream_t s);
-// After a selection: hands the unoccupied rows, in ascending order, to slots K..P-1 of the next
-// pool and (the last K) to the spare list; clears the other bitmap for the next selection.
-hipError_t launch_free_rows(const uint32_t *occupied, uint32_t *occupied_other, uint32_t P, uint32_t K,
-                            uint32_t *row_of_next, uint32_t *spare_row, hipStream_t s);
 hipError_t launch_zero_words(uint32_t *words, uint32_t n, hipStream_t s);
 hipError_t launch_bucket_select(const double *fit_row, const uint32_t *parent_row, const BucketArgs &bk,
                                 const RowPlan &rp, uint32_t K, uint32_t *count_next, int32_t *sel, hipStream_t s);

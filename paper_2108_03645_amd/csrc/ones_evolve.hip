@@ -120,15 +120,23 @@ struct Smem {
   double   *terms;   // [R][E][64] T_j c_j of job (row, lane) at GPU-count code e, or null
   uint64_t *split;   // [kMaxBuckets] bucket splitters, then [1] the K-th survivor's score bits
   uint8_t  *stash;   // [waves][Jp] second crossover child while the first is repaired
+  uint32_t *free_in_group; // [groups] free rows in each group of kRowGroupWords bitmap words
+  uint32_t *rows;          // [4 * kRound] rows of the slots this workgroup fills in the current round
 };
 
 // E = entries per job of the term table kept in LDS, 0 = keep the four model parameters.
-inline size_t smem_bytes(uint32_t Jp, int waves, uint32_t E) {
-  return static_cast<size_t>(Jp) * (8 + 4 + (E ? 8 * E : 32)) + (kMaxBuckets + 1) * 8 +
-         static_cast<size_t>(waves) * Jp;
+constexpr uint32_t kRound = 256;                     // survivors' ranks a workgroup covers between two barriers
+
+inline uint32_t row_groups(uint32_t rows) {
+  return ((rows + 31) / 32 + kRowGroupWords - 1) / kRowGroupWords;
 }
 
-__device__ __forceinline__ Smem carve(unsigned char *base, uint32_t Jp, uint32_t E) {
+inline size_t smem_bytes(uint32_t Jp, int waves, uint32_t E, uint32_t rows) {
+  return static_cast<size_t>(Jp) * (8 + 4 + (E ? 8 * E : 32)) + (kMaxBuckets + 1) * 8 +
+         static_cast<size_t>(waves) * Jp + static_cast<size_t>(row_groups(rows)) * 4 + 4 * kRound * 4;
+}
+
+__device__ __forceinline__ Smem carve(unsigned char *base, uint32_t Jp, uint32_t E, uint32_t waves) {
   Smem s;
   s.abl = reinterpret_cast<double *>(base);
   s.cc = s.abl + Jp;
@@ -139,9 +147,12 @@ __device__ __forceinline__ Smem carve(unsigned char *base, uint32_t Jp, uint32_t
   s.cc2 = reinterpret_cast<uint2 *>(s.split + kMaxBuckets + 1);
   s.info = reinterpret_cast<uint32_t *>(s.cc2 + Jp);
   s.stash = reinterpret_cast<uint8_t *>(s.info + Jp);
+  s.rows = reinterpret_cast<uint32_t *>(s.stash + static_cast<size_t>(waves) * Jp);   // Jp is a multiple of 64
+  s.free_in_group = s.rows + 4 * kRound;
   return s;
 }
 
+// No barrier at the end: the caller places one before the first use.
 __device__ __forceinline__ void stage_table(const JobTable &tab, const BucketArgs &bk, const Smem &s, uint32_t Jp,
                                             uint32_t E) {
   if (bk.nb != 0) {
@@ -160,7 +171,94 @@ __device__ __forceinline__ void stage_table(const JobTable &tab, const BucketArg
   }
   if (E != 0)
     for (uint32_t q = threadIdx.x; q < Jp * E; q += blockDim.x) s.terms[q] = tab.terms[q];
+}
+
+// ------------------------------------------------------------------ free rows ----
+// Bits of bitmap word w that stand for free rows (rows beyond P + K count as taken).
+__device__ __forceinline__ uint32_t free_bits(const uint32_t *occupied, uint32_t w, uint32_t rows) {
+  const uint32_t words = (rows + 31) / 32;
+  if (w >= words) return 0u;
+  uint32_t f = ~occupied[w];
+  if (w == words - 1 && rows % 32 != 0) f &= (1u << (rows % 32)) - 1u;
+  return f;
+}
+
+// Every workgroup builds the same small index: the number of free rows in each group of
+// kRowGroupWords bitmap words.  The first bitmap loads are issued before the job table is
+// staged and counted after it, so that their latency overlaps the staging.
+constexpr int kIndexAhead = 4;                       // groups per wave whose words are loaded ahead
+
+struct IndexLoads { uint32_t bits[kIndexAhead]; };
+
+__device__ __forceinline__ IndexLoads index_free_rows_begin(const EvolveArgs &a, int lane) {
+  const uint32_t rows = a.P + a.K;
+  const uint32_t wave = threadIdx.x >> 6, waves = blockDim.x >> 6;
+  IndexLoads ld;
+#pragma unroll
+  for (int k = 0; k < kIndexAhead; ++k) ld.bits[k] = free_bits(a.occupied, (wave + k * waves) * kRowGroupWords + lane, rows);
+  return ld;
+}
+
+// Also clears this workgroup's share of the other bitmap.  Ends with a barrier (which also
+// publishes the staged job table).
+__device__ __forceinline__ void index_free_rows_end(const EvolveArgs &a, const Smem &s, const IndexLoads &ld, int lane) {
+  const uint32_t rows = a.P + a.K, words = (rows + 31) / 32;
+  const uint32_t groups = (words + kRowGroupWords - 1) / kRowGroupWords;
+  const uint32_t wave = threadIdx.x >> 6, waves = blockDim.x >> 6;
+#pragma unroll
+  for (int k = 0; k < kIndexAhead; ++k) {
+    const uint32_t n = wave_sum(__popc(ld.bits[k]));
+    if (lane == 0 && wave + k * waves < groups) s.free_in_group[wave + k * waves] = n;
+  }
+  for (uint32_t g = wave + kIndexAhead * waves; g < groups; g += waves) {
+    const uint32_t n = wave_sum(__popc(free_bits(a.occupied, g * kRowGroupWords + lane, rows)));
+    if (lane == 0) s.free_in_group[g] = n;
+  }
+  for (uint32_t w = blockIdx.x * blockDim.x + threadIdx.x; w < words; w += gridDim.x * blockDim.x)
+    a.occupied_other[w] = 0;
   __syncthreads();
+}
+
+// One wave lists the free rows number q0 .. q0 + count - 1 (in ascending order; all below the
+// number of free rows) into dst.
+__device__ __forceinline__ void list_free_rows(const EvolveArgs &a, const Smem &s, uint32_t q0, uint32_t count,
+                                               uint32_t *dst, int lane) {
+  const uint32_t rows = a.P + a.K;
+  const uint32_t groups = ((rows + 31) / 32 + kRowGroupWords - 1) / kRowGroupWords;
+  // the group that holds free row q0, and the free rows before that group
+  uint32_t g = groups, before = 0;
+  for (uint32_t g0 = 0; g0 < groups; g0 += kLanes) {
+    const uint32_t n = g0 + lane < groups ? s.free_in_group[g0 + lane] : 0u;
+    const uint32_t incl = wave_inclusive_scan(n);
+    const uint64_t beyond = __ballot(before + incl > q0);
+    if (beyond != 0) {
+      const int l = __builtin_amdgcn_readfirstlane(__ffsll(static_cast<long long>(beyond)) - 1);
+      g = g0 + static_cast<uint32_t>(l);
+      before += __builtin_amdgcn_readlane(incl - n, l);
+      break;
+    }
+    before += __builtin_amdgcn_readlane(incl, kLanes - 1);
+  }
+  // position in dst of the first free row of the group being read
+  int32_t base = -static_cast<int32_t>(q0 - before);
+  for (; g < groups && base < static_cast<int32_t>(count); ++g) {
+    const uint32_t w = g * kRowGroupWords + lane;
+    uint32_t bits = free_bits(a.occupied, w, rows);
+    const uint32_t n = __popc(bits);
+    const uint32_t incl = wave_inclusive_scan(n);
+    int32_t pos = base + static_cast<int32_t>(incl - n);
+    while (bits) {
+      if (pos >= 0 && pos < static_cast<int32_t>(count)) dst[pos] = w * 32 + (__ffs(static_cast<int>(bits)) - 1);
+      bits &= bits - 1;
+      ++pos;
+    }
+    base += static_cast<int32_t>(__builtin_amdgcn_readlane(incl, kLanes - 1));
+  }
+}
+
+// Row listed at position i of the current round (wave-uniform); never outside the genome array.
+__device__ __forceinline__ uint32_t row_at(const Smem &s, uint32_t i, const EvolveArgs &a) {
+  return min(static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(s.rows[i])), a.P + a.K - 1);
 }
 
 // Global batch -> GPU count.  In general: clamp to the window and lift for free to the
@@ -367,8 +465,9 @@ template <int R> struct Shape { static constexpr int kWaves = R > 16 ? ONES_WAVE
 template <int R>
 __global__ __launch_bounds__(Shape<R>::kWaves *kLanes) void init_kernel(EvolveArgs a) {
   extern __shared__ __align__(16) unsigned char smem_raw[];
-  const Smem s = carve(smem_raw, a.Jp, a.term_lds);
+  const Smem s = carve(smem_raw, a.Jp, a.term_lds, Shape<R>::kWaves);
   stage_table(a.tab, a.bk, s, a.Jp, a.term_lds);
+  __syncthreads();
   const int lane0 = threadIdx.x & (kLanes - 1);
   const uint32_t wave = __builtin_amdgcn_readfirstlane(blockIdx.x * Shape<R>::kWaves + (threadIdx.x >> 6));
   const uint32_t stride = gridDim.x * Shape<R>::kWaves;
@@ -395,17 +494,35 @@ __global__ __launch_bounds__(Shape<R>::kWaves *kLanes) void init_kernel(EvolveAr
 template <int R, bool kSameTable>
 __global__ __launch_bounds__(Shape<R>::kWaves *kLanes) void evolve_kernel(EvolveArgs a) {
   extern __shared__ __align__(16) unsigned char smem_raw[];
-  const Smem s = carve(smem_raw, a.Jp, a.term_lds);
-  stage_table(a.tab, a.bk, s, a.Jp, a.term_lds);
+  const Smem s = carve(smem_raw, a.Jp, a.term_lds, Shape<R>::kWaves);
   const int lane0 = threadIdx.x & (kLanes - 1);
-  const uint32_t wave_in_block = threadIdx.x >> 6;
-  const uint32_t wave = __builtin_amdgcn_readfirstlane(blockIdx.x * Shape<R>::kWaves + wave_in_block);
-  const uint32_t stride = gridDim.x * Shape<R>::kWaves;
+  const IndexLoads index_loads = index_free_rows_begin(a, lane0);
+  stage_table(a.tab, a.bk, s, a.Jp, a.term_lds);
+  index_free_rows_end(a, s, index_loads, lane0);
+  const uint32_t wave_in_block = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const uint32_t K = a.K;
   uint8_t *stash = s.stash + static_cast<size_t>(wave_in_block) * a.Jp;
-  const uint32_t items = kSameTable ? 2 * K : 3 * K;
-  for (uint32_t item = wave; item < items; item += stride) {
+  // This workgroup's share of the ranks 0..K-1: for each rank a pair, a mutant and, after a
+  // table change, a survivor.  Slot K + q of the new pool takes the q-th free row and the
+  // refreshed survivor of rank e the (3K + e)-th, so every share needs three runs of
+  // consecutive free rows, which one wave each lists into LDS, a round of kRound ranks at a time.
+  const uint32_t first = static_cast<uint32_t>(static_cast<uint64_t>(K) * blockIdx.x / gridDim.x);
+  const uint32_t last = static_cast<uint32_t>(static_cast<uint64_t>(K) * (blockIdx.x + 1) / gridDim.x);
+  for (uint32_t ra = first; ra < last; ra += kRound) {
+  const uint32_t n = min(kRound, last - ra);
+  if (ra != first) __syncthreads();                  // the previous round's rows have been used
+  if (wave_in_block == 0) list_free_rows(a, s, 2 * ra, 2 * n, s.rows, lane0);
+  if (wave_in_block == 1) list_free_rows(a, s, 2 * K + ra, n, s.rows + 2 * n, lane0);
+  if (!kSameTable && wave_in_block == 2) list_free_rows(a, s, 3 * K + ra, n, s.rows + 3 * n, lane0);
+  __syncthreads();
+  for (uint32_t i = threadIdx.x; i < (kSameTable ? 3 : 4) * n; i += blockDim.x) {
+    const uint32_t p = i < 2 * n ? K + 2 * ra + i : i < 3 * n ? 3 * K + ra + (i - 2 * n) : ra + (i - 3 * n);
+    a.row_of[p] = min(s.rows[i], a.P + a.K - 1);
+  }
+  for (uint32_t idx = wave_in_block; idx < (kSameTable ? 2 : 3) * n; idx += Shape<R>::kWaves) {
     const int lane = opaque(lane0);
+    // pairs first, then mutants, then survivors; item as numbered over the whole pool
+    const uint32_t item = idx < n ? ra + idx : idx < 2 * n ? K + ra + (idx - n) : 2 * K + ra + (idx - 2 * n);
     uint32_t c[R];
     if (item < K) {
       // uniform crossover: per gene the children swap their parents' genes with rate chi
@@ -436,12 +553,12 @@ __global__ __launch_bounds__(Shape<R>::kWaves *kLanes) void evolve_kernel(Evolve
         }
       }
       phase_fence();
-      const double f0 = finish<R>(a, s, a.row_of[p0], d0.r, c, lane);
+      const double f0 = finish<R>(a, s, row_at(s, 2 * idx, a), d0.r, c, lane);
       if (kSameTable && a.bk.nb != 0) drop_in_bucket(a, s, p0, f0, lane);
       phase_fence();
 #pragma unroll
       for (int i = 0; i < R; ++i) c[i] = (1u << stash[lane + kLanes * i]) >> 1;
-      const double f1 = finish<R>(a, s, a.row_of[p0 + 1], d1.r, c, lane);
+      const double f1 = finish<R>(a, s, row_at(s, 2 * idx + 1, a), d1.r, c, lane);
       if (kSameTable && a.bk.nb != 0) drop_in_bucket(a, s, p0 + 1, f1, lane);
     } else if (item < 2 * K) {
       // uniform mutation: each job redrawn with rate theta (k = 0 pre-empts it)
@@ -464,31 +581,32 @@ __global__ __launch_bounds__(Shape<R>::kWaves *kLanes) void evolve_kernel(Evolve
       }
       phase_fence();
       gpus_from_batches<R, false>(s, lane, c);
-      const double f = finish<R>(a, s, a.row_of[p], d.r, c, lane);
+      const double f = finish<R>(a, s, row_at(s, idx + n, a), d.r, c, lane);
       if (kSameTable && a.bk.nb != 0) drop_in_bucket(a, s, p, f, lane);
     } else {
-      // refresh: the survivor of rank p, projected onto the new job table, goes to a spare row
-      // (its old row is still being read as a parent by other waves)
+      // refresh: the survivor of rank p, projected onto the new job table, goes to one of the
+      // last K free rows (its old row is still being read as a parent by other waves)
       const uint32_t p = item - 2 * K;
       const Draw d = candidate_draw(a, p);
       load_genes<R>(a.genes + static_cast<size_t>(a.parent_row[p]) * a.Jp, lane, c);
       gpus_from_batches<R, false>(s, lane, c);
-      const uint32_t dst = a.spare_row[p];
-      finish<R>(a, s, dst, d.r, c, lane);
-      if (lane == 0) a.row_of[p] = dst;
+      finish<R>(a, s, row_at(s, idx + n, a), d.r, c, lane);
     }
+  }
   }
 }
 
 template <typename Kernel>
-hipError_t launch_persistent(Kernel k, EvolveArgs a, int waves, uint32_t items, int n_cus, hipStream_t s) {
+hipError_t launch_persistent(Kernel k, EvolveArgs a, int waves, uint32_t items, uint32_t max_blocks, int n_cus,
+                             hipStream_t s) {
   // the term table goes to LDS when it fits beside the rest
-  a.term_lds = (a.tab.term_E != 0 && smem_bytes(a.Jp, waves, a.tab.term_E) <= kLdsBudget) ? a.tab.term_E : 0u;
-  const size_t lds = smem_bytes(a.Jp, waves, a.term_lds);
+  const uint32_t rows = a.P + a.K;
+  a.term_lds = (a.tab.term_E != 0 && smem_bytes(a.Jp, waves, a.tab.term_E, rows) <= kLdsBudget) ? a.tab.term_E : 0u;
+  const size_t lds = smem_bytes(a.Jp, waves, a.term_lds, rows);
   // as many workgroups as can be resident (LDS- and wave-limited), at most one wave per item
   const size_t per_cu = std::max<size_t>(1, std::min<size_t>(kLdsBudget / lds, 32 / waves));
-  const uint32_t blocks = std::max<uint32_t>(1u, std::min<uint32_t>((items + waves - 1) / waves,
-                                                                    static_cast<uint32_t>(n_cus * per_cu)));
+  const uint32_t blocks = std::max<uint32_t>(
+      1u, std::min<uint32_t>({(items + waves - 1) / waves, static_cast<uint32_t>(n_cus * per_cu), max_blocks}));
   hipError_t rc = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize,
                                       static_cast<int>(lds));
   if (rc != hipSuccess) return rc;
@@ -499,9 +617,9 @@ hipError_t launch_persistent(Kernel k, EvolveArgs a, int waves, uint32_t items, 
 template <int R>
 hipError_t launch_rows(const EvolveArgs &a, bool same_table, int n_cus, hipStream_t s) {
   constexpr int kWaves = Shape<R>::kWaves;
-  if (a.t == 0) return launch_persistent(init_kernel<R>, a, kWaves, a.P, n_cus, s);
-  if (same_table) return launch_persistent(evolve_kernel<R, true>, a, kWaves, 2 * a.K, n_cus, s);
-  return launch_persistent(evolve_kernel<R, false>, a, kWaves, 3 * a.K, n_cus, s);
+  if (a.t == 0) return launch_persistent(init_kernel<R>, a, kWaves, a.P, a.P, n_cus, s);
+  if (same_table) return launch_persistent(evolve_kernel<R, true>, a, kWaves, 2 * a.K, a.K, n_cus, s);   // a share of the ranks each
+  return launch_persistent(evolve_kernel<R, false>, a, kWaves, 3 * a.K, a.K, n_cus, s);
 }
 
 template <int... Rs>

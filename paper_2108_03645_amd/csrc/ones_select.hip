@@ -274,53 +274,6 @@ __global__ __launch_bounds__(kBucketThreads) void bucket_select_kernel(const dou
   if (b == 0 && tid < 2) count_next[kMaxBuckets + tid] = 0;
 }
 
-// After a selection (which set the bits of the survivors' rows): every other row of the
-// P + K is free.  Free rows in ascending order: the first 3K go to the children and mutants of
-// the next pool (slots K..P-1), the last K are spares for survivors that must be refreshed
-// after a table change.  Each workgroup counts the free rows before its share of the bitmap by
-// itself (the bitmap is a few KB), so the workgroups need no synchronisation.
-constexpr int kFreeThreads = 256;
-__global__ __launch_bounds__(kFreeThreads) void free_rows_kernel(const uint32_t *occupied, uint32_t *occupied_other,
-                                                                uint32_t P, uint32_t K, uint32_t *row_of_next,
-                                                                uint32_t *spare_row) {
-  __shared__ uint32_t part[kFreeThreads];
-  const uint32_t tid = threadIdx.x, rows = P + K, words = (rows + 31) / 32;
-  const uint32_t w0 = blockIdx.x * kFreeThreads;                  // this workgroup: words w0 .. w0 + 255
-  auto free_bits_of = [&](uint32_t w) {
-    uint32_t f = ~occupied[w];
-    if (w == words - 1 && rows % 32 != 0) f &= (1u << (rows % 32)) - 1u;
-    return f;
-  };
-  uint32_t before = 0;
-  for (uint32_t w = tid; w < w0; w += kFreeThreads) before += __popc(free_bits_of(w));
-  const uint32_t mine = w0 + tid < words ? free_bits_of(w0 + tid) : 0u;
-  part[tid] = before;
-  __syncthreads();
-  for (uint32_t d = kFreeThreads / 2; d > 0; d >>= 1) {           // sum of `before` over the workgroup
-    if (tid < d) part[tid] += part[tid + d];
-    __syncthreads();
-  }
-  const uint32_t base = part[0];
-  __syncthreads();
-  part[tid] = __popc(mine);
-  __syncthreads();
-  for (uint32_t d = 1; d < kFreeThreads; d <<= 1) {               // inclusive scan of the word counts
-    const uint32_t add = tid >= d ? part[tid - d] : 0u;
-    __syncthreads();
-    part[tid] += add;
-    __syncthreads();
-  }
-  uint32_t q = base + part[tid] - __popc(mine);
-  uint32_t bits = mine;
-  while (bits) {
-    const uint32_t r = (w0 + tid) * 32 + (__ffs(static_cast<int>(bits)) - 1);
-    bits &= bits - 1;
-    if (q < 3 * K) row_of_next[K + q] = r; else spare_row[q - 3 * K] = r;
-    ++q;
-  }
-  if (w0 + tid < words) occupied_other[w0 + tid] = 0;             // ready for the next selection
-}
-
 __global__ void zero_words_kernel(uint32_t *words, uint32_t n) {
   const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) words[i] = 0;
@@ -421,14 +374,6 @@ hipError_t launch_reset_slots(int32_t *genes, const uint32_t *changed, uint32_t 
   const size_t n = static_cast<size_t>(P) * Jp;
   const uint32_t blocks = static_cast<uint32_t>(std::min<size_t>((n + 255) / 256, 65536));
   hipLaunchKernelGGL(reset_slots_kernel, dim3(blocks), dim3(256), 0, s, genes, changed, P, Jp);
-  return hipGetLastError();
-}
-
-hipError_t launch_free_rows(const uint32_t *occupied, uint32_t *occupied_other, uint32_t P, uint32_t K,
-                            uint32_t *row_of_next, uint32_t *spare_row, hipStream_t s) {
-  const uint32_t words = (P + K + 31) / 32;
-  hipLaunchKernelGGL(free_rows_kernel, dim3((words + kFreeThreads - 1) / kFreeThreads), dim3(kFreeThreads), 0, s,
-                     occupied, occupied_other, P, K, row_of_next, spare_row);
   return hipGetLastError();
 }
 
