@@ -47,6 +47,8 @@ struct ones_ref_ctx {
   int32_t *sel;            /* [K] */
   int      cur;
   int64_t  t;              /* generation counter; 0 = initial population */
+  int      sampling;       /* Alg. 1: remaining work drawn per generation */
+  double  *alpha, *beta, *processed, *Y_fixed;   /* Jn entries each */
 };
 
 static int g_threads = 1;
@@ -349,6 +351,107 @@ static void finish_slot(ones_ref_ctx *c, int32_t *dst, int p, int *g, uint32_t r
   for (int j = 0; j < c->Jp; ++j) row[j] = batch_of(g[j]);
 }
 
+/* ------------------------------------------------- probability sampling ---------- */
+/* Natural logarithm of a positive normal double, by the textbook route: x = m * 2^e with m
+ * in [sqrt(1/2), sqrt(2)), ln m = 2 artanh(s) with s = (m-1)/(m+1) = f/(2+f), f = m-1, and the
+ * artanh series s + s^3/3 + s^5/5 + ... cut after s^23/23 (|s| < 0.1716, so the next term is
+ * below 2e-20 of the first).  Every operation is a plain IEEE double operation in the order
+ * written, so that any other implementation of these lines gives the same bits.  ln 2 is
+ * split into a 32-bit head (e * head is exact) and a tail. */
+double ones_ref_log(double x) {
+  uint64_t bits;
+  memcpy(&bits, &x, sizeof bits);
+  int e = (int)((bits >> 52) & 0x7FF) - 1023;
+  bits = (bits & 0x000FFFFFFFFFFFFFull) | 0x3FF0000000000000ull;
+  double m;
+  memcpy(&m, &bits, sizeof m);
+  if (m > 1.4142135623730951) { m = m * 0.5; e = e + 1; }
+  double f = m - 1.0;
+  double s = f / (2.0 + f);
+  double z = s * s;
+  double p = 1.0 / 23.0;
+  for (int k = 21; k >= 3; k -= 2) p = p * z + 1.0 / (double)k;
+  double s2 = 2.0 * s;
+  double lm = s2 + s2 * (z * p);
+  double ef = (double)e;
+  return ef * 0.6931471803691238 + (ef * 1.9082149292705877e-10 + lm);
+}
+
+/* Gamma(shape, 1), shape >= 1, by Marsaglia and Tsang's method (ACM TOMS 26, 2000): with
+ * d = shape - 1/3 and c = 1/sqrt(9 d), draw x ~ N(0,1), v = (1 + c x)^3, and accept d*v when
+ * v > 0 and ln u < x^2/2 + d - d v + d ln v for a uniform u.  The normal deviate comes from
+ * the polar method (a point uniform in the unit disc, rejected outside).  Candidate draw
+ * n = 0, 1, ... takes its four random words from Philox with counter (n, j, t, which):
+ * words 0, 1 the point, words 2, 3 a 52-bit uniform.  After 64 rejected candidates the
+ * draw gives up and returns d (probability below 1e-30). */
+#define GAMMA_ATTEMPTS 64
+double ones_ref_gamma_draw(uint64_t seed, uint32_t j, uint32_t t, uint32_t which, double shape,
+                           int *attempts_out) {
+  const uint32_t key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)};
+  const double d = shape - 1.0 / 3.0;
+  const double c = 1.0 / sqrt(9.0 * d);
+  for (uint32_t n = 0; n < GAMMA_ATTEMPTS; ++n) {
+    if (attempts_out) *attempts_out = (int)n + 1;
+    const uint32_t ctr[4] = {n, j, t, which};
+    uint32_t w[4];
+    ones_ref_philox4x32_10(ctr, key, w);
+    const double u1 = ((double)w[0] + 0.5) * (1.0 / 2147483648.0) - 1.0;    /* in (-1, 1) */
+    const double u2 = ((double)w[1] + 0.5) * (1.0 / 2147483648.0) - 1.0;
+    const double s = u1 * u1 + u2 * u2;
+    if (s >= 1.0) continue;
+    const double x = u1 * sqrt((-2.0 * ones_ref_log(s)) / s);
+    const double t1 = 1.0 + c * x;
+    if (t1 <= 0.0) continue;
+    const double v = (t1 * t1) * t1;
+    const uint64_t k = ((uint64_t)w[2] << 20) | (uint64_t)(w[3] >> 12);
+    const double u = ((double)k + 0.5) * (1.0 / 4503599627370496.0);        /* in (0, 1) */
+    const double bound = ((0.5 * (x * x) + d) - d * v) + d * ones_ref_log(v);
+    if (ones_ref_log(u) < bound) return d * v;
+  }
+  return d;
+}
+
+/* rho ~ Be(alpha, beta) as Ga/(Ga + Gb) with independent Ga ~ Gamma(alpha), Gb ~ Gamma(beta);
+ * then Eq. 7.  The ratio 1/rho - 1 and the product are capped at the largest parameter. */
+double ones_ref_sampled_remaining(uint64_t seed, uint32_t j, uint32_t t, double alpha, double beta,
+                                  double processed, double *rho_out) {
+  const double ga = ones_ref_gamma_draw(seed, j, t, 1u, alpha, NULL);
+  const double gb = ones_ref_gamma_draw(seed, j, t, 2u, beta, NULL);
+  const double rho = ga / (ga + gb);
+  if (rho_out) *rho_out = rho;
+  double ratio = 1.0 / rho - 1.0;
+  if (ratio > MAX_PARAM) ratio = MAX_PARAM;
+  double y = processed * ratio;
+  if (y > MAX_PARAM) y = MAX_PARAM;
+  return y;
+}
+
+int ones_ref_set_progress(ones_ref_ctx *c, const double *alpha, const double *beta, const double *processed) {
+  if (!c) return ONES_REF_E_INVALID_ARG;
+  if (!alpha && !beta && !processed) {
+    if (c->sampling) for (int j = 0; j < c->Jn; ++j) c->tab[j].Y = c->Y_fixed[j];
+    c->sampling = 0;
+    return ONES_REF_OK;
+  }
+  if (!alpha || !beta || !processed) return ONES_REF_E_INVALID_ARG;
+  for (int j = 0; j < c->Jn; ++j) {
+    if (!isfinite(alpha[j]) || !isfinite(beta[j]) || !isfinite(processed[j])) return ONES_REF_E_NONFINITE;
+    if (alpha[j] < 1.0 || beta[j] < 1.0 || processed[j] < 0.0) return ONES_REF_E_INVALID_ARG;
+    if (alpha[j] > MAX_PARAM || beta[j] > MAX_PARAM || processed[j] > MAX_PARAM) return ONES_REF_E_BOUNDS;
+  }
+  for (int j = 0; j < c->Jn; ++j) {
+    c->alpha[j] = alpha[j]; c->beta[j] = beta[j]; c->processed[j] = processed[j];
+  }
+  c->sampling = 1;
+  return ONES_REF_OK;
+}
+
+int ones_ref_export_remaining(ones_ref_ctx *c, double *remaining_out) {
+  if (!c || !remaining_out) return ONES_REF_E_INVALID_ARG;
+  for (int j = 0; j < c->Jn; ++j) remaining_out[j] = c->tab[j].Y;
+  return ONES_REF_OK;
+}
+
 /* ------------------------------------------------------------- public ------------ */
 int ones_ref_init(ones_ref_ctx **out, const ones_ref_config *cfg, const ones_ref_jobs *jobs) {
   if (!out) return ONES_REF_E_INVALID_ARG;
@@ -368,6 +471,12 @@ int ones_ref_init(ones_ref_ctx **out, const ones_ref_config *cfg, const ones_ref
   c->genes[1] = (int32_t *)calloc(n, sizeof(int32_t));
   c->fit = (double *)calloc((size_t)c->P, sizeof(double));
   c->sel = (int32_t *)calloc((size_t)c->K, sizeof(int32_t));
+  size_t jn = (size_t)(c->Jn > 0 ? c->Jn : 1);
+  c->alpha = (double *)calloc(jn, sizeof(double));
+  c->beta = (double *)calloc(jn, sizeof(double));
+  c->processed = (double *)calloc(jn, sizeof(double));
+  c->Y_fixed = (double *)calloc(jn, sizeof(double));
+  for (int j = 0; j < c->Jn; ++j) c->Y_fixed[j] = c->tab[j].Y;
   c->cur = 0; c->t = 0;
   /* initial population: random genomes, repaired, scored, ranked */
 #pragma omp parallel for num_threads(g_threads) schedule(static)
@@ -393,6 +502,7 @@ int ones_ref_set_jobs(ones_ref_ctx *c, const ones_ref_jobs *jobs) {
   }
   free(c->tab);
   c->tab = tab;
+  for (int j = 0; j < c->Jn; ++j) c->Y_fixed[j] = tab[j].Y;
   return ONES_REF_OK;
 }
 
@@ -403,6 +513,12 @@ int ones_ref_generation(ones_ref_ctx *c, int32_t n_generations) {
     const int32_t *prev = c->genes[c->cur];
     int32_t *next = c->genes[c->cur ^ 1];
     uint32_t t = (uint32_t)(c->t + 1);
+    if (c->sampling) {               /* Alg. 1: one draw of every job's progress per selection */
+      uint64_t seed = ((uint64_t)c->key[1] << 32) | c->key[0];
+      for (int j = 0; j < c->Jn; ++j)
+        c->tab[j].Y = ones_ref_sampled_remaining(seed, (uint32_t)j, t, c->alpha[j], c->beta[j],
+                                                 c->processed[j], NULL);
+    }
 #pragma omp parallel for num_threads(g_threads) schedule(static)
     for (int p = 0; p < c->P; ++p) {
       int g[MAX_SLOTS], pa, pb; uint32_t r;
@@ -439,7 +555,8 @@ int ones_ref_export(ones_ref_ctx *c, int32_t *genes, double *fit, int32_t *sel, 
 
 void ones_ref_destroy(ones_ref_ctx *c) {
   if (!c) return;
-  free(c->tab); free(c->genes[0]); free(c->genes[1]); free(c->fit); free(c->sel); free(c);
+  free(c->tab); free(c->genes[0]); free(c->genes[1]); free(c->fit); free(c->sel);
+  free(c->alpha); free(c->beta); free(c->processed); free(c->Y_fixed); free(c);
 }
 
 int ones_ref_compose_slot(ones_ref_ctx *c, int32_t p, int32_t *genes_out, uint32_t *r_out,

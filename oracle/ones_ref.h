@@ -15,6 +15,13 @@
  *   compose (crossover, mutation, init): complementarity of children, coin
  *                            frequencies, chi-square on redraws and parent ranks,
  *                            theta = chi = 0 and chi = 1 special cases.
+ *   ones_ref_log           : the C library's log within 2 ulp over the whole range.
+ *   ones_ref_gamma_draw    : mean = variance = shape, Kolmogorov-Smirnov against the
+ *                            gamma distribution function, shape 1 = exponential.
+ *   ones_ref_sampled_remaining : Beta mean alpha/(alpha+beta) and variance
+ *                            alpha*beta/((alpha+beta)^2 (alpha+beta+1)), KS against the
+ *                            Beta distribution function, Be(1,1) uniform,
+ *                            E[1/rho - 1] = beta/(alpha-1), a Python transcription.
  *   scheduling quality against the paper's JCT numbers: parity unpinned (the paper's
  *                            trace, jobs and comparison schedulers do not exist here).
  */
@@ -66,7 +73,26 @@ int  ones_ref_padded_jobs(int32_t n_slots);     /* Jp = 64*ceil(max(n,1)/64) */
 void ones_ref_set_threads(int n);               /* candidates split over n OpenMP threads */
 int  ones_ref_get_threads(void);
 
+/* Probability sampling (Alg. 1, Eq. 7).  HOST arrays of n_slots entries: alpha_j, beta_j
+ * (each in [1, 1e100]: the thresholded parameters of the progress distribution Be_j) and
+ * the samples job j has processed (in [0, 1e100]).  From the next generation on, every
+ * generation first draws rho_j ~ Be(alpha_j, beta_j) for every slot and scores the whole
+ * pool with Y_j = processed_j * (1/rho_j - 1).  Three NULL pointers switch back to the
+ * job table's fixed remaining work. */
+int  ones_ref_set_progress(ones_ref_ctx *ctx, const double *alpha, const double *beta,
+                           const double *processed);
+/* the remaining work Y_j (n_slots entries) the last generation was scored with */
+int  ones_ref_export_remaining(ones_ref_ctx *ctx, double *remaining_out);
+
 /* single steps, exposed so that tests can pin them one at a time */
+double ones_ref_log(double x);                  /* natural logarithm of a positive normal number */
+/* Gamma(shape, 1) draw number `which` (1 or 2) of slot j in generation t, shape >= 1;
+ * attempts_out (may be NULL) receives the number of candidate draws used */
+double ones_ref_gamma_draw(uint64_t seed, uint32_t j, uint32_t t, uint32_t which, double shape,
+                           int *attempts_out);
+/* Eq. 7 with rho ~ Be(alpha, beta); rho_out may be NULL */
+double ones_ref_sampled_remaining(uint64_t seed, uint32_t j, uint32_t t, double alpha, double beta,
+                                  double processed, double *rho_out);
 void ones_ref_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]);
 /* genes: n_slots int32 batch sizes (0 or a power of two), repaired in place with
  * rotation r in [0,Jp); fill_rounds_out (may be NULL) receives the number of fill rounds */

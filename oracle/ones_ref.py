@@ -69,8 +69,37 @@ def lib():
                                             C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
         L.ones_ref_initial_genome.argtypes = [C.POINTER(_Config), C.POINTER(_Jobs), C.c_int32,
                                               C.c_void_p, C.POINTER(C.c_uint32)]
+        L.ones_ref_set_progress.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.ones_ref_export_remaining.argtypes = [C.c_void_p, C.c_void_p]
+        L.ones_ref_log.argtypes = [C.c_double]
+        L.ones_ref_log.restype = C.c_double
+        L.ones_ref_gamma_draw.argtypes = [C.c_uint64, C.c_uint32, C.c_uint32, C.c_uint32, C.c_double,
+                                          C.POINTER(C.c_int)]
+        L.ones_ref_gamma_draw.restype = C.c_double
+        L.ones_ref_sampled_remaining.argtypes = [C.c_uint64, C.c_uint32, C.c_uint32, C.c_double, C.c_double,
+                                                 C.c_double, C.POINTER(C.c_double)]
+        L.ones_ref_sampled_remaining.restype = C.c_double
         _lib = L
     return _lib
+
+
+def log(x: float) -> float:
+    return lib().ones_ref_log(float(x))
+
+
+def gamma_draw(seed, j, t, which, shape):
+    """(value, candidate draws used)"""
+    n = C.c_int(0)
+    v = lib().ones_ref_gamma_draw(int(seed), int(j), int(t), int(which), float(shape), C.byref(n))
+    return v, n.value
+
+
+def sampled_remaining(seed, j, t, alpha, beta, processed):
+    """(Y, rho) of Eq. 7 for slot j in generation t"""
+    rho = C.c_double(0.0)
+    y = lib().ones_ref_sampled_remaining(int(seed), int(j), int(t), float(alpha), float(beta),
+                                         float(processed), C.byref(rho))
+    return y, rho.value
 
 
 class RefError(RuntimeError):
@@ -164,6 +193,22 @@ class RefSearch:
 
     def generation(self, n=1):
         _check(lib().ones_ref_generation(self._h, int(n)))
+
+    def set_progress(self, alpha=None, beta=None, processed=None):
+        """Alg. 1: per-slot Be(alpha, beta) and processed samples; all None switches it off."""
+        if alpha is None and beta is None and processed is None:
+            _check(lib().ones_ref_set_progress(self._h, None, None, None))
+            return
+        arrs = [np.ascontiguousarray(x, np.float64) for x in (alpha, beta, processed)]
+        if any(a.shape != (self.n_slots,) for a in arrs):
+            raise ValueError("alpha, beta, processed: one entry per slot")
+        _check(lib().ones_ref_set_progress(self._h, *[a.ctypes.data for a in arrs]))
+
+    def export_remaining(self):
+        y = np.zeros(self.n_slots, np.float64)
+        if self.n_slots:
+            _check(lib().ones_ref_export_remaining(self._h, y.ctypes.data))
+        return y
 
     def best(self):
         b = np.zeros(self.n_slots, np.int32); g = np.zeros(self.n_slots, np.int32)

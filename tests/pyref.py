@@ -162,3 +162,60 @@ def exact_objective(jobs, genes):
         T = Fraction(float(jobs.remaining[j])) / X
         total += T * g
     return total
+
+
+# ---- probability sampling (Alg. 1, Eq. 7): second implementation with Python floats ----
+import math as _math
+import struct as _struct
+
+LN2_HEAD = 0.6931471803691238          # ln 2 rounded to 32 significant bits
+LN2_TAIL = 1.9082149292705877e-10      # ln 2 - LN2_HEAD
+
+
+def series_log(x):
+    """ln x = e ln 2 + 2 artanh((m-1)/(m+1)), series cut after the s^23 term."""
+    bits = _struct.unpack("<Q", _struct.pack("<d", x))[0]
+    e = ((bits >> 52) & 0x7FF) - 1023
+    m = _struct.unpack("<d", _struct.pack("<Q", (bits & ((1 << 52) - 1)) | (1023 << 52)))[0]
+    if m > 1.4142135623730951:
+        m, e = m * 0.5, e + 1
+    f = m - 1.0
+    s = f / (2.0 + f)
+    z = s * s
+    p = 1.0 / 23.0
+    for k in range(21, 2, -2):
+        p = p * z + 1.0 / k
+    s2 = 2.0 * s
+    lm = s2 + s2 * (z * p)
+    return e * LN2_HEAD + (e * LN2_TAIL + lm)
+
+
+def gamma_draw(seed, j, t, which, shape):
+    """Marsaglia-Tsang with a polar normal; candidate n reads Philox counter (n, j, t, which)."""
+    key = (seed & M32, seed >> 32)
+    d = shape - 1.0 / 3.0
+    c = 1.0 / _math.sqrt(9.0 * d)
+    for n in range(64):
+        w = philox4x32_10((n, j, t, which), key)
+        u1 = (w[0] + 0.5) * 2.0 ** -31 - 1.0
+        u2 = (w[1] + 0.5) * 2.0 ** -31 - 1.0
+        s = u1 * u1 + u2 * u2
+        if s >= 1.0:
+            continue
+        x = u1 * _math.sqrt((-2.0 * series_log(s)) / s)
+        t1 = 1.0 + c * x
+        if t1 <= 0.0:
+            continue
+        v = (t1 * t1) * t1
+        u = (((w[2] << 20) | (w[3] >> 12)) + 0.5) * 2.0 ** -52
+        if series_log(u) < ((0.5 * (x * x) + d) - d * v) + d * series_log(v):
+            return d * v, n + 1
+    return d, 64
+
+
+def sampled_remaining(seed, j, t, alpha, beta, processed, cap=1e100):
+    ga, _ = gamma_draw(seed, j, t, 1, alpha)
+    gb, _ = gamma_draw(seed, j, t, 2, beta)
+    rho = ga / (ga + gb)
+    ratio = min(1.0 / rho - 1.0, cap)
+    return min(processed * ratio, cap), rho
