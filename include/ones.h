@@ -93,6 +93,25 @@ int ones_init(ones_ctx **out, const ones_config *cfg, const ones_jobs *jobs,
  * generation counter keeps running.  Synchronises the stream. */
 int ones_set_jobs(ones_ctx *ctx, const ones_jobs *jobs);
 
+/* Probability sampling (Alg. 1, Eq. 7): instead of a fixed remaining work, every generation
+ * from the next one on first draws the progress rho_j ~ Be(alpha_j, beta_j) of every slot
+ * and scores the whole pool, survivors included, with Y_j = processed_j * (1/rho_j - 1),
+ * capped at ONES_MAX_PARAM.  alpha, beta, processed: HOST arrays of n_slots entries, copied
+ * during the call; alpha_j, beta_j in [1, ONES_MAX_PARAM] (the thresholded parameters of
+ * Section 3.2.1), processed_j (samples job j has processed) in [0, ONES_MAX_PARAM]; entries
+ * of empty slots are checked too.  The draw of slot j in generation t is a function of
+ * (seed, j, t) only: rho = Ga / (Ga + Gb) with Marsaglia-Tsang gamma deviates fed by
+ * Philox4x32-10 counters (n, j, t, 1) and (n, j, t, 2), n = 0, 1, ... the candidate number.
+ * The values persist across ones_set_jobs.  Three NULL pointers switch back to the job
+ * table's remaining work.  Errors: ONES_E_INVALID_ARG (only some pointers NULL, alpha or
+ * beta below 1, processed negative), ONES_E_NONFINITE, ONES_E_BOUNDS.  Synchronises. */
+int ones_set_progress(ones_ctx *ctx, const double *alpha, const double *beta,
+                      const double *processed);
+
+/* The remaining work Y_j the last generation was scored with (HOST array of n_slots
+ * entries): the job table's, or the last draw under ones_set_progress.  Synchronises. */
+int ones_export_remaining(ones_ctx *ctx, double *remaining_out);
+
 /* Runs n_generations >= 0 generations (compose, repair, score, select), asynchronously
  * on the stream. */
 int ones_generation(ones_ctx *ctx, int32_t n_generations);

@@ -11,7 +11,8 @@ CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB = os.path.join(HERE, "libones.so")
 # (source, object, extra flags); the evolve kernel is built once per group of eight row counts
-UNITS = [("ones_api.hip", "ones_api.o", []), ("ones_select.hip", "ones_select.o", [])] + [
+UNITS = [("ones_api.hip", "ones_api.o", []), ("ones_select.hip", "ones_select.o", []),
+         ("ones_sample.hip", "ones_sample.o", [])] + [
     ("ones_evolve.hip", f"ones_evolve_{g}.o", [f"-DONES_ROW_GROUP={g}"]) for g in range(4)]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",

@@ -30,7 +30,7 @@ size_t align_up(size_t v) { return (v + 255) & ~static_cast<size_t>(255); }
 
 struct Layout {
   size_t genes, fit_row, row_of[2], parent_row[2], occupied[2], sel, keys, idx, split, thresh, bcount[2], bkeys, bidx, skeys, sidx, sbucket, pkeys, pidx, cstart, cmax, info, abl, cc, d, Y, terms;
-  size_t rawinfo, changed, ra, rc, rd, rY, best_batch, best_gpus, best_fit, total;
+  size_t rawinfo, changed, ra, rc, rd, rY, alpha, beta, processed, best_batch, best_gpus, best_fit, total;
 };
 
 // Buckets: about 16 survivors each, at most kMaxBuckets.  A bucket stores eight times its fair
@@ -84,6 +84,7 @@ Layout make_layout(uint32_t P, uint32_t Jp) {
   L.terms = take(static_cast<size_t>(Jp) * kMaxTermEntries * 8);
   L.rawinfo = take(Jp * 4); L.changed = take(Jp * 4);
   L.ra = take(Jp * 8); L.rc = take(Jp * 8); L.rd = take(Jp * 8); L.rY = take(Jp * 8);
+  L.alpha = take(Jp * 8); L.beta = take(Jp * 8); L.processed = take(Jp * 8);
   L.best_batch = take(Jp * 4); L.best_gpus = take(Jp * 4); L.best_fit = take(8);
   L.total = off;
   return L;
@@ -165,6 +166,7 @@ struct ones_ctx {
   Layout L;
   int cur;                    // which row_of array describes the current generation
   bool table_changed;         // job table replaced since the current generation was computed
+  bool sampling;              // remaining work drawn per generation (Alg. 1) instead of the table's
   BucketPlan bp;              // nb == 0: pool small enough for the single-chunk sort
   int bucket_phase;           // which counter set the next bucketed generation fills
   int n_cus;
@@ -243,9 +245,13 @@ int run_generation(ones_ctx *c, uint32_t t) {
   a.key0 = static_cast<uint32_t>(c->cfg.seed);
   a.key1 = static_cast<uint32_t>(c->cfg.seed >> 32);
   a.t = t; a.T_mut = c->T_mut; a.T_x = c->T_x;
-  // quantile buckets: only when the survivors reappear unchanged (same table, not generation 0)
+  // same table: the survivors are fixed points of the repair.  Under probability sampling their
+  // scores still change with every draw of the remaining work, so they are scored again.
   const bool same_table = t != 0 && !c->table_changed;
-  const bool buckets = same_table && c->bp.nb != 0;
+  const bool sampled = t != 0 && c->sampling;
+  a.rescore = same_table && sampled ? 1u : 0u;
+  // quantile buckets: only when the survivors reappear with the scores they had
+  const bool buckets = same_table && !sampled && c->bp.nb != 0;
   a.bk.nb = buckets ? c->bp.nb : 0;
   a.bk.seg = c->bp.seg;
   a.bk.split = a.bk.split_next = c->at<uint64_t>(c->L.split);
@@ -266,6 +272,10 @@ int run_generation(ones_ctx *c, uint32_t t) {
   rp.occupied = c->at<uint32_t>(c->L.occupied[next]);
   int rc;
   if ((rc = timed(c, c->evolve_ev, c->evolve_used, true))) return rc;
+  if (sampled) {
+    const Progress pr{c->at<double>(c->L.alpha), c->at<double>(c->L.beta), c->at<double>(c->L.processed)};
+    HIP_TRY(launch_sample_remaining(pr, a.tab, c->Jn, c->Jp, a.key0, a.key1, t, c->stream));
+  }
   HIP_TRY(launch_evolve(a, static_cast<int>(c->R), same_table, c->n_cus, c->stream));
   if ((rc = timed(c, c->evolve_ev, c->evolve_used, false))) return rc;
   if ((rc = timed(c, c->select_ev, c->select_used, true))) return rc;
@@ -330,6 +340,7 @@ int ones_init(ones_ctx **out, const ones_config *cfg, const ones_jobs *jobs, voi
   c->L = L;
   c->cur = 0; c->t = 0;
   c->table_changed = false;
+  c->sampling = false;
   c->bp = bucket_plan(c->P);
   c->bucket_phase = 0;
   c->ids = h.id;
@@ -367,6 +378,44 @@ int ones_set_jobs(ones_ctx *c, const ones_jobs *jobs) {
   if ((rc = upload_table(c, h, any ? &changed : nullptr))) return rc;
   c->ids = h.id;
   c->table_changed = true;
+  return ONES_OK;
+}
+
+int ones_set_progress(ones_ctx *c, const double *alpha, const double *beta, const double *processed) {
+  if (!c) return ONES_E_INVALID_ARG;
+  if (!alpha && !beta && !processed) {
+    if (c->sampling) {
+      // back to the table's remaining work (still staged on the device); every score is stale
+      HIP_TRY(hipMemcpyAsync(c->ws + c->L.Y, c->ws + c->L.rY, static_cast<size_t>(c->Jp) * 8,
+                             hipMemcpyDeviceToDevice, c->stream));
+      HIP_TRY(launch_build_terms(c->table(), c->Jp, c->stream));
+      HIP_TRY(hipStreamSynchronize(c->stream));
+      c->sampling = false;
+      c->table_changed = true;
+    }
+    return ONES_OK;
+  }
+  if (!alpha || !beta || !processed) return ONES_E_INVALID_ARG;
+  for (uint32_t j = 0; j < c->Jn; ++j) {
+    if (!std::isfinite(alpha[j]) || !std::isfinite(beta[j]) || !std::isfinite(processed[j])) return ONES_E_NONFINITE;
+    if (alpha[j] < 1.0 || beta[j] < 1.0 || processed[j] < 0.0) return ONES_E_INVALID_ARG;
+    if (alpha[j] > ONES_MAX_PARAM || beta[j] > ONES_MAX_PARAM || processed[j] > ONES_MAX_PARAM) return ONES_E_BOUNDS;
+  }
+  std::vector<double> ha(c->Jp, 1.0), hb(c->Jp, 1.0), hp(c->Jp, 0.0);
+  for (uint32_t j = 0; j < c->Jn; ++j) { ha[j] = alpha[j]; hb[j] = beta[j]; hp[j] = processed[j]; }
+  const size_t n8 = static_cast<size_t>(c->Jp) * 8;
+  HIP_TRY(hipMemcpyAsync(c->ws + c->L.alpha, ha.data(), n8, hipMemcpyHostToDevice, c->stream));
+  HIP_TRY(hipMemcpyAsync(c->ws + c->L.beta, hb.data(), n8, hipMemcpyHostToDevice, c->stream));
+  HIP_TRY(hipMemcpyAsync(c->ws + c->L.processed, hp.data(), n8, hipMemcpyHostToDevice, c->stream));
+  HIP_TRY(hipStreamSynchronize(c->stream));     // the staging vectors may go away now
+  c->sampling = true;
+  return ONES_OK;
+}
+
+int ones_export_remaining(ones_ctx *c, double *remaining_out) {
+  if (!c || !remaining_out) return ONES_E_INVALID_ARG;
+  HIP_TRY(hipStreamSynchronize(c->stream));
+  if (c->Jn) HIP_TRY(hipMemcpy(remaining_out, c->ws + c->L.Y, static_cast<size_t>(c->Jn) * 8, hipMemcpyDeviceToHost));
   return ONES_OK;
 }
 

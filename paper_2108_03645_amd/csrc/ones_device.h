@@ -1,5 +1,5 @@
 // Internal interface between the host side of libones (ones_api.hip) and its kernels
-// (ones_evolve.hip, ones_select.hip).  Not installed; the public boundary is include/ones.h.
+// (ones_evolve.hip, ones_select.hip, ones_sample.hip).  Not installed; the public boundary is include/ones.h.
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -14,6 +14,27 @@ constexpr int kMaxTermEntries = 22; // waiting + GPU counts 2^0 .. 2^20
 #define ONES_SORT_CHUNK 4096
 #endif
 constexpr int kSortChunk = ONES_SORT_CHUNK;   // keys sorted per workgroup in LDS
+
+// Philox4x32-10 (Salmon, Moraes, Dror, Shaw, SC'11).
+struct Words { uint32_t w[4]; };
+
+__device__ __forceinline__ Words philox4x32_10(uint32_t x0, uint32_t x1, uint32_t x2, uint32_t x3,
+                                               uint32_t k0, uint32_t k1) {
+#pragma unroll
+  for (int round = 0; round < 10; ++round) {
+    const uint64_t pa = static_cast<uint64_t>(x0) * 0xD2511F53ull;
+    const uint64_t pb = static_cast<uint64_t>(x2) * 0xCD9E8D57ull;
+    const uint32_t n0 = static_cast<uint32_t>(pb >> 32) ^ x1 ^ k0;
+    const uint32_t n2 = static_cast<uint32_t>(pa >> 32) ^ x3 ^ k1;
+    x1 = static_cast<uint32_t>(pb);
+    x3 = static_cast<uint32_t>(pa);
+    x0 = n0;
+    x2 = n2;
+    k0 += 0x9E3779B9u;
+    k1 += 0xBB67AE85u;
+  }
+  return Words{{x0, x1, x2, x3}};
+}
 
 // Per-slot constants derived from the job table, structure of arrays over the padded
 // slots (column = slot mod 64, row = slot div 64).  A gene is handled on the device as
@@ -83,6 +104,7 @@ struct EvolveArgs {
   uint32_t       key0, key1;  // seed
   uint32_t       t;           // generation counter (0 = initial population)
   uint32_t       T_mut, T_x;  // rate thresholds on a 32-bit word
+  uint32_t       rescore;     // the survivors' scores are stale (remaining work redrawn): score them again
   uint32_t       term_lds;    // set by the launcher: entries per job of the term table in LDS, 0 = none
   BucketArgs     bk;
 };
@@ -95,6 +117,17 @@ struct RowPlan {
   uint32_t       *occupied;     // bitmap over the P + K rows, zero on entry; survivors' rows get set
 };
 
+// T_j c_j of a job at GPU-count code e (0 = waiting, e = 1 + log2 of the GPU count): Eq. 3
+// with T = Y / X (Eq. 5) and the iteration time a*b + c*log2(g) + d at the job's local batch
+// b = 2^blexp; abl = a * b.  Same operations in the same order wherever a term is computed.
+__device__ __forceinline__ double term_of(double abl, double cc, double d, double Y, uint32_t blexp, uint32_t e) {
+  if (e == 0) return 0.0;
+  const double lg = static_cast<double>(e - 1);
+  const double inv_bl = __hiloint2double(static_cast<int>((1023u - blexp) << 20), 0);
+  const double t = (abl + cc * lg) + d;
+  return (Y * t) * inv_bl;
+}
+
 struct RawJobs {              // uploaded by the host after validation, [Jp] each
   const uint32_t *rawinfo;    // bits 0-4 lo, 5-9 hi, 10-14 mu, 15 active
   const double   *a, *c, *d, *Y;
@@ -103,6 +136,14 @@ struct RawJobs {              // uploaded by the host after validation, [Jp] eac
 // launchers (each returns the hipGetLastError of its launch)
 hipError_t launch_prepare_table(const RawJobs &raw, const JobTable &tab, uint32_t Jp, hipStream_t s);
 hipError_t launch_build_terms(const JobTable &tab, uint32_t Jp, hipStream_t s);
+// Remaining work of slot j under probability sampling (Alg. 1, Eq. 7) for generation t:
+// tab.Y[j] = processed[j] * (1/rho - 1), rho ~ Be(alpha[j], beta[j]), for j < Jn; then the
+// slot's entries of the term table.
+struct Progress {
+  const double *alpha, *beta, *processed;   // [Jp]
+};
+hipError_t launch_sample_remaining(const Progress &pr, const JobTable &tab, uint32_t Jn, uint32_t Jp,
+                                   uint32_t key0, uint32_t key1, uint32_t t, hipStream_t s);
 hipError_t launch_reset_slots(int32_t *genes, const uint32_t *changed, uint32_t P, uint32_t Jp, hipStream_t s);
 // same_table: the job table is the one the previous generation was repaired and scored with
 hipError_t launch_evolve_group0(const EvolveArgs &a, int rows, bool same_table, int n_cus, hipStream_t s);

@@ -39,27 +39,6 @@ template <typename T> __device__ __forceinline__ void pin(T &x) { asm volatile("
 __device__ __forceinline__ int opaque(int v) { asm volatile("" : "+v"(v)); return v; }
 
 // ------------------------------------------------------------------ RNG ------------
-// Philox4x32-10 (Salmon, Moraes, Dror, Shaw, SC'11).
-struct Words { uint32_t w[4]; };
-
-__device__ __forceinline__ Words philox4x32_10(uint32_t x0, uint32_t x1, uint32_t x2, uint32_t x3,
-                                               uint32_t k0, uint32_t k1) {
-#pragma unroll
-  for (int round = 0; round < 10; ++round) {
-    const uint64_t pa = static_cast<uint64_t>(x0) * 0xD2511F53ull;
-    const uint64_t pb = static_cast<uint64_t>(x2) * 0xCD9E8D57ull;
-    const uint32_t n0 = static_cast<uint32_t>(pb >> 32) ^ x1 ^ k0;
-    const uint32_t n2 = static_cast<uint32_t>(pa >> 32) ^ x3 ^ k1;
-    x1 = static_cast<uint32_t>(pb);
-    x3 = static_cast<uint32_t>(pa);
-    x0 = n0;
-    x2 = n2;
-    k0 += 0x9E3779B9u;
-    k1 += 0xBB67AE85u;
-  }
-  return Words{{x0, x1, x2, x3}};
-}
-
 __device__ __forceinline__ uint32_t bounded(uint32_t w, uint32_t n) { return __umulhi(w, n); }
 
 // Per-candidate draw: ranks of the two parents among the K survivors and the rotation of
@@ -488,7 +467,7 @@ __global__ __launch_bounds__(Shape<R>::kWaves *kLanes) void init_kernel(EvolveAr
 }
 
 // One generation.  Work items: K crossover pairs, K mutants and, after a table change, the K
-// survivors to refresh.  kSameTable: the job table has not changed since the previous
+// survivors to refresh (or, when only the remaining work changed, to score again).  kSameTable: the job table has not changed since the previous
 // generation was repaired and scored, so a survivor is a fixed point of the repair with the
 // same score: it stays in its row untouched, and stored genes need no clamp.
 template <int R, bool kSameTable>
@@ -519,7 +498,8 @@ __global__ __launch_bounds__(Shape<R>::kWaves *kLanes) void evolve_kernel(Evolve
     const uint32_t p = i < 2 * n ? K + 2 * ra + i : i < 3 * n ? 3 * K + ra + (i - 2 * n) : ra + (i - 3 * n);
     a.row_of[p] = min(s.rows[i], a.P + a.K - 1);
   }
-  for (uint32_t idx = wave_in_block; idx < (kSameTable ? 2 : 3) * n; idx += Shape<R>::kWaves) {
+  const uint32_t kinds = (!kSameTable || a.rescore) ? 3u : 2u;
+  for (uint32_t idx = wave_in_block; idx < kinds * n; idx += Shape<R>::kWaves) {
     const int lane = opaque(lane0);
     // pairs first, then mutants, then survivors; item as numbered over the whole pool
     const uint32_t item = idx < n ? ra + idx : idx < 2 * n ? K + ra + (idx - n) : 2 * K + ra + (idx - 2 * n);
@@ -583,6 +563,14 @@ __global__ __launch_bounds__(Shape<R>::kWaves *kLanes) void evolve_kernel(Evolve
       gpus_from_batches<R, false>(s, lane, c);
       const double f = finish<R>(a, s, row_at(s, idx + n, a), d.r, c, lane);
       if (kSameTable && a.bk.nb != 0) drop_in_bucket(a, s, p, f, lane);
+    } else if (kSameTable) {
+      // the remaining work was drawn anew: the survivor of this rank keeps its genome and row
+      // and only gets its score under the new draw
+      const uint32_t row = a.parent_row[item - 2 * K];
+      load_genes<R>(a.genes + static_cast<size_t>(row) * a.Jp, lane, c);
+      gpus_from_batches<R, true>(s, lane, c);
+      const double f = score<R>(c, s, a.term_lds, lane);
+      if (lane == 0) a.fit_row[row] = f;
     } else {
       // refresh: the survivor of rank p, projected onto the new job table, goes to one of the
       // last K free rows (its old row is still being read as a parent by other waves)
@@ -618,7 +606,8 @@ template <int R>
 hipError_t launch_rows(const EvolveArgs &a, bool same_table, int n_cus, hipStream_t s) {
   constexpr int kWaves = Shape<R>::kWaves;
   if (a.t == 0) return launch_persistent(init_kernel<R>, a, kWaves, a.P, a.P, n_cus, s);
-  if (same_table) return launch_persistent(evolve_kernel<R, true>, a, kWaves, 2 * a.K, a.K, n_cus, s);   // a share of the ranks each
+  if (same_table)
+    return launch_persistent(evolve_kernel<R, true>, a, kWaves, (a.rescore ? 3 : 2) * a.K, a.K, n_cus, s);   // a share of the ranks each
   return launch_persistent(evolve_kernel<R, false>, a, kWaves, 3 * a.K, a.K, n_cus, s);
 }
 

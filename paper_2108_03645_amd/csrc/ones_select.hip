@@ -321,14 +321,7 @@ __global__ void build_terms_kernel(JobTable tab, uint32_t Jp) {
   if (q >= Jp * E) return;
   const uint32_t lane = q % kLanes, e = (q / kLanes) % E, row = q / (kLanes * E);
   const uint32_t j = row * kLanes + lane;
-  double term = 0.0;
-  if (e != 0) {
-    const double lg = static_cast<double>(e - 1);
-    const double inv_bl = __hiloint2double(static_cast<int>((1023u - info_blexp(tab.info[j])) << 20), 0);
-    const double t = (tab.abl[j] + tab.cc[j] * lg) + tab.d[j];
-    term = (tab.Y[j] * t) * inv_bl;
-  }
-  tab.terms[q] = term;
+  tab.terms[q] = term_of(tab.abl[j], tab.cc[j], tab.d[j], tab.Y[j], info_blexp(tab.info[j]), e);
 }
 
 __global__ void reset_slots_kernel(int32_t *genes, const uint32_t *changed, uint32_t P, uint32_t Jp) {

@@ -35,7 +35,8 @@ _JOB_DTYPES = {"job_id": np.int64, "active": np.uint8, "bmin": np.int32, "bmax":
                "remaining": np.float64}
 
 EXPORTS = ["ones_workspace_bytes", "ones_init", "ones_set_jobs", "ones_generation", "ones_best",
-           "ones_export", "ones_padded_jobs", "ones_profile_enable", "ones_profile_read",
+           "ones_export", "ones_set_progress", "ones_export_remaining", "ones_padded_jobs",
+           "ones_profile_enable", "ones_profile_read",
            "ones_destroy", "ones_strerror"]
 
 
@@ -63,6 +64,8 @@ def load():
     L.ones_generation.argtypes = [C.c_void_p, C.c_int32]
     L.ones_best.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(C.c_double)]
     L.ones_export.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(C.c_int64)]
+    L.ones_set_progress.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+    L.ones_export_remaining.argtypes = [C.c_void_p, C.c_void_p]
     L.ones_padded_jobs.argtypes = [C.c_int32]
     L.ones_padded_jobs.restype = C.c_int32
     L.ones_profile_enable.argtypes = [C.c_void_p, C.c_int32]
@@ -138,6 +141,23 @@ class Search:
     def generation(self, n: int = 1):
         with self._torch.cuda.device(self.device):
             _check(load().ones_generation(self._h, int(n)))
+
+    def set_progress(self, alpha=None, beta=None, processed=None):
+        """ones_set_progress: one entry per slot each; all None switches the sampling off."""
+        with self._torch.cuda.device(self.device):
+            if alpha is None and beta is None and processed is None:
+                _check(load().ones_set_progress(self._h, None, None, None))
+                return
+            arrs = [np.ascontiguousarray(x, np.float64) for x in (alpha, beta, processed)]
+            if any(a.shape != (self.n_slots,) for a in arrs):
+                raise ValueError("alpha, beta, processed: one entry per slot")
+            _check(load().ones_set_progress(self._h, *[a.ctypes.data for a in arrs]))
+
+    def export_remaining(self):
+        y = np.zeros(max(self.n_slots, 1), np.float64)
+        with self._torch.cuda.device(self.device):
+            _check(load().ones_export_remaining(self._h, y.ctypes.data))
+        return y[:self.n_slots]
 
     def best(self):
         b = np.zeros(self.n_slots, np.int32)

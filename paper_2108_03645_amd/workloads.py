@@ -145,6 +145,19 @@ def stress(seed: int = 4, population: int = 65536, n_jobs: int = 2048, n_gpus: i
             _pack(n, a, c, d, y, bmin, bmax, np.full(n, 256)))
 
 
+def progress(n_slots: int, seed: int = 0):
+    """Per-slot inputs of the probability sampling (Alg. 1): the samples a job has processed,
+    ~ U(1e4, 1e7); alpha = processed / epoch size with the epoch size log-uniform in
+    [1e4, 1e6], and beta (epochs still to come) ~ U(1, 60), both thresholded at 1 as in
+    Section 3.2.1.  Returns (alpha, beta, processed)."""
+    rng = np.random.default_rng([seed, 0xBE7A])
+    processed = rng.uniform(1e4, 1e7, n_slots)
+    epoch = np.exp(rng.uniform(np.log(1e4), np.log(1e6), n_slots))
+    alpha = np.maximum(processed / epoch, 1.0)
+    beta = np.maximum(rng.uniform(1.0, 60.0, n_slots), 1.0)
+    return alpha, beta, processed
+
+
 class OnlineSequence:
     """Online arrivals for the 64-GPU cluster: 64 slots, at most 60 busy, one scheduling
     epoch = 60 s, arrivals per epoch ~ Poisson(0.5), deferred first-in-first-out while 60

@@ -275,3 +275,92 @@ def test_profile_hook_counts_launches(ones):
     s.profile_enable(0)
     s.generation(1)
     assert s.profile_read()["evolve_launches"] == 0
+
+
+# ------------------------------------------------ probability sampling (Alg. 1, Eq. 7) ----
+def test_sampled_remaining_work_matches_the_oracle_bit_for_bit(ones, ref):
+    """Every slot's draw, over several generations, for shapes from 1 to 1e100."""
+    n = 2048
+    rng = np.random.default_rng(21)
+    cl = cluster(256, n, 64, seed=0xFEEDFACE12345678)
+    jobs = random_jobs(rng, n)
+    alpha = np.exp(rng.uniform(0, 12, n)); beta = np.exp(rng.uniform(0, 12, n))
+    proc = rng.uniform(0, 1e7, n)
+    alpha[:8] = [1.0, 1.0, 1.0000000001, 1e100, 1e100, 1.0, 3.5, 1e6]
+    beta[:8] = [1.0, 1e100, 1.0, 1.0, 1e100, 1.0000000001, 1e6, 3.5]
+    proc[:8] = [0.0, 1e100, 1e100, 1e100, 1.0, 5.0, 1e100, 0.0]
+    say(f"[sampling] draws: slots={n} seed={cl.seed:#x}")
+    gpu = ones.Search(cl, jobs)
+    gpu.set_progress(alpha, beta, proc)
+    for step in range(4):
+        gpu.generation(1 if step else 3)
+        t = gpu.export(genes=False)[3]
+        got = gpu.export_remaining()
+        want = np.array([ref.sampled_remaining(cl.seed, j, t, alpha[j], beta[j], proc[j])[0] for j in range(n)])
+        bad = np.flatnonzero(got.view(np.uint64) != want.view(np.uint64))
+        assert bad.size == 0, f"generation {t}: {bad.size} draws differ, first slots {bad[:5]}"
+    gpu.close()
+
+
+@pytest.mark.parametrize("name", ["tiny", "paper_scale", "ragged", "buckets"])
+def test_sampled_search_matches_the_oracle(ones, ref, name):
+    """Sampling switched on after a few generations, a job-table change under it, switched
+    off again: genomes, scores and survivor lists agree after every call."""
+    if name == "tiny":
+        cl, jobs = W.tiny()
+    elif name == "paper_scale":
+        cl, jobs = W.paper_scale()
+    elif name == "ragged":
+        cl = cluster(700, 333, 512, seed=31)
+        jobs = random_jobs(np.random.default_rng(31), 333)
+    else:
+        cl = cluster(300, 200, 8192, seed=32)                  # large enough for the bucketed selection
+        jobs = random_jobs(np.random.default_rng(32), 200)
+    alpha, beta, proc = W.progress(cl.n_slots, seed=5)
+    say(f"[sampling] search {name}: G={cl.n_gpus} slots={cl.n_slots} P={cl.population} seed={cl.seed}")
+    gpu, cpu = ones.Search(cl, jobs), ref.RefSearch(cl, jobs)
+
+    def both(call, where):
+        call(gpu); call(cpu)
+        assert_same_state(gpu, cpu, f"{name} {where}")
+        assert np.array_equal(gpu.export_remaining().view(np.uint64), cpu.export_remaining().view(np.uint64)), where
+
+    both(lambda s: s.generation(3), "fixed remaining work")
+    both(lambda s: s.set_progress(alpha, beta, proc), "sampling on")
+    for i in range(4):
+        both(lambda s: s.generation(1), f"sampled generation {i}")
+    both(lambda s: s.generation(5), "five sampled generations")
+    # a slot changes hands and another job's window shrinks while sampling is on
+    j2 = make_jobs(cl.n_slots, **{k: np.array(getattr(jobs, k)) for k in
+                                  ("job_id", "active", "bmin", "bmax", "gpu_max_batch", "a", "c", "d", "remaining")})
+    j2.job_id[0] += 1000
+    j2.bmax[cl.n_slots - 1] = j2.bmin[cl.n_slots - 1]
+    both(lambda s: s.set_jobs(j2), "table change under sampling")
+    both(lambda s: s.generation(1), "first generation after the table change")
+    both(lambda s: s.generation(2), "sampled generations after the table change")
+    both(lambda s: s.set_progress(), "sampling off")
+    both(lambda s: s.generation(1), "first generation with the table's remaining work")
+    both(lambda s: s.generation(3), "fixed remaining work again")
+    gb, cb = gpu.best(), cpu.best()
+    assert gb[0].tolist() == cb[0].tolist() and gb[1].tolist() == cb[1].tolist() and gb[2] == cb[2]
+    gpu.close(); cpu.close()
+
+
+def test_set_progress_rejects_bad_arguments_and_keeps_state(ones, ref):
+    cl, jobs = W.tiny()
+    gpu, cpu = ones.Search(cl, jobs), ref.RefSearch(cl, jobs)
+    n = cl.n_slots
+    one, proc = np.ones(n), np.full(n, 1e5)
+    for bad, code in [((np.full(n, 0.5), one, proc), -1), ((one, np.full(n, 0.99), proc), -1),
+                      ((one, one, np.full(n, -1.0)), -1), ((np.full(n, np.nan), one, proc), -4),
+                      ((one, np.full(n, np.inf), proc), -4), ((np.full(n, 1e101), one, proc), -3),
+                      ((one, one, np.full(n, 1e101)), -3)]:
+        with pytest.raises(ones.OnesError) as e:
+            gpu.set_progress(*bad)
+        assert e.value.code == code
+    lib = ones.load()
+    assert lib.ones_set_progress(gpu._h, one.ctypes.data, None, proc.ctypes.data) == -1
+    assert lib.ones_export_remaining(gpu._h, None) == -1
+    gpu.generation(2); cpu.generation(2)
+    assert_same_state(gpu, cpu, "after rejected calls")
+    gpu.close(); cpu.close()
