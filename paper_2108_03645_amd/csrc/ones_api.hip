@@ -287,7 +287,8 @@ int run_generation(ones_ctx *c, uint32_t t) {
   } else {
     HIP_TRY(launch_select(a.fit_row, rp, c->P, c->K, c->at<uint64_t>(c->L.keys), c->at<uint32_t>(c->L.idx),
                           c->at<int32_t>(c->L.sel), c->stream));
-    if (c->bp.nb != 0)   // splitters for the bucketed generations that follow; clears both counter sets
+    if (c->bp.nb != 0 && !sampled)   // splitters for the bucketed generations that follow; clears both
+                                     // counter sets.  Under sampling no bucketed generation can follow.
       HIP_TRY(launch_splitters(a.fit_row, a.row_of, c->at<int32_t>(c->L.sel), c->K, c->bp.nb,
                                c->at<uint64_t>(c->L.split),
                                c->at<uint64_t>(c->L.thresh), c->at<uint32_t>(c->L.bcount[0]),
