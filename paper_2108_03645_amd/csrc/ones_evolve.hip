@@ -101,6 +101,7 @@ struct Smem {
   uint8_t  *stash;   // [waves][Jp] second crossover child while the first is repaired
   uint32_t *free_in_group; // [groups] free rows in each group of kRowGroupWords bitmap words
   uint32_t *rows;          // [4 * kRound] rows of the slots this workgroup fills in the current round
+  uint32_t *next_item;     // [1] the next work item of the round that no wave has taken yet
 };
 
 // E = entries per job of the term table kept in LDS, 0 = keep the four model parameters.
@@ -112,7 +113,7 @@ inline uint32_t row_groups(uint32_t rows) {
 
 inline size_t smem_bytes(uint32_t Jp, int waves, uint32_t E, uint32_t rows) {
   return static_cast<size_t>(Jp) * (8 + 4 + (E ? 8 * E : 32)) + (kMaxBuckets + 1) * 8 +
-         static_cast<size_t>(waves) * Jp + static_cast<size_t>(row_groups(rows)) * 4 + 4 * kRound * 4;
+         static_cast<size_t>(waves) * Jp + static_cast<size_t>(row_groups(rows)) * 4 + 4 * kRound * 4 + 16;
 }
 
 __device__ __forceinline__ Smem carve(unsigned char *base, uint32_t Jp, uint32_t E, uint32_t waves) {
@@ -127,7 +128,8 @@ __device__ __forceinline__ Smem carve(unsigned char *base, uint32_t Jp, uint32_t
   s.info = reinterpret_cast<uint32_t *>(s.cc2 + Jp);
   s.stash = reinterpret_cast<uint8_t *>(s.info + Jp);
   s.rows = reinterpret_cast<uint32_t *>(s.stash + static_cast<size_t>(waves) * Jp);   // Jp is a multiple of 64
-  s.free_in_group = s.rows + 4 * kRound;
+  s.next_item = s.rows + 4 * kRound;
+  s.free_in_group = s.next_item + 4;
   return s;
 }
 
@@ -493,14 +495,21 @@ __global__ __launch_bounds__(Shape<R>::kWaves *kLanes) void evolve_kernel(Evolve
   if (wave_in_block == 0) list_free_rows(a, s, 2 * ra, 2 * n, s.rows, lane0);
   if (wave_in_block == 1) list_free_rows(a, s, 2 * K + ra, n, s.rows + 2 * n, lane0);
   if (!kSameTable && wave_in_block == 2) list_free_rows(a, s, 3 * K + ra, n, s.rows + 3 * n, lane0);
+  if (threadIdx.x == blockDim.x - 1) *s.next_item = 0;
   __syncthreads();
   for (uint32_t i = threadIdx.x; i < (kSameTable ? 3 : 4) * n; i += blockDim.x) {
     const uint32_t p = i < 2 * n ? K + 2 * ra + i : i < 3 * n ? 3 * K + ra + (i - 2 * n) : ra + (i - 3 * n);
     a.row_of[p] = min(s.rows[i], a.P + a.K - 1);
   }
   const uint32_t kinds = (!kSameTable || a.rescore) ? 3u : 2u;
-  for (uint32_t idx = wave_in_block; idx < kinds * n; idx += Shape<R>::kWaves) {
+  // The waves take the items one by one (the pairs first: they take twice as long), so that a
+  // wave whose items needed many fill rounds does not hold the others up at the end.
+  for (;;) {
     const int lane = opaque(lane0);
+    uint32_t taken = 0;
+    if (lane == 0) taken = atomicAdd(s.next_item, 1u);
+    const uint32_t idx = __builtin_amdgcn_readfirstlane(taken);
+    if (idx >= kinds * n) break;
     // pairs first, then mutants, then survivors; item as numbered over the whole pool
     const uint32_t item = idx < n ? ra + idx : idx < 2 * n ? K + ra + (idx - n) : 2 * K + ra + (idx - 2 * n);
     uint32_t c[R];

@@ -364,3 +364,25 @@ def test_set_progress_rejects_bad_arguments_and_keeps_state(ones, ref):
     gpu.generation(2); cpu.generation(2)
     assert_same_state(gpu, cpu, "after rejected calls")
     gpu.close(); cpu.close()
+
+
+def test_full_size_stress_with_sampled_remaining_work_matches_oracle(ones, ref):
+    """The launch configuration of `bench.py --sampled`: pool 65536, 2048 jobs, remaining work
+    drawn every generation (the survivors are scored again in place, general selection)."""
+    import os
+    cl, jobs = W.stress()
+    alpha, beta, proc = W.progress(cl.n_slots, seed=cl.seed)
+    ref.set_threads(min(16, os.cpu_count() or 1))
+    say(f"[sampling] stress full size: P={cl.population} slots={cl.n_slots} seed={cl.seed}")
+    try:
+        gpu, cpu = ones.Search(cl, jobs), ref.RefSearch(cl, jobs)
+        for s in (gpu, cpu):
+            s.generation(1)
+            s.set_progress(alpha, beta, proc)
+        for i in range(2):
+            gpu.generation(1); cpu.generation(1)
+            assert_same_state(gpu, cpu, f"stress sampled generation {i + 1}")
+        assert np.array_equal(gpu.export_remaining().view(np.uint64), cpu.export_remaining().view(np.uint64))
+        gpu.close(); cpu.close()
+    finally:
+        ref.set_threads(1)
