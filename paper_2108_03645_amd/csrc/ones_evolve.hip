@@ -37,6 +37,9 @@ __device__ __forceinline__ void fence_every(int i, int n) { if (i % n == n - 1) 
 // Forces x to be computed before the following fence (its producers cannot sink below it).
 template <typename T> __device__ __forceinline__ void pin(T &x) { asm volatile("" : "+v"(x)); }
 __device__ __forceinline__ int opaque(int v) { asm volatile("" : "+v"(v)); return v; }
+// The same for a wave-uniform value: what is derived from it is computed where it is used
+// instead of once before the item loop, where it would sit in (spilled) scalar registers.
+__device__ __forceinline__ uint32_t opaque_uniform(uint32_t v) { asm volatile("" : "+s"(v)); return v; }
 
 // ------------------------------------------------------------------ RNG ------------
 __device__ __forceinline__ uint32_t bounded(uint32_t w, uint32_t n) { return __umulhi(w, n); }
@@ -353,6 +356,7 @@ __device__ __forceinline__ void repair(uint32_t (&c)[R], const Smem &s, uint32_t
 template <int R>
 __device__ __forceinline__ double score(const uint32_t (&c)[R], const Smem &s, uint32_t E, int lane) {
   double acc = 0.0;
+  E = opaque_uniform(E);
   if (E != 0) {
     // the job's term only depends on its GPU count c = 2^(code-1) (code 0: waiting), and the
     // table holds exactly the value the formula below produces
@@ -394,16 +398,25 @@ __device__ __forceinline__ void drop_in_bucket(const EvolveArgs &a, const Smem &
   for (uint32_t q = 0; q * kLanes + 1 < a.bk.nb; ++q)      // splitters 0 .. nb-2, the rest is +inf
     b += static_cast<uint32_t>(__popcll(__ballot(s.split[q * kLanes + lane] <= bits)));
   if (lane == 0) {
-    const uint32_t slot = atomicAdd(&a.bk.count[b], 1u);
-    if (slot < a.bk.seg) {
-      const size_t at = static_cast<size_t>(b) * a.bk.seg + slot;
-      a.bk.keys[at] = bits;
-      a.bk.idx[at] = p;
+    // The pointers of the bucket storage are read from the kernel's argument block here, where
+    // the few candidates that get this far need them, instead of being carried (and spilled)
+    // through every work item.  The kernels of this file take one EvolveArgs by value, so the
+    // argument block is that struct.
+    using KernelArgs = const __attribute__((address_space(4))) EvolveArgs;
+    KernelArgs *ka = (KernelArgs *)__builtin_amdgcn_kernarg_segment_ptr();
+    asm volatile("" : "+s"(ka));
+    uint32_t *count = ka->bk.count;
+    const uint32_t seg = ka->bk.seg;
+    const uint32_t slot = atomicAdd(&count[b], 1u);
+    if (slot < seg) {
+      const size_t at = static_cast<size_t>(b) * seg + slot;
+      ka->bk.keys[at] = bits;
+      ka->bk.idx[at] = p;
     } else {                                               // bucket full: shared spill list
-      const uint32_t at = atomicAdd(&a.bk.count[kSpillCounter], 1u);
-      a.bk.spill_keys[at] = bits;
-      a.bk.spill_idx[at] = p;
-      a.bk.spill_bucket[at] = b;
+      const uint32_t at = atomicAdd(&count[kSpillCounter], 1u);
+      ka->bk.spill_keys[at] = bits;
+      ka->bk.spill_idx[at] = p;
+      ka->bk.spill_bucket[at] = b;
     }
   }
 }
