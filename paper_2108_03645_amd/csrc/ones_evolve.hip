@@ -327,22 +327,19 @@ __device__ __forceinline__ void repair(uint32_t (&c)[R], const Smem &s, uint32_t
   // admit: jobs beyond the capacity in visiting order wait (Eq. 4)
   const uint32_t used = accept_prefix<R>(c, G, lr, ir, lane);
   // fill: a waiting job asks for cstart GPUs, a running one below its limit asks to double.
-  // Every round accepts at least its first ask, and a job doubles at most 20 times, so
-  // kMaxRows * 64 * 21 rounds always suffice; the bound and the got == 0 exit only make the
+  // Every round accepts at least its first ask (got == 0: nobody could ask), and a job doubles
+  // at most 20 times, so kMaxRows * 64 * 21 rounds always suffice; the bound only makes the
   // loop end whatever happens.
   uint32_t idle = G - used;
   for (int round = 0; round < kMaxRows * kLanes * 21 && idle > 0; ++round) {
     uint32_t v[R];
-    uint32_t any = 0;
 #pragma unroll
     for (int i = 0; i < R; ++i) {
       const uint2 k = s.cc2[lane + kLanes * i];
       const uint32_t cost = max(c[i], k.x);
       v[i] = (c[i] < k.y && cost <= idle) ? cost : 0u;
-      any |= v[i];
-      if (i % 8 == 7) { pin(any); phase_fence(); }
+      if (i % 8 == 7) { pin(v[i]); phase_fence(); }
     }
-    if (__ballot(any != 0) == 0) break;
     const uint32_t got = accept_prefix<R>(v, idle, lr, ir, lane);
 #pragma unroll
     for (int i = 0; i < R; ++i) c[i] += v[i];
