@@ -37,9 +37,6 @@ __device__ __forceinline__ void fence_every(int i, int n) { if (i % n == n - 1) 
 // Forces x to be computed before the following fence (its producers cannot sink below it).
 template <typename T> __device__ __forceinline__ void pin(T &x) { asm volatile("" : "+v"(x)); }
 __device__ __forceinline__ int opaque(int v) { asm volatile("" : "+v"(v)); return v; }
-// The same for a wave-uniform value: what is derived from it is computed where it is used
-// instead of once before the item loop, where it would sit in (spilled) scalar registers.
-__device__ __forceinline__ uint32_t opaque_uniform(uint32_t v) { asm volatile("" : "+s"(v)); return v; }
 
 // ------------------------------------------------------------------ RNG ------------
 __device__ __forceinline__ uint32_t bounded(uint32_t w, uint32_t n) { return __umulhi(w, n); }
@@ -99,7 +96,7 @@ struct Smem {
   uint2    *cc2;     // [Jp] {cstart, cmax}: GPUs a waiting job resumes with / at the limit R_j
   uint32_t *info;    // [Jp]
   double   *abl, *cc, *d, *Y;   // [Jp] model parameters (when the term table does not fit)
-  double   *terms;   // [R][E][64] T_j c_j of job (row, lane) at GPU-count code e, or null
+  double   *terms;   // [E][R][64] T_j c_j of job (row, lane) at GPU-count code E-1-e, or null
   uint64_t *split;   // [kMaxBuckets] bucket splitters, then [1] the K-th survivor's score bits
   uint8_t  *stash;   // [waves][Jp] second crossover child while the first is repaired
   uint32_t *free_in_group; // [groups] free rows in each group of kRowGroupWords bitmap words
@@ -137,6 +134,7 @@ __device__ __forceinline__ Smem carve(unsigned char *base, uint32_t Jp, uint32_t
 }
 
 // No barrier at the end: the caller places one before the first use.
+template <int R>
 __device__ __forceinline__ void stage_table(const JobTable &tab, const BucketArgs &bk, const Smem &s, uint32_t Jp,
                                             uint32_t E) {
   if (bk.nb != 0) {
@@ -154,7 +152,13 @@ __device__ __forceinline__ void stage_table(const JobTable &tab, const BucketArg
     }
   }
   if (E != 0)
-    for (uint32_t q = threadIdx.x; q < Jp * E; q += blockDim.x) s.terms[q] = tab.terms[q];
+    // global memory holds the table row-major ([row][code][lane]); here the code is the slowest
+    // index, so that a row's part of the LDS address is a compile-time offset, and the codes
+    // run backwards, so that the index follows the count of leading zeros of the GPU count
+    for (uint32_t tile = threadIdx.x / kLanes; tile < E * R; tile += blockDim.x / kLanes) {   // 64 entries each
+      const uint32_t e = tile / R, row = tile % R, l = threadIdx.x % kLanes;
+      s.terms[((E - 1 - e) * R + row) * kLanes + l] = tab.terms[(row * E + e) * kLanes + l];
+    }
 }
 
 // ------------------------------------------------------------------ free rows ----
@@ -353,14 +357,17 @@ __device__ __forceinline__ void repair(uint32_t (&c)[R], const Smem &s, uint32_t
 template <int R>
 __device__ __forceinline__ double score(const uint32_t (&c)[R], const Smem &s, uint32_t E, int lane) {
   double acc = 0.0;
-  E = opaque_uniform(E);
   if (E != 0) {
     // the job's term only depends on its GPU count c = 2^(code-1) (code 0: waiting), and the
     // table holds exactly the value the formula below produces
+    // code = 32 - z with z the leading zeros of c (32 for a waiting job); the table is stored
+    // with the codes backwards, entry E-1-code = z - (33 - E)
+    // (column itself lies before the table; every address formed from it lies inside: z >= 33 - E)
+    const double *column = s.terms + lane + (static_cast<int>(E) - 33) * (R * kLanes);
 #pragma unroll
     for (int i = 0; i < R; ++i) {
-      const uint32_t code = c[i] ? 32u - static_cast<uint32_t>(__clz(static_cast<int>(c[i]))) : 0u;
-      acc = acc + s.terms[(i * E + code) * kLanes + lane];
+      const int z = __clz(static_cast<int>(c[i]));
+      acc = acc + (column + z * (R * kLanes))[i * kLanes];
       if (i % 8 == 7) { pin(acc); phase_fence(); }
     }
   } else
@@ -457,7 +464,7 @@ template <int R>
 __global__ __launch_bounds__(Shape<R>::kWaves *kLanes) void init_kernel(EvolveArgs a) {
   extern __shared__ __align__(16) unsigned char smem_raw[];
   const Smem s = carve(smem_raw, a.Jp, a.term_lds, Shape<R>::kWaves);
-  stage_table(a.tab, a.bk, s, a.Jp, a.term_lds);
+  stage_table<R>(a.tab, a.bk, s, a.Jp, a.term_lds);
   __syncthreads();
   const int lane0 = threadIdx.x & (kLanes - 1);
   const uint32_t wave = __builtin_amdgcn_readfirstlane(blockIdx.x * Shape<R>::kWaves + (threadIdx.x >> 6));
@@ -488,7 +495,7 @@ __global__ __launch_bounds__(Shape<R>::kWaves *kLanes) void evolve_kernel(Evolve
   const Smem s = carve(smem_raw, a.Jp, a.term_lds, Shape<R>::kWaves);
   const int lane0 = threadIdx.x & (kLanes - 1);
   const IndexLoads index_loads = index_free_rows_begin(a, lane0);
-  stage_table(a.tab, a.bk, s, a.Jp, a.term_lds);
+  stage_table<R>(a.tab, a.bk, s, a.Jp, a.term_lds);
   index_free_rows_end(a, s, index_loads, lane0);
   const uint32_t wave_in_block = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const uint32_t K = a.K;
