@@ -24,8 +24,8 @@ HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published peak
 
 # HBM bytes per evolve launch on the stress workload from rocprofv3 --pmc FETCH_SIZE and
 # WRITE_SIZE (see profiles/), valid only for the kernel source with this hash.
-MEASURED_TRAFFIC = {"source_sha256": "67fb4912b7146c0c67e091a1bf98f1fe6bf98f9eed132181f196a20e5811346c",
-                    "bytes_per_launch": 802817165}
+MEASURED_TRAFFIC = {"source_sha256": "295d3f0c6f8c3a474d50edcd14eaa786f297b438ac87d1625139d37968b72d54",
+                    "bytes_per_launch": 802739249}
 
 
 def evolve_source_hash() -> str:
