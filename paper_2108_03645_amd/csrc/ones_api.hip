@@ -29,7 +29,7 @@ int hip_fail(hipError_t e, const char *what) {
 size_t align_up(size_t v) { return (v + 255) & ~static_cast<size_t>(255); }
 
 struct Layout {
-  size_t genes, fit_row, row_of[2], parent_row[2], occupied[2], sel, keys, idx, split, thresh, bcount[2], bkeys, bidx, skeys, sidx, sbucket, pkeys, pidx, cstart, cmax, info, abl, cc, d, Y, terms;
+  size_t genes, fit_row, row_of[2], parent_row[2], occupied[2], sel, split, thresh, bcount[2], bkeys, bidx, skeys, sidx, sbucket, pkeys, pidx, cstart, cmax, info, abl, cc, d, Y, terms;
   size_t rawinfo, changed, ra, rc, rd, rY, alpha, beta, processed, best_batch, best_gpus, best_fit, total;
 };
 
@@ -45,9 +45,9 @@ BucketPlan bucket_plan(uint32_t P) {
   const uint32_t K = P / 4;
   BucketPlan bp;
   bp.nb = std::min<uint32_t>(kMaxBuckets, std::max<uint32_t>(1, K / 16));
-  bp.spill = 3 * K;
-  bp.pool = 2 * pow2_at_least(3 * K);
-  bp.seg = std::min(pow2_at_least(std::max<uint32_t>(256, 8 * ((3 * K + bp.nb - 1) / bp.nb))), bp.pool / 2);
+  bp.spill = P;                                            // the general selection may spill a whole pool
+  bp.pool = 2 * pow2_at_least(P);                          // every slice is a power of two below twice its bucket
+  bp.seg = std::min(pow2_at_least(std::max<uint32_t>(256, 8 * ((3 * K + bp.nb - 1) / bp.nb))), bp.pool / 4);
   return bp;
 }
 
@@ -55,7 +55,6 @@ Layout make_layout(uint32_t P, uint32_t Jp) {
   Layout L;
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t at = off; off = align_up(off + bytes); return at; };
-  const size_t chunks = (P + kSortChunk - 1) / kSortChunk;
   const size_t rows = static_cast<size_t>(P) + P / 4;      // a pool of P slots lives in P + K physical rows
   L.genes = take(rows * Jp * 4);
   L.fit_row = take(rows * 8);
@@ -66,8 +65,6 @@ Layout make_layout(uint32_t P, uint32_t Jp) {
   L.occupied[0] = take((rows + 31) / 32 * 4);     // bitmaps of the rows the survivors keep
   L.occupied[1] = take((rows + 31) / 32 * 4);
   L.sel = take(static_cast<size_t>(P / 4) * 4);
-  L.keys = take(chunks * kSortChunk * 8);
-  L.idx = take(chunks * kSortChunk * 4);
   // quantile buckets of the selection (pools larger than one sort chunk)
   const BucketPlan bp = bucket_plan(P);
   L.split = take(kMaxBuckets * 8); L.thresh = take(8);
@@ -285,8 +282,10 @@ int run_generation(ones_ctx *c, uint32_t t) {
                                  c->stream));
     c->bucket_phase ^= 1;
   } else {
-    HIP_TRY(launch_select(a.fit_row, rp, c->P, c->K, c->at<uint64_t>(c->L.keys), c->at<uint32_t>(c->L.idx),
-                          c->at<int32_t>(c->L.sel), c->stream));
+    BucketArgs store = a.bk;                       // same storage; always the first counter set
+    store.nb = c->bp.nb;
+    store.count = c->at<uint32_t>(c->L.bcount[0]);
+    HIP_TRY(launch_select(a.fit_row, rp, c->P, c->K, store, c->at<int32_t>(c->L.sel), c->stream));
     if (c->bp.nb != 0 && !sampled)   // splitters for the bucketed generations that follow; clears both
                                      // counter sets.  Under sampling no bucketed generation can follow.
       HIP_TRY(launch_splitters(a.fit_row, a.row_of, c->at<int32_t>(c->L.sel), c->K, c->bp.nb,

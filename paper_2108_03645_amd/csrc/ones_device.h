@@ -13,7 +13,7 @@ constexpr int kMaxTermEntries = 22; // waiting + GPU counts 2^0 .. 2^20
 #ifndef ONES_SORT_CHUNK
 #define ONES_SORT_CHUNK 4096
 #endif
-constexpr int kSortChunk = ONES_SORT_CHUNK;   // keys sorted per workgroup in LDS
+constexpr int kSortChunk = ONES_SORT_CHUNK;   // largest pool that one workgroup sorts in LDS
 
 // Philox4x32-10 (Salmon, Moraes, Dror, Shaw, SC'11).
 struct Words { uint32_t w[4]; };
@@ -76,7 +76,7 @@ struct BucketArgs {
   uint32_t       *count;      // [kBucketCounters] offspring per bucket (spilled ones included), this generation
   uint64_t       *keys;       // [nb][seg] score bits of the bucket's offspring
   uint32_t       *idx;        // [nb][seg] their pool slots
-  uint64_t       *spill_keys; // [3K] surplus offspring: score bits, slot, bucket
+  uint64_t       *spill_keys; // [P] surplus candidates: score bits, slot, bucket
   uint32_t       *spill_idx;
   uint32_t       *spill_bucket;
   uint64_t       *pool_keys;  // [pool] scratch for buckets that do not fit LDS
@@ -159,8 +159,11 @@ inline hipError_t launch_evolve(const EvolveArgs &a, int rows, bool same_table, 
     default: return hipErrorInvalidValue;
   }
 }
-hipError_t launch_select(const double *fit_row, const RowPlan &rp, uint32_t P, uint32_t K, uint64_t *keys,
-                         uint32_t *idx, int32_t *sel, hipStream_t s);
+// General selection (any scores).  store: the bucket storage (count, keys, idx, spill and pool
+// arrays, split as scratch for the splitters, nb * seg entries of bucket space); used for pools
+// above kSortChunk slots.
+hipError_t launch_select(const double *fit_row, const RowPlan &rp, uint32_t P, uint32_t K, const BucketArgs &store,
+                         int32_t *sel, hipStream_t s);
 hipError_t launch_zero_words(uint32_t *words, uint32_t n, hipStream_t s);
 hipError_t launch_bucket_select(const double *fit_row, const uint32_t *parent_row, const BucketArgs &bk,
                                 const RowPlan &rp, uint32_t K, uint32_t *count_next, int32_t *sel, hipStream_t s);

@@ -52,60 +52,22 @@ __device__ __forceinline__ uint32_t pow2_at_least(uint32_t v) {
 }
 
 // ---------------------------------------------------------------- general path -----
-// Each workgroup sorts one chunk of n (power of two, <= kSortChunk) keys in LDS.  With a
-// single chunk the survivors are written directly.
-__global__ __launch_bounds__(kSortThreads) void sort_chunks_kernel(const double *fit_row, RowPlan rp, uint32_t P,
-                                                                  uint32_t K, uint32_t n, uint64_t *keys,
-                                                                  uint32_t *idx, int32_t *sel, int single) {
+// Pools of at most kSortChunk slots: one workgroup sorts all (score, slot) keys in LDS (n = the
+// pool size rounded up to a power of two) and writes the survivors.
+__global__ __launch_bounds__(kSortThreads) void sort_pool_kernel(const double *fit_row, RowPlan rp, uint32_t P,
+                                                                uint32_t K, uint32_t n, int32_t *sel) {
   const uint32_t *row_of = rp.row_of_cur;
   __shared__ uint64_t sk[kSortChunk];
   __shared__ uint32_t si[kSortChunk];
-  const uint32_t base = blockIdx.x * n;
   for (uint32_t e = threadIdx.x; e < n; e += kSortThreads) {
-    const uint32_t p = base + e;
-    sk[e] = p < P ? static_cast<uint64_t>(__double_as_longlong(fit_row[row_of[p]])) : ~0ull;   // padding sorts last
-    si[e] = p < P ? p : 0xFFFFFFFFu;
+    sk[e] = e < P ? static_cast<uint64_t>(__double_as_longlong(fit_row[row_of[e]])) : ~0ull;   // padding sorts last
+    si[e] = e < P ? e : 0xFFFFFFFFu;
   }
   __syncthreads();
   bitonic_sort(sk, si, n);
-  if (single) {
-    for (uint32_t e = threadIdx.x; e < K; e += kSortThreads) {
-      sel[e] = static_cast<int32_t>(si[e]);
-      keep_row(rp, e, si[e]);
-    }
-  } else {
-    for (uint32_t e = threadIdx.x; e < n; e += kSortThreads) {
-      keys[base + e] = sk[e];
-      idx[base + e] = si[e];
-    }
-  }
-}
-
-// Global rank of every element = its position in its own sorted chunk + the number of
-// smaller elements in every other chunk (binary search).  Ranks below K are survivors.
-__global__ __launch_bounds__(256) void rank_kernel(const uint64_t *keys, const uint32_t *idx, uint32_t chunks,
-                                                  uint32_t K, RowPlan rp, int32_t *sel) {
-  const uint32_t e = blockIdx.x * blockDim.x + threadIdx.x;
-  if (e >= chunks * kSortChunk) return;
-  const uint32_t mine = e / kSortChunk, pos = e % kSortChunk;
-  const uint32_t id = idx[e];
-  if (pos >= K || id == 0xFFFFFFFFu) return;
-  const uint64_t key = keys[e];
-  uint32_t rank = pos;
-  for (uint32_t c = 0; c < chunks && rank < K; ++c) {
-    if (c == mine) continue;
-    const uint64_t *ck = keys + static_cast<size_t>(c) * kSortChunk;
-    const uint32_t *ci = idx + static_cast<size_t>(c) * kSortChunk;
-    uint32_t lo = 0, hi = kSortChunk;                 // count of chunk elements below (key, id)
-    while (lo < hi) {
-      const uint32_t mid = (lo + hi) >> 1;
-      if (key_less(ck[mid], ci[mid], key, id)) lo = mid + 1; else hi = mid;
-    }
-    rank += lo;
-  }
-  if (rank < K) {
-    sel[rank] = static_cast<int32_t>(id);
-    keep_row(rp, rank, id);
+  for (uint32_t e = threadIdx.x; e < K; e += kSortThreads) {
+    sel[e] = static_cast<int32_t>(si[e]);
+    keep_row(rp, e, si[e]);
   }
 }
 
@@ -209,11 +171,11 @@ __device__ __forceinline__ void gather_bucket(K64 *dk, I32 *di, const BucketArgs
   const uint32_t n_main = n < bk.seg ? n : bk.seg;
   const uint64_t *gk = bk.keys + static_cast<size_t>(b) * bk.seg;
   const uint32_t *gi = bk.idx + static_cast<size_t>(b) * bk.seg;
-  for (uint32_t e = tid; e < n_main; e += kBucketThreads) { dk[e] = gk[e]; di[e] = gi[e]; }
-  for (uint32_t e = n + tid; e < npad; e += kBucketThreads) { dk[e] = ~0ull; di[e] = 0xFFFFFFFFu; }
+  for (uint32_t e = tid; e < n_main; e += blockDim.x) { dk[e] = gk[e]; di[e] = gi[e]; }
+  for (uint32_t e = n + tid; e < npad; e += blockDim.x) { dk[e] = ~0ull; di[e] = 0xFFFFFFFFu; }
   if (n > n_main) {
     const uint32_t spilled = bk.count[kSpillCounter];
-    for (uint32_t q = tid; q < spilled; q += kBucketThreads) {
+    for (uint32_t q = tid; q < spilled; q += blockDim.x) {
       if (bk.spill_bucket[q] == b) {
         const uint32_t at = n_main + atomicAdd(lds_counter, 1u);
         dk[at] = bk.spill_keys[q];
@@ -272,6 +234,172 @@ __global__ __launch_bounds__(kBucketThreads) void bucket_select_kernel(const dou
   // the other counter set, for the next generation
   if (tid == 0) count_next[b] = 0;
   if (b == 0 && tid < 2) count_next[kMaxBuckets + tid] = 0;
+}
+
+// ------------------------------------------------- general path, larger pools -----
+// Sample sort over the same bucket storage: a sorted sample of the pool's scores gives the
+// splitters, every candidate is dropped into its bucket, and one workgroup per bucket sorts its
+// share; buckets concatenate to the global (score, slot) order and only those that reach below
+// rank K do any work.  The sample only decides how even the buckets are, never the result.
+
+// Splitters: `sample` = 2 nb scores taken at a fixed stride from the pool; those of odd rank
+// 2c + 1 among them become splitter c.  Ranks by counting: every workgroup loads the whole
+// sample and ranks eight of its elements, 128 threads each over their share of the sample.
+constexpr int kSampleThreads = 1024;
+constexpr int kSamplePer = 8;
+constexpr int kSampleMax = 2 * kMaxBuckets;
+__global__ __launch_bounds__(kSampleThreads) void sample_splitters_kernel(const double *fit_row, const uint32_t *row_of,
+                                                                         uint32_t P, uint32_t sample,
+                                                                         uint64_t *split, uint32_t *count) {
+  __shared__ uint64_t sk[kSampleMax];
+  __shared__ uint32_t rank[kSamplePer];
+  const uint32_t t = threadIdx.x;
+  if (blockIdx.x == 0)
+    for (uint32_t c = t; c < static_cast<uint32_t>(kBucketCounters); c += kSampleThreads) count[c] = 0;
+  uint64_t mine_of[kSampleMax / kSampleThreads];
+#pragma unroll
+  for (int u = 0; u < kSampleMax / kSampleThreads; ++u) {          // all loads first, then the stores
+    const uint32_t e = t + u * kSampleThreads;
+    mine_of[u] = e < sample ? static_cast<uint64_t>(__double_as_longlong(
+                                  fit_row[row_of[static_cast<uint64_t>(e) * P / sample]])) : ~0ull;
+  }
+#pragma unroll
+  for (int u = 0; u < kSampleMax / kSampleThreads; ++u)
+    if (t + u * kSampleThreads < sample) sk[t + u * kSampleThreads] = mine_of[u];
+  if (t < kSamplePer) rank[t] = 0;
+  __syncthreads();
+  // this workgroup ranks kSamplePer elements, a team of threads each (eight comparisons or more
+  // per thread; sample and team are powers of two)
+  const uint32_t kTeam = min(static_cast<uint32_t>(kSampleThreads / kSamplePer), sample / 8);
+  const bool idle = t / kTeam >= static_cast<uint32_t>(kSamplePer);
+  const uint32_t mine = blockIdx.x * kSamplePer + (idle ? 0u : t / kTeam);   // sample = kSamplePer * gridDim.x
+  const uint32_t part = sample / kTeam, from = (t % kTeam) * part;
+  const uint64_t key = sk[mine];
+  uint32_t below = 0;
+  for (uint32_t q = from; q < from + part && !idle; q += 8) {
+#pragma unroll
+    for (int u = 0; u < 8; ++u) below += key_less(sk[q + u], q + u, key, mine) ? 1u : 0u;
+  }
+  if (below != 0) atomicAdd(&rank[t / kTeam], below);
+  __syncthreads();
+  if (t % kTeam == 0 && !idle) {
+    const uint32_t r = rank[t / kTeam];
+    if ((r & 1u) && r / 2 + 1 < sample / 2) split[r / 2] = key;
+    // the splitters beyond the sample are +inf: nothing lands in those buckets
+    if (mine == 0)
+      for (uint32_t c = sample / 2 - 1; c < static_cast<uint32_t>(kMaxBuckets); ++c) split[c] = ~0ull;
+  }
+}
+
+// Bucket of a score = number of splitters <= it (equal scores share a bucket).  A workgroup
+// first counts its candidates per bucket in LDS and reserves their places with one global
+// atomic per bucket, instead of one per candidate.
+constexpr int kDropThreads = 1024;
+__global__ __launch_bounds__(kDropThreads) void drop_all_kernel(const double *fit_row, const uint32_t *row_of, uint32_t P,
+                                                               BucketArgs bk) {
+  __shared__ uint64_t split[kMaxBuckets];
+  __shared__ uint32_t here[kMaxBuckets], base[kMaxBuckets];
+  const uint32_t t = threadIdx.x, nb = bk.nb;
+  for (uint32_t c = t; c < nb; c += kDropThreads) { split[c] = bk.split[c]; here[c] = 0; }
+  __syncthreads();
+  const uint32_t p = blockIdx.x * kDropThreads + t;
+  uint64_t key = 0;
+  uint32_t b = 0, r = 0;
+  if (p < P) {
+    key = static_cast<uint64_t>(__double_as_longlong(fit_row[row_of[p]]));
+    uint32_t lo = 0, hi = nb - 1;                    // splitters 0 .. nb-2
+    while (lo < hi) {
+      const uint32_t mid = (lo + hi) >> 1;
+      if (split[mid] <= key) lo = mid + 1; else hi = mid;
+    }
+    b = lo;
+    r = atomicAdd(&here[b], 1u);
+  }
+  __syncthreads();
+  for (uint32_t c = t; c < nb; c += kDropThreads) base[c] = here[c] ? atomicAdd(&bk.count[c], here[c]) : 0u;
+  __syncthreads();
+  if (p < P) {
+    const uint32_t slot = base[b] + r;
+    if (slot < bk.seg) {
+      const size_t at = static_cast<size_t>(b) * bk.seg + slot;
+      bk.keys[at] = key;
+      bk.idx[at] = p;
+    } else {                                         // bucket full: shared spill list (holds a whole pool)
+      const uint32_t at = atomicAdd(&bk.count[kSpillCounter], 1u);
+      bk.spill_keys[at] = key;
+      bk.spill_idx[at] = p;
+      bk.spill_bucket[at] = b;
+    }
+  }
+}
+
+// One workgroup per bucket: its first rank is the number of candidates in the buckets before it.
+// Buckets up to kCountSort elements are ranked by counting (an element's place is the number of
+// elements below it; several threads share an element's comparisons), larger ones by the
+// sorting network.
+constexpr int kSortBucketThreads = 1024;
+constexpr int kCountSort = 512;
+__global__ __launch_bounds__(kSortBucketThreads) void bucket_sort_kernel(BucketArgs bk, RowPlan rp, uint32_t K,
+                                                                        int32_t *sel) {
+  __shared__ uint64_t sk[kBucketLds];
+  __shared__ uint32_t si[kBucketLds];
+  __shared__ uint32_t below[kCountSort];
+  __shared__ uint32_t red[kSortBucketThreads / kLanes];
+  __shared__ uint32_t spill_cursor, pool_base;
+  const uint32_t b = blockIdx.x, tid = threadIdx.x;
+  uint32_t before = 0;
+  for (uint32_t c = tid; c < b; c += kSortBucketThreads) before += bk.count[c];
+  before = wave_sum_u32(before);
+  if ((tid & (kLanes - 1)) == 0) red[tid / kLanes] = before;
+  const uint32_t n = bk.count[b];
+  const uint32_t npad = pow2_at_least(n);
+  const bool in_lds = npad <= static_cast<uint32_t>(kBucketLds);
+  if (tid == 0) {
+    spill_cursor = 0;
+    pool_base = in_lds ? 0u : atomicAdd(&bk.count[kPoolCounter], npad);   // a slice of the scratch pool
+  }
+  if (tid < static_cast<uint32_t>(kCountSort)) below[tid] = 0;
+  __syncthreads();
+  uint32_t off = 0;
+#pragma unroll
+  for (int w = 0; w < kSortBucketThreads / kLanes; ++w) off += red[w];
+  if (off >= K || n == 0) return;                    // nothing of this bucket survives (uniform)
+  if (n <= static_cast<uint32_t>(kCountSort)) {
+    // the threads form npad columns (one element each) by kSortBucketThreads / npad rows
+    // (a share of the comparisons each); padding keys are never below a real one
+    const uint32_t cols = npad < 8 ? 8 : npad, rows_of_threads = kSortBucketThreads / cols;
+    gather_bucket(sk, si, bk, b, n, cols, &spill_cursor);
+    const uint32_t e = tid % cols, share = ((cols + rows_of_threads - 1) / rows_of_threads + 7) & ~7u, from = (tid / cols) * share;
+    const uint64_t key = sk[e];
+    const uint32_t id = si[e];
+    uint32_t cnt = 0;
+    for (uint32_t q = from; q < min(from + share, cols); q += 8) {
+#pragma unroll
+      for (int u = 0; u < 8; ++u) cnt += key_less(sk[q + u], si[q + u], key, id) ? 1u : 0u;
+    }
+    if (e < n && cnt != 0) atomicAdd(&below[e], cnt);
+    __syncthreads();
+    if (tid < n && off + below[tid] < K) {
+      sel[off + below[tid]] = static_cast<int32_t>(si[tid]);
+      keep_row(rp, off + below[tid], si[tid]);
+    }
+  } else if (in_lds) {
+    gather_bucket(sk, si, bk, b, n, npad, &spill_cursor);
+    bitonic_sort(sk, si, npad);
+    for (uint32_t e = tid; e < n && off + e < K; e += kSortBucketThreads) {
+      sel[off + e] = static_cast<int32_t>(si[e]);
+      keep_row(rp, off + e, si[e]);
+    }
+  } else {                                           // oversized bucket: same network in global memory
+    uint64_t *pk = bk.pool_keys + pool_base;
+    uint32_t *pi = bk.pool_idx + pool_base;
+    gather_bucket(pk, pi, bk, b, n, npad, &spill_cursor);
+    bitonic_sort(pk, pi, npad);
+    for (uint32_t e = tid; e < n && off + e < K; e += kSortBucketThreads) {
+      sel[off + e] = static_cast<int32_t>(pi[e]);
+      keep_row(rp, off + e, pi[e]);
+    }
+  }
 }
 
 __global__ void zero_words_kernel(uint32_t *words, uint32_t n) {
@@ -375,20 +503,28 @@ hipError_t launch_zero_words(uint32_t *words, uint32_t n, hipStream_t s) {
   return hipGetLastError();
 }
 
-hipError_t launch_select(const double *fit, const RowPlan &rp, uint32_t P, uint32_t K, uint64_t *keys,
-                         uint32_t *idx, int32_t *sel, hipStream_t s) {
+hipError_t launch_select(const double *fit, const RowPlan &rp, uint32_t P, uint32_t K, const BucketArgs &store,
+                         int32_t *sel, hipStream_t s) {
   if (P <= static_cast<uint32_t>(kSortChunk)) {
-    hipLaunchKernelGGL(sort_chunks_kernel, dim3(1), dim3(kSortThreads), 0, s, fit, rp, P, K, next_pow2(P), keys,
-                       idx, sel, 1);
+    hipLaunchKernelGGL(sort_pool_kernel, dim3(1), dim3(kSortThreads), 0, s, fit, rp, P, K, next_pow2(P), sel);
     return hipGetLastError();
   }
-  const uint32_t chunks = (P + kSortChunk - 1) / kSortChunk;
-  hipLaunchKernelGGL(sort_chunks_kernel, dim3(chunks), dim3(kSortThreads), 0, s, fit, rp, P, K,
-                     static_cast<uint32_t>(kSortChunk), keys, idx, sel, 0);
+  // about 64 candidates per bucket, two sample points per bucket
+  BucketArgs bk = store;
+  uint32_t nb = 64;
+  while (nb < static_cast<uint32_t>(kMaxBuckets) && nb * 128 <= P) nb <<= 1;
+  const uint32_t sample = 2 * nb;
+  bk.seg = static_cast<uint32_t>(static_cast<size_t>(store.nb) * store.seg / nb);   // the same storage, re-divided
+  bk.nb = nb;
+  hipLaunchKernelGGL(sample_splitters_kernel, dim3(sample / kSamplePer), dim3(kSampleThreads), 0, s, fit, rp.row_of_cur,
+                     P, sample, const_cast<uint64_t *>(bk.split), bk.count);
   hipError_t rc = hipGetLastError();
   if (rc != hipSuccess) return rc;
-  const uint32_t n = chunks * kSortChunk;
-  hipLaunchKernelGGL(rank_kernel, dim3((n + 255) / 256), dim3(256), 0, s, keys, idx, chunks, K, rp, sel);
+  hipLaunchKernelGGL(drop_all_kernel, dim3((P + kDropThreads - 1) / kDropThreads), dim3(kDropThreads), 0, s, fit,
+                     rp.row_of_cur, P, bk);
+  rc = hipGetLastError();
+  if (rc != hipSuccess) return rc;
+  hipLaunchKernelGGL(bucket_sort_kernel, dim3(nb), dim3(kSortBucketThreads), 0, s, bk, rp, K, sel);
   return hipGetLastError();
 }
 
