@@ -24,8 +24,8 @@ HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published peak
 
 # HBM bytes per evolve launch on the stress workload from rocprofv3 --pmc FETCH_SIZE and
 # WRITE_SIZE (see profiles/), valid only for the kernel source with this hash.
-MEASURED_TRAFFIC = {"source_sha256": "295d3f0c6f8c3a474d50edcd14eaa786f297b438ac87d1625139d37968b72d54",
-                    "bytes_per_launch": 802739249}
+MEASURED_TRAFFIC = {"source_sha256": "87ac40224b9cdf28d27cf2158054894dc18e2e197af3ca9cdd2f2ee2f39c1e9e",
+                    "bytes_per_launch": 802699019}
 
 
 def evolve_source_hash() -> str:
