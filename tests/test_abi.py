@@ -41,7 +41,8 @@ def test_host_side_argument_checks_need_no_gpu():
     assert L.ones_workspace_bytes(ctypes.byref(bad)) == 0
     ok = ones.ones_config(64, 40, 1024, 1, 0.1, 0.5)
     need = L.ones_workspace_bytes(ctypes.byref(ok))
-    assert need >= 2 * 1024 * 64 * 4 + 1024 * 8 + 256 * 4
+    # P + K genome rows of 64 padded slots, a score per row, the survivor list
+    assert need >= (1024 + 256) * 64 * 4 + (1024 + 256) * 8 + 256 * 4
     assert L.ones_padded_jobs(0) == 64 and L.ones_padded_jobs(64) == 64 and L.ones_padded_jobs(65) == 128
     h = ctypes.c_void_p()
     assert L.ones_init(ctypes.byref(h), ctypes.byref(bad), None, None, 0, None) == -1
