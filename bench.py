@@ -121,7 +121,7 @@ def main() -> int:
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: the search runs on one GPU; --gpus above 1 is not supported "
-              "(the pool would shard by candidates, see DESIGN.md)", file=sys.stderr)
+              "(the pool would shard by candidates; only the selection couples them)", file=sys.stderr)
         return 2
 
     import torch
