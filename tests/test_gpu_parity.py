@@ -386,3 +386,51 @@ def test_full_size_stress_with_sampled_remaining_work_matches_oracle(ones, ref):
         gpu.close(); cpu.close()
     finally:
         ref.set_threads(1)
+
+
+def test_shares_of_more_than_one_round(ones, ref):
+    """A pool so large that a workgroup's share of the ranks exceeds what it lists free rows for at
+    a time (more than 256 ranks per workgroup at 18 rows), with a table change in between."""
+    import os
+    cl = cluster(3000, 1100, 280000, seed=41)
+    jobs = random_jobs(np.random.default_rng(41), 1100)
+    ref.set_threads(min(16, os.cpu_count() or 1))
+    say(f"[parity] large shares: P={cl.population} slots={cl.n_slots} seed={cl.seed}")
+    try:
+        gpu, cpu = ones.Search(cl, jobs), ref.RefSearch(cl, jobs)
+        assert_same_state(gpu, cpu, "large shares generation 0")
+        gpu.generation(1); cpu.generation(1)
+        assert_same_state(gpu, cpu, "large shares generation 1")
+        j2 = make_jobs(cl.n_slots, **{k: np.array(getattr(jobs, k)) for k in
+                                      ("job_id", "active", "bmin", "bmax", "gpu_max_batch", "a", "c", "d", "remaining")})
+        j2.job_id[5] += 7
+        j2.remaining[:] = j2.remaining * 0.9
+        gpu.set_jobs(j2); cpu.set_jobs(j2)
+        gpu.generation(1); cpu.generation(1)
+        assert_same_state(gpu, cpu, "large shares after a table change")
+        gpu.generation(1); cpu.generation(1)
+        assert_same_state(gpu, cpu, "large shares, bucketed generation")
+        gpu.close(); cpu.close()
+    finally:
+        ref.set_threads(1)
+
+
+def test_largest_population(ones, ref):
+    """P = 2^20, the largest pool the interface accepts (few job slots, so that the oracle keeps up)."""
+    import os
+    cl = cluster(9, 6, 1 << 20, seed=43)
+    jobs = random_jobs(np.random.default_rng(43), 6, inactive_frac=0.0)
+    ref.set_threads(min(16, os.cpu_count() or 1))
+    say(f"[parity] largest population: P={cl.population} slots={cl.n_slots} seed={cl.seed}")
+    try:
+        gpu, cpu = ones.Search(cl, jobs), ref.RefSearch(cl, jobs)
+        assert_same_state(gpu, cpu, "largest population generation 0")
+        gpu.generation(2); cpu.generation(2)
+        assert_same_state(gpu, cpu, "largest population generation 2")
+        alpha, beta, proc = W.progress(cl.n_slots, seed=43)
+        gpu.set_progress(alpha, beta, proc); cpu.set_progress(alpha, beta, proc)
+        gpu.generation(1); cpu.generation(1)
+        assert_same_state(gpu, cpu, "largest population, sampled remaining work")
+        gpu.close(); cpu.close()
+    finally:
+        ref.set_threads(1)
