@@ -47,6 +47,7 @@ struct ones_ref_ctx {
   int32_t *sel;            /* [K] */
   int      cur;
   int64_t  t;              /* generation counter; 0 = initial population */
+  int      stale;          /* job table replaced since the last generation */
   int      sampling;       /* Alg. 1: remaining work drawn per generation */
   double  *alpha, *beta, *processed, *Y_fixed;   /* Jn entries each */
 };
@@ -502,6 +503,7 @@ int ones_ref_set_jobs(ones_ref_ctx *c, const ones_ref_jobs *jobs) {
   }
   free(c->tab);
   c->tab = tab;
+  c->stale = 1;
   for (int j = 0; j < c->Jn; ++j) c->Y_fixed[j] = tab[j].Y;
   return ONES_REF_OK;
 }
@@ -528,6 +530,7 @@ int ones_ref_generation(ones_ref_ctx *c, int32_t n_generations) {
     ones_ref_select(c->fit, c->P, c->sel);
     c->cur ^= 1;
     c->t += 1;
+    c->stale = 0;
   }
   return ONES_REF_OK;
 }
@@ -541,6 +544,26 @@ int ones_ref_best(ones_ref_ctx *c, int32_t *batch_out, int32_t *gpus_out, double
     if (gpus_out) gpus_out[j] = (int32_t)gpus_of(exponent_of(row[j]), c->tab[j].mu);
   }
   if (fitness_out) *fitness_out = c->fit[best];
+  return ONES_REF_OK;
+}
+
+/* Eq. 1 for the winner after the reorder operator: walk the slots in order and hand each
+ * running job its c_j GPUs, B_j / c_j samples each; what is left is idle. */
+int ones_ref_placement(ones_ref_ctx *c, int32_t *slot_of_gpu, int32_t *batch_of_gpu) {
+  if (!c || c->stale) return ONES_REF_E_INVALID_ARG;
+  const int32_t *row = c->genes[c->cur] + (size_t)c->sel[0] * c->Jp;
+  int gpu = 0;
+  for (int j = 0; j < c->Jn; ++j) {
+    int64_t gpus = gpus_of(exponent_of(row[j]), c->tab[j].mu);
+    for (int64_t k = 0; k < gpus && gpu < c->G; ++k, ++gpu) {
+      if (slot_of_gpu) slot_of_gpu[gpu] = j;
+      if (batch_of_gpu) batch_of_gpu[gpu] = (int32_t)(row[j] / gpus);
+    }
+  }
+  for (; gpu < c->G; ++gpu) {
+    if (slot_of_gpu) slot_of_gpu[gpu] = -1;
+    if (batch_of_gpu) batch_of_gpu[gpu] = 0;
+  }
   return ONES_REF_OK;
 }
 

@@ -22,6 +22,8 @@
  *                            alpha*beta/((alpha+beta)^2 (alpha+beta+1)), KS against the
  *                            Beta distribution function, Be(1,1) uniform,
  *                            E[1/rho - 1] = beta/(alpha-1), a Python transcription.
+ *   ones_ref_placement     : Eq. 2 (B_j and c_j recovered from the per-GPU batches), one job
+ *                            per GPU, packing in slot order, a hand-worked example.
  *   scheduling quality against the paper's JCT numbers: parity unpinned (the paper's
  *                            trace, jobs and comparison schedulers do not exist here).
  */
@@ -83,6 +85,14 @@ int  ones_ref_set_progress(ones_ref_ctx *ctx, const double *alpha, const double 
                            const double *processed);
 /* the remaining work Y_j (n_slots entries) the last generation was scored with */
 int  ones_ref_export_remaining(ones_ref_ctx *ctx, double *remaining_out);
+
+/* The winner as the paper's mapping from (job, GPU) to a local batch (Eq. 1), packed the way
+ * the reorder operator leaves it (Section 3.2.2): the jobs in slot order, each on c_j
+ * consecutive GPUs with B_j / c_j samples per GPU.  n_gpus entries each: the slot whose worker
+ * GPU i runs (-1 = idle) and that worker's batch (0 = idle); either may be NULL.  Fails with
+ * ONES_REF_E_INVALID_ARG between ones_ref_set_jobs and the next generation, when no schedule
+ * exists under the current job table. */
+int  ones_ref_placement(ones_ref_ctx *ctx, int32_t *slot_of_gpu, int32_t *batch_of_gpu);
 
 /* single steps, exposed so that tests can pin them one at a time */
 double ones_ref_log(double x);                  /* natural logarithm of a positive normal number */

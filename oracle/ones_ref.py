@@ -69,6 +69,7 @@ def lib():
                                             C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
         L.ones_ref_initial_genome.argtypes = [C.POINTER(_Config), C.POINTER(_Jobs), C.c_int32,
                                               C.c_void_p, C.POINTER(C.c_uint32)]
+        L.ones_ref_placement.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
         L.ones_ref_set_progress.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         L.ones_ref_export_remaining.argtypes = [C.c_void_p, C.c_void_p]
         L.ones_ref_log.argtypes = [C.c_double]
@@ -179,6 +180,7 @@ class RefSearch:
 
     def __init__(self, cluster, jobs):
         self.n_slots = int(cluster.n_slots)
+        self.n_gpus = int(cluster.n_gpus)
         self.population = int(cluster.population)
         self.jp = padded_jobs(self.n_slots)
         cfg = _cfg(cluster.n_gpus, cluster.n_slots, cluster.population, cluster.seed,
@@ -215,6 +217,12 @@ class RefSearch:
         f = C.c_double(0.0)
         _check(lib().ones_ref_best(self._h, b.ctypes.data, g.ctypes.data, C.byref(f)))
         return b, g, f.value
+
+    def placement(self):
+        """(slot of every GPU, -1 = idle; batch of every GPU's worker)"""
+        slot = np.zeros(max(self.n_gpus, 1), np.int32); batch = np.zeros(max(self.n_gpus, 1), np.int32)
+        _check(lib().ones_ref_placement(self._h, slot.ctypes.data, batch.ctypes.data))
+        return slot[:self.n_gpus], batch[:self.n_gpus]
 
     def export(self):
         genes = np.zeros((self.population, self.jp), np.int32)

@@ -378,3 +378,57 @@ def test_argument_validation(ref):
     assert code(cluster(4, 4, 16), make_jobs(4, c=1e101)) == -3
     # garbage in an inactive slot is ignored
     R(cluster(4, 4, 16), make_jobs(4, active=[1, 0, 1, 1], bmin=[32, 3, 32, 32], a=[1e-3, float("nan"), 1e-3, 1e-3]))
+
+
+# ------------------------------------------------ the winner as a map onto the GPUs (Eq. 1) ----
+def test_placement_hand_example(ref):
+    """Job 0 can only run 256 samples on one GPU, job 1 only 512 on two (256 per GPU), job 2 only
+    1024 on four.  On 4 GPUs the fill leaves no GPU idle when it can: the winner runs jobs 0 and 1
+    (3 GPUs, job 2 does not fit beside either) or job 2 alone; the scores decide.  Job 2 is given
+    so much work that running it alone scores worse, so the map is 0, 1, 1, idle."""
+    jobs = make_jobs(3, bmin=[256, 512, 1024], bmax=[256, 512, 1024], gpu_max_batch=256,
+                     remaining=[1e6, 1e6, 1e9])
+    cl = SimpleNamespace(n_gpus=4, n_slots=3, population=16, seed=5, mutation_rate=0.1, crossover_rate=0.5)
+    s = ref.RefSearch(cl, jobs)
+    s.generation(30)
+    batch, gpus, _ = s.best()
+    assert batch.tolist() == [256, 512, 0] and gpus.tolist() == [1, 2, 0]
+    slot, per_gpu = s.placement()
+    assert slot.tolist() == [0, 1, 1, -1] and per_gpu.tolist() == [256, 256, 256, 0]
+    # with 7 GPUs everything runs: 0 | 1 1 | 2 2 2 2
+    cl7 = SimpleNamespace(n_gpus=7, n_slots=3, population=16, seed=5, mutation_rate=0.1, crossover_rate=0.5)
+    s7 = ref.RefSearch(cl7, jobs)
+    s7.generation(30)
+    slot, per_gpu = s7.placement()
+    assert slot.tolist() == [0, 1, 1, 2, 2, 2, 2] and per_gpu.tolist() == [256] * 7
+
+
+def test_placement_satisfies_eq_2(ref):
+    """B_j = sum_i b_j^i and c_j = sum_i min(1, b_j^i) recover the winner; one job per GPU; the
+    workers of a job are adjacent and the jobs appear in slot order (reorder); idle GPUs last."""
+    for maker in (W.tiny, W.paper_scale):
+        cluster, jobs = maker()
+        s = ref.RefSearch(cluster, jobs)
+        for gens in (0, 3):
+            s.generation(gens)
+            batch, gpus, _ = s.best()
+            slot, per_gpu = s.placement()
+            assert len(slot) == cluster.n_gpus
+            for j in range(cluster.n_slots):
+                mine = per_gpu[slot == j]
+                assert mine.sum() == batch[j] and np.minimum(1, mine).sum() == gpus[j]
+            used = int(gpus.sum())
+            assert (slot[:used] >= 0).all() and (slot[used:] == -1).all() and (per_gpu[used:] == 0).all()
+            assert (np.diff(slot[:used]) >= 0).all()
+
+
+def test_placement_needs_a_schedule_under_the_current_table(ref):
+    cluster, jobs = W.tiny()
+    s = ref.RefSearch(cluster, jobs)
+    s.placement()
+    s.set_jobs(jobs)
+    with pytest.raises(ref.RefError) as e:
+        s.placement()
+    assert e.value.code == -1
+    s.generation(1)
+    s.placement()
