@@ -120,6 +120,15 @@ int ones_generation(ones_ctx *ctx, int32_t n_generations);
  * arrays of n_slots entries, either may be NULL) and its score.  Synchronises. */
 int ones_best(ones_ctx *ctx, int32_t *batch_out, int32_t *gpus_out, double *fitness_out);
 
+/* The winner as the paper's mapping from (job, GPU) to a local batch (Eq. 1), packed the way
+ * the reorder operator leaves it (Section 3.2.2): the jobs in slot order, each on c_j
+ * consecutive GPUs with B_j / c_j samples per GPU, idle GPUs last.  HOST arrays of n_gpus
+ * entries, either may be NULL: the slot whose worker GPU i runs (-1 = idle) and that worker's
+ * batch (0 = idle).  Eq. 2 recovers ones_best's outputs from them.  ONES_E_INVALID_ARG between
+ * ones_set_jobs and the next generation (no schedule exists under the current job table).
+ * Synchronises. */
+int ones_placement(ones_ctx *ctx, int32_t *slot_of_gpu, int32_t *batch_of_gpu);
+
 /* Copies the whole state to HOST arrays (any may be NULL): genes[P][Jp] batch sizes with
  * Jp = ones_padded_jobs(n_slots), fit[P], sel[K] (survivor slots by ascending
  * (fitness, slot)), generation counter.  For parity checks and checkpoints.  Synchronises. */

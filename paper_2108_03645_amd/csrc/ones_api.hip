@@ -30,7 +30,7 @@ size_t align_up(size_t v) { return (v + 255) & ~static_cast<size_t>(255); }
 
 struct Layout {
   size_t genes, fit_row, row_of[2], parent_row[2], occupied[2], sel, split, thresh, bcount[2], bkeys, bidx, skeys, sidx, sbucket, pkeys, pidx, cstart, cmax, info, abl, cc, d, Y, terms;
-  size_t rawinfo, changed, ra, rc, rd, rY, alpha, beta, processed, best_batch, best_gpus, best_fit, total;
+  size_t rawinfo, changed, ra, rc, rd, rY, alpha, beta, processed, best_batch, best_gpus, best_fit, place_slot, place_batch, total;
 };
 
 // Buckets: about 16 survivors each, at most kMaxBuckets.  A bucket stores eight times its fair
@@ -51,7 +51,7 @@ BucketPlan bucket_plan(uint32_t P) {
   return bp;
 }
 
-Layout make_layout(uint32_t P, uint32_t Jp) {
+Layout make_layout(uint32_t P, uint32_t Jp, uint32_t G) {
   Layout L;
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t at = off; off = align_up(off + bytes); return at; };
@@ -83,6 +83,7 @@ Layout make_layout(uint32_t P, uint32_t Jp) {
   L.ra = take(Jp * 8); L.rc = take(Jp * 8); L.rd = take(Jp * 8); L.rY = take(Jp * 8);
   L.alpha = take(Jp * 8); L.beta = take(Jp * 8); L.processed = take(Jp * 8);
   L.best_batch = take(Jp * 4); L.best_gpus = take(Jp * 4); L.best_fit = take(8);
+  L.place_slot = take(static_cast<size_t>(G) * 4); L.place_batch = take(static_cast<size_t>(G) * 4);
   L.total = off;
   return L;
 }
@@ -163,6 +164,7 @@ struct ones_ctx {
   Layout L;
   int cur;                    // which row_of array describes the current generation
   bool table_changed;         // job table replaced since the current generation was computed
+  bool no_schedule;           // ... by ones_set_jobs: the winner is not a schedule under the new table
   bool sampling;              // remaining work drawn per generation (Alg. 1) instead of the table's
   BucketPlan bp;              // nb == 0: pool small enough for the single-chunk sort
   int bucket_phase;           // which counter set the next bucketed generation fills
@@ -296,6 +298,7 @@ int run_generation(ones_ctx *c, uint32_t t) {
   if ((rc = timed(c, c->select_ev, c->select_used, false))) return rc;
   c->cur = next;
   c->table_changed = false;
+  c->no_schedule = false;
   c->profile_tick += 1;
   return ONES_OK;
 }
@@ -311,8 +314,8 @@ int32_t ones_padded_jobs(int32_t n_slots) {
 
 size_t ones_workspace_bytes(const ones_config *cfg) {
   if (check_config(cfg) != ONES_OK) return 0;
-  return make_layout(static_cast<uint32_t>(cfg->population),
-                     static_cast<uint32_t>(ones_padded_jobs(cfg->n_slots))).total;
+  return make_layout(static_cast<uint32_t>(cfg->population), static_cast<uint32_t>(ones_padded_jobs(cfg->n_slots)),
+                     static_cast<uint32_t>(cfg->n_gpus)).total;
 }
 
 int ones_init(ones_ctx **out, const ones_config *cfg, const ones_jobs *jobs, void *d_workspace,
@@ -323,7 +326,8 @@ int ones_init(ones_ctx **out, const ones_config *cfg, const ones_jobs *jobs, voi
   const int Jp = ones_padded_jobs(cfg->n_slots);
   HostJobs h;
   if ((rc = stage_jobs(cfg->n_slots, Jp, jobs, h))) return rc;
-  const Layout L = make_layout(static_cast<uint32_t>(cfg->population), static_cast<uint32_t>(Jp));
+  const Layout L = make_layout(static_cast<uint32_t>(cfg->population), static_cast<uint32_t>(Jp),
+                               static_cast<uint32_t>(cfg->n_gpus));
   if (!d_workspace) return ONES_E_INVALID_ARG;
   if (workspace_bytes < L.total || (reinterpret_cast<uintptr_t>(d_workspace) & 255u) != 0)
     return ONES_E_WORKSPACE_TOO_SMALL;
@@ -340,6 +344,7 @@ int ones_init(ones_ctx **out, const ones_config *cfg, const ones_jobs *jobs, voi
   c->L = L;
   c->cur = 0; c->t = 0;
   c->table_changed = false;
+  c->no_schedule = false;
   c->sampling = false;
   c->bp = bucket_plan(c->P);
   c->bucket_phase = 0;
@@ -378,6 +383,7 @@ int ones_set_jobs(ones_ctx *c, const ones_jobs *jobs) {
   if ((rc = upload_table(c, h, any ? &changed : nullptr))) return rc;
   c->ids = h.id;
   c->table_changed = true;
+  c->no_schedule = true;
   return ONES_OK;
 }
 
@@ -447,6 +453,23 @@ int ones_best(ones_ctx *c, int32_t *batch_out, int32_t *gpus_out, double *fitnes
   if (batch_out && c->Jn) memcpy(batch_out, b.data(), c->Jn * 4);
   if (gpus_out && c->Jn) memcpy(gpus_out, g.data(), c->Jn * 4);
   if (fitness_out) *fitness_out = f;
+  return ONES_OK;
+}
+
+int ones_placement(ones_ctx *c, int32_t *slot_of_gpu, int32_t *batch_of_gpu) {
+  if (!c || c->no_schedule) return ONES_E_INVALID_ARG;
+  const size_t n4 = static_cast<size_t>(c->G) * 4;
+  HIP_TRY(launch_placement(c->at<int32_t>(c->L.genes), c->at<uint32_t>(c->L.row_of[c->cur]), c->at<int32_t>(c->L.sel),
+                           c->at<uint32_t>(c->L.info), c->Jn, c->Jp, c->G, c->at<int32_t>(c->L.place_slot),
+                           c->at<int32_t>(c->L.place_batch), c->stream));
+  std::vector<int32_t> slot(c->G), batch(c->G);
+  if (c->G) {
+    HIP_TRY(hipMemcpyAsync(slot.data(), c->ws + c->L.place_slot, n4, hipMemcpyDeviceToHost, c->stream));
+    HIP_TRY(hipMemcpyAsync(batch.data(), c->ws + c->L.place_batch, n4, hipMemcpyDeviceToHost, c->stream));
+  }
+  HIP_TRY(hipStreamSynchronize(c->stream));
+  if (slot_of_gpu && c->G) memcpy(slot_of_gpu, slot.data(), n4);
+  if (batch_of_gpu && c->G) memcpy(batch_of_gpu, batch.data(), n4);
   return ONES_OK;
 }
 

@@ -170,6 +170,11 @@ hipError_t launch_bucket_select(const double *fit_row, const uint32_t *parent_ro
 hipError_t launch_splitters(const double *fit_row, const uint32_t *row_of, const int32_t *sel, uint32_t K,
                             uint32_t nb, uint64_t *split, uint64_t *thresh, uint32_t *count0, uint32_t *count1,
                             hipStream_t s);
+// Eq. 1 for the winner: GPU i runs slot slot_of_gpu[i] (-1 = idle) with batch_of_gpu[i] samples;
+// jobs in slot order on consecutive GPUs.  G entries each.
+hipError_t launch_placement(const int32_t *genes, const uint32_t *row_of, const int32_t *sel, const uint32_t *info,
+                            uint32_t Jn, uint32_t Jp, uint32_t G, int32_t *slot_of_gpu, int32_t *batch_of_gpu,
+                            hipStream_t s);
 hipError_t launch_best(const int32_t *genes, const double *fit_row, const uint32_t *row_of, const int32_t *sel,
                        const uint32_t *info,
                        uint32_t Jn, uint32_t Jp, int32_t *batch_out, int32_t *gpus_out, double *fit_out,

@@ -472,6 +472,61 @@ __global__ void best_kernel(const int32_t *genes, const double *fit_row, const u
   if (threadIdx.x == 0) *fit_out = fit_row[best];
 }
 
+// The winner unrolled over the GPUs (Eq. 1, reorder): every workgroup scans the jobs' GPU
+// counts in LDS (at most 2048 slots), then each thread finds the job of one GPU by binary
+// search over the prefix sums.
+constexpr int kPlaceThreads = 1024;
+__global__ __launch_bounds__(kPlaceThreads) void placement_kernel(const int32_t *genes, const uint32_t *row_of,
+                                                                 const int32_t *sel, const uint32_t *info, uint32_t Jn,
+                                                                 uint32_t Jp, uint32_t G, int32_t *slot_of_gpu,
+                                                                 int32_t *batch_of_gpu) {
+  __shared__ uint32_t first[2 * kPlaceThreads + 1];    // first GPU of every slot, then the GPUs in use
+  __shared__ uint32_t per_gpu[2 * kPlaceThreads];      // local batch of every slot's workers
+  __shared__ uint32_t wave_total[kPlaceThreads / kLanes];
+  const int32_t *row = genes + static_cast<size_t>(row_of[sel[0]]) * Jp;
+  const uint32_t t = threadIdx.x;
+  // thread t owns slots 2t and 2t + 1
+  uint32_t c[2];
+#pragma unroll
+  for (int u = 0; u < 2; ++u) {
+    const uint32_t j = 2 * t + u;
+    const uint32_t B = j < Jn ? static_cast<uint32_t>(row[j]) : 0u;
+    c[u] = B ? max(1u, B >> info_mu(info[j < Jn ? j : 0])) : 0u;
+    per_gpu[j] = B ? B / c[u] : 0u;
+  }
+  const uint32_t mine = c[0] + c[1];
+  uint32_t incl = mine;
+#pragma unroll
+  for (int d = 1; d < kLanes; d <<= 1) {
+    const uint32_t up = __shfl_up(incl, d, kLanes);
+    if ((t & (kLanes - 1)) >= static_cast<uint32_t>(d)) incl += up;
+  }
+  if ((t & (kLanes - 1)) == kLanes - 1) wave_total[t / kLanes] = incl;
+  __syncthreads();
+  uint32_t before = 0;
+  for (uint32_t w = 0; w < t / kLanes; ++w) before += wave_total[w];
+  const uint32_t excl = before + incl - mine;
+  first[2 * t] = excl;
+  first[2 * t + 1] = excl + c[0];
+  if (t == kPlaceThreads - 1) first[2 * kPlaceThreads] = excl + mine;
+  __syncthreads();
+  const uint32_t used = first[2 * kPlaceThreads];
+  for (uint32_t i = blockIdx.x * kPlaceThreads + t; i < G; i += gridDim.x * kPlaceThreads) {
+    int32_t slot = -1, batch = 0;
+    if (i < used) {
+      uint32_t lo = 0, hi = 2 * kPlaceThreads;       // last slot with first[slot] <= i
+      while (hi - lo > 1) {
+        const uint32_t mid = (lo + hi) >> 1;
+        if (first[mid] <= i) lo = mid; else hi = mid;
+      }
+      slot = static_cast<int32_t>(lo);
+      batch = static_cast<int32_t>(per_gpu[lo]);
+    }
+    if (slot_of_gpu) slot_of_gpu[i] = slot;
+    if (batch_of_gpu) batch_of_gpu[i] = batch;
+  }
+}
+
 uint32_t next_pow2(uint32_t v) {
   uint32_t n = 1;
   while (n < v) n <<= 1;
@@ -540,6 +595,15 @@ hipError_t launch_splitters(const double *fit_row, const uint32_t *row_of, const
                             hipStream_t s) {
   hipLaunchKernelGGL(splitters_kernel, dim3((kBucketCounters + 255) / 256), dim3(256), 0, s, fit_row, row_of, sel, K,
                      nb, split, thresh, count0, count1);
+  return hipGetLastError();
+}
+
+hipError_t launch_placement(const int32_t *genes, const uint32_t *row_of, const int32_t *sel, const uint32_t *info,
+                            uint32_t Jn, uint32_t Jp, uint32_t G, int32_t *slot_of_gpu, int32_t *batch_of_gpu,
+                            hipStream_t s) {
+  const uint32_t blocks = std::max<uint32_t>(1u, std::min<uint32_t>((G + kPlaceThreads - 1) / kPlaceThreads, 1024u));
+  hipLaunchKernelGGL(placement_kernel, dim3(blocks), dim3(kPlaceThreads), 0, s, genes, row_of, sel, info, Jn, Jp, G,
+                     slot_of_gpu, batch_of_gpu);
   return hipGetLastError();
 }
 

@@ -35,7 +35,7 @@ _JOB_DTYPES = {"job_id": np.int64, "active": np.uint8, "bmin": np.int32, "bmax":
                "remaining": np.float64}
 
 EXPORTS = ["ones_workspace_bytes", "ones_init", "ones_set_jobs", "ones_generation", "ones_best",
-           "ones_export", "ones_set_progress", "ones_export_remaining", "ones_padded_jobs",
+           "ones_export", "ones_placement", "ones_set_progress", "ones_export_remaining", "ones_padded_jobs",
            "ones_profile_enable", "ones_profile_read",
            "ones_destroy", "ones_strerror"]
 
@@ -64,6 +64,7 @@ def load():
     L.ones_generation.argtypes = [C.c_void_p, C.c_int32]
     L.ones_best.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(C.c_double)]
     L.ones_export.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(C.c_int64)]
+    L.ones_placement.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
     L.ones_set_progress.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
     L.ones_export_remaining.argtypes = [C.c_void_p, C.c_void_p]
     L.ones_padded_jobs.argtypes = [C.c_int32]
@@ -116,6 +117,7 @@ class Search:
         self._torch = torch
         self.device = torch.device(device)
         self.n_slots = int(cluster.n_slots)
+        self.n_gpus = int(cluster.n_gpus)
         self.population = int(cluster.population)
         self.jp = padded_jobs(self.n_slots)
         cfg = make_config(cluster)
@@ -166,6 +168,14 @@ class Search:
         with self._torch.cuda.device(self.device):
             _check(load().ones_best(self._h, b.ctypes.data, g.ctypes.data, C.byref(f)))
         return b, g, f.value
+
+    def placement(self):
+        """(slot of every GPU, -1 = idle; batch of every GPU's worker): Eq. 1 for the winner."""
+        slot = np.zeros(max(self.n_gpus, 1), np.int32)
+        batch = np.zeros(max(self.n_gpus, 1), np.int32)
+        with self._torch.cuda.device(self.device):
+            _check(load().ones_placement(self._h, slot.ctypes.data, batch.ctypes.data))
+        return slot[:self.n_gpus], batch[:self.n_gpus]
 
     def export(self, genes=True):
         g = np.zeros((self.population, self.jp), np.int32) if genes else None

@@ -434,3 +434,28 @@ def test_largest_population(ones, ref):
         gpu.close(); cpu.close()
     finally:
         ref.set_threads(1)
+
+
+@pytest.mark.parametrize("n_slots,n_gpus,pop,seed", [(8, 16, 64, 0), (40, 64, 256, 1), (333, 700, 128, 2),
+                                                     (2048, 4096, 64, 3), (1500, 100000, 64, 4), (5, 0, 16, 5),
+                                                     (2048, 1 << 20, 16, 6)])
+def test_placement_matches_the_oracle(ones, ref, n_slots, n_gpus, pop, seed):
+    """Eq. 1 for the winner (slot and batch per GPU), from few GPUs to the largest cluster."""
+    cl = cluster(n_gpus, n_slots, pop, seed=seed)
+    jobs = random_jobs(np.random.default_rng(seed), n_slots)
+    say(f"[placement] G={n_gpus} slots={n_slots} P={pop} seed={seed}")
+    gpu, cpu = ones.Search(cl, jobs), ref.RefSearch(cl, jobs)
+    for gens in (0, 2):
+        gpu.generation(gens); cpu.generation(gens)
+        gs, gb = gpu.placement()
+        cs, cb = cpu.placement()
+        assert np.array_equal(gs, cs) and np.array_equal(gb, cb)
+        batch, gpus, _ = gpu.best()
+        assert int((gs >= 0).sum()) == int(gpus.sum())
+    gpu.set_jobs(jobs); cpu.set_jobs(jobs)
+    with pytest.raises(ones.OnesError) as e:
+        gpu.placement()
+    assert e.value.code == -1
+    gpu.generation(1); cpu.generation(1)
+    assert np.array_equal(gpu.placement()[0], cpu.placement()[0])
+    gpu.close(); cpu.close()
