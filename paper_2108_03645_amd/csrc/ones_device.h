@@ -24,8 +24,9 @@ __device__ __forceinline__ Words philox4x32_10(uint32_t x0, uint32_t x1, uint32_
   for (int round = 0; round < 10; ++round) {
     const uint64_t pa = static_cast<uint64_t>(x0) * 0xD2511F53ull;
     const uint64_t pb = static_cast<uint64_t>(x2) * 0xCD9E8D57ull;
-    const uint32_t n0 = static_cast<uint32_t>(pb >> 32) ^ x1 ^ k0;
-    const uint32_t n2 = static_cast<uint32_t>(pa >> 32) ^ x3 ^ k1;
+    // three-input xor in one instruction (truth table 0x96)
+    const uint32_t n0 = __builtin_amdgcn_bitop3_b32(static_cast<uint32_t>(pb >> 32), x1, k0, 0x96);
+    const uint32_t n2 = __builtin_amdgcn_bitop3_b32(static_cast<uint32_t>(pa >> 32), x3, k1, 0x96);
     x1 = static_cast<uint32_t>(pb);
     x3 = static_cast<uint32_t>(pa);
     x0 = n0;
