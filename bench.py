@@ -24,8 +24,8 @@ HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published peak
 
 # HBM bytes per evolve launch on the stress workload from rocprofv3 --pmc FETCH_SIZE and
 # WRITE_SIZE (see profiles/), valid only for the kernel source with this hash.
-MEASURED_TRAFFIC = {"source_sha256": "87ac40224b9cdf28d27cf2158054894dc18e2e197af3ca9cdd2f2ee2f39c1e9e",
-                    "bytes_per_launch": 802699019}
+MEASURED_TRAFFIC = {"source_sha256": "a31e14f80345a9951941d3836aae08a5c4b9f40c6899bedf5dcd7b9f7441400f",
+                    "bytes_per_launch": 802730044}
 
 
 def evolve_source_hash() -> str:
