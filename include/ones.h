@@ -7,7 +7,9 @@
  * the refresh / uniform crossover / uniform mutation operators (Section 3.2.2), the
  * repair of every candidate to the cluster's capacity (Eq. 4), the scoring with the
  * "smallest remaining utilisation" objective sum_j T_j * c_j (Eq. 3 with T = Y/X,
- * Eq. 5 / Eq. 8) and the selection of the best K candidates.
+ * Eq. 5 / Eq. 8) and the selection of the best K candidates; optionally with the remaining
+ * work Y_j drawn per generation from the jobs' progress distributions (Alg. 1, Eq. 7), and
+ * with the winner unrolled into the paper's map from GPUs to jobs (Eq. 1).
  *
  * Encoding.  A schedule is one gene per job slot: the job's global batch size B_j,
  * either 0 (the job waits, "B_j = c_j = 0" of Section 3) or a power of two inside

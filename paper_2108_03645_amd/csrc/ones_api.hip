@@ -33,10 +33,12 @@ struct Layout {
   size_t rawinfo, changed, ra, rc, rd, rY, alpha, beta, processed, best_batch, best_gpus, best_fit, place_slot, place_batch, total;
 };
 
-// Buckets: about 16 survivors each, at most kMaxBuckets.  A bucket stores eight times its fair
-// share of the 3P/4 children and mutants (at least 256, a power of two); the surplus goes to a
-// spill list that could hold all of them, and buckets too large for LDS are sorted in a scratch
-// pool of twice that size (each takes a power-of-two slice).
+// Buckets of the selection: about 16 survivors each, at most kMaxBuckets.  A bucket stores eight
+// times its fair share of the 3P/4 children and mutants (at least 256, a power of two); the
+// surplus goes to a spill list that can hold a whole pool (the general selection drops every
+// candidate, and equal scores all land in one bucket), and buckets too large for LDS are sorted
+// in a scratch pool (each takes a power-of-two slice below twice its size).  The general
+// selection re-divides the same bucket space among its own number of buckets.
 struct BucketPlan { uint32_t nb, seg, spill, pool; };
 constexpr uint32_t kMinBucketPool = 256;
 uint32_t pow2_at_least(uint32_t v) { uint32_t n = 1; while (n < v) n <<= 1; return n; }

@@ -6,8 +6,9 @@
 // uniform crossover, uniform mutation), repairs it to the cluster capacity (refresh + fill
 // under Eq. 4), scores it (Eq. 3 with T = Y/X, Eq. 5) and writes genome and score.
 //
-// Workgroups are persistent: each stages the job table in LDS once and its waves then walk
-// the work items with a grid stride; waves never synchronise with each other after that.
+// Workgroups are persistent: each stages the job table in LDS once, owns a contiguous share
+// of the work and lists the free genome rows its share will fill; its waves then take the
+// share's items one by one from an LDS counter and never wait for each other.
 #include "ones_device.h"
 
 #include <algorithm>
@@ -32,10 +33,10 @@ __device__ __forceinline__ void phase_fence() {
   __builtin_amdgcn_sched_barrier(0);    // ... and in the instruction scheduler
 }
 __device__ __forceinline__ void fence_every(int i, int n) { if (i % n == n - 1) phase_fence(); }
-// The lane number, re-materialised so that nothing derived from it (LDS addresses, the first
-// Philox round) is hoisted out of the work-item loop and kept live, or spilled, across it.
 // Forces x to be computed before the following fence (its producers cannot sink below it).
 template <typename T> __device__ __forceinline__ void pin(T &x) { asm volatile("" : "+v"(x)); }
+// The lane number, re-materialised so that nothing derived from it (LDS addresses, the first
+// Philox round) is hoisted out of the work-item loop and kept live, or spilled, across it.
 __device__ __forceinline__ int opaque(int v) { asm volatile("" : "+v"(v)); return v; }
 
 // ------------------------------------------------------------------ RNG ------------
