@@ -567,6 +567,57 @@ int ones_ref_placement(ones_ref_ctx *c, int32_t *slot_of_gpu, int32_t *batch_of_
   return ONES_REF_OK;
 }
 
+/* ------------------------------------------------ batch-size limit policies ------ */
+static int32_t floor_pow2(int64_t v) {
+  int32_t p = 1;
+  while ((int64_t)p * 2 <= v) p *= 2;
+  return p;
+}
+
+int ones_ref_update_limits(int32_t n_slots, const ones_ref_limit_inputs *in, double sigma, int32_t *limit) {
+  if (n_slots < 0 || n_slots > MAX_SLOTS) return ONES_REF_E_INVALID_ARG;
+  if (n_slots > 0 && (!in || !limit || !in->state || !in->bmin || !in->bcap || !in->gpu_max_batch ||
+                      !in->last_batch || !in->finished_epoch || !in->elapsed))
+    return ONES_REF_E_INVALID_ARG;
+  if (!isfinite(sigma)) return ONES_REF_E_NONFINITE;
+  if (sigma < 0.0) return ONES_REF_E_INVALID_ARG;
+  for (int j = 0; j < n_slots; ++j) {            /* check everything before changing anything */
+    if (in->state[j] > 3) return ONES_REF_E_INVALID_ARG;
+    if (in->state[j] == 0) continue;
+    if (ilog2_exact(in->bmin[j]) < 0 || ilog2_exact(in->bcap[j]) < 0 || ilog2_exact(in->gpu_max_batch[j]) < 0)
+      return ONES_REF_E_NOT_POW2;
+    if (in->bmin[j] > in->bcap[j] || in->bcap[j] > (1 << 30)) return ONES_REF_E_BOUNDS;
+    if (in->state[j] >= 2 && limit[j] < 1) return ONES_REF_E_INVALID_ARG;
+    if (in->state[j] == 2 && in->last_batch[j] < 0) return ONES_REF_E_INVALID_ARG;
+    if (in->state[j] == 3) {
+      if (!isfinite(in->elapsed[j])) return ONES_REF_E_NONFINITE;
+      if (in->elapsed[j] < 0.0) return ONES_REF_E_INVALID_ARG;
+      if (sigma * in->elapsed[j] > 1e15) return ONES_REF_E_BOUNDS;
+    }
+  }
+  for (int j = 0; j < n_slots; ++j) {
+    int64_t r = limit[j];
+    switch (in->state[j]) {
+      case 0: limit[j] = 0; continue;
+      case 1: r = in->gpu_max_batch[j]; break;                       /* Start: one GPU */
+      case 2:                                                         /* Resume */
+        if (in->last_batch[j] > 0) { if (r > in->last_batch[j]) r = in->last_batch[j]; }
+        else r = r / 2;
+        break;
+      default:                                                        /* Scale-up and Scale-down */
+        if (in->finished_epoch[j]) {
+          int64_t den = (int64_t)ceil(sigma * in->elapsed[j] + 1.0);
+          r = (2 * r + den - 1) / den;
+        }
+        break;
+    }
+    if (r < in->bmin[j]) r = in->bmin[j];
+    if (r > in->bcap[j]) r = in->bcap[j];
+    limit[j] = floor_pow2(r);
+  }
+  return ONES_REF_OK;
+}
+
 int ones_ref_export(ones_ref_ctx *c, int32_t *genes, double *fit, int32_t *sel, int64_t *generation) {
   if (!c) return ONES_REF_E_INVALID_ARG;
   if (genes) memcpy(genes, c->genes[c->cur], sizeof(int32_t) * (size_t)c->P * c->Jp);

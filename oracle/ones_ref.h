@@ -24,6 +24,9 @@
  *                            E[1/rho - 1] = beta/(alpha-1), a Python transcription.
  *   ones_ref_placement     : Eq. 2 (B_j and c_j recovered from the per-GPU batches), one job
  *                            per GPU, packing in slot order, a hand-worked example.
+ *   ones_ref_update_limits : the four policies worked by hand (doubling at T = 0, the
+ *                            printed penalty formula at several sigma*T, halving on rejection,
+ *                            the cap at the batch before pre-emption), monotonicity in T.
  *   scheduling quality against the paper's JCT numbers: parity unpinned (the paper's
  *                            trace, jobs and comparison schedulers do not exist here).
  */
@@ -93,6 +96,23 @@ int  ones_ref_export_remaining(ones_ref_ctx *ctx, double *remaining_out);
  * ONES_REF_E_INVALID_ARG between ones_ref_set_jobs and the next generation, when no schedule
  * exists under the current job table. */
 int  ones_ref_placement(ones_ref_ctx *ctx, int32_t *slot_of_gpu, int32_t *batch_of_gpu);
+
+/* The batch-size limit policies of Section 3.3.2, the producer of bmax_j between scheduling
+ * epochs.  state_j: 0 empty slot (limit 0), 1 Start (the job arrived or is still warming up:
+ * limit = one GPU's batch), 2 Resume (the job is waiting: the first update after it was
+ * pre-empted, marked by last_batch_j > 0, caps the limit at that batch; every further one
+ * halves it), 3 running (when it finished an epoch: R' = ceil(2R / ceil(sigma*T + 1)), the
+ * doubling of Scale-up with the penalty of Scale-down; otherwise unchanged).  Results are
+ * rounded down to a power of two and kept inside [bmin_j, bcap_j].  limit: in/out. */
+typedef struct {
+  const uint8_t *state;
+  const int32_t *bmin, *bcap, *gpu_max_batch;   /* powers of two, bmin <= bcap */
+  const int32_t *last_batch;                    /* waiting jobs: batch before pre-emption, or 0 */
+  const uint8_t *finished_epoch;                /* running jobs */
+  const double  *elapsed;                       /* running jobs: T_processed in seconds */
+} ones_ref_limit_inputs;
+int  ones_ref_update_limits(int32_t n_slots, const ones_ref_limit_inputs *in, double sigma,
+                            int32_t *limit);
 
 /* single steps, exposed so that tests can pin them one at a time */
 double ones_ref_log(double x);                  /* natural logarithm of a positive normal number */

@@ -40,6 +40,14 @@ _DTYPES = {"job_id": np.int64, "active": np.uint8, "bmin": np.int32, "bmax": np.
            "gpu_max_batch": np.int32, "a": np.float64, "c": np.float64, "d": np.float64,
            "remaining": np.float64}
 
+class _LimitInputs(C.Structure):
+    _fields_ = [("state", C.c_void_p), ("bmin", C.c_void_p), ("bcap", C.c_void_p), ("gpu_max_batch", C.c_void_p),
+                ("last_batch", C.c_void_p), ("finished_epoch", C.c_void_p), ("elapsed", C.c_void_p)]
+
+
+_LIMIT_DTYPES = {"state": np.uint8, "bmin": np.int32, "bcap": np.int32, "gpu_max_batch": np.int32,
+                 "last_batch": np.int32, "finished_epoch": np.uint8, "elapsed": np.float64}
+
 _lib = None
 
 
@@ -69,6 +77,7 @@ def lib():
                                             C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
         L.ones_ref_initial_genome.argtypes = [C.POINTER(_Config), C.POINTER(_Jobs), C.c_int32,
                                               C.c_void_p, C.POINTER(C.c_uint32)]
+        L.ones_ref_update_limits.argtypes = [C.c_int32, C.POINTER(_LimitInputs), C.c_double, C.c_void_p]
         L.ones_ref_placement.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
         L.ones_ref_set_progress.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         L.ones_ref_export_remaining.argtypes = [C.c_void_p, C.c_void_p]
@@ -82,6 +91,18 @@ def lib():
         L.ones_ref_sampled_remaining.restype = C.c_double
         _lib = L
     return _lib
+
+
+def update_limits(limit, sigma, **arrays):
+    """Section 3.3.2: returns the new limits; arrays: state, bmin, bcap, gpu_max_batch, last_batch,
+    finished_epoch, elapsed (one entry per slot)."""
+    out = np.array(limit, np.int32)
+    keep = [np.ascontiguousarray(arrays[k], dtype=dt) for k, dt in _LIMIT_DTYPES.items()]
+    if any(a.shape != out.shape for a in keep):
+        raise ValueError("one entry per slot in every array")
+    inp = _LimitInputs(*[a.ctypes.data for a in keep])
+    _check(lib().ones_ref_update_limits(len(out), C.byref(inp), float(sigma), out.ctypes.data))
+    return out
 
 
 def log(x: float) -> float:
