@@ -149,6 +149,34 @@ int ones_profile_enable(ones_ctx *ctx, int32_t every);
 int ones_profile_read(ones_ctx *ctx, double *evolve_ms, int64_t *evolve_launches,
                       double *select_ms, int64_t *select_launches);
 
+/* The batch-size limit policies of Section 3.3.2: produces the limits R_j (the bmax of the
+ * next ones_set_jobs) from the cluster's state between two scheduling epochs.  Host code, no
+ * context, no device work.  One entry per slot, all HOST arrays:
+ *   state 0  empty slot: limit 0.
+ *   state 1  Start: the job arrived, or is still in its warm-up steps: limit = gpu_max_batch
+ *            (it must fit one GPU).
+ *   state 2  Resume: the job waits.  The first update after it was pre-empted (marked by
+ *            last_batch > 0, its global batch before pre-emption) caps the limit at that
+ *            batch; every further update finds it rejected again and halves the limit.
+ *   state 3  running: when finished_epoch is set, R' = ceil(2R / ceil(sigma * elapsed + 1)):
+ *            the doubling of Scale-up (elapsed = 0) with the penalty of Scale-down for long
+ *            executed time; otherwise unchanged.  sigma: the paper suggests the job arrival
+ *            rate.
+ * Every result is rounded down to a power of two and kept inside [bmin, bcap] (bcap: the
+ * job's own largest batch).  limit is read (states 2, 3) and written.  Nothing is written
+ * on error: ONES_E_INVALID_ARG (null pointer, state above 3, n_slots outside
+ * 0..ONES_MAX_SLOTS, negative sigma / elapsed / last_batch, limit below 1 for a waiting or
+ * running job), ONES_E_NOT_POW2, ONES_E_BOUNDS (bmin > bcap, bcap > 2^30, sigma * elapsed >
+ * 1e15), ONES_E_NONFINITE. */
+typedef struct {
+  const uint8_t *state;
+  const int32_t *bmin, *bcap, *gpu_max_batch;
+  const int32_t *last_batch;
+  const uint8_t *finished_epoch;
+  const double  *elapsed;
+} ones_limit_inputs;
+int ones_update_limits(int32_t n_slots, const ones_limit_inputs *in, double sigma, int32_t *limit);
+
 void ones_destroy(ones_ctx *ctx);           /* NULL is allowed */
 const char *ones_strerror(int code);        /* static or thread-local storage */
 

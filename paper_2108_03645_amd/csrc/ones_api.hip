@@ -533,6 +533,47 @@ int ones_profile_read(ones_ctx *c, double *evolve_ms, int64_t *evolve_launches, 
   return ONES_OK;
 }
 
+int ones_update_limits(int32_t n_slots, const ones_limit_inputs *in, double sigma, int32_t *limit) {
+  if (n_slots < 0 || n_slots > ONES_MAX_SLOTS) return ONES_E_INVALID_ARG;
+  if (n_slots > 0 && (!in || !limit || !in->state || !in->bmin || !in->bcap || !in->gpu_max_batch ||
+                      !in->last_batch || !in->finished_epoch || !in->elapsed))
+    return ONES_E_INVALID_ARG;
+  if (!std::isfinite(sigma)) return ONES_E_NONFINITE;
+  if (sigma < 0.0) return ONES_E_INVALID_ARG;
+  std::vector<int32_t> next(static_cast<size_t>(n_slots), 0);
+  for (int32_t j = 0; j < n_slots; ++j) {
+    const uint8_t state = in->state[j];
+    if (state > 3) return ONES_E_INVALID_ARG;
+    if (state == 0) continue;
+    if (log2_pow2(in->bmin[j]) < 0 || log2_pow2(in->bcap[j]) < 0 || log2_pow2(in->gpu_max_batch[j]) < 0)
+      return ONES_E_NOT_POW2;
+    if (in->bmin[j] > in->bcap[j] || in->bcap[j] > (1 << 30)) return ONES_E_BOUNDS;
+    int64_t r = limit[j];
+    if (state == 1) {                              // Start
+      r = in->gpu_max_batch[j];
+    } else {
+      if (r < 1) return ONES_E_INVALID_ARG;
+      if (state == 2) {                            // Resume
+        if (in->last_batch[j] < 0) return ONES_E_INVALID_ARG;
+        r = in->last_batch[j] > 0 ? std::min<int64_t>(r, in->last_batch[j]) : r / 2;
+      } else {                                     // Scale-up with the Scale-down penalty
+        const double T = in->elapsed[j];
+        if (!std::isfinite(T)) return ONES_E_NONFINITE;
+        if (T < 0.0) return ONES_E_INVALID_ARG;
+        if (sigma * T > 1e15) return ONES_E_BOUNDS;
+        if (in->finished_epoch[j]) {
+          const int64_t penalty = static_cast<int64_t>(std::ceil(sigma * T + 1.0));
+          r = (2 * r + penalty - 1) / penalty;
+        }
+      }
+    }
+    r = std::min<int64_t>(std::max<int64_t>(r, in->bmin[j]), in->bcap[j]);
+    next[j] = 1 << (63 - __builtin_clzll(static_cast<unsigned long long>(r)));   // largest power of two <= r
+  }
+  if (n_slots) memcpy(limit, next.data(), static_cast<size_t>(n_slots) * 4);
+  return ONES_OK;
+}
+
 void ones_destroy(ones_ctx *c) {
   if (!c) return;
   for (auto &e : c->evolve_ev) { (void)hipEventDestroy(e.start); (void)hipEventDestroy(e.stop); }

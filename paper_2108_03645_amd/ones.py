@@ -35,9 +35,30 @@ _JOB_DTYPES = {"job_id": np.int64, "active": np.uint8, "bmin": np.int32, "bmax":
                "remaining": np.float64}
 
 EXPORTS = ["ones_workspace_bytes", "ones_init", "ones_set_jobs", "ones_generation", "ones_best",
-           "ones_export", "ones_placement", "ones_set_progress", "ones_export_remaining", "ones_padded_jobs",
+           "ones_export", "ones_placement", "ones_update_limits", "ones_set_progress", "ones_export_remaining", "ones_padded_jobs",
            "ones_profile_enable", "ones_profile_read",
            "ones_destroy", "ones_strerror"]
+
+
+class ones_limit_inputs(C.Structure):
+    _fields_ = [("state", C.c_void_p), ("bmin", C.c_void_p), ("bcap", C.c_void_p), ("gpu_max_batch", C.c_void_p),
+                ("last_batch", C.c_void_p), ("finished_epoch", C.c_void_p), ("elapsed", C.c_void_p)]
+
+
+_LIMIT_DTYPES = {"state": np.uint8, "bmin": np.int32, "bcap": np.int32, "gpu_max_batch": np.int32,
+                 "last_batch": np.int32, "finished_epoch": np.uint8, "elapsed": np.float64}
+
+
+def update_limits(limit, sigma, **arrays):
+    """ones_update_limits (Section 3.3.2): returns the new limits.  arrays: state, bmin, bcap,
+    gpu_max_batch, last_batch, finished_epoch, elapsed, one entry per slot.  Host code only."""
+    out = np.array(limit, np.int32)
+    keep = [np.ascontiguousarray(arrays[k], dtype=dt) for k, dt in _LIMIT_DTYPES.items()]
+    if any(a.shape != out.shape for a in keep):
+        raise ValueError("one entry per slot in every array")
+    inp = ones_limit_inputs(*[a.ctypes.data for a in keep])
+    _check(load().ones_update_limits(len(out), C.byref(inp), float(sigma), out.ctypes.data))
+    return out
 
 
 def library_path() -> str:
@@ -65,6 +86,7 @@ def load():
     L.ones_best.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(C.c_double)]
     L.ones_export.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(C.c_int64)]
     L.ones_placement.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
+    L.ones_update_limits.argtypes = [C.c_int32, C.POINTER(ones_limit_inputs), C.c_double, C.c_void_p]
     L.ones_set_progress.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
     L.ones_export_remaining.argtypes = [C.c_void_p, C.c_void_p]
     L.ones_padded_jobs.argtypes = [C.c_int32]
