@@ -52,22 +52,45 @@ __device__ __forceinline__ uint32_t pow2_at_least(uint32_t v) {
 }
 
 // ---------------------------------------------------------------- general path -----
-// Pools of at most kSortChunk slots: one workgroup sorts all (score, slot) keys in LDS (n = the
-// pool size rounded up to a power of two) and writes the survivors.
-__global__ __launch_bounds__(kSortThreads) void sort_pool_kernel(const double *fit_row, RowPlan rp, uint32_t P,
-                                                                uint32_t K, uint32_t n, int32_t *sel) {
+// Pools of at most kSortChunk slots: the rank of a candidate is the number of candidates below
+// it in (score, slot) order.  Every workgroup loads all scores into LDS and ranks 64 of them:
+// lane l of every wave works on element l, each wave over its own sixteenth of the pool (so a
+// wave reads one LDS address at a time, a broadcast); ranks below K are survivors.
+constexpr int kRankPoolPer = 64;
+__global__ __launch_bounds__(kSortThreads) void rank_pool_kernel(const double *fit_row, RowPlan rp, uint32_t P,
+                                                                uint32_t K, int32_t *sel) {
   const uint32_t *row_of = rp.row_of_cur;
   __shared__ uint64_t sk[kSortChunk];
-  __shared__ uint32_t si[kSortChunk];
-  for (uint32_t e = threadIdx.x; e < n; e += kSortThreads) {
-    sk[e] = e < P ? static_cast<uint64_t>(__double_as_longlong(fit_row[row_of[e]])) : ~0ull;   // padding sorts last
-    si[e] = e < P ? e : 0xFFFFFFFFu;
+  __shared__ uint32_t below[kRankPoolPer];
+  constexpr uint32_t kTeam = kSortThreads / kRankPoolPer;
+  const uint32_t t = threadIdx.x;
+  const uint32_t padded = (P + 8 * kTeam - 1) / (8 * kTeam) * (8 * kTeam);     // eight comparisons per step
+  uint64_t loaded[kSortChunk / kSortThreads];
+#pragma unroll
+  for (int u = 0; u < kSortChunk / kSortThreads; ++u) {                         // all loads first
+    const uint32_t e = t + u * kSortThreads;
+    loaded[u] = e < P ? static_cast<uint64_t>(__double_as_longlong(fit_row[row_of[e]])) : ~0ull;
+  }
+#pragma unroll
+  for (int u = 0; u < kSortChunk / kSortThreads; ++u)
+    if (t + u * kSortThreads < padded) sk[t + u * kSortThreads] = loaded[u];
+  if (t < kRankPoolPer) below[t] = 0;
+  __syncthreads();
+  const uint32_t mine = blockIdx.x * kRankPoolPer + t % kRankPoolPer;
+  const uint32_t part = padded / kTeam, from = (t / kRankPoolPer) * part;
+  if (mine < P) {
+    const uint64_t key = sk[mine];
+    uint32_t n = 0;
+    for (uint32_t q = from; q < from + part; q += 8) {
+#pragma unroll
+      for (int u = 0; u < 8; ++u) n += key_less(sk[q + u], q + u, key, mine) ? 1u : 0u;   // padding is never below
+    }
+    if (n != 0) atomicAdd(&below[t % kRankPoolPer], n);
   }
   __syncthreads();
-  bitonic_sort(sk, si, n);
-  for (uint32_t e = threadIdx.x; e < K; e += kSortThreads) {
-    sel[e] = static_cast<int32_t>(si[e]);
-    keep_row(rp, e, si[e]);
+  if (t < kRankPoolPer && mine < P && below[t] < K) {
+    sel[below[t]] = static_cast<int32_t>(mine);
+    keep_row(rp, below[t], mine);
   }
 }
 
@@ -243,16 +266,16 @@ __global__ __launch_bounds__(kBucketThreads) void bucket_select_kernel(const dou
 // rank K do any work.  The sample only decides how even the buckets are, never the result.
 
 // Splitters: `sample` = 2 nb scores taken at a fixed stride from the pool; those of odd rank
-// 2c + 1 among them become splitter c.  Ranks by counting: every workgroup loads the whole
-// sample and ranks eight of its elements, 128 threads each over their share of the sample.
+// 2c + 1 among them become splitter c.  Ranks by counting, laid out like rank_pool_kernel: every
+// workgroup loads the whole sample and ranks 64 of its elements, one per lane, each wave over
+// its own share of the sample.
 constexpr int kSampleThreads = 1024;
-constexpr int kSamplePer = 8;
 constexpr int kSampleMax = 2 * kMaxBuckets;
 __global__ __launch_bounds__(kSampleThreads) void sample_splitters_kernel(const double *fit_row, const uint32_t *row_of,
                                                                          uint32_t P, uint32_t sample,
                                                                          uint64_t *split, uint32_t *count) {
   __shared__ uint64_t sk[kSampleMax];
-  __shared__ uint32_t rank[kSamplePer];
+  __shared__ uint32_t rank[kLanes];
   const uint32_t t = threadIdx.x;
   if (blockIdx.x == 0)
     for (uint32_t c = t; c < static_cast<uint32_t>(kBucketCounters); c += kSampleThreads) count[c] = 0;
@@ -266,24 +289,21 @@ __global__ __launch_bounds__(kSampleThreads) void sample_splitters_kernel(const 
 #pragma unroll
   for (int u = 0; u < kSampleMax / kSampleThreads; ++u)
     if (t + u * kSampleThreads < sample) sk[t + u * kSampleThreads] = mine_of[u];
-  if (t < kSamplePer) rank[t] = 0;
+  if (t < kLanes) rank[t] = 0;
   __syncthreads();
-  // this workgroup ranks kSamplePer elements, a team of threads each (eight comparisons or more
-  // per thread; sample and team are powers of two)
-  const uint32_t kTeam = min(static_cast<uint32_t>(kSampleThreads / kSamplePer), sample / 8);
-  const bool idle = t / kTeam >= static_cast<uint32_t>(kSamplePer);
-  const uint32_t mine = blockIdx.x * kSamplePer + (idle ? 0u : t / kTeam);   // sample = kSamplePer * gridDim.x
-  const uint32_t part = sample / kTeam, from = (t % kTeam) * part;
+  constexpr uint32_t kWaves = kSampleThreads / kLanes;
+  const uint32_t mine = blockIdx.x * kLanes + t % kLanes;              // sample = 64 * gridDim.x
+  const uint32_t part = sample / kWaves, from = (t / kLanes) * part;   // sample is a multiple of 128
   const uint64_t key = sk[mine];
   uint32_t below = 0;
-  for (uint32_t q = from; q < from + part && !idle; q += 8) {
+  for (uint32_t q = from; q < from + part; q += 8) {
 #pragma unroll
     for (int u = 0; u < 8; ++u) below += key_less(sk[q + u], q + u, key, mine) ? 1u : 0u;
   }
-  if (below != 0) atomicAdd(&rank[t / kTeam], below);
+  if (below != 0) atomicAdd(&rank[t % kLanes], below);
   __syncthreads();
-  if (t % kTeam == 0 && !idle) {
-    const uint32_t r = rank[t / kTeam];
+  if (t < kLanes) {
+    const uint32_t r = rank[t];
     if ((r & 1u) && r / 2 + 1 < sample / 2) split[r / 2] = key;
     // the splitters beyond the sample are +inf: nothing lands in those buckets
     if (mine == 0)
@@ -527,12 +547,6 @@ __global__ __launch_bounds__(kPlaceThreads) void placement_kernel(const int32_t 
   }
 }
 
-uint32_t next_pow2(uint32_t v) {
-  uint32_t n = 1;
-  while (n < v) n <<= 1;
-  return n;
-}
-
 }  // namespace
 
 hipError_t launch_prepare_table(const RawJobs &raw, const JobTable &tab, uint32_t Jp, hipStream_t s) {
@@ -561,7 +575,8 @@ hipError_t launch_zero_words(uint32_t *words, uint32_t n, hipStream_t s) {
 hipError_t launch_select(const double *fit, const RowPlan &rp, uint32_t P, uint32_t K, const BucketArgs &store,
                          int32_t *sel, hipStream_t s) {
   if (P <= static_cast<uint32_t>(kSortChunk)) {
-    hipLaunchKernelGGL(sort_pool_kernel, dim3(1), dim3(kSortThreads), 0, s, fit, rp, P, K, next_pow2(P), sel);
+    hipLaunchKernelGGL(rank_pool_kernel, dim3((P + kRankPoolPer - 1) / kRankPoolPer), dim3(kSortThreads), 0, s, fit, rp,
+                       P, K, sel);
     return hipGetLastError();
   }
   // about 64 candidates per bucket, two sample points per bucket
@@ -571,7 +586,7 @@ hipError_t launch_select(const double *fit, const RowPlan &rp, uint32_t P, uint3
   const uint32_t sample = 2 * nb;
   bk.seg = static_cast<uint32_t>(static_cast<size_t>(store.nb) * store.seg / nb);   // the same storage, re-divided
   bk.nb = nb;
-  hipLaunchKernelGGL(sample_splitters_kernel, dim3(sample / kSamplePer), dim3(kSampleThreads), 0, s, fit, rp.row_of_cur,
+  hipLaunchKernelGGL(sample_splitters_kernel, dim3(sample / kLanes), dim3(kSampleThreads), 0, s, fit, rp.row_of_cur,
                      P, sample, const_cast<uint64_t *>(bk.split), bk.count);
   hipError_t rc = hipGetLastError();
   if (rc != hipSuccess) return rc;
