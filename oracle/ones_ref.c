@@ -48,6 +48,9 @@ struct ones_ref_ctx {
   int      cur;
   int64_t  t;              /* generation counter; 0 = initial population */
   int      stale;          /* job table replaced since the last generation */
+  int      new_jobs_first; /* option: the first generation after a table change serves new jobs first */
+  int      serve_new;      /* ... and this is that generation */
+  uint8_t *is_new;         /* Jp entries: slot changed hands in the last ones_ref_set_jobs */
   int      sampling;       /* Alg. 1: remaining work drawn per generation */
   double  *alpha, *beta, *processed, *Y_fixed;   /* Jn entries each */
 };
@@ -182,7 +185,12 @@ static int gene_from_draw(const slot_t *s, uint32_t k) {
  * limit R_j, (3) make room when capacity is exceeded (Eq. 4: a GPU hosts one worker),
  * then fill idle GPUs by resuming waiting jobs or scaling up running ones until no
  * single step fits.  Jobs are visited in a fixed order rotated by r. */
-static int repair(const slot_t *tab, int Jp, int R, int64_t G, int *g, uint32_t r) {
+/* is_new (may be NULL): slots of jobs that arrived with the last job table.  They are
+ * served first ("allocates N new jobs with N available GPUs ... avoid starvation of new jobs
+ * by the preferential allocation", Section 3.2.2 refresh (3)): in visiting order each starts
+ * with the batch a waiting job resumes with while the capacity lasts, and only what they leave
+ * is shared out among the others. */
+static int repair(const slot_t *tab, int Jp, int R, int64_t G, int *g, uint32_t r, const uint8_t *is_new) {
   int order[MAX_SLOTS];
   for (int j = 0; j < Jp; ++j) {
     int sigma = (j % LANES) * R + (j / LANES);
@@ -197,13 +205,24 @@ static int repair(const slot_t *tab, int Jp, int R, int64_t G, int *g, uint32_t 
   /* 2. lift: a larger batch that needs no extra GPU */
   for (int j = 0; j < Jp; ++j)
     if (g[j] != WAIT) g[j] = imax(g[j], imin(tab[j].mu, tab[j].hi));
+  /* 2b. new jobs first */
+  int64_t Q = 0, taken = 0;
+  if (is_new) {
+    for (int pos = 0; pos < Jp; ++pos) {
+      int j = order[pos];
+      if (!is_new[j] || !tab[j].active) continue;
+      int start = imax(tab[j].lo, imin(tab[j].mu, tab[j].hi));
+      Q += gpus_of(start, tab[j].mu);
+      if (Q <= G) { g[j] = start; taken = Q; } else g[j] = WAIT;
+    }
+  }
   /* 3. admit: prefix sum of GPU counts in visiting order; beyond capacity -> wait */
-  int64_t Q = 0;
+  Q = 0;
   for (int pos = 0; pos < Jp; ++pos) {
     int j = order[pos];
-    if (g[j] == WAIT) continue;
+    if (g[j] == WAIT || (is_new && is_new[j])) continue;
     Q += gpus_of(g[j], tab[j].mu);
-    if (Q > G) g[j] = WAIT;
+    if (Q > G - taken) g[j] = WAIT;
   }
   /* 4. fill */
   int rounds = 0;
@@ -346,7 +365,7 @@ static void initial_genome(const ones_ref_ctx *c, int p, int *g, uint32_t *r_out
 }
 
 static void finish_slot(ones_ref_ctx *c, int32_t *dst, int p, int *g, uint32_t r) {
-  repair(c->tab, c->Jp, c->R, c->G, g, r);
+  repair(c->tab, c->Jp, c->R, c->G, g, r, c->serve_new ? c->is_new : NULL);
   c->fit[p] = score(c->tab, c->R, g);
   int32_t *row = dst + (size_t)p * c->Jp;
   for (int j = 0; j < c->Jp; ++j) row[j] = batch_of(g[j]);
@@ -447,6 +466,12 @@ int ones_ref_set_progress(ones_ref_ctx *c, const double *alpha, const double *be
   return ONES_REF_OK;
 }
 
+int ones_ref_set_new_jobs_first(ones_ref_ctx *c, int32_t on) {
+  if (!c) return ONES_REF_E_INVALID_ARG;
+  c->new_jobs_first = on != 0;
+  return ONES_REF_OK;
+}
+
 int ones_ref_export_remaining(ones_ref_ctx *c, double *remaining_out) {
   if (!c || !remaining_out) return ONES_REF_E_INVALID_ARG;
   for (int j = 0; j < c->Jn; ++j) remaining_out[j] = c->tab[j].Y;
@@ -477,6 +502,7 @@ int ones_ref_init(ones_ref_ctx **out, const ones_ref_config *cfg, const ones_ref
   c->beta = (double *)calloc(jn, sizeof(double));
   c->processed = (double *)calloc(jn, sizeof(double));
   c->Y_fixed = (double *)calloc(jn, sizeof(double));
+  c->is_new = (uint8_t *)calloc((size_t)c->Jp, 1);
   for (int j = 0; j < c->Jn; ++j) c->Y_fixed[j] = c->tab[j].Y;
   c->cur = 0; c->t = 0;
   /* initial population: random genomes, repaired, scored, ranked */
@@ -497,8 +523,10 @@ int ones_ref_set_jobs(ones_ref_ctx *c, const ones_ref_jobs *jobs) {
   int rc = build_table(c->Jn, c->Jp, jobs, tab);
   if (rc) { free(tab); return rc; }
   /* a slot that changed hands starts from "waiting" in every candidate */
+  memset(c->is_new, 0, (size_t)c->Jp);
   for (int j = 0; j < c->Jn; ++j) {
     if (tab[j].id == c->tab[j].id) continue;
+    c->is_new[j] = 1;
     for (int p = 0; p < c->P; ++p) c->genes[c->cur][(size_t)p * c->Jp + j] = 0;
   }
   free(c->tab);
@@ -515,6 +543,7 @@ int ones_ref_generation(ones_ref_ctx *c, int32_t n_generations) {
     const int32_t *prev = c->genes[c->cur];
     int32_t *next = c->genes[c->cur ^ 1];
     uint32_t t = (uint32_t)(c->t + 1);
+    c->serve_new = c->new_jobs_first && c->stale;
     if (c->sampling) {               /* Alg. 1: one draw of every job's progress per selection */
       uint64_t seed = ((uint64_t)c->key[1] << 32) | c->key[0];
       for (int j = 0; j < c->Jn; ++j)
@@ -630,7 +659,7 @@ int ones_ref_export(ones_ref_ctx *c, int32_t *genes, double *fit, int32_t *sel, 
 void ones_ref_destroy(ones_ref_ctx *c) {
   if (!c) return;
   free(c->tab); free(c->genes[0]); free(c->genes[1]); free(c->fit); free(c->sel);
-  free(c->alpha); free(c->beta); free(c->processed); free(c->Y_fixed); free(c);
+  free(c->alpha); free(c->beta); free(c->processed); free(c->Y_fixed); free(c->is_new); free(c);
 }
 
 int ones_ref_compose_slot(ones_ref_ctx *c, int32_t p, int32_t *genes_out, uint32_t *r_out,
@@ -686,7 +715,7 @@ int ones_ref_repair_genome(const ones_ref_config *cfg, const ones_ref_jobs *jobs
   slot_t tab[MAX_SLOTS]; int g[MAX_SLOTS];
   if ((rc = build_table(Jn, Jp, jobs, tab))) return rc;
   if ((rc = load_genome(tab, Jn, Jp, genes, g))) return rc;
-  int rounds = repair(tab, Jp, Jp / LANES, cfg->n_gpus, g, r);
+  int rounds = repair(tab, Jp, Jp / LANES, cfg->n_gpus, g, r, NULL);
   for (int j = 0; j < Jn; ++j) genes[j] = batch_of(g[j]);
   if (fill_rounds_out) *fill_rounds_out = rounds;
   return ONES_REF_OK;

@@ -27,6 +27,9 @@
  *   ones_ref_update_limits : the four policies worked by hand (doubling at T = 0, the
  *                            printed penalty formula at several sigma*T, halving on rejection,
  *                            the cap at the batch before pre-emption), monotonicity in T.
+ *   new jobs first         : a hand-worked two-GPU example, every new job running in every
+ *                            candidate when the capacity allows, Eq. 4, no effect when off or
+ *                            when no job is new.
  *   scheduling quality against the paper's JCT numbers: parity unpinned (the paper's
  *                            trace, jobs and comparison schedulers do not exist here).
  */
@@ -86,6 +89,12 @@ int  ones_ref_get_threads(void);
  * job table's fixed remaining work. */
 int  ones_ref_set_progress(ones_ref_ctx *ctx, const double *alpha, const double *beta,
                            const double *processed);
+/* Option (off at first): the first generation after ones_ref_set_jobs serves the jobs that
+ * arrived with that table first (refresh (3) of Section 3.2.2): in every candidate, in visiting
+ * order, each new job starts with the batch a waiting job resumes with while the capacity
+ * lasts; the other jobs are admitted to what is left, then the fill runs as always. */
+int  ones_ref_set_new_jobs_first(ones_ref_ctx *ctx, int32_t on);
+
 /* the remaining work Y_j (n_slots entries) the last generation was scored with */
 int  ones_ref_export_remaining(ones_ref_ctx *ctx, double *remaining_out);
 

@@ -78,6 +78,7 @@ def lib():
         L.ones_ref_initial_genome.argtypes = [C.POINTER(_Config), C.POINTER(_Jobs), C.c_int32,
                                               C.c_void_p, C.POINTER(C.c_uint32)]
         L.ones_ref_update_limits.argtypes = [C.c_int32, C.POINTER(_LimitInputs), C.c_double, C.c_void_p]
+        L.ones_ref_set_new_jobs_first.argtypes = [C.c_void_p, C.c_int32]
         L.ones_ref_placement.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
         L.ones_ref_set_progress.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         L.ones_ref_export_remaining.argtypes = [C.c_void_p, C.c_void_p]
@@ -226,6 +227,9 @@ class RefSearch:
         if any(a.shape != (self.n_slots,) for a in arrs):
             raise ValueError("alpha, beta, processed: one entry per slot")
         _check(lib().ones_ref_set_progress(self._h, *[a.ctypes.data for a in arrs]))
+
+    def set_new_jobs_first(self, on=True):
+        _check(lib().ones_ref_set_new_jobs_first(self._h, int(bool(on))))
 
     def export_remaining(self):
         y = np.zeros(self.n_slots, np.float64)

@@ -432,3 +432,82 @@ def test_placement_needs_a_schedule_under_the_current_table(ref):
     assert e.value.code == -1
     s.generation(1)
     s.placement()
+
+
+# ------------------------------------------------ new jobs are served first (refresh (3)) ----
+def changed(jobs, **edits):
+    d = {k: np.array(getattr(jobs, k)) for k in ("job_id", "active", "bmin", "bmax", "gpu_max_batch", "a", "c", "d",
+                                                  "remaining")}
+    for k, (j, v) in edits.items():
+        d[k][j] = v
+    return make_jobs(len(jobs.bmin), **d)
+
+
+def test_new_job_first_hand_example(ref):
+    """Two GPUs.  Job 0 (window 256..512, 256 per GPU) holds both; then job 1 arrives in slot 1.
+    Served first, it takes one GPU with its starting batch 256; job 0's 512 on two GPUs no longer
+    fits the one GPU left and is dropped, and the fill gives it the idle GPU back with 256.
+    Without the option job 0 keeps both GPUs in the survivors and job 1 has to win its GPU in
+    the search."""
+    cl = SimpleNamespace(n_gpus=2, n_slots=2, population=8, seed=3, mutation_rate=0.0, crossover_rate=0.5)
+    alone = make_jobs(2, active=[1, 0], bmin=256, bmax=512, gpu_max_batch=256)
+    both = changed(alone, active=(1, 1), job_id=(1, 77))
+    for option in (True, False):
+        s = ref.RefSearch(cl, alone)
+        s.generation(3)
+        assert s.best()[0].tolist() == [512, 0]
+        s.set_new_jobs_first(option)
+        s.set_jobs(both)
+        s.generation(1)
+        genes = s.export()[0][:, :2]
+        if option:
+            assert (genes == [256, 256]).all()                 # every candidate, survivors included
+        else:
+            assert (genes[:2] == [512, 0]).all()               # the refreshed survivors kept job 0's GPUs
+
+
+def test_new_jobs_run_in_every_candidate_when_they_fit(ref):
+    cluster, jobs = W.paper_scale()
+    s = ref.RefSearch(cluster, jobs)
+    s.set_new_jobs_first(True)
+    s.generation(5)
+    new_slots = [3, 17, 30]
+    j2 = changed(jobs)
+    for j in new_slots:
+        j2.job_id[j] += 1000
+    s.set_jobs(j2)
+    s.generation(1)
+    genes = s.export()[0]
+    assert (genes[:, new_slots] > 0).all()
+    for p in range(0, cluster.population, 41):
+        check_invariants(cluster.n_gpus, j2, genes[p, :cluster.n_slots])
+    # the generation after that is an ordinary one again
+    t = ref.RefSearch(cluster, jobs); t.generation(5); t.set_jobs(j2); t.generation(1)
+    assert not (t.export()[0][:, new_slots] > 0).all()         # without the option some candidates leave them waiting
+
+
+def test_more_new_jobs_than_gpus(ref):
+    """Eight one-GPU jobs arrive on a three-GPU cluster: exactly three of them run, nothing else."""
+    cl = SimpleNamespace(n_gpus=3, n_slots=9, population=16, seed=8, mutation_rate=0.1, crossover_rate=0.5)
+    before = make_jobs(9, active=[1] + [0] * 8, bmin=64, bmax=1024, gpu_max_batch=256)
+    after = changed(before)
+    after.active[1:] = 1
+    after.job_id[1:] += 50
+    s = ref.RefSearch(cl, before)
+    s.set_new_jobs_first(True)
+    s.generation(2)
+    s.set_jobs(after)
+    s.generation(1)
+    genes = s.export()[0][:, :9]
+    assert (genes[:, 0] == 0).all()                            # the old job had to make room
+    assert ((genes[:, 1:] > 0).sum(axis=1) == 3).all() and (genes[:, 1:].max(axis=1) == 256).all()
+
+
+def test_option_changes_nothing_without_new_jobs(ref):
+    cluster, jobs = W.tiny()
+    a, b = ref.RefSearch(cluster, jobs), ref.RefSearch(cluster, jobs)
+    a.set_new_jobs_first(True)
+    j2 = changed(jobs, remaining=(2, 5e6))                     # same jobs, new remaining work
+    for s in (a, b):
+        s.generation(2); s.set_jobs(j2); s.generation(2)
+    assert all(np.array_equal(x, y) for x, y in zip(a.export()[:3], b.export()[:3]))
