@@ -24,8 +24,8 @@ HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published peak
 
 # HBM bytes per evolve launch on the stress workload from rocprofv3 --pmc FETCH_SIZE and
 # WRITE_SIZE (see profiles/), valid only for the kernel source with this hash.
-MEASURED_TRAFFIC = {"source_sha256": "7f1905a3e932fb517e4fb52c1e6086ce4d389979c63be5c80d83aee3d16477a1",
-                    "bytes_per_launch": 802741953}
+MEASURED_TRAFFIC = {"source_sha256": "d2670deea506be2560ca5cd99ba985c91f76d2459c3f99082b2a49dd21cf25b9",
+                    "bytes_per_launch": 802770138}
 
 
 def evolve_source_hash() -> str:

@@ -110,6 +110,14 @@ int ones_set_jobs(ones_ctx *ctx, const ones_jobs *jobs);
 int ones_set_progress(ones_ctx *ctx, const double *alpha, const double *beta,
                       const double *processed);
 
+/* Option, off at first.  When on, the first generation after ones_set_jobs serves the jobs that
+ * arrived with that table (active slots whose job_id changed) first, in every candidate
+ * (refresh (3) of Section 3.2.2: new jobs are allocated before the others so that they do
+ * not starve): in the candidate's visiting order each new job starts with the batch a waiting
+ * job resumes with while the cluster's capacity lasts; the other jobs are admitted to what is
+ * left; then the fill runs as always.  Later generations treat those jobs like any other. */
+int ones_set_new_jobs_first(ones_ctx *ctx, int32_t on);
+
 /* The remaining work Y_j the last generation was scored with (HOST array of n_slots
  * entries): the job table's, or the last draw under ones_set_progress.  Synchronises. */
 int ones_export_remaining(ones_ctx *ctx, double *remaining_out);

@@ -167,6 +167,7 @@ struct ones_ctx {
   int cur;                    // which row_of array describes the current generation
   bool table_changed;         // job table replaced since the current generation was computed
   bool no_schedule;           // ... by ones_set_jobs: the winner is not a schedule under the new table
+  bool new_jobs_first;        // option: the generation after ones_set_jobs serves the arrived jobs first
   bool sampling;              // remaining work drawn per generation (Alg. 1) instead of the table's
   BucketPlan bp;              // nb == 0: pool small enough for the single-chunk sort
   int bucket_phase;           // which counter set the next bucketed generation fills
@@ -251,6 +252,7 @@ int run_generation(ones_ctx *c, uint32_t t) {
   const bool same_table = t != 0 && !c->table_changed;
   const bool sampled = t != 0 && c->sampling;
   a.rescore = same_table && sampled ? 1u : 0u;
+  a.new_first = c->new_jobs_first && c->no_schedule ? 1u : 0u;   // the table's "arrived" marks are fresh
   // quantile buckets: only when the survivors reappear with the scores they had
   const bool buckets = same_table && !sampled && c->bp.nb != 0;
   a.bk.nb = buckets ? c->bp.nb : 0;
@@ -347,6 +349,7 @@ int ones_init(ones_ctx **out, const ones_config *cfg, const ones_jobs *jobs, voi
   c->cur = 0; c->t = 0;
   c->table_changed = false;
   c->no_schedule = false;
+  c->new_jobs_first = false;
   c->sampling = false;
   c->bp = bucket_plan(c->P);
   c->bucket_phase = 0;
@@ -381,7 +384,11 @@ int ones_set_jobs(ones_ctx *c, const ones_jobs *jobs) {
   std::vector<uint32_t> changed(c->Jp, 0u);
   bool any = false;
   for (uint32_t j = 0; j < c->Jn; ++j)
-    if (h.id[j] != c->ids[j]) { changed[j] = 1u; any = true; }
+    if (h.id[j] != c->ids[j]) {
+      changed[j] = 1u;
+      any = true;
+      if ((h.rawinfo[j] >> 15) & 1u) h.rawinfo[j] |= 1u << 16;   // an active job arrived in this slot
+    }
   if ((rc = upload_table(c, h, any ? &changed : nullptr))) return rc;
   c->ids = h.id;
   c->table_changed = true;
@@ -417,6 +424,12 @@ int ones_set_progress(ones_ctx *c, const double *alpha, const double *beta, cons
   HIP_TRY(hipMemcpyAsync(c->ws + c->L.processed, hp.data(), n8, hipMemcpyHostToDevice, c->stream));
   HIP_TRY(hipStreamSynchronize(c->stream));     // the staging vectors may go away now
   c->sampling = true;
+  return ONES_OK;
+}
+
+int ones_set_new_jobs_first(ones_ctx *c, int32_t on) {
+  if (!c) return ONES_E_INVALID_ARG;
+  c->new_jobs_first = on != 0;
   return ONES_OK;
 }
 

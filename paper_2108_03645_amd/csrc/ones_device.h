@@ -44,7 +44,7 @@ __device__ __forceinline__ Words philox4x32_10(uint32_t x0, uint32_t x1, uint32_
 struct JobTable {
   uint32_t *cstart;   // GPU count a waiting job resumes with; 0 for an empty slot
   uint32_t *cmax;     // GPU count at the batch-size limit R_j;  0 for an empty slot
-  uint32_t *info;     // bits 0-4 lo, 5-10 (hi-lo+2), 11-15 mu, 16-20 bl_exp, 21 active
+  uint32_t *info;     // bits 0-4 lo, 5-10 (hi-lo+2), 11-15 mu, 16-20 bl_exp, 21 active, 22 arrived with this table
   double   *abl;      // a * 2^bl_exp: compute time of one iteration at the local batch
   double   *cc;       // synchronisation cost per doubling of the GPU count
   double   *d;        // fixed cost per iteration
@@ -60,6 +60,7 @@ __host__ __device__ inline uint32_t info_n(uint32_t w)      { return (w >> 5) & 
 __host__ __device__ inline uint32_t info_mu(uint32_t w)     { return (w >> 11) & 31u; }
 __host__ __device__ inline uint32_t info_blexp(uint32_t w)  { return (w >> 16) & 31u; }
 __host__ __device__ inline uint32_t info_active(uint32_t w) { return (w >> 21) & 1u; }
+__host__ __device__ inline uint32_t info_new(uint32_t w)    { return (w >> 22) & 1u; }
 
 // Quantile buckets of the selection (valid while the job table stays the same): children and
 // mutants that beat the K-th survivor are dropped into the bucket of the survivors they fall
@@ -105,6 +106,7 @@ struct EvolveArgs {
   uint32_t       key0, key1;  // seed
   uint32_t       t;           // generation counter (0 = initial population)
   uint32_t       T_mut, T_x;  // rate thresholds on a 32-bit word
+  uint32_t       new_first;   // after a table change: the jobs that arrived with it are served first
   uint32_t       rescore;     // the survivors' scores are stale (remaining work redrawn): score them again
   uint32_t       term_lds;    // set by the launcher: entries per job of the term table in LDS, 0 = none
   BucketArgs     bk;
@@ -130,7 +132,7 @@ __device__ __forceinline__ double term_of(double abl, double cc, double d, doubl
 }
 
 struct RawJobs {              // uploaded by the host after validation, [Jp] each
-  const uint32_t *rawinfo;    // bits 0-4 lo, 5-9 hi, 10-14 mu, 15 active
+  const uint32_t *rawinfo;    // bits 0-4 lo, 5-9 hi, 10-14 mu, 15 active, 16 arrived with this table
   const double   *a, *c, *d, *Y;
 };
 

@@ -326,11 +326,33 @@ __device__ __forceinline__ uint32_t accept_prefix(uint32_t (&v)[R], uint32_t lim
 }
 
 // Refresh + fill (Section 3.2.2) on GPU counts c[]; clamp and lift already applied.
+// new_first (only in the generation after a table change): the jobs that arrived with the table
+// are served first (refresh (3)): each starts on cstart GPUs while the capacity lasts, in
+// visiting order, and the others are admitted to what is left.
 template <int R>
-__device__ __forceinline__ void repair(uint32_t (&c)[R], const Smem &s, uint32_t G, uint32_t r, int lane) {
+__device__ __forceinline__ void repair(uint32_t (&c)[R], const Smem &s, uint32_t G, uint32_t r, int lane,
+                                       bool new_first) {
   const uint32_t lr = r / R, ir = r % R;
-  // admit: jobs beyond the capacity in visiting order wait (Eq. 4)
-  const uint32_t used = accept_prefix<R>(c, G, lr, ir, lane);
+  uint32_t used;
+  if (new_first) {
+    uint32_t v[R];
+#pragma unroll
+    for (int i = 0; i < R; ++i) v[i] = info_new(s.info[lane + kLanes * i]) ? s.cc2[lane + kLanes * i].x : 0u;
+    const uint32_t taken = accept_prefix<R>(v, G, lr, ir, lane);
+#pragma unroll
+    for (int i = 0; i < R; ++i) {
+      const bool is_new = info_new(s.info[lane + kLanes * i]) != 0;
+      c[i] = is_new ? v[i] : c[i];
+      v[i] = is_new ? 0u : c[i];
+    }
+    phase_fence();
+    used = taken + accept_prefix<R>(v, G - taken, lr, ir, lane);
+#pragma unroll
+    for (int i = 0; i < R; ++i) c[i] = info_new(s.info[lane + kLanes * i]) ? c[i] : v[i];
+  } else {
+    // admit: jobs beyond the capacity in visiting order wait (Eq. 4)
+    used = accept_prefix<R>(c, G, lr, ir, lane);
+  }
   // fill: a waiting job asks for cstart GPUs, a running one below its limit asks to double.
   // Every round accepts at least its first ask (got == 0: nobody could ask), and a job doubles
   // at most 20 times, so kMaxRows * 64 * 21 rounds always suffice; the bound only makes the
@@ -428,8 +450,8 @@ __device__ __forceinline__ void drop_in_bucket(const EvolveArgs &a, const Smem &
 
 template <int R>
 __device__ __forceinline__ double finish(const EvolveArgs &a, const Smem &s, uint32_t dst_row, uint32_t r,
-                                         uint32_t (&c)[R], int lane) {
-  repair<R>(c, s, a.G, r, lane);
+                                         uint32_t (&c)[R], int lane, bool new_first = false) {
+  repair<R>(c, s, a.G, r, lane, new_first);
   phase_fence();
   const double f = score<R>(c, s, a.term_lds, lane);
   phase_fence();
@@ -520,6 +542,7 @@ __global__ __launch_bounds__(Shape<R>::kWaves *kLanes) void evolve_kernel(Evolve
     a.row_of[p] = min(s.rows[i], a.P + a.K - 1);
   }
   const uint32_t kinds = (!kSameTable || a.rescore) ? 3u : 2u;
+  const bool new_first = !kSameTable && a.new_first != 0;       // never under an unchanged table
   // The waves take the items one by one (the pairs first: they take twice as long), so that a
   // wave whose items needed many fill rounds does not hold the others up at the end.
   for (;;) {
@@ -560,12 +583,12 @@ __global__ __launch_bounds__(Shape<R>::kWaves *kLanes) void evolve_kernel(Evolve
         }
       }
       phase_fence();
-      const double f0 = finish<R>(a, s, row_at(s, 2 * idx, a), d0.r, c, lane);
+      const double f0 = finish<R>(a, s, row_at(s, 2 * idx, a), d0.r, c, lane, new_first);
       if (kSameTable && a.bk.nb != 0) drop_in_bucket(a, s, p0, f0, lane);
       phase_fence();
 #pragma unroll
       for (int i = 0; i < R; ++i) c[i] = (1u << stash[lane + kLanes * i]) >> 1;
-      const double f1 = finish<R>(a, s, row_at(s, 2 * idx + 1, a), d1.r, c, lane);
+      const double f1 = finish<R>(a, s, row_at(s, 2 * idx + 1, a), d1.r, c, lane, new_first);
       if (kSameTable && a.bk.nb != 0) drop_in_bucket(a, s, p0 + 1, f1, lane);
     } else if (item < 2 * K) {
       // uniform mutation: each job redrawn with rate theta (k = 0 pre-empts it)
@@ -588,7 +611,7 @@ __global__ __launch_bounds__(Shape<R>::kWaves *kLanes) void evolve_kernel(Evolve
       }
       phase_fence();
       gpus_from_batches<R, false>(s, lane, c);
-      const double f = finish<R>(a, s, row_at(s, idx + n, a), d.r, c, lane);
+      const double f = finish<R>(a, s, row_at(s, idx + n, a), d.r, c, lane, new_first);
       if (kSameTable && a.bk.nb != 0) drop_in_bucket(a, s, p, f, lane);
     } else if (kSameTable) {
       // the remaining work was drawn anew: the survivor of this rank keeps its genome and row
@@ -605,7 +628,7 @@ __global__ __launch_bounds__(Shape<R>::kWaves *kLanes) void evolve_kernel(Evolve
       const Draw d = candidate_draw(a, p);
       load_genes<R>(a.genes + static_cast<size_t>(a.parent_row[p]) * a.Jp, lane, c);
       gpus_from_batches<R, false>(s, lane, c);
-      finish<R>(a, s, row_at(s, idx + n, a), d.r, c, lane);
+      finish<R>(a, s, row_at(s, idx + n, a), d.r, c, lane, new_first);
     }
   }
   }

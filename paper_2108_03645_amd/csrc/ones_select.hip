@@ -454,7 +454,8 @@ __global__ void prepare_table_kernel(RawJobs raw, JobTable tab, uint32_t Jp) {
   tab.cstart[j] = 1u << max(0, gstart - mu);
   tab.cmax[j] = 1u << max(0, hi - mu);
   tab.info[j] = static_cast<uint32_t>(lo) | (static_cast<uint32_t>(hi - lo + 2) << 5) |
-                (static_cast<uint32_t>(mu) << 11) | (static_cast<uint32_t>(bl) << 16) | (1u << 21);
+                (static_cast<uint32_t>(mu) << 11) | (static_cast<uint32_t>(bl) << 16) | (1u << 21) |
+                (((w >> 16) & 1u) << 22);
   tab.abl[j] = raw.a[j] * static_cast<double>(1u << bl);
   tab.cc[j] = raw.c[j];
   tab.d[j] = raw.d[j];

@@ -35,7 +35,8 @@ _JOB_DTYPES = {"job_id": np.int64, "active": np.uint8, "bmin": np.int32, "bmax":
                "remaining": np.float64}
 
 EXPORTS = ["ones_workspace_bytes", "ones_init", "ones_set_jobs", "ones_generation", "ones_best",
-           "ones_export", "ones_placement", "ones_update_limits", "ones_set_progress", "ones_export_remaining", "ones_padded_jobs",
+           "ones_export", "ones_placement", "ones_update_limits", "ones_set_new_jobs_first",
+           "ones_set_progress", "ones_export_remaining", "ones_padded_jobs",
            "ones_profile_enable", "ones_profile_read",
            "ones_destroy", "ones_strerror"]
 
@@ -86,6 +87,7 @@ def load():
     L.ones_best.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(C.c_double)]
     L.ones_export.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(C.c_int64)]
     L.ones_placement.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
+    L.ones_set_new_jobs_first.argtypes = [C.c_void_p, C.c_int32]
     L.ones_update_limits.argtypes = [C.c_int32, C.POINTER(ones_limit_inputs), C.c_double, C.c_void_p]
     L.ones_set_progress.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
     L.ones_export_remaining.argtypes = [C.c_void_p, C.c_void_p]
@@ -176,6 +178,9 @@ class Search:
             if any(a.shape != (self.n_slots,) for a in arrs):
                 raise ValueError("alpha, beta, processed: one entry per slot")
             _check(load().ones_set_progress(self._h, *[a.ctypes.data for a in arrs]))
+
+    def set_new_jobs_first(self, on=True):
+        _check(load().ones_set_new_jobs_first(self._h, int(bool(on))))
 
     def export_remaining(self):
         y = np.zeros(max(self.n_slots, 1), np.float64)

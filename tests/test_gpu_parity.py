@@ -459,3 +459,39 @@ def test_placement_matches_the_oracle(ones, ref, n_slots, n_gpus, pop, seed):
     gpu.generation(1); cpu.generation(1)
     assert np.array_equal(gpu.placement()[0], cpu.placement()[0])
     gpu.close(); cpu.close()
+
+
+@pytest.mark.parametrize("n_slots,n_gpus,pop,seed,n_new", [(8, 3, 64, 0, 6), (40, 64, 1024, 1, 3), (333, 700, 512, 2, 40),
+                                                           (2048, 4096, 256, 3, 300), (2048, 100, 64, 4, 500),
+                                                           (200, 300, 8192, 5, 17)])
+def test_new_jobs_first_matches_the_oracle(ones, ref, n_slots, n_gpus, pop, seed, n_new):
+    """The option of serving arrived jobs first: the generation after the table change and the
+    ordinary ones that follow, with more and with fewer new jobs than GPUs."""
+    rng = np.random.default_rng(seed)
+    cl = cluster(n_gpus, n_slots, pop, seed=seed)
+    jobs = random_jobs(rng, n_slots)
+    say(f"[new first] G={n_gpus} slots={n_slots} P={pop} seed={seed} new={n_new}")
+    gpu, cpu = ones.Search(cl, jobs), ref.RefSearch(cl, jobs)
+    for s in (gpu, cpu):
+        s.set_new_jobs_first(True)
+        s.generation(3)
+    assert_same_state(gpu, cpu, "before the arrivals")
+    j2 = make_jobs(n_slots, **{k: np.array(getattr(jobs, k)) for k in
+                               ("job_id", "active", "bmin", "bmax", "gpu_max_batch", "a", "c", "d", "remaining")})
+    arrived = rng.choice(n_slots, size=min(n_new, n_slots), replace=False)
+    j2.job_id[arrived] += 100000
+    j2.active[arrived[: len(arrived) // 2]] = 1
+    for step in range(2):
+        gpu.set_jobs(j2); cpu.set_jobs(j2)
+        assert_same_state(gpu, cpu, "after the table change")
+        gpu.generation(1); cpu.generation(1)
+        assert_same_state(gpu, cpu, "the generation that serves the new jobs")
+        gpu.generation(2); cpu.generation(2)
+        assert_same_state(gpu, cpu, "ordinary generations after it")
+        j2.job_id[arrived[:3]] += 7                                   # a few of them are replaced again
+    for s in (gpu, cpu):
+        s.set_new_jobs_first(False)
+        s.set_jobs(jobs)
+        s.generation(1)
+    assert_same_state(gpu, cpu, "option off again")
+    gpu.close(); cpu.close()
