@@ -167,15 +167,26 @@ class OnlineSequence:
     global batch B on ceil(B/m) GPUs processes 60*B/t samples, t = a*B/g + c*log2(g) + d;
     a job whose remaining work reaches zero frees its slot.  This is the simulated
     cluster, not the scheduler: the same code feeds either implementation.
+
+    With ``limits`` (a function with the signature of ``update_limits``: the library's or the
+    oracle's) the batch-size limits follow the policies of Section 3.3.2 instead of staying at
+    the job's own maximum: a job starts on one GPU's batch, doubles its limit after every
+    epoch it ran (penalised by its executed time, sigma = the arrival rate), is capped at its
+    last batch when it gets pre-empted and halved for every further epoch it waits.
     """
     EPOCH_S = 60.0
     MAX_BUSY = 60
 
-    def __init__(self, seed: int = 2, n_slots: int = 64, epochs: int = 200):
+    def __init__(self, seed: int = 2, n_slots: int = 64, epochs: int = 200, limits=None):
         self.cluster = Cluster("online", 64, n_slots, 2048, 20, seed, epochs=epochs)
         self.rng = np.random.default_rng(seed)
         self.jobs = empty_jobs(n_slots)
         self.jobs.gpu_max_batch[:] = 256
+        self.limits = limits
+        self.cap = np.zeros(n_slots, np.int32)          # the job's own largest batch
+        self.elapsed = np.zeros(n_slots)                # executed seconds
+        self.prev_batch = np.zeros(n_slots, np.int32)   # batch in the epoch before
+        self.arrived = np.zeros(n_slots, np.uint8)      # arrived since the last limit update
         self.next_id = 1
         self.backlog = 0
         self.completed = 0
@@ -192,8 +203,11 @@ class OnlineSequence:
             j.job_id[s], j.active[s] = self.next_id, 1
             j.a[s], j.c[s], j.d[s], j.remaining[s] = a[0], c[0], d[0], y[0]
             j.bmin[s], j.bmax[s], j.gpu_max_batch[s] = bmin[0], bmax[0], 256
+            self.cap[s], self.elapsed[s], self.prev_batch[s], self.arrived[s] = bmax[0], 0.0, 0, 1
             self.next_id += 1
             self.backlog -= 1
+        if self.limits is not None:
+            self._update_limits(np.zeros(self.jobs.n_slots, np.int32))
 
     def advance(self, batch: np.ndarray):
         """Run the cluster for one epoch under the schedule ``batch`` (global batch per
@@ -211,7 +225,26 @@ class OnlineSequence:
                 j.active[s] = 0
                 j.remaining[s] = 0.0
                 self.completed += 1
+            if self.limits is not None:
+                self.elapsed[s] += self.EPOCH_S
         self._arrive(int(self.rng.poisson(0.5)))
+        if self.limits is not None:
+            self._update_limits(np.asarray(batch, np.int32))
+
+    def _update_limits(self, batch):
+        """Section 3.3.2: the limits the scheduler sees in the next epoch."""
+        j = self.jobs
+        ran = (batch > 0) & (j.active != 0)
+        state = np.where(j.active == 0, 0, np.where(self.arrived != 0, 1, np.where(ran, 3, 2))).astype(np.uint8)
+        just_preempted = (state == 2) & (self.prev_batch > 0)
+        new = self.limits(j.bmax, 0.5 / self.EPOCH_S, state=state, bmin=np.maximum(j.bmin, 1),
+                          bcap=np.maximum(self.cap, 1), gpu_max_batch=j.gpu_max_batch,
+                          last_batch=np.where(just_preempted, self.prev_batch, 0), finished_epoch=ran.astype(np.uint8),
+                          elapsed=self.elapsed)
+        active = j.active != 0
+        j.bmax[active] = new[active]
+        self.prev_batch = np.where(ran, batch, 0).astype(np.int32)
+        self.arrived[:] = 0
 
 
 CONFIGS = {"tiny": tiny, "paper_scale": paper_scale, "large": large, "stress": stress}

@@ -181,6 +181,32 @@ def test_online_sequence(ones, ref):
     gpu.close(); cpu.close()
 
 
+def test_online_sequence_with_limit_policies(ones, ref):
+    """The online sequence with the batch-size limits of Section 3.3.2 (each side computes them
+    with its own update_limits) and newly arrived jobs served first after every table change
+    (refresh (3) of Section 3.2.2)."""
+    sims = [W.OnlineSequence(epochs=40, limits=ones.update_limits), W.OnlineSequence(epochs=40, limits=ref.update_limits)]
+    cl = sims[0].cluster
+    cl.population = 512
+    say(f"[parity] online with limit policies: P={cl.population} epochs=40 gens/epoch=5")
+    gpu = ones.Search(cl, sims[0].jobs)
+    cpu = ref.RefSearch(cl, sims[1].jobs)
+    gpu.set_new_jobs_first(True); cpu.set_new_jobs_first(True)
+    limits_seen = set()
+    for epoch in range(40):
+        gpu.generation(5); cpu.generation(5)
+        assert_same_state(gpu, cpu, f"online+policies epoch {epoch}")
+        gb, gg, gf = gpu.best(); cb, cg, cf = cpu.best()
+        assert gb.tolist() == cb.tolist() and gg.tolist() == cg.tolist() and gf == cf
+        sims[0].advance(gb); sims[1].advance(cb)
+        assert sims[0].jobs.sha256() == sims[1].jobs.sha256()
+        limits_seen.update(sims[0].jobs.bmax[sims[0].jobs.active != 0].tolist())
+        gpu.set_jobs(sims[0].jobs); cpu.set_jobs(sims[1].jobs)
+        assert_same_state(gpu, cpu, f"online+policies epoch {epoch} after set_jobs")
+    assert sims[0].completed > 0 and len(limits_seen) > 3      # the limits really moved
+    gpu.close(); cpu.close()
+
+
 def test_set_jobs_rejects_bad_tables_and_keeps_state(ones, ref):
     rng = np.random.default_rng(31)
     jobs = random_jobs(rng, 64)

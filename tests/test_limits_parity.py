@@ -62,3 +62,28 @@ def test_rejections_agree_and_leave_the_limits_alone(ones, ref):
     assert lib.ones_update_limits(3, None, 0.1, limit.ctypes.data) == -1
     assert lib.ones_update_limits(-1, None, 0.1, None) == -1
     assert lib.ones_update_limits(0, None, 0.1, None) == 0
+
+
+def test_online_sequence_is_the_same_under_either_implementation(ones, ref):
+    """The simulated cluster driven by the oracle's search, once with the library's limits and
+    once with the oracle's: identical job tables at every epoch, and the limits do move."""
+    from paper_2108_03645_amd import workloads as W
+    sims = [W.OnlineSequence(epochs=25, limits=ones.update_limits), W.OnlineSequence(epochs=25, limits=ref.update_limits)]
+    cl = sims[1].cluster
+    cl.population = 128
+    search = ref.RefSearch(cl, sims[1].jobs)
+    search.set_new_jobs_first(True)
+    seen = set()
+    for epoch in range(25):
+        search.generation(3)
+        batch, _, _ = search.best()
+        for sim in sims:
+            sim.advance(batch)
+        assert sims[0].jobs.sha256() == sims[1].jobs.sha256(), epoch
+        j = sims[1].jobs
+        live = j.active != 0
+        assert np.all(j.bmax[live] >= j.bmin[live]) and np.all(j.bmax[live] <= sims[1].cap[live])
+        seen.update(j.bmax[live].tolist())
+        search.set_jobs(j)
+    assert len(seen) > 3
+    search.close()
