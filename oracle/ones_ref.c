@@ -51,6 +51,8 @@ struct ones_ref_ctx {
   int      new_jobs_first; /* option: the first generation after a table change serves new jobs first */
   int      serve_new;      /* ... and this is that generation */
   uint8_t *is_new;         /* Jp entries: slot changed hands in the last ones_ref_set_jobs */
+  double  *t_processed;    /* Jp entries: executed time per slot, or NULL (ones_ref_set_processed_time) */
+  int     *by_time;        /* Jp entries: the slots in ascending (t_processed, slot) order */
   int      sampling;       /* Alg. 1: remaining work drawn per generation */
   double  *alpha, *beta, *processed, *Y_fixed;   /* Jn entries each */
 };
@@ -189,8 +191,13 @@ static int gene_from_draw(const slot_t *s, uint32_t k) {
  * served first ("allocates N new jobs with N available GPUs ... avoid starvation of new jobs
  * by the preferential allocation", Section 3.2.2 refresh (3)): in visiting order each starts
  * with the batch a waiting job resumes with while the capacity lasts, and only what they leave
- * is shared out among the others. */
-static int repair(const slot_t *tab, int Jp, int R, int64_t G, int *g, uint32_t r, const uint8_t *is_new) {
+ * is shared out among the others.
+ * by_time (may be NULL; only looked at together with is_new): the slots in ascending order of
+ * the time their jobs have executed.  The others are then admitted in that order instead of
+ * the rotated one, so that the room for the new jobs is taken from the jobs with the largest
+ * T_processed (same passage). */
+static int repair(const slot_t *tab, int Jp, int R, int64_t G, int *g, uint32_t r, const uint8_t *is_new,
+                  const int *by_time) {
   int order[MAX_SLOTS];
   for (int j = 0; j < Jp; ++j) {
     int sigma = (j % LANES) * R + (j / LANES);
@@ -219,7 +226,7 @@ static int repair(const slot_t *tab, int Jp, int R, int64_t G, int *g, uint32_t 
   /* 3. admit: prefix sum of GPU counts in visiting order; beyond capacity -> wait */
   Q = 0;
   for (int pos = 0; pos < Jp; ++pos) {
-    int j = order[pos];
+    int j = (is_new && by_time) ? by_time[pos] : order[pos];
     if (g[j] == WAIT || (is_new && is_new[j])) continue;
     Q += gpus_of(g[j], tab[j].mu);
     if (Q > G - taken) g[j] = WAIT;
@@ -365,7 +372,7 @@ static void initial_genome(const ones_ref_ctx *c, int p, int *g, uint32_t *r_out
 }
 
 static void finish_slot(ones_ref_ctx *c, int32_t *dst, int p, int *g, uint32_t r) {
-  repair(c->tab, c->Jp, c->R, c->G, g, r, c->serve_new ? c->is_new : NULL);
+  repair(c->tab, c->Jp, c->R, c->G, g, r, c->serve_new ? c->is_new : NULL, c->t_processed ? c->by_time : NULL);
   c->fit[p] = score(c->tab, c->R, g);
   int32_t *row = dst + (size_t)p * c->Jp;
   for (int j = 0; j < c->Jp; ++j) row[j] = batch_of(g[j]);
@@ -469,6 +476,42 @@ int ones_ref_set_progress(ones_ref_ctx *c, const double *alpha, const double *be
 int ones_ref_set_new_jobs_first(ones_ref_ctx *c, int32_t on) {
   if (!c) return ONES_REF_E_INVALID_ARG;
   c->new_jobs_first = on != 0;
+  return ONES_REF_OK;
+}
+
+/* slots in ascending (time, slot) order: insertion into a sorted list, stable by construction */
+static void order_by_time(const double *time, int Jp, int *out) {
+  for (int j = 0; j < Jp; ++j) {
+    int pos = j;
+    while (pos > 0 && time[out[pos - 1]] > time[j]) { out[pos] = out[pos - 1]; --pos; }
+    out[pos] = j;
+  }
+}
+
+static int check_times(const double *t, int n) {
+  for (int j = 0; j < n; ++j) {
+    if (!isfinite(t[j])) return ONES_REF_E_NONFINITE;
+    if (t[j] < 0.0) return ONES_REF_E_INVALID_ARG;
+    if (t[j] > MAX_PARAM) return ONES_REF_E_BOUNDS;
+  }
+  return ONES_REF_OK;
+}
+
+int ones_ref_set_processed_time(ones_ref_ctx *c, const double *t_processed) {
+  if (!c) return ONES_REF_E_INVALID_ARG;
+  if (!t_processed) {
+    free(c->t_processed); free(c->by_time);
+    c->t_processed = NULL; c->by_time = NULL;
+    return ONES_REF_OK;
+  }
+  int rc = check_times(t_processed, c->Jn);
+  if (rc) return rc;
+  if (!c->t_processed) {
+    c->t_processed = (double *)calloc((size_t)c->Jp, sizeof(double));
+    c->by_time = (int *)calloc((size_t)c->Jp, sizeof(int));
+  }
+  for (int j = 0; j < c->Jp; ++j) c->t_processed[j] = j < c->Jn ? t_processed[j] : 0.0;
+  order_by_time(c->t_processed, c->Jp, c->by_time);
   return ONES_REF_OK;
 }
 
@@ -659,7 +702,8 @@ int ones_ref_export(ones_ref_ctx *c, int32_t *genes, double *fit, int32_t *sel, 
 void ones_ref_destroy(ones_ref_ctx *c) {
   if (!c) return;
   free(c->tab); free(c->genes[0]); free(c->genes[1]); free(c->fit); free(c->sel);
-  free(c->alpha); free(c->beta); free(c->processed); free(c->Y_fixed); free(c->is_new); free(c);
+  free(c->alpha); free(c->beta); free(c->processed); free(c->Y_fixed); free(c->is_new);
+  free(c->t_processed); free(c->by_time); free(c);
 }
 
 int ones_ref_compose_slot(ones_ref_ctx *c, int32_t p, int32_t *genes_out, uint32_t *r_out,
@@ -715,7 +759,32 @@ int ones_ref_repair_genome(const ones_ref_config *cfg, const ones_ref_jobs *jobs
   slot_t tab[MAX_SLOTS]; int g[MAX_SLOTS];
   if ((rc = build_table(Jn, Jp, jobs, tab))) return rc;
   if ((rc = load_genome(tab, Jn, Jp, genes, g))) return rc;
-  int rounds = repair(tab, Jp, Jp / LANES, cfg->n_gpus, g, r, NULL);
+  int rounds = repair(tab, Jp, Jp / LANES, cfg->n_gpus, g, r, NULL, NULL);
+  for (int j = 0; j < Jn; ++j) genes[j] = batch_of(g[j]);
+  if (fill_rounds_out) *fill_rounds_out = rounds;
+  return ONES_REF_OK;
+}
+
+int ones_ref_repair_arrivals(const ones_ref_config *cfg, const ones_ref_jobs *jobs, int32_t *genes, uint32_t r,
+                             const uint8_t *arrived, const double *t_processed, int32_t *fill_rounds_out) {
+  int rc = check_config(cfg);
+  if (rc) return rc;
+  int Jn = cfg->n_slots, Jp = ones_ref_padded_jobs(Jn);
+  if ((int64_t)r >= Jp || !genes || !arrived) return ONES_REF_E_INVALID_ARG;
+  if (t_processed && (rc = check_times(t_processed, Jn))) return rc;
+  slot_t tab[MAX_SLOTS]; int g[MAX_SLOTS];
+  if ((rc = build_table(Jn, Jp, jobs, tab))) return rc;
+  if ((rc = load_genome(tab, Jn, Jp, genes, g))) return rc;
+  uint8_t is_new[MAX_SLOTS];
+  double time[MAX_SLOTS];
+  int by_time[MAX_SLOTS];
+  for (int j = 0; j < Jp; ++j) {
+    is_new[j] = j < Jn && arrived[j] != 0;
+    time[j] = (t_processed && j < Jn) ? t_processed[j] : 0.0;
+    if (is_new[j]) g[j] = WAIT;                 /* the slot changed hands: it starts from waiting */
+  }
+  order_by_time(time, Jp, by_time);
+  int rounds = repair(tab, Jp, Jp / LANES, cfg->n_gpus, g, r, is_new, t_processed ? by_time : NULL);
   for (int j = 0; j < Jn; ++j) genes[j] = batch_of(g[j]);
   if (fill_rounds_out) *fill_rounds_out = rounds;
   return ONES_REF_OK;

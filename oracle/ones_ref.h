@@ -30,6 +30,10 @@
  *   new jobs first         : a hand-worked two-GPU example, every new job running in every
  *                            candidate when the capacity allows, Eq. 4, no effect when off or
  *                            when no job is new.
+ *   ones_ref_repair_arrivals / ones_ref_set_processed_time : a sequential Python
+ *                            transcription on random cases, a hand-worked example (the job
+ *                            with the largest T_processed gives up its GPUs), equal times =
+ *                            slot order, the admitted jobs form a prefix of the time order.
  *   scheduling quality against the paper's JCT numbers: parity unpinned (the paper's
  *                            trace, jobs and comparison schedulers do not exist here).
  */
@@ -94,6 +98,12 @@ int  ones_ref_set_progress(ones_ref_ctx *ctx, const double *alpha, const double 
  * order, each new job starts with the batch a waiting job resumes with while the capacity
  * lasts; the other jobs are admitted to what is left, then the fill runs as always. */
 int  ones_ref_set_new_jobs_first(ones_ref_ctx *ctx, int32_t on);
+/* The time every slot's job has executed (T_processed; n_slots finite entries >= 0), or NULL to
+ * forget it.  While set, the generation that serves new jobs first admits the other jobs in
+ * ascending order of that time (equal times: lower slot first) instead of the rotated order:
+ * when the new jobs leave too little room, the GPUs are taken from the jobs with the largest
+ * T_processed (same passage).  The fill rounds keep the rotated order. */
+int  ones_ref_set_processed_time(ones_ref_ctx *ctx, const double *t_processed);
 
 /* the remaining work Y_j (n_slots entries) the last generation was scored with */
 int  ones_ref_export_remaining(ones_ref_ctx *ctx, double *remaining_out);
@@ -137,6 +147,11 @@ void ones_ref_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32
  * rotation r in [0,Jp); fill_rounds_out (may be NULL) receives the number of fill rounds */
 int  ones_ref_repair_genome(const ones_ref_config *cfg, const ones_ref_jobs *jobs,
                             int32_t *genes, uint32_t r, int32_t *fill_rounds_out);
+/* The same with the refresh (3) of Section 3.2.2: arrived (n_slots bytes) marks the slots whose
+ * jobs arrived (their genes start from waiting and they are served first); t_processed
+ * (n_slots entries or NULL) is the executed time that orders the admission of the others. */
+int  ones_ref_repair_arrivals(const ones_ref_config *cfg, const ones_ref_jobs *jobs, int32_t *genes, uint32_t r,
+                              const uint8_t *arrived, const double *t_processed, int32_t *fill_rounds_out);
 int  ones_ref_score_genome(const ones_ref_config *cfg, const ones_ref_jobs *jobs,
                            const int32_t *genes, double *fitness_out);
 void ones_ref_select(const double *fit, int32_t population, int32_t *sel /* population/4 */);

@@ -79,6 +79,9 @@ def lib():
                                               C.c_void_p, C.POINTER(C.c_uint32)]
         L.ones_ref_update_limits.argtypes = [C.c_int32, C.POINTER(_LimitInputs), C.c_double, C.c_void_p]
         L.ones_ref_set_new_jobs_first.argtypes = [C.c_void_p, C.c_int32]
+        L.ones_ref_set_processed_time.argtypes = [C.c_void_p, C.c_void_p]
+        L.ones_ref_repair_arrivals.argtypes = [C.POINTER(_Config), C.POINTER(_Jobs), C.c_void_p, C.c_uint32,
+                                               C.c_void_p, C.c_void_p, C.POINTER(C.c_int32)]
         L.ones_ref_placement.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
         L.ones_ref_set_progress.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         L.ones_ref_export_remaining.argtypes = [C.c_void_p, C.c_void_p]
@@ -170,6 +173,21 @@ def repair_genome(n_gpus, jobs, genes, r, population=4):
     return g, rounds.value
 
 
+def repair_arrivals(n_gpus, jobs, genes, r, arrived, t_processed=None, population=4):
+    """Repair with the jobs marked in arrived served first; t_processed orders the others."""
+    cfg = _cfg(n_gpus, len(genes), population, 0, 0.0, 0.0)
+    js, keep = _jobs(jobs)
+    g = np.ascontiguousarray(genes, np.int32).copy()
+    new = np.ascontiguousarray(arrived, np.uint8)
+    times = None if t_processed is None else np.ascontiguousarray(t_processed, np.float64)
+    if len(new) != len(g) or (times is not None and len(times) != len(g)):
+        raise ValueError("arrived, t_processed: one entry per slot")
+    rounds = C.c_int32(0)
+    _check(lib().ones_ref_repair_arrivals(C.byref(cfg), C.byref(js), g.ctypes.data, int(r), new.ctypes.data,
+                                          None if times is None else times.ctypes.data, C.byref(rounds)))
+    return g, rounds.value
+
+
 def score_genome(n_gpus, jobs, genes):
     cfg = _cfg(n_gpus, len(genes), 4, 0, 0.0, 0.0)
     js, keep = _jobs(jobs)
@@ -230,6 +248,15 @@ class RefSearch:
 
     def set_new_jobs_first(self, on=True):
         _check(lib().ones_ref_set_new_jobs_first(self._h, int(bool(on))))
+
+    def set_processed_time(self, t_processed=None):
+        if t_processed is None:
+            _check(lib().ones_ref_set_processed_time(self._h, None))
+            return
+        t = np.ascontiguousarray(t_processed, np.float64)
+        if len(t) != self.n_slots:
+            raise ValueError("t_processed: one entry per slot")
+        _check(lib().ones_ref_set_processed_time(self._h, t.ctypes.data))
 
     def export_remaining(self):
         y = np.zeros(self.n_slots, np.float64)

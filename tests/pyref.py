@@ -124,6 +124,40 @@ def repair(G, jobs, genes, r):
     return np.array(B, np.int32), rounds
 
 
+def repair_arrivals(G, jobs, genes, r, arrived, t_processed=None):
+    """The repair when jobs arrived (Section 3.2.2, refresh (3)), stated sequentially: the
+    arrived jobs, in visiting order, each take their starting batch while the cluster has room;
+    the others keep their GPUs in visiting order (or, with t_processed, least executed time
+    first) while what is left has room; then the usual fill."""
+    n = len(genes)
+    B = [int(v) for v in genes]
+    order = visiting_order(n, r)
+    m = jobs.gpu_max_batch
+    for j in range(n):
+        if not jobs.active[j] or arrived[j]:
+            B[j] = 0
+        elif B[j]:
+            B[j] = min(max(B[j], int(jobs.bmin[j])), int(jobs.bmax[j]))
+            B[j] = max(B[j], min(int(m[j]), int(jobs.bmax[j])))
+    asked = room = 0
+    for j in order:
+        if arrived[j] and jobs.active[j]:
+            asked += gpus(start_batch(jobs, j), m[j])
+            if asked <= G:
+                B[j] = start_batch(jobs, j)
+                room = asked
+    others = [j for j in order if not arrived[j]]
+    if t_processed is not None:
+        others = sorted((j for j in range(n) if not arrived[j]), key=lambda j: (t_processed[j], j))
+    total = 0
+    for j in others:
+        total += gpus(B[j], m[j])
+        if total > G - room:
+            B[j] = 0
+    filled, rounds = repair(G, jobs, B, r)      # clamp, lift and admission change nothing any more
+    return filled, rounds
+
+
 def check_invariants(G, jobs, genes):
     """I1 window / inactive, I2 capacity (Eq. 4), I3 maximality.  Returns idle GPUs."""
     n = len(genes)
