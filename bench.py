@@ -24,8 +24,7 @@ HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published peak
 
 # HBM bytes per evolve launch on the stress workload from rocprofv3 --pmc FETCH_SIZE and
 # WRITE_SIZE (see profiles/), valid only for the kernel source with this hash.
-MEASURED_TRAFFIC = {"source_sha256": "d2670deea506be2560ca5cd99ba985c91f76d2459c3f99082b2a49dd21cf25b9",
-                    "bytes_per_launch": 802770138}
+MEASURED_TRAFFIC = {"source_sha256": "7fda7fb629d974bda34646af18812066cb73e4df706c8d36937a886e25f9a460", "bytes_per_launch": 802741924}
 
 
 def evolve_source_hash() -> str:
@@ -95,6 +94,8 @@ def online(args, torch, ones, W) -> int:
         sim.advance(batch)
         t3 = time.perf_counter()
         search.set_jobs(sim.jobs)
+        if args.policies:
+            search.set_processed_time(sim.elapsed)
         t4 = time.perf_counter()
         if timed:
             t_gen += t1 - t0; t_best += t2 - t1; t_set += t4 - t3

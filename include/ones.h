@@ -118,6 +118,16 @@ int ones_set_progress(ones_ctx *ctx, const double *alpha, const double *beta,
  * left; then the fill runs as always.  Later generations treat those jobs like any other. */
 int ones_set_new_jobs_first(ones_ctx *ctx, int32_t on);
 
+/* The time the job of every slot has executed (T_processed; HOST array of n_slots finite
+ * entries in [0, 1e100], copied; empty slots' entries are ignored), or NULL to forget the
+ * times.  While they are known, the generation that serves new jobs first admits the other
+ * jobs in ascending order of executed time (equal times: lower slot first) instead of the
+ * candidate's visiting order, so that the GPUs the new jobs need are taken from the jobs with
+ * the largest T_processed (same passage).  The fill keeps the visiting order.  The times
+ * persist across ones_set_jobs; a scheduler sets them anew with every table.  Errors:
+ * ONES_E_NONFINITE, ONES_E_INVALID_ARG (negative), ONES_E_BOUNDS.  Synchronises. */
+int ones_set_processed_time(ones_ctx *ctx, const double *t_processed);
+
 /* The remaining work Y_j the last generation was scored with (HOST array of n_slots
  * entries): the job table's, or the last draw under ones_set_progress.  Synchronises. */
 int ones_export_remaining(ones_ctx *ctx, double *remaining_out);

@@ -30,7 +30,7 @@ size_t align_up(size_t v) { return (v + 255) & ~static_cast<size_t>(255); }
 
 struct Layout {
   size_t genes, fit_row, row_of[2], parent_row[2], occupied[2], sel, split, thresh, bcount[2], bkeys, bidx, skeys, sidx, sbucket, pkeys, pidx, cstart, cmax, info, abl, cc, d, Y, terms;
-  size_t rawinfo, changed, ra, rc, rd, rY, alpha, beta, processed, best_batch, best_gpus, best_fit, place_slot, place_batch, total;
+  size_t rawinfo, changed, ra, rc, rd, rY, alpha, beta, processed, time_rank, best_batch, best_gpus, best_fit, place_slot, place_batch, total;
 };
 
 // Buckets of the selection: about 16 survivors each, at most kMaxBuckets.  A bucket stores eight
@@ -84,6 +84,7 @@ Layout make_layout(uint32_t P, uint32_t Jp, uint32_t G) {
   L.rawinfo = take(Jp * 4); L.changed = take(Jp * 4);
   L.ra = take(Jp * 8); L.rc = take(Jp * 8); L.rd = take(Jp * 8); L.rY = take(Jp * 8);
   L.alpha = take(Jp * 8); L.beta = take(Jp * 8); L.processed = take(Jp * 8);
+  L.time_rank = take(Jp * 4);
   L.best_batch = take(Jp * 4); L.best_gpus = take(Jp * 4); L.best_fit = take(8);
   L.place_slot = take(static_cast<size_t>(G) * 4); L.place_batch = take(static_cast<size_t>(G) * 4);
   L.total = off;
@@ -169,6 +170,7 @@ struct ones_ctx {
   bool no_schedule;           // ... by ones_set_jobs: the winner is not a schedule under the new table
   bool new_jobs_first;        // option: the generation after ones_set_jobs serves the arrived jobs first
   bool sampling;              // remaining work drawn per generation (Alg. 1) instead of the table's
+  bool has_times;             // executed times known (ones_set_processed_time): their ranks are on the device
   BucketPlan bp;              // nb == 0: pool small enough for the single-chunk sort
   int bucket_phase;           // which counter set the next bucketed generation fills
   int n_cus;
@@ -253,6 +255,7 @@ int run_generation(ones_ctx *c, uint32_t t) {
   const bool sampled = t != 0 && c->sampling;
   a.rescore = same_table && sampled ? 1u : 0u;
   a.new_first = c->new_jobs_first && c->no_schedule ? 1u : 0u;   // the table's "arrived" marks are fresh
+  a.time_rank = c->has_times ? c->at<uint32_t>(c->L.time_rank) : nullptr;
   // quantile buckets: only when the survivors reappear with the scores they had
   const bool buckets = same_table && !sampled && c->bp.nb != 0;
   a.bk.nb = buckets ? c->bp.nb : 0;
@@ -351,6 +354,7 @@ int ones_init(ones_ctx **out, const ones_config *cfg, const ones_jobs *jobs, voi
   c->no_schedule = false;
   c->new_jobs_first = false;
   c->sampling = false;
+  c->has_times = false;
   c->bp = bucket_plan(c->P);
   c->bucket_phase = 0;
   c->ids = h.id;
@@ -430,6 +434,26 @@ int ones_set_progress(ones_ctx *c, const double *alpha, const double *beta, cons
 int ones_set_new_jobs_first(ones_ctx *c, int32_t on) {
   if (!c) return ONES_E_INVALID_ARG;
   c->new_jobs_first = on != 0;
+  return ONES_OK;
+}
+
+int ones_set_processed_time(ones_ctx *c, const double *t_processed) {
+  if (!c) return ONES_E_INVALID_ARG;
+  if (!t_processed) { c->has_times = false; return ONES_OK; }
+  for (uint32_t j = 0; j < c->Jn; ++j) {
+    int rc = check_param(t_processed[j]);
+    if (rc) return rc;
+  }
+  // position of every slot in ascending (time, slot) order; the padding slots count as time 0
+  std::vector<uint32_t> order(c->Jp), rank(c->Jp);
+  for (uint32_t j = 0; j < c->Jp; ++j) order[j] = j;
+  auto time_of = [&](uint32_t j) { return j < c->Jn ? t_processed[j] : 0.0; };
+  std::stable_sort(order.begin(), order.end(), [&](uint32_t x, uint32_t y) { return time_of(x) < time_of(y); });
+  for (uint32_t pos = 0; pos < c->Jp; ++pos) rank[order[pos]] = pos;
+  HIP_TRY(hipMemcpyAsync(c->ws + c->L.time_rank, rank.data(), static_cast<size_t>(c->Jp) * 4, hipMemcpyHostToDevice,
+                         c->stream));
+  HIP_TRY(hipStreamSynchronize(c->stream));     // the staging vector may go away now
+  c->has_times = true;
   return ONES_OK;
 }
 

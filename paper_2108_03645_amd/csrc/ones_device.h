@@ -107,6 +107,8 @@ struct EvolveArgs {
   uint32_t       t;           // generation counter (0 = initial population)
   uint32_t       T_mut, T_x;  // rate thresholds on a 32-bit word
   uint32_t       new_first;   // after a table change: the jobs that arrived with it are served first
+  const uint32_t *time_rank;  // [Jp] with new_first: position of every slot in ascending order of executed
+                              //      time, the order the other jobs are admitted in; null = visiting order
   uint32_t       rescore;     // the survivors' scores are stale (remaining work redrawn): score them again
   uint32_t       term_lds;    // set by the launcher: entries per job of the term table in LDS, 0 = none
   BucketArgs     bk;

@@ -328,10 +328,12 @@ __device__ __forceinline__ uint32_t accept_prefix(uint32_t (&v)[R], uint32_t lim
 // Refresh + fill (Section 3.2.2) on GPU counts c[]; clamp and lift already applied.
 // new_first (only in the generation after a table change): the jobs that arrived with the table
 // are served first (refresh (3)): each starts on cstart GPUs while the capacity lasts, in
-// visiting order, and the others are admitted to what is left.
+// visiting order, and the others are admitted to what is left: in visiting order too, or, with
+// time_rank (position of every job in ascending order of executed time), least executed time
+// first, so that the room is taken from the jobs with the largest T_processed.
 template <int R>
 __device__ __forceinline__ void repair(uint32_t (&c)[R], const Smem &s, uint32_t G, uint32_t r, int lane,
-                                       bool new_first) {
+                                       bool new_first, const uint32_t *time_rank = nullptr) {
   const uint32_t lr = r / R, ir = r % R;
   uint32_t used;
   if (new_first) {
@@ -346,7 +348,28 @@ __device__ __forceinline__ void repair(uint32_t (&c)[R], const Smem &s, uint32_t
       v[i] = is_new ? 0u : c[i];
     }
     phase_fence();
-    used = taken + accept_prefix<R>(v, G - taken, lr, ir, lane);
+    if (time_rank) {
+      // The running sum over the ranks never decreases, so the admitted jobs are the ranks below
+      // some bound: the largest n whose first n ranks ask for no more than what is left.
+      const uint32_t cap = G - taken;
+      uint32_t rk[R];
+#pragma unroll
+      for (int i = 0; i < R; ++i) rk[i] = time_rank[lane + kLanes * i];
+      uint32_t lo = 0, hi = static_cast<uint32_t>(R * kLanes), fits = 0;   // the first lo ranks fit (sum fits)
+      while (lo < hi) {                                                    // at most log2(R * 64) + 1 steps
+        const uint32_t mid = (lo + hi + 1) / 2;
+        uint32_t sum = 0;
+#pragma unroll
+        for (int i = 0; i < R; ++i) sum += rk[i] < mid ? v[i] : 0u;
+        sum = wave_sum(sum);
+        if (sum <= cap) { lo = mid; fits = sum; } else { hi = mid - 1; }
+      }
+#pragma unroll
+      for (int i = 0; i < R; ++i) v[i] = rk[i] < lo ? v[i] : 0u;
+      used = taken + fits;
+    } else {
+      used = taken + accept_prefix<R>(v, G - taken, lr, ir, lane);
+    }
 #pragma unroll
     for (int i = 0; i < R; ++i) c[i] = info_new(s.info[lane + kLanes * i]) ? c[i] : v[i];
   } else {
@@ -451,7 +474,7 @@ __device__ __forceinline__ void drop_in_bucket(const EvolveArgs &a, const Smem &
 template <int R>
 __device__ __forceinline__ double finish(const EvolveArgs &a, const Smem &s, uint32_t dst_row, uint32_t r,
                                          uint32_t (&c)[R], int lane, bool new_first = false) {
-  repair<R>(c, s, a.G, r, lane, new_first);
+  repair<R>(c, s, a.G, r, lane, new_first, a.time_rank);
   phase_fence();
   const double f = score<R>(c, s, a.term_lds, lane);
   phase_fence();

@@ -35,7 +35,7 @@ _JOB_DTYPES = {"job_id": np.int64, "active": np.uint8, "bmin": np.int32, "bmax":
                "remaining": np.float64}
 
 EXPORTS = ["ones_workspace_bytes", "ones_init", "ones_set_jobs", "ones_generation", "ones_best",
-           "ones_export", "ones_placement", "ones_update_limits", "ones_set_new_jobs_first",
+           "ones_export", "ones_placement", "ones_update_limits", "ones_set_new_jobs_first", "ones_set_processed_time",
            "ones_set_progress", "ones_export_remaining", "ones_padded_jobs",
            "ones_profile_enable", "ones_profile_read",
            "ones_destroy", "ones_strerror"]
@@ -88,6 +88,7 @@ def load():
     L.ones_export.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(C.c_int64)]
     L.ones_placement.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
     L.ones_set_new_jobs_first.argtypes = [C.c_void_p, C.c_int32]
+    L.ones_set_processed_time.argtypes = [C.c_void_p, C.c_void_p]
     L.ones_update_limits.argtypes = [C.c_int32, C.POINTER(ones_limit_inputs), C.c_double, C.c_void_p]
     L.ones_set_progress.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
     L.ones_export_remaining.argtypes = [C.c_void_p, C.c_void_p]
@@ -181,6 +182,15 @@ class Search:
 
     def set_new_jobs_first(self, on=True):
         _check(load().ones_set_new_jobs_first(self._h, int(bool(on))))
+
+    def set_processed_time(self, t_processed=None):
+        if t_processed is None:
+            _check(load().ones_set_processed_time(self._h, None))
+            return
+        t = np.ascontiguousarray(t_processed, np.float64)
+        if len(t) != self.n_slots:
+            raise ValueError("t_processed: one entry per slot")
+        _check(load().ones_set_processed_time(self._h, t.ctypes.data))
 
     def export_remaining(self):
         y = np.zeros(max(self.n_slots, 1), np.float64)

@@ -202,6 +202,7 @@ def test_online_sequence_with_limit_policies(ones, ref):
         assert sims[0].jobs.sha256() == sims[1].jobs.sha256()
         limits_seen.update(sims[0].jobs.bmax[sims[0].jobs.active != 0].tolist())
         gpu.set_jobs(sims[0].jobs); cpu.set_jobs(sims[1].jobs)
+        gpu.set_processed_time(sims[0].elapsed); cpu.set_processed_time(sims[1].elapsed)
         assert_same_state(gpu, cpu, f"online+policies epoch {epoch} after set_jobs")
     assert sims[0].completed > 0 and len(limits_seen) > 3      # the limits really moved
     gpu.close(); cpu.close()
@@ -490,13 +491,15 @@ def test_placement_matches_the_oracle(ones, ref, n_slots, n_gpus, pop, seed):
 @pytest.mark.parametrize("n_slots,n_gpus,pop,seed,n_new", [(8, 3, 64, 0, 6), (40, 64, 1024, 1, 3), (333, 700, 512, 2, 40),
                                                            (2048, 4096, 256, 3, 300), (2048, 100, 64, 4, 500),
                                                            (200, 300, 8192, 5, 17)])
-def test_new_jobs_first_matches_the_oracle(ones, ref, n_slots, n_gpus, pop, seed, n_new):
+@pytest.mark.parametrize("times", ["none", "ties", "distinct"])
+def test_new_jobs_first_matches_the_oracle(ones, ref, n_slots, n_gpus, pop, seed, n_new, times):
     """The option of serving arrived jobs first: the generation after the table change and the
-    ordinary ones that follow, with more and with fewer new jobs than GPUs."""
+    ordinary ones that follow, with more and with fewer new jobs than GPUs; the others admitted
+    in visiting order or by executed time (many equal times, or all distinct)."""
     rng = np.random.default_rng(seed)
     cl = cluster(n_gpus, n_slots, pop, seed=seed)
     jobs = random_jobs(rng, n_slots)
-    say(f"[new first] G={n_gpus} slots={n_slots} P={pop} seed={seed} new={n_new}")
+    say(f"[new first] G={n_gpus} slots={n_slots} P={pop} seed={seed} new={n_new} times={times}")
     gpu, cpu = ones.Search(cl, jobs), ref.RefSearch(cl, jobs)
     for s in (gpu, cpu):
         s.set_new_jobs_first(True)
@@ -509,6 +512,9 @@ def test_new_jobs_first_matches_the_oracle(ones, ref, n_slots, n_gpus, pop, seed
     j2.active[arrived[: len(arrived) // 2]] = 1
     for step in range(2):
         gpu.set_jobs(j2); cpu.set_jobs(j2)
+        if times != "none":
+            t_processed = rng.integers(0, 4, n_slots) * 60.0 if times == "ties" else rng.permutation(n_slots) * 1.5
+            gpu.set_processed_time(t_processed); cpu.set_processed_time(t_processed)
         assert_same_state(gpu, cpu, "after the table change")
         gpu.generation(1); cpu.generation(1)
         assert_same_state(gpu, cpu, "the generation that serves the new jobs")
@@ -516,8 +522,29 @@ def test_new_jobs_first_matches_the_oracle(ones, ref, n_slots, n_gpus, pop, seed
         assert_same_state(gpu, cpu, "ordinary generations after it")
         j2.job_id[arrived[:3]] += 7                                   # a few of them are replaced again
     for s in (gpu, cpu):
-        s.set_new_jobs_first(False)
+        s.set_processed_time(None)
         s.set_jobs(jobs)
         s.generation(1)
+    assert_same_state(gpu, cpu, "times forgotten")
+    for s in (gpu, cpu):
+        s.set_new_jobs_first(False)
+        s.set_jobs(j2)
+        s.generation(1)
     assert_same_state(gpu, cpu, "option off again")
+    gpu.close(); cpu.close()
+
+
+def test_set_processed_time_rejects_bad_arguments(ones, ref):
+    cl, jobs = W.tiny()
+    gpu, cpu = ones.Search(cl, jobs), ref.RefSearch(cl, jobs)
+    good = np.arange(cl.n_slots, dtype=np.float64)
+    for slot, value in [(2, -1.0), (0, float("nan")), (5, float("inf")), (1, 1e101)]:
+        bad = good.copy(); bad[slot] = value
+        with pytest.raises(ones.OnesError) as g:
+            gpu.set_processed_time(bad)
+        with pytest.raises(ref.RefError) as c:
+            cpu.set_processed_time(bad)
+        assert g.value.code == c.value.code
+    gpu.generation(2); cpu.generation(2)
+    assert_same_state(gpu, cpu, "after rejected times")
     gpu.close(); cpu.close()
