@@ -53,6 +53,7 @@ struct ones_ref_ctx {
   uint8_t *is_new;         /* Jp entries: slot changed hands in the last ones_ref_set_jobs */
   double  *t_processed;    /* Jp entries: executed time per slot, or NULL (ones_ref_set_processed_time) */
   int     *by_time;        /* Jp entries: the slots in ascending (t_processed, slot) order */
+  int      per_gpu;        /* uniform crossover scans the GPUs (the paper's encoding) instead of the jobs */
   int      sampling;       /* Alg. 1: remaining work drawn per generation */
   double  *alpha, *beta, *processed, *Y_fixed;   /* Jn entries each */
 };
@@ -317,6 +318,52 @@ void ones_ref_select(const double *fit, int32_t population, int32_t *sel) {
   free(k);
 }
 
+/* ------------------------------------------- crossover over the GPUs ------------- */
+/* Uniform crossover as the paper states it (Section 3.2.2), on the encoding of Eq. 1: a
+ * schedule maps every GPU to the job whose worker it hosts.  The parents are laid out the way
+ * the reorder operator leaves them (jobs in slot order on consecutive GPUs, cA[j] resp. cB[j]
+ * GPUs each, GPUs beyond the cluster do not exist), every GPU is scanned on its own, and
+ * with a fair coin the job of the first parent goes to the first child and the job of the
+ * second parent to the second child, or the other way round.  n1[j], n2[j]: the number of GPUs
+ * on which each child inherited job j.
+ * Coin of GPU i for the pair whose first child is pool slot p0, generation t: bit i mod 32 of
+ * word (i mod 128) div 32 of the Philox block with counter (i div 128, p0, t, 3). */
+void ones_ref_gpu_crossover(uint64_t seed, uint32_t p0, uint32_t t, int32_t n_gpus, int32_t n,
+                            const int32_t *cA, const int32_t *cB, int32_t *n1, int32_t *n2) {
+  const uint32_t key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)};
+  int32_t *gpuA = (int32_t *)malloc(sizeof(int32_t) * (size_t)(n_gpus > 0 ? n_gpus : 1));
+  int32_t *gpuB = (int32_t *)malloc(sizeof(int32_t) * (size_t)(n_gpus > 0 ? n_gpus : 1));
+  for (int which = 0; which < 2; ++which) {
+    const int32_t *c = which ? cB : cA;
+    int32_t *gpu = which ? gpuB : gpuA;
+    int32_t pos = 0;
+    for (int32_t j = 0; j < n; ++j)
+      for (int32_t k = 0; k < c[j] && pos < n_gpus; ++k) gpu[pos++] = j;
+    while (pos < n_gpus) gpu[pos++] = -1;              /* idle */
+  }
+  for (int32_t j = 0; j < n; ++j) n1[j] = n2[j] = 0;
+  for (int32_t i = 0; i < n_gpus; ++i) {
+    uint32_t ctr[4] = {(uint32_t)(i / 128), p0, t, 3u}, w[4];
+    ones_ref_philox4x32_10(ctr, key, w);
+    int coin = (int)((w[(i % 128) / 32] >> (i % 32)) & 1u);
+    int32_t to_first = coin ? gpuA[i] : gpuB[i];
+    int32_t to_second = coin ? gpuB[i] : gpuA[i];
+    if (to_first >= 0) n1[to_first] += 1;
+    if (to_second >= 0) n2[to_second] += 1;
+  }
+  free(gpuA); free(gpuB);
+}
+
+/* GPUs a parent's gene stands for under the current job table (what clamp and lift of the
+ * repair make of it); an empty slot or a waiting job holds none */
+static int32_t parent_gpus(const slot_t *s, int32_t batch) {
+  int g = exponent_of(batch);
+  if (!s->active || g == WAIT) return 0;
+  g = imin(imax(g, s->lo), s->hi);
+  g = imax(g, imin(s->mu, s->hi));
+  return (int32_t)gpus_of(g, s->mu);
+}
+
 /* ------------------------------------------------------------ compose ------------ */
 /* Genome of pool slot p of generation t, before repair, read from the previous
  * generation through its survivor list.  Pool = K refreshed survivors, K parent pairs
@@ -338,6 +385,21 @@ static void compose(const ones_ref_ctx *c, const int32_t *prev, uint32_t t, int 
     candidate_draw(c, (uint32_t)p0, t, &ra, &rb, &unused);   /* both children share parents */
     const int32_t *A = prev + (size_t)c->sel[ra] * Jp;
     const int32_t *B = prev + (size_t)c->sel[rb] * Jp;
+    if (c->per_gpu) {
+      /* a child runs job j with the largest power-of-two GPU count among the GPUs it
+       * inherited for it, at the job's local batch; the repair does the rest */
+      int32_t cA[MAX_SLOTS], cB[MAX_SLOTS], n1[MAX_SLOTS], n2[MAX_SLOTS];
+      for (int j = 0; j < Jp; ++j) { cA[j] = parent_gpus(&c->tab[j], A[j]); cB[j] = parent_gpus(&c->tab[j], B[j]); }
+      uint64_t seed = ((uint64_t)c->key[1] << 32) | c->key[0];
+      ones_ref_gpu_crossover(seed, (uint32_t)p0, t, c->G, Jp, cA, cB, n1, n2);
+      for (int j = 0; j < Jp; ++j) {
+        int32_t n = side == 0 ? n1[j] : n2[j];
+        if (n == 0) { g[j] = WAIT; continue; }
+        int lg = 0;
+        while ((n >> (lg + 1)) != 0) ++lg;
+        g[j] = imin(c->tab[j].mu, c->tab[j].hi) + lg;
+      }
+    } else
     for (int j = 0; j < Jp; ++j) {
       int swap = gene_word(c, (uint32_t)p0, t, j) < c->T_x;
       int from_b = side == 0 ? swap : !swap;            /* the children are complementary */
@@ -470,6 +532,13 @@ int ones_ref_set_progress(ones_ref_ctx *c, const double *alpha, const double *be
     c->alpha[j] = alpha[j]; c->beta[j] = beta[j]; c->processed[j] = processed[j];
   }
   c->sampling = 1;
+  return ONES_REF_OK;
+}
+
+int ones_ref_set_crossover(ones_ref_ctx *c, int32_t mode) {
+  if (!c || (mode != 0 && mode != 1)) return ONES_REF_E_INVALID_ARG;
+  if (mode == 1 && c->G > 8192) return ONES_REF_E_BOUNDS;
+  c->per_gpu = mode;
   return ONES_REF_OK;
 }
 

@@ -34,6 +34,11 @@
  *                            transcription on random cases, a hand-worked example (the job
  *                            with the largest T_processed gives up its GPUs), equal times =
  *                            slot order, the admitted jobs form a prefix of the time order.
+ *   ones_ref_gpu_crossover / ones_ref_set_crossover(1) : every GPU's job goes to exactly one
+ *                            child (n1 + n2 = the parents' counts inside the cluster), equal
+ *                            parents give equal children, coin frequencies, a Python
+ *                            transcription with the coins recomputed from Philox, a hand-worked
+ *                            example; in the search: Eq. 4, children between their parents.
  *   scheduling quality against the paper's JCT numbers: parity unpinned (the paper's
  *                            trace, jobs and comparison schedulers do not exist here).
  */
@@ -98,6 +103,12 @@ int  ones_ref_set_progress(ones_ref_ctx *ctx, const double *alpha, const double 
  * order, each new job starts with the batch a waiting job resumes with while the capacity
  * lasts; the other jobs are admitted to what is left, then the fill runs as always. */
 int  ones_ref_set_new_jobs_first(ones_ref_ctx *ctx, int32_t on);
+/* Which positions the uniform crossover scans (Section 3.2.2): 0 (at first) the jobs, a coin
+ * per job with the configured rate; 1 the GPUs of the paper's encoding (Eq. 1), a fair coin per
+ * GPU, the parents laid out as the reorder operator leaves them (ones_ref_gpu_crossover); a
+ * child then runs each job on the largest power-of-two number of GPUs it inherited for it.
+ * Mode 1 needs n_gpus <= 8192 (ONES_REF_E_BOUNDS). */
+int  ones_ref_set_crossover(ones_ref_ctx *ctx, int32_t mode);
 /* The time every slot's job has executed (T_processed; n_slots finite entries >= 0), or NULL to
  * forget it.  While set, the generation that serves new jobs first admits the other jobs in
  * ascending order of that time (equal times: lower slot first) instead of the rotated order:
@@ -143,6 +154,10 @@ double ones_ref_gamma_draw(uint64_t seed, uint32_t j, uint32_t t, uint32_t which
 double ones_ref_sampled_remaining(uint64_t seed, uint32_t j, uint32_t t, double alpha, double beta,
                                   double processed, double *rho_out);
 void ones_ref_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]);
+/* GPUs per job each child of a pair inherits under the crossover over the GPUs (mode 1 of
+ * ones_ref_set_crossover): cA, cB, n1, n2 have n entries (GPU counts per job) */
+void ones_ref_gpu_crossover(uint64_t seed, uint32_t p0, uint32_t t, int32_t n_gpus, int32_t n,
+                            const int32_t *cA, const int32_t *cB, int32_t *n1, int32_t *n2);
 /* genes: n_slots int32 batch sizes (0 or a power of two), repaired in place with
  * rotation r in [0,Jp); fill_rounds_out (may be NULL) receives the number of fill rounds */
 int  ones_ref_repair_genome(const ones_ref_config *cfg, const ones_ref_jobs *jobs,

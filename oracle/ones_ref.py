@@ -80,6 +80,10 @@ def lib():
         L.ones_ref_update_limits.argtypes = [C.c_int32, C.POINTER(_LimitInputs), C.c_double, C.c_void_p]
         L.ones_ref_set_new_jobs_first.argtypes = [C.c_void_p, C.c_int32]
         L.ones_ref_set_processed_time.argtypes = [C.c_void_p, C.c_void_p]
+        L.ones_ref_set_crossover.argtypes = [C.c_void_p, C.c_int32]
+        L.ones_ref_gpu_crossover.argtypes = [C.c_uint64, C.c_uint32, C.c_uint32, C.c_int32, C.c_int32,
+                                             C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.ones_ref_gpu_crossover.restype = None
         L.ones_ref_repair_arrivals.argtypes = [C.POINTER(_Config), C.POINTER(_Jobs), C.c_void_p, C.c_uint32,
                                                C.c_void_p, C.c_void_p, C.POINTER(C.c_int32)]
         L.ones_ref_placement.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
@@ -188,6 +192,18 @@ def repair_arrivals(n_gpus, jobs, genes, r, arrived, t_processed=None, populatio
     return g, rounds.value
 
 
+def gpu_crossover(seed, p0, t, n_gpus, c_a, c_b):
+    """GPUs per job that each child inherits when the crossover scans the GPUs."""
+    a = np.ascontiguousarray(c_a, np.int32)
+    b = np.ascontiguousarray(c_b, np.int32)
+    if len(a) != len(b):
+        raise ValueError("one GPU count per job in both parents")
+    n1, n2 = np.zeros(len(a), np.int32), np.zeros(len(a), np.int32)
+    lib().ones_ref_gpu_crossover(int(seed), int(p0), int(t), int(n_gpus), len(a), a.ctypes.data, b.ctypes.data,
+                                 n1.ctypes.data, n2.ctypes.data)
+    return n1, n2
+
+
 def score_genome(n_gpus, jobs, genes):
     cfg = _cfg(n_gpus, len(genes), 4, 0, 0.0, 0.0)
     js, keep = _jobs(jobs)
@@ -248,6 +264,9 @@ class RefSearch:
 
     def set_new_jobs_first(self, on=True):
         _check(lib().ones_ref_set_new_jobs_first(self._h, int(bool(on))))
+
+    def set_crossover(self, per_gpu=False):
+        _check(lib().ones_ref_set_crossover(self._h, int(bool(per_gpu))))
 
     def set_processed_time(self, t_processed=None):
         if t_processed is None:

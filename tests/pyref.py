@@ -253,3 +253,25 @@ def sampled_remaining(seed, j, t, alpha, beta, processed, cap=1e100):
     rho = ga / (ga + gb)
     ratio = min(1.0 / rho - 1.0, cap)
     return min(processed * ratio, cap), rho
+
+
+def gpu_crossover(seed, p0, t, G, c_a, c_b):
+    """Crossover that scans the GPUs (Section 3.2.2 on the encoding of Eq. 1), by intervals:
+    job j of a parent holds the GPUs [start_j, start_j + c_j) below G.  Returns the GPU counts
+    the two children inherit per job."""
+    key = (seed & M32, seed >> 32)
+    coin = []
+    for block in range(-(-G // 128)):
+        w = philox4x32_10((block, p0, t, 3), key)
+        coin += [(w[b // 32] >> (b % 32)) & 1 for b in range(128)]
+    coin = coin[:G]
+    n1, n2 = [0] * len(c_a), [0] * len(c_a)
+    for counts, heads_to in ((c_a, n1), (c_b, n2)):
+        tails_to = n2 if heads_to is n1 else n1
+        start = 0
+        for j, c in enumerate(counts):
+            mine = coin[min(start, G):min(start + int(c), G)]
+            heads_to[j] += sum(mine)
+            tails_to[j] += len(mine) - sum(mine)
+            start += int(c)
+    return n1, n2
