@@ -24,7 +24,7 @@ HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published peak
 
 # HBM bytes per evolve launch on the stress workload from rocprofv3 --pmc FETCH_SIZE and
 # WRITE_SIZE (see profiles/), valid only for the kernel source with this hash.
-MEASURED_TRAFFIC = {"source_sha256": "7fda7fb629d974bda34646af18812066cb73e4df706c8d36937a886e25f9a460", "bytes_per_launch": 802741924}
+MEASURED_TRAFFIC = {"source_sha256": "6dac99c578ba0c25ce4941ca0c9572a49ed6c275535907a78eea900516888205", "bytes_per_launch": 802763903}
 
 
 def evolve_source_hash() -> str:
@@ -126,6 +126,9 @@ def main() -> int:
     ap.add_argument("--sampled", action="store_true",
                     help="probability sampling of the remaining work (Alg. 1): every generation draws it anew "
                          "and scores the survivors again; not the headline configuration")
+    ap.add_argument("--crossover", default="jobs", choices=["jobs", "gpus"],
+                    help="positions the uniform crossover scans: the jobs (headline configuration) or the GPUs of "
+                         "the paper's encoding (Eq. 1)")
     ap.add_argument("--policies", action="store_true",
                     help="online workload only: batch-size limits from the policies of Section 3.3.2 "
                          "(ones_update_limits, timed as a leg of its own) and new jobs served first")
@@ -152,6 +155,7 @@ def main() -> int:
     search = ones.Search(cl, jobs, device="cuda:0")       # initial population, not timed
     if args.sampled:
         search.set_progress(*W.progress(cl.n_slots, seed=cl.seed))
+    search.set_crossover(per_gpu=args.crossover == "gpus")
     search.generation(args.warmup)
     search.synchronize()
     torch.cuda.synchronize()
@@ -176,7 +180,8 @@ def main() -> int:
         alg_bytes = (cl.population * 3 // 4) * cl.n_slots * 8 + (cl.population // 4) * cl.n_slots * 4 + cl.population * 8
     achieved = alg_bytes / (evolve_ms * 1e-3) / 1e9
     traffic = None
-    if MEASURED_TRAFFIC["source_sha256"] == evolve_source_hash() and args.workload == "stress" and not args.sampled:
+    if MEASURED_TRAFFIC["source_sha256"] == evolve_source_hash() and args.workload == "stress" and not args.sampled \
+            and args.crossover == "jobs":
         traffic = MEASURED_TRAFFIC["bytes_per_launch"]
 
     out = {
@@ -191,7 +196,8 @@ def main() -> int:
                    "slots_padded": jp, "population": cl.population, "survivors": cl.population // 4,
                    "mutation_rate": cl.mutation_rate, "crossover_rate": cl.crossover_rate,
                    "seed": cl.seed, "jobs_sha256": jobs.sha256()[:16],
-                   "remaining_work": "sampled per generation" if args.sampled else "fixed"},
+                   "remaining_work": "sampled per generation" if args.sampled else "fixed",
+                   "crossover": "over " + args.crossover},
         "generations_per_s": args.steps / dt,
         "best_fitness": best_fit,
         "kernels": {"evolve_ms": evolve_ms, "select_ms": select_ms},

@@ -118,6 +118,24 @@ int ones_set_progress(ones_ctx *ctx, const double *alpha, const double *beta,
  * left; then the fill runs as always.  Later generations treat those jobs like any other. */
 int ones_set_new_jobs_first(ones_ctx *ctx, int32_t on);
 
+/* Which positions the uniform crossover scans (Section 3.2.2).
+ *   ONES_CROSSOVER_JOBS (at first): the jobs; per job the two children swap their parents' batch
+ *     sizes with the configured crossover_rate.
+ *   ONES_CROSSOVER_GPUS: the GPUs of the paper's encoding (Eq. 1, a schedule maps every GPU to
+ *     the job whose worker it hosts).  Both parents are laid out as the reorder operator leaves
+ *     them (jobs in slot order on consecutive GPUs); every GPU has a fair coin (crossover_rate is
+ *     not used): heads, the first parent's job on that GPU goes to the first child and the
+ *     second parent's to the second child; tails, the other way round.  A child runs each job on
+ *     the largest power-of-two number of GPUs it inherited for it, at the job's local batch,
+ *     pulled inside the job's window; then the repair runs as always.  Coin of GPU i of the pair
+ *     whose first child is pool slot p0 in generation t: bit i mod 32 of word (i mod 128) div 32
+ *     of the Philox4x32-10 block with counter (i div 128, p0, t, 3).  Needs n_gpus <= 8192.
+ * Takes effect with the next generation.  Errors: ONES_E_INVALID_ARG (unknown mode),
+ * ONES_E_BOUNDS (ONES_CROSSOVER_GPUS on a larger cluster). */
+#define ONES_CROSSOVER_JOBS 0
+#define ONES_CROSSOVER_GPUS 1
+int ones_set_crossover(ones_ctx *ctx, int32_t mode);
+
 /* The time the job of every slot has executed (T_processed; HOST array of n_slots finite
  * entries in [0, 1e100], copied; empty slots' entries are ignored), or NULL to forget the
  * times.  While they are known, the generation that serves new jobs first admits the other

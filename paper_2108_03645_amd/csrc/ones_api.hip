@@ -170,6 +170,7 @@ struct ones_ctx {
   bool no_schedule;           // ... by ones_set_jobs: the winner is not a schedule under the new table
   bool new_jobs_first;        // option: the generation after ones_set_jobs serves the arrived jobs first
   bool sampling;              // remaining work drawn per generation (Alg. 1) instead of the table's
+  bool per_gpu;               // uniform crossover over the GPUs instead of the jobs (ones_set_crossover)
   bool has_times;             // executed times known (ones_set_processed_time): their ranks are on the device
   BucketPlan bp;              // nb == 0: pool small enough for the single-chunk sort
   int bucket_phase;           // which counter set the next bucketed generation fills
@@ -255,6 +256,8 @@ int run_generation(ones_ctx *c, uint32_t t) {
   const bool sampled = t != 0 && c->sampling;
   a.rescore = same_table && sampled ? 1u : 0u;
   a.new_first = c->new_jobs_first && c->no_schedule ? 1u : 0u;   // the table's "arrived" marks are fresh
+  a.per_gpu = c->per_gpu ? 1u : 0u;
+  a.stash_stride = 0;                                            // the launcher sets it
   a.time_rank = c->has_times ? c->at<uint32_t>(c->L.time_rank) : nullptr;
   // quantile buckets: only when the survivors reappear with the scores they had
   const bool buckets = same_table && !sampled && c->bp.nb != 0;
@@ -355,6 +358,7 @@ int ones_init(ones_ctx **out, const ones_config *cfg, const ones_jobs *jobs, voi
   c->new_jobs_first = false;
   c->sampling = false;
   c->has_times = false;
+  c->per_gpu = false;
   c->bp = bucket_plan(c->P);
   c->bucket_phase = 0;
   c->ids = h.id;
@@ -434,6 +438,13 @@ int ones_set_progress(ones_ctx *c, const double *alpha, const double *beta, cons
 int ones_set_new_jobs_first(ones_ctx *c, int32_t on) {
   if (!c) return ONES_E_INVALID_ARG;
   c->new_jobs_first = on != 0;
+  return ONES_OK;
+}
+
+int ones_set_crossover(ones_ctx *c, int32_t mode) {
+  if (!c || (mode != ONES_CROSSOVER_JOBS && mode != ONES_CROSSOVER_GPUS)) return ONES_E_INVALID_ARG;
+  if (mode == ONES_CROSSOVER_GPUS && c->G > static_cast<uint32_t>(kMaxCoinGpus)) return ONES_E_BOUNDS;
+  c->per_gpu = mode == ONES_CROSSOVER_GPUS;
   return ONES_OK;
 }
 

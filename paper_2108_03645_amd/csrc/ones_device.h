@@ -10,6 +10,7 @@ namespace ones {
 constexpr int kLanes = 64;          // one candidate schedule per wave64, job columns across lanes
 constexpr int kMaxRows = 32;        // 2048 job slots / 64 columns
 constexpr int kMaxTermEntries = 22; // waiting + GPU counts 2^0 .. 2^20
+constexpr int kMaxCoinGpus = 8192;  // crossover over the GPUs: one Philox block of 128 coins per lane
 #ifndef ONES_SORT_CHUNK
 #define ONES_SORT_CHUNK 4096
 #endif
@@ -110,6 +111,8 @@ struct EvolveArgs {
   const uint32_t *time_rank;  // [Jp] with new_first: position of every slot in ascending order of executed
                               //      time, the order the other jobs are admitted in; null = visiting order
   uint32_t       rescore;     // the survivors' scores are stale (remaining work redrawn): score them again
+  uint32_t       per_gpu;     // the uniform crossover scans the GPUs (Eq. 1) instead of the jobs; needs G <= kMaxCoinGpus
+  uint32_t       stash_stride; // set by the launcher: bytes of LDS scratch per wave
   uint32_t       term_lds;    // set by the launcher: entries per job of the term table in LDS, 0 = none
   BucketArgs     bk;
 };

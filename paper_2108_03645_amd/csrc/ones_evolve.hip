@@ -99,7 +99,8 @@ struct Smem {
   double   *abl, *cc, *d, *Y;   // [Jp] model parameters (when the term table does not fit)
   double   *terms;   // [E][R][64] T_j c_j of job (row, lane) at GPU-count code E-1-e, or null
   uint64_t *split;   // [kMaxBuckets] bucket splitters, then [1] the K-th survivor's score bits
-  uint8_t  *stash;   // [waves][Jp] second crossover child while the first is repaired
+  uint8_t  *stash;   // [waves][stash_stride] second crossover child while the first is repaired; before
+                     //                       that, the coins of a crossover over the GPUs
   uint32_t *free_in_group; // [groups] free rows in each group of kRowGroupWords bitmap words
   uint32_t *rows;          // [4 * kRound] rows of the slots this workgroup fills in the current round
   uint32_t *next_item;     // [1] the next work item of the round that no wave has taken yet
@@ -112,12 +113,17 @@ inline uint32_t row_groups(uint32_t rows) {
   return ((rows + 31) / 32 + kRowGroupWords - 1) / kRowGroupWords;
 }
 
-inline size_t smem_bytes(uint32_t Jp, int waves, uint32_t E, uint32_t rows) {
-  return static_cast<size_t>(Jp) * (8 + 4 + (E ? 8 * E : 32)) + (kMaxBuckets + 1) * 8 +
-         static_cast<size_t>(waves) * Jp + static_cast<size_t>(row_groups(rows)) * 4 + 4 * kRound * 4 + 16;
+// LDS scratch per wave: a byte per job, or the 256 coin words with their running counts
+inline uint32_t stash_stride(uint32_t Jp, bool per_gpu) {
+  return per_gpu ? std::max<uint32_t>(Jp, kMaxCoinGpus / 32 * 8) : Jp;
 }
 
-__device__ __forceinline__ Smem carve(unsigned char *base, uint32_t Jp, uint32_t E, uint32_t waves) {
+inline size_t smem_bytes(uint32_t Jp, int waves, uint32_t E, uint32_t rows, uint32_t stride) {
+  return static_cast<size_t>(Jp) * (8 + 4 + (E ? 8 * E : 32)) + (kMaxBuckets + 1) * 8 +
+         static_cast<size_t>(waves) * stride + static_cast<size_t>(row_groups(rows)) * 4 + 4 * kRound * 4 + 16;
+}
+
+__device__ __forceinline__ Smem carve(unsigned char *base, uint32_t Jp, uint32_t E, uint32_t waves, uint32_t stride) {
   Smem s;
   s.abl = reinterpret_cast<double *>(base);
   s.cc = s.abl + Jp;
@@ -128,7 +134,7 @@ __device__ __forceinline__ Smem carve(unsigned char *base, uint32_t Jp, uint32_t
   s.cc2 = reinterpret_cast<uint2 *>(s.split + kMaxBuckets + 1);
   s.info = reinterpret_cast<uint32_t *>(s.cc2 + Jp);
   s.stash = reinterpret_cast<uint8_t *>(s.info + Jp);
-  s.rows = reinterpret_cast<uint32_t *>(s.stash + static_cast<size_t>(waves) * Jp);   // Jp is a multiple of 64
+  s.rows = reinterpret_cast<uint32_t *>(s.stash + static_cast<size_t>(waves) * stride);   // a multiple of 64
   s.next_item = s.rows + 4 * kRound;
   s.free_in_group = s.next_item + 4;
   return s;
@@ -493,6 +499,59 @@ __device__ __forceinline__ void load_genes(const int32_t *row, int lane, uint32_
   for (int i = 0; i < R; ++i) B[i] = static_cast<uint32_t>(row[lane + kLanes * i]);
 }
 
+// Uniform crossover over the GPUs (Section 3.2.2 on the encoding of Eq. 1).  Both parents are
+// laid out as the reorder operator leaves them: the jobs in slot order on consecutive GPUs, cA
+// resp. cB GPUs each, GPUs beyond the cluster do not exist.  Every GPU has a fair coin: heads,
+// the first parent's job on it goes to the first child and the second parent's to the second
+// child; tails, the other way round.  A child then runs each job on the largest power of two
+// among the GPUs it inherited for it, inside the job's window.  On return cA holds the first
+// child and cB the second.
+// Coin of GPU i: bit i mod 32 of word (i mod 128) div 32 of Philox block (i div 128, p0, t, 3);
+// lane l draws the coins of GPUs 128 l .. 128 l + 127.  coins: this wave's kMaxCoinGpus / 32
+// entries of LDS, each a coin word and, above it, the number of heads on the GPUs before it.
+template <int R>
+__device__ __forceinline__ void crossover_over_gpus(const EvolveArgs &a, const Smem &s, uint64_t *coins, uint32_t p0,
+                                                    int lane, uint32_t (&cA)[R], uint32_t (&cB)[R]) {
+  {
+    const Words w = philox4x32_10(static_cast<uint32_t>(lane), p0, a.t, 3u, a.key0, a.key1);
+    const uint32_t heads = __popc(w.w[0]) + __popc(w.w[1]) + __popc(w.w[2]) + __popc(w.w[3]);
+    uint32_t before = wave_inclusive_scan(heads) - heads;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      coins[4 * lane + k] = (static_cast<uint64_t>(before) << 32) | w.w[k];
+      before += __popc(w.w[k]);
+    }
+  }
+  // the lanes read each other's entries: one wave, whose LDS operations complete in order
+  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+  phase_fence();
+  // heads among the GPUs below x, x <= G <= kMaxCoinGpus
+  auto heads_below = [&](uint32_t x) {
+    const uint32_t word = min(x >> 5, static_cast<uint32_t>(kMaxCoinGpus / 32 - 1));
+    const uint32_t bits = x - (word << 5);                       // 0 .. 32
+    const uint64_t e = coins[word];
+    const uint32_t mask = bits >= 32u ? 0xFFFFFFFFu : (1u << bits) - 1u;
+    return static_cast<uint32_t>(e >> 32) + static_cast<uint32_t>(__popc(static_cast<uint32_t>(e) & mask));
+  };
+  uint32_t carry_a = 0, carry_b = 0;                             // GPUs of the rows above (wave-uniform)
+#pragma unroll
+  for (int i = 0; i < R; ++i) {
+    const uint32_t incl_a = wave_inclusive_scan(cA[i]), incl_b = wave_inclusive_scan(cB[i]);
+    const uint32_t end_a = min(carry_a + incl_a, a.G), start_a = min(carry_a + incl_a - cA[i], a.G);
+    const uint32_t end_b = min(carry_b + incl_b, a.G), start_b = min(carry_b + incl_b - cB[i], a.G);
+    carry_a += __builtin_amdgcn_readlane(incl_a, kLanes - 1);
+    carry_b += __builtin_amdgcn_readlane(incl_b, kLanes - 1);
+    const uint32_t heads_a = heads_below(end_a) - heads_below(start_a);
+    const uint32_t heads_b = heads_below(end_b) - heads_below(start_b);
+    const uint32_t n1 = heads_a + ((end_b - start_b) - heads_b);
+    const uint32_t n2 = ((end_a - start_a) - heads_a) + heads_b;
+    const uint2 k = s.cc2[lane + kLanes * i];
+    cA[i] = n1 ? min(max(0x80000000u >> __clz(static_cast<int>(n1)), k.x), k.y) : 0u;
+    cB[i] = n2 ? min(max(0x80000000u >> __clz(static_cast<int>(n2)), k.x), k.y) : 0u;
+    fence_every(i, 4);
+  }
+}
+
 // Redraw of a gene from k in [0, n): 0 = the job is pre-empted, else 2^(lo + k - 1).
 __device__ __forceinline__ uint32_t batch_from_draw(uint32_t k, uint32_t info) {
   const uint32_t b = (info_active(info) << (info_lo(info) + k)) >> 1;   // k = 0 or empty slot -> 0
@@ -509,7 +568,7 @@ template <int R> struct Shape { static constexpr int kWaves = R > 16 ? ONES_WAVE
 template <int R>
 __global__ __launch_bounds__(Shape<R>::kWaves *kLanes) void init_kernel(EvolveArgs a) {
   extern __shared__ __align__(16) unsigned char smem_raw[];
-  const Smem s = carve(smem_raw, a.Jp, a.term_lds, Shape<R>::kWaves);
+  const Smem s = carve(smem_raw, a.Jp, a.term_lds, Shape<R>::kWaves, a.stash_stride);
   stage_table<R>(a.tab, a.bk, s, a.Jp, a.term_lds);
   __syncthreads();
   const int lane0 = threadIdx.x & (kLanes - 1);
@@ -535,17 +594,18 @@ __global__ __launch_bounds__(Shape<R>::kWaves *kLanes) void init_kernel(EvolveAr
 // survivors to refresh (or, when only the remaining work changed, to score again).  kSameTable: the job table has not changed since the previous
 // generation was repaired and scored, so a survivor is a fixed point of the repair with the
 // same score: it stays in its row untouched, and stored genes need no clamp.
-template <int R, bool kSameTable>
+// kOverGpus: the uniform crossover scans the GPUs instead of the jobs.
+template <int R, bool kSameTable, bool kOverGpus>
 __global__ __launch_bounds__(Shape<R>::kWaves *kLanes) void evolve_kernel(EvolveArgs a) {
   extern __shared__ __align__(16) unsigned char smem_raw[];
-  const Smem s = carve(smem_raw, a.Jp, a.term_lds, Shape<R>::kWaves);
+  const Smem s = carve(smem_raw, a.Jp, a.term_lds, Shape<R>::kWaves, a.stash_stride);
   const int lane0 = threadIdx.x & (kLanes - 1);
   const IndexLoads index_loads = index_free_rows_begin(a, lane0);
   stage_table<R>(a.tab, a.bk, s, a.Jp, a.term_lds);
   index_free_rows_end(a, s, index_loads, lane0);
   const uint32_t wave_in_block = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const uint32_t K = a.K;
-  uint8_t *stash = s.stash + static_cast<size_t>(wave_in_block) * a.Jp;
+  uint8_t *stash = s.stash + static_cast<size_t>(wave_in_block) * a.stash_stride;
   // This workgroup's share of the ranks 0..K-1: for each rank a pair, a mutant and, after a
   // table change, a survivor.  Slot K + q of the new pool takes the q-th free row and the
   // refreshed survivor of rank e the (3K + e)-th, so every share needs three runs of
@@ -582,6 +642,18 @@ __global__ __launch_bounds__(Shape<R>::kWaves *kLanes) void evolve_kernel(Evolve
       const uint32_t p0 = K + 2 * item;
       const Draw d0 = candidate_draw(a, p0);
       const Draw d1 = candidate_draw(a, p0 + 1);
+      if (kOverGpus) {
+        uint32_t B[R];
+        load_genes<R>(a.genes + static_cast<size_t>(a.parent_row[d0.ra]) * a.Jp, lane, c);
+        load_genes<R>(a.genes + static_cast<size_t>(a.parent_row[d0.rb]) * a.Jp, lane, B);
+        gpus_from_batches<R, kSameTable>(s, lane, c);
+        gpus_from_batches<R, kSameTable>(s, lane, B);
+        phase_fence();
+        crossover_over_gpus<R>(a, s, reinterpret_cast<uint64_t *>(stash), p0, lane, c, B);
+        phase_fence();                                   // the coins are no longer needed: their place holds the second child
+#pragma unroll
+        for (int i = 0; i < R; ++i) stash[lane + kLanes * i] = static_cast<uint8_t>(32 - __clz(static_cast<int>(B[i])));
+      } else {
       uint32_t swap = 0;
       {
         uint32_t w[R];
@@ -604,6 +676,7 @@ __global__ __launch_bounds__(Shape<R>::kWaves *kLanes) void evolve_kernel(Evolve
           c[i] = sw ? B[i] : c[i];
           stash[lane + kLanes * i] = static_cast<uint8_t>(32 - __clz(static_cast<int>(second)));
         }
+      }
       }
       phase_fence();
       const double f0 = finish<R>(a, s, row_at(s, 2 * idx, a), d0.r, c, lane, new_first);
@@ -662,8 +735,10 @@ hipError_t launch_persistent(Kernel k, EvolveArgs a, int waves, uint32_t items, 
                              hipStream_t s) {
   // the term table goes to LDS when it fits beside the rest
   const uint32_t rows = a.P + a.K;
-  a.term_lds = (a.tab.term_E != 0 && smem_bytes(a.Jp, waves, a.tab.term_E, rows) <= kLdsBudget) ? a.tab.term_E : 0u;
-  const size_t lds = smem_bytes(a.Jp, waves, a.term_lds, rows);
+  a.stash_stride = stash_stride(a.Jp, a.per_gpu != 0);
+  a.term_lds = (a.tab.term_E != 0 && smem_bytes(a.Jp, waves, a.tab.term_E, rows, a.stash_stride) <= kLdsBudget)
+                   ? a.tab.term_E : 0u;
+  const size_t lds = smem_bytes(a.Jp, waves, a.term_lds, rows, a.stash_stride);
   // as many workgroups as can be resident (LDS- and wave-limited), at most one wave per item
   const size_t per_cu = std::max<size_t>(1, std::min<size_t>(kLdsBudget / lds, 32 / waves));
   const uint32_t blocks = std::max<uint32_t>(
@@ -679,9 +754,12 @@ template <int R>
 hipError_t launch_rows(const EvolveArgs &a, bool same_table, int n_cus, hipStream_t s) {
   constexpr int kWaves = Shape<R>::kWaves;
   if (a.t == 0) return launch_persistent(init_kernel<R>, a, kWaves, a.P, a.P, n_cus, s);
-  if (same_table)
-    return launch_persistent(evolve_kernel<R, true>, a, kWaves, (a.rescore ? 3 : 2) * a.K, a.K, n_cus, s);   // a share of the ranks each
-  return launch_persistent(evolve_kernel<R, false>, a, kWaves, 3 * a.K, a.K, n_cus, s);
+  const uint32_t items = (!same_table || a.rescore ? 3 : 2) * a.K;       // a share of the ranks each
+  if (a.per_gpu)
+    return same_table ? launch_persistent(evolve_kernel<R, true, true>, a, kWaves, items, a.K, n_cus, s)
+                      : launch_persistent(evolve_kernel<R, false, true>, a, kWaves, items, a.K, n_cus, s);
+  return same_table ? launch_persistent(evolve_kernel<R, true, false>, a, kWaves, items, a.K, n_cus, s)
+                    : launch_persistent(evolve_kernel<R, false, false>, a, kWaves, items, a.K, n_cus, s);
 }
 
 template <int... Rs>

@@ -35,7 +35,7 @@ _JOB_DTYPES = {"job_id": np.int64, "active": np.uint8, "bmin": np.int32, "bmax":
                "remaining": np.float64}
 
 EXPORTS = ["ones_workspace_bytes", "ones_init", "ones_set_jobs", "ones_generation", "ones_best",
-           "ones_export", "ones_placement", "ones_update_limits", "ones_set_new_jobs_first", "ones_set_processed_time",
+           "ones_export", "ones_placement", "ones_update_limits", "ones_set_new_jobs_first", "ones_set_processed_time", "ones_set_crossover",
            "ones_set_progress", "ones_export_remaining", "ones_padded_jobs",
            "ones_profile_enable", "ones_profile_read",
            "ones_destroy", "ones_strerror"]
@@ -89,6 +89,7 @@ def load():
     L.ones_placement.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
     L.ones_set_new_jobs_first.argtypes = [C.c_void_p, C.c_int32]
     L.ones_set_processed_time.argtypes = [C.c_void_p, C.c_void_p]
+    L.ones_set_crossover.argtypes = [C.c_void_p, C.c_int32]
     L.ones_update_limits.argtypes = [C.c_int32, C.POINTER(ones_limit_inputs), C.c_double, C.c_void_p]
     L.ones_set_progress.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
     L.ones_export_remaining.argtypes = [C.c_void_p, C.c_void_p]
@@ -182,6 +183,9 @@ class Search:
 
     def set_new_jobs_first(self, on=True):
         _check(load().ones_set_new_jobs_first(self._h, int(bool(on))))
+
+    def set_crossover(self, per_gpu=False):
+        _check(load().ones_set_crossover(self._h, 1 if per_gpu else 0))
 
     def set_processed_time(self, t_processed=None):
         if t_processed is None:

@@ -548,3 +548,71 @@ def test_set_processed_time_rejects_bad_arguments(ones, ref):
     gpu.generation(2); cpu.generation(2)
     assert_same_state(gpu, cpu, "after rejected times")
     gpu.close(); cpu.close()
+
+
+# ---- uniform crossover over the GPUs of the paper's encoding (Section 3.2.2, Eq. 1) ----
+
+@pytest.mark.parametrize("n_slots,n_gpus,pop,seed", [(1, 1, 8, 7), (8, 3, 64, 0), (40, 64, 1024, 1), (333, 700, 512, 2),
+                                                     (700, 129, 256, 8), (64, 127, 8192, 6), (100, 8191, 128, 5),
+                                                     (2048, 4096, 256, 3), (2048, 8192, 64, 4), (1500, 33, 64, 9)])
+def test_crossover_over_gpus_matches_the_oracle(ones, ref, n_slots, n_gpus, pop, seed):
+    """Ordinary generations, a table change (parents that overfill the cluster under the new
+    table), sampled remaining work, and back to the crossover over the jobs."""
+    rng = np.random.default_rng(seed)
+    cl = cluster(n_gpus, n_slots, pop, seed=seed)
+    jobs = random_jobs(rng, n_slots)
+    say(f"[crossover over GPUs] G={n_gpus} slots={n_slots} P={pop} seed={seed}")
+    gpu, cpu = ones.Search(cl, jobs), ref.RefSearch(cl, jobs)
+
+    def both(f, where):
+        f(gpu); f(cpu)
+        assert_same_state(gpu, cpu, where)
+
+    both(lambda s: s.set_crossover(per_gpu=True), "mode set")
+    for gen in range(3):
+        both(lambda s: s.generation(1), f"generation {gen + 1}")
+    j2 = random_jobs(np.random.default_rng(seed + 100), n_slots)      # other windows and per-GPU batches
+    j2.job_id[: n_slots // 2] = jobs.job_id[: n_slots // 2]           # half of the jobs stay
+    both(lambda s: s.set_jobs(j2), "table change")
+    both(lambda s: s.generation(1), "generation after the table change")
+    both(lambda s: s.generation(2), "two more")
+    alpha, beta, proc = W.progress(n_slots, seed=seed)
+    both(lambda s: s.set_progress(alpha, beta, proc), "sampling on")
+    both(lambda s: s.generation(2), "sampled generations")
+    both(lambda s: s.set_progress(), "sampling off")
+    both(lambda s: s.generation(1), "fixed remaining work again")
+    both(lambda s: s.set_crossover(per_gpu=False), "back to the jobs")
+    both(lambda s: s.generation(2), "crossover over the jobs again")
+    gpu.close(); cpu.close()
+
+
+def test_crossover_over_gpus_needs_a_small_enough_cluster(ones, ref):
+    cl = cluster(8193, 16, 64, seed=1)
+    jobs = random_jobs(np.random.default_rng(1), 16)
+    gpu, cpu = ones.Search(cl, jobs), ref.RefSearch(cl, jobs)
+    with pytest.raises(ones.OnesError) as g:
+        gpu.set_crossover(per_gpu=True)
+    with pytest.raises(ref.RefError) as c:
+        cpu.set_crossover(per_gpu=True)
+    assert g.value.code == c.value.code == -3
+    assert ones.load().ones_set_crossover(gpu._h, 2) == -1
+    gpu.generation(1); cpu.generation(1)
+    assert_same_state(gpu, cpu, "after the rejected mode")
+    gpu.close(); cpu.close()
+
+
+def test_full_size_stress_with_the_crossover_over_gpus(ones, ref):
+    """The benchmark's launch configuration (2048 jobs, 4096 GPUs, pool 65536) in this mode."""
+    import os
+    cl, jobs = W.stress()
+    say(f"[parity] stress full size, crossover over GPUs: P={cl.population}")
+    ref.set_threads(min(16, os.cpu_count() or 1))
+    try:
+        gpu, cpu = ones.Search(cl, jobs), ref.RefSearch(cl, jobs)
+        for s in (gpu, cpu):
+            s.set_crossover(per_gpu=True)
+            s.generation(2)
+        assert_same_state(gpu, cpu, "stress, crossover over GPUs, generation 2")
+        gpu.close(); cpu.close()
+    finally:
+        ref.set_threads(1)
