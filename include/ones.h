@@ -49,7 +49,8 @@ enum {
   ONES_E_NONFINITE = -4,           /* NaN or infinity in a, c, d or remaining            */
   ONES_E_WORKSPACE_TOO_SMALL = -5, /* workspace_bytes < ones_workspace_bytes(cfg), or
                                       the workspace pointer is not 256-byte aligned      */
-  ONES_E_HIP = -6                  /* a HIP call failed; ones_strerror names it          */
+  ONES_E_HIP = -6                  /* a HIP call failed, or host memory ran out;
+                                      ones_strerror says which (per thread)               */
 };
 
 typedef struct ones_ctx ones_ctx;  /* opaque, host side; owns no device memory */
@@ -84,7 +85,10 @@ size_t ones_workspace_bytes(const ones_config *cfg);
  * P random genomes, each gene uniform over {waiting, bmin..bmax}, repaired, scored and
  * ranked.  d_workspace: DEVICE pointer, 256-byte aligned, workspace_bytes long.
  * hip_stream: a hipStream_t (NULL = the default stream).  Synchronises the stream
- * before returning.  *out is written only on success. */
+ * before returning.  *out is written only on success.  Besides the context the library
+ * allocates one pinned host buffer (a few bytes per slot and per GPU) through which every
+ * later host transfer goes in a single copy; ones_destroy frees both.  A context is used by
+ * one thread at a time. */
 int ones_init(ones_ctx **out, const ones_config *cfg, const ones_jobs *jobs,
               void *d_workspace, size_t workspace_bytes, void *hip_stream);
 

@@ -7,6 +7,7 @@
 #include <cmath>
 #include <cstdio>
 #include <cstring>
+#include <memory>
 #include <new>
 #include <vector>
 
@@ -25,6 +26,18 @@ int hip_fail(hipError_t e, const char *what) {
     hipError_t e__ = (expr);                                  \
     if (e__ != hipSuccess) return hip_fail(e__, #expr);       \
   } while (0)
+
+template <typename F>
+int guarded(F &&body) noexcept {
+  try {
+    return body();
+  } catch (const std::bad_alloc &) {
+    snprintf(g_hip_msg, sizeof(g_hip_msg), "out of host memory");
+  } catch (...) {
+    snprintf(g_hip_msg, sizeof(g_hip_msg), "unexpected C++ exception");
+  }
+  return ONES_E_HIP;
+}
 
 size_t align_up(size_t v) { return (v + 255) & ~static_cast<size_t>(255); }
 
@@ -89,6 +102,17 @@ Layout make_layout(uint32_t P, uint32_t Jp, uint32_t G) {
   L.place_slot = take(static_cast<size_t>(G) * 4); L.place_batch = take(static_cast<size_t>(G) * 4);
   L.total = off;
   return L;
+}
+
+// Host transfers go through one pinned staging buffer, a single copy per call: the arrays that
+// travel together lie next to each other in the workspace (every size below is a multiple of the
+// 256-byte alignment except the last of a group).
+size_t stage_bytes(const Layout &L, uint32_t Jp, uint32_t G) {
+  const size_t table = L.rY + static_cast<size_t>(Jp) * 8 - L.rawinfo;        // rawinfo, changed, a, c, d, Y
+  const size_t progress = L.processed + static_cast<size_t>(Jp) * 8 - L.alpha; // alpha, beta, processed
+  const size_t best = L.best_fit + 8 - L.best_batch;                           // batch, gpus, fitness
+  const size_t place = L.place_batch + static_cast<size_t>(G) * 4 - L.place_slot;
+  return std::max({table, progress, best, place, static_cast<size_t>(Jp) * 4});
 }
 
 int check_config(const ones_config *cfg) {
@@ -164,6 +188,7 @@ struct ones_ctx {
   uint32_t T_mut, T_x;
   hipStream_t stream;
   char *ws;
+  char *stage;                // pinned host staging buffer (stage_bytes), free between calls
   Layout L;
   int cur;                    // which row_of array describes the current generation
   bool table_changed;         // job table replaced since the current generation was computed
@@ -197,23 +222,26 @@ namespace {
 
 int upload_table(ones_ctx *c, const HostJobs &h, const std::vector<uint32_t> *changed) {
   const size_t n4 = static_cast<size_t>(c->Jp) * 4, n8 = static_cast<size_t>(c->Jp) * 8;
-  HIP_TRY(hipMemcpyAsync(c->ws + c->L.rawinfo, h.rawinfo.data(), n4, hipMemcpyHostToDevice, c->stream));
-  HIP_TRY(hipMemcpyAsync(c->ws + c->L.ra, h.a.data(), n8, hipMemcpyHostToDevice, c->stream));
-  HIP_TRY(hipMemcpyAsync(c->ws + c->L.rc, h.c.data(), n8, hipMemcpyHostToDevice, c->stream));
-  HIP_TRY(hipMemcpyAsync(c->ws + c->L.rd, h.d.data(), n8, hipMemcpyHostToDevice, c->stream));
-  HIP_TRY(hipMemcpyAsync(c->ws + c->L.rY, h.Y.data(), n8, hipMemcpyHostToDevice, c->stream));
+  const Layout &L = c->L;
+  auto staged = [&](size_t off) { return c->stage + (off - L.rawinfo); };   // laid out as in the workspace
+  memcpy(staged(L.rawinfo), h.rawinfo.data(), n4);
+  if (changed) memcpy(staged(L.changed), changed->data(), n4); else memset(staged(L.changed), 0, n4);
+  memcpy(staged(L.ra), h.a.data(), n8);
+  memcpy(staged(L.rc), h.c.data(), n8);
+  memcpy(staged(L.rd), h.d.data(), n8);
+  memcpy(staged(L.rY), h.Y.data(), n8);
+  HIP_TRY(hipMemcpyAsync(c->ws + L.rawinfo, c->stage, L.rY + n8 - L.rawinfo, hipMemcpyHostToDevice, c->stream));
   RawJobs raw{c->at<uint32_t>(c->L.rawinfo), c->at<double>(c->L.ra), c->at<double>(c->L.rc),
               c->at<double>(c->L.rd), c->at<double>(c->L.rY)};
   c->term_E = h.term_E;
   HIP_TRY(launch_prepare_table(raw, c->table(), c->Jp, c->stream));
   HIP_TRY(launch_build_terms(c->table(), c->Jp, c->stream));
   if (changed) {
-    HIP_TRY(hipMemcpyAsync(c->ws + c->L.changed, changed->data(), n4, hipMemcpyHostToDevice, c->stream));
     // every physical row, whether a candidate lives in it or not
     HIP_TRY(launch_reset_slots(c->at<int32_t>(c->L.genes), c->at<uint32_t>(c->L.changed), c->P + c->K, c->Jp,
                                c->stream));
   }
-  HIP_TRY(hipStreamSynchronize(c->stream));     // the staging vectors may go away now
+  HIP_TRY(hipStreamSynchronize(c->stream));     // the staging buffer is free again
   return ONES_OK;
 }
 
@@ -328,8 +356,8 @@ size_t ones_workspace_bytes(const ones_config *cfg) {
                      static_cast<uint32_t>(cfg->n_gpus)).total;
 }
 
-int ones_init(ones_ctx **out, const ones_config *cfg, const ones_jobs *jobs, void *d_workspace,
-              size_t workspace_bytes, void *hip_stream) {
+static int init_impl(ones_ctx **out, const ones_config *cfg, const ones_jobs *jobs, void *d_workspace,
+                     size_t workspace_bytes, void *hip_stream) {
   if (!out) return ONES_E_INVALID_ARG;
   int rc = check_config(cfg);
   if (rc) return rc;
@@ -341,8 +369,8 @@ int ones_init(ones_ctx **out, const ones_config *cfg, const ones_jobs *jobs, voi
   if (!d_workspace) return ONES_E_INVALID_ARG;
   if (workspace_bytes < L.total || (reinterpret_cast<uintptr_t>(d_workspace) & 255u) != 0)
     return ONES_E_WORKSPACE_TOO_SMALL;
-  ones_ctx *c = new (std::nothrow) ones_ctx();
-  if (!c) return ONES_E_INVALID_ARG;
+  std::unique_ptr<ones_ctx, void (*)(ones_ctx *)> owner(new ones_ctx(), ones_destroy);   // freed on every way out but the last
+  ones_ctx *c = owner.get();
   c->cfg = *cfg;
   c->P = static_cast<uint32_t>(cfg->population); c->K = c->P / 4;
   c->Jn = static_cast<uint32_t>(cfg->n_slots); c->Jp = static_cast<uint32_t>(Jp); c->R = c->Jp / kLanes;
@@ -352,6 +380,13 @@ int ones_init(ones_ctx **out, const ones_config *cfg, const ones_jobs *jobs, voi
   c->stream = static_cast<hipStream_t>(hip_stream);
   c->ws = static_cast<char *>(d_workspace);
   c->L = L;
+  c->stage = nullptr;
+  {
+    void *pinned = nullptr;
+    HIP_TRY(hipHostMalloc(&pinned, stage_bytes(L, static_cast<uint32_t>(Jp), static_cast<uint32_t>(cfg->n_gpus)),
+                          hipHostMallocDefault));
+    c->stage = static_cast<char *>(pinned);
+  }
   c->cur = 0; c->t = 0;
   c->table_changed = false;
   c->no_schedule = false;
@@ -367,7 +402,7 @@ int ones_init(ones_ctx **out, const ones_config *cfg, const ones_jobs *jobs, voi
     hipDeviceProp_t prop;
     hipError_t e = hipGetDevice(&dev);
     if (e == hipSuccess) e = hipGetDeviceProperties(&prop, dev);
-    if (e != hipSuccess) { delete c; return hip_fail(e, "hipGetDeviceProperties"); }
+    if (e != hipSuccess) return hip_fail(e, "hipGetDeviceProperties");
     c->n_cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
   }
   c->profiling = false; c->profile_every = 1; c->profile_tick = 0; c->evolve_used = c->select_used = 0;
@@ -375,16 +410,16 @@ int ones_init(ones_ctx **out, const ones_config *cfg, const ones_jobs *jobs, voi
     const uint32_t words = (c->P + c->K + 31) / 32;
     hipError_t e = launch_zero_words(c->at<uint32_t>(c->L.occupied[0]), words, c->stream);
     if (e == hipSuccess) e = launch_zero_words(c->at<uint32_t>(c->L.occupied[1]), words, c->stream);
-    if (e != hipSuccess) { delete c; return hip_fail(e, "launch_zero_words"); }
+    if (e != hipSuccess) return hip_fail(e, "launch_zero_words");
   }
-  if ((rc = upload_table(c, h, nullptr)) || (rc = run_generation(c, 0))) { ones_destroy(c); return rc; }
+  if ((rc = upload_table(c, h, nullptr)) || (rc = run_generation(c, 0))) return rc;
   hipError_t e = hipStreamSynchronize(c->stream);
-  if (e != hipSuccess) { ones_destroy(c); return hip_fail(e, "hipStreamSynchronize"); }
-  *out = c;
+  if (e != hipSuccess) return hip_fail(e, "hipStreamSynchronize");
+  *out = owner.release();
   return ONES_OK;
 }
 
-int ones_set_jobs(ones_ctx *c, const ones_jobs *jobs) {
+static int set_jobs_impl(ones_ctx *c, const ones_jobs *jobs) {
   if (!c) return ONES_E_INVALID_ARG;
   HostJobs h;
   int rc = stage_jobs(static_cast<int>(c->Jn), static_cast<int>(c->Jp), jobs, h);
@@ -404,7 +439,7 @@ int ones_set_jobs(ones_ctx *c, const ones_jobs *jobs) {
   return ONES_OK;
 }
 
-int ones_set_progress(ones_ctx *c, const double *alpha, const double *beta, const double *processed) {
+static int set_progress_impl(ones_ctx *c, const double *alpha, const double *beta, const double *processed) {
   if (!c) return ONES_E_INVALID_ARG;
   if (!alpha && !beta && !processed) {
     if (c->sampling) {
@@ -424,31 +459,34 @@ int ones_set_progress(ones_ctx *c, const double *alpha, const double *beta, cons
     if (alpha[j] < 1.0 || beta[j] < 1.0 || processed[j] < 0.0) return ONES_E_INVALID_ARG;
     if (alpha[j] > ONES_MAX_PARAM || beta[j] > ONES_MAX_PARAM || processed[j] > ONES_MAX_PARAM) return ONES_E_BOUNDS;
   }
-  std::vector<double> ha(c->Jp, 1.0), hb(c->Jp, 1.0), hp(c->Jp, 0.0);
-  for (uint32_t j = 0; j < c->Jn; ++j) { ha[j] = alpha[j]; hb[j] = beta[j]; hp[j] = processed[j]; }
-  const size_t n8 = static_cast<size_t>(c->Jp) * 8;
-  HIP_TRY(hipMemcpyAsync(c->ws + c->L.alpha, ha.data(), n8, hipMemcpyHostToDevice, c->stream));
-  HIP_TRY(hipMemcpyAsync(c->ws + c->L.beta, hb.data(), n8, hipMemcpyHostToDevice, c->stream));
-  HIP_TRY(hipMemcpyAsync(c->ws + c->L.processed, hp.data(), n8, hipMemcpyHostToDevice, c->stream));
-  HIP_TRY(hipStreamSynchronize(c->stream));     // the staging vectors may go away now
+  const Layout &L = c->L;
+  auto staged = [&](size_t off) { return reinterpret_cast<double *>(c->stage + (off - L.alpha)); };
+  double *ha = staged(L.alpha), *hb = staged(L.beta), *hp = staged(L.processed);   // laid out as in the workspace
+  for (uint32_t j = 0; j < c->Jp; ++j) {
+    const bool real = j < c->Jn;
+    ha[j] = real ? alpha[j] : 1.0; hb[j] = real ? beta[j] : 1.0; hp[j] = real ? processed[j] : 0.0;
+  }
+  HIP_TRY(hipMemcpyAsync(c->ws + L.alpha, c->stage, L.processed + static_cast<size_t>(c->Jp) * 8 - L.alpha,
+                         hipMemcpyHostToDevice, c->stream));
+  HIP_TRY(hipStreamSynchronize(c->stream));     // the staging buffer is free again
   c->sampling = true;
   return ONES_OK;
 }
 
-int ones_set_new_jobs_first(ones_ctx *c, int32_t on) {
+static int set_new_jobs_first_impl(ones_ctx *c, int32_t on) {
   if (!c) return ONES_E_INVALID_ARG;
   c->new_jobs_first = on != 0;
   return ONES_OK;
 }
 
-int ones_set_crossover(ones_ctx *c, int32_t mode) {
+static int set_crossover_impl(ones_ctx *c, int32_t mode) {
   if (!c || (mode != ONES_CROSSOVER_JOBS && mode != ONES_CROSSOVER_GPUS)) return ONES_E_INVALID_ARG;
   if (mode == ONES_CROSSOVER_GPUS && c->G > static_cast<uint32_t>(kMaxCoinGpus)) return ONES_E_BOUNDS;
   c->per_gpu = mode == ONES_CROSSOVER_GPUS;
   return ONES_OK;
 }
 
-int ones_set_processed_time(ones_ctx *c, const double *t_processed) {
+static int set_processed_time_impl(ones_ctx *c, const double *t_processed) {
   if (!c) return ONES_E_INVALID_ARG;
   if (!t_processed) { c->has_times = false; return ONES_OK; }
   for (uint32_t j = 0; j < c->Jn; ++j) {
@@ -456,26 +494,27 @@ int ones_set_processed_time(ones_ctx *c, const double *t_processed) {
     if (rc) return rc;
   }
   // position of every slot in ascending (time, slot) order; the padding slots count as time 0
-  std::vector<uint32_t> order(c->Jp), rank(c->Jp);
+  std::vector<uint32_t> order(c->Jp);
+  uint32_t *rank = reinterpret_cast<uint32_t *>(c->stage);
   for (uint32_t j = 0; j < c->Jp; ++j) order[j] = j;
   auto time_of = [&](uint32_t j) { return j < c->Jn ? t_processed[j] : 0.0; };
   std::stable_sort(order.begin(), order.end(), [&](uint32_t x, uint32_t y) { return time_of(x) < time_of(y); });
   for (uint32_t pos = 0; pos < c->Jp; ++pos) rank[order[pos]] = pos;
-  HIP_TRY(hipMemcpyAsync(c->ws + c->L.time_rank, rank.data(), static_cast<size_t>(c->Jp) * 4, hipMemcpyHostToDevice,
+  HIP_TRY(hipMemcpyAsync(c->ws + c->L.time_rank, rank, static_cast<size_t>(c->Jp) * 4, hipMemcpyHostToDevice,
                          c->stream));
-  HIP_TRY(hipStreamSynchronize(c->stream));     // the staging vector may go away now
+  HIP_TRY(hipStreamSynchronize(c->stream));     // the staging buffer is free again
   c->has_times = true;
   return ONES_OK;
 }
 
-int ones_export_remaining(ones_ctx *c, double *remaining_out) {
+static int export_remaining_impl(ones_ctx *c, double *remaining_out) {
   if (!c || !remaining_out) return ONES_E_INVALID_ARG;
   HIP_TRY(hipStreamSynchronize(c->stream));
   if (c->Jn) HIP_TRY(hipMemcpy(remaining_out, c->ws + c->L.Y, static_cast<size_t>(c->Jn) * 8, hipMemcpyDeviceToHost));
   return ONES_OK;
 }
 
-int ones_generation(ones_ctx *c, int32_t n_generations) {
+static int generation_impl(ones_ctx *c, int32_t n_generations) {
   if (!c || n_generations < 0) return ONES_E_INVALID_ARG;
   if (c->t + n_generations > 0xFFFFFFFFll) return ONES_E_INVALID_ARG;
   for (int32_t i = 0; i < n_generations; ++i) {
@@ -486,44 +525,41 @@ int ones_generation(ones_ctx *c, int32_t n_generations) {
   return ONES_OK;
 }
 
-int ones_best(ones_ctx *c, int32_t *batch_out, int32_t *gpus_out, double *fitness_out) {
+static int best_impl(ones_ctx *c, int32_t *batch_out, int32_t *gpus_out, double *fitness_out) {
   if (!c) return ONES_E_INVALID_ARG;
   HIP_TRY(launch_best(c->at<int32_t>(c->L.genes), c->at<double>(c->L.fit_row), c->at<uint32_t>(c->L.row_of[c->cur]),
                       c->at<int32_t>(c->L.sel),
                       c->at<uint32_t>(c->L.info), c->Jn, c->Jp, c->at<int32_t>(c->L.best_batch),
                       c->at<int32_t>(c->L.best_gpus), c->at<double>(c->L.best_fit), c->stream));
-  std::vector<int32_t> b(c->Jn), g(c->Jn);
-  double f = 0.0;
-  if (c->Jn) {
-    HIP_TRY(hipMemcpyAsync(b.data(), c->ws + c->L.best_batch, c->Jn * 4, hipMemcpyDeviceToHost, c->stream));
-    HIP_TRY(hipMemcpyAsync(g.data(), c->ws + c->L.best_gpus, c->Jn * 4, hipMemcpyDeviceToHost, c->stream));
-  }
-  HIP_TRY(hipMemcpyAsync(&f, c->ws + c->L.best_fit, 8, hipMemcpyDeviceToHost, c->stream));
+  const Layout &L = c->L;
+  HIP_TRY(hipMemcpyAsync(c->stage, c->ws + L.best_batch, L.best_fit + 8 - L.best_batch, hipMemcpyDeviceToHost,
+                         c->stream));
   HIP_TRY(hipStreamSynchronize(c->stream));
-  if (batch_out && c->Jn) memcpy(batch_out, b.data(), c->Jn * 4);
-  if (gpus_out && c->Jn) memcpy(gpus_out, g.data(), c->Jn * 4);
-  if (fitness_out) *fitness_out = f;
+  auto staged = [&](size_t off) { return c->stage + (off - L.best_batch); };   // laid out as in the workspace
+  if (batch_out && c->Jn) memcpy(batch_out, staged(L.best_batch), c->Jn * 4);
+  if (gpus_out && c->Jn) memcpy(gpus_out, staged(L.best_gpus), c->Jn * 4);
+  if (fitness_out) memcpy(fitness_out, staged(L.best_fit), 8);
   return ONES_OK;
 }
 
-int ones_placement(ones_ctx *c, int32_t *slot_of_gpu, int32_t *batch_of_gpu) {
+static int placement_impl(ones_ctx *c, int32_t *slot_of_gpu, int32_t *batch_of_gpu) {
   if (!c || c->no_schedule) return ONES_E_INVALID_ARG;
   const size_t n4 = static_cast<size_t>(c->G) * 4;
   HIP_TRY(launch_placement(c->at<int32_t>(c->L.genes), c->at<uint32_t>(c->L.row_of[c->cur]), c->at<int32_t>(c->L.sel),
                            c->at<uint32_t>(c->L.info), c->Jn, c->Jp, c->G, c->at<int32_t>(c->L.place_slot),
                            c->at<int32_t>(c->L.place_batch), c->stream));
-  std::vector<int32_t> slot(c->G), batch(c->G);
-  if (c->G) {
-    HIP_TRY(hipMemcpyAsync(slot.data(), c->ws + c->L.place_slot, n4, hipMemcpyDeviceToHost, c->stream));
-    HIP_TRY(hipMemcpyAsync(batch.data(), c->ws + c->L.place_batch, n4, hipMemcpyDeviceToHost, c->stream));
-  }
+  const Layout &L = c->L;
+  if (c->G)
+    HIP_TRY(hipMemcpyAsync(c->stage, c->ws + L.place_slot, L.place_batch + n4 - L.place_slot, hipMemcpyDeviceToHost,
+                           c->stream));
   HIP_TRY(hipStreamSynchronize(c->stream));
-  if (slot_of_gpu && c->G) memcpy(slot_of_gpu, slot.data(), n4);
-  if (batch_of_gpu && c->G) memcpy(batch_of_gpu, batch.data(), n4);
+  auto staged = [&](size_t off) { return c->stage + (off - L.place_slot); };   // laid out as in the workspace
+  if (slot_of_gpu && c->G) memcpy(slot_of_gpu, staged(L.place_slot), n4);
+  if (batch_of_gpu && c->G) memcpy(batch_of_gpu, staged(L.place_batch), n4);
   return ONES_OK;
 }
 
-int ones_export(ones_ctx *c, int32_t *genes, double *fit, int32_t *sel, int64_t *generation) {
+static int export_impl(ones_ctx *c, int32_t *genes, double *fit, int32_t *sel, int64_t *generation) {
   if (!c) return ONES_E_INVALID_ARG;
   HIP_TRY(hipStreamSynchronize(c->stream));
   // candidates live in physical rows: fetch the rows and put them in slot order on the host
@@ -549,7 +585,7 @@ int ones_export(ones_ctx *c, int32_t *genes, double *fit, int32_t *sel, int64_t 
   return ONES_OK;
 }
 
-int ones_profile_enable(ones_ctx *c, int32_t on) {
+static int profile_enable_impl(ones_ctx *c, int32_t on) {
   if (!c) return ONES_E_INVALID_ARG;
   HIP_TRY(hipStreamSynchronize(c->stream));
   c->profiling = on > 0;
@@ -559,7 +595,7 @@ int ones_profile_enable(ones_ctx *c, int32_t on) {
   return ONES_OK;
 }
 
-int ones_profile_read(ones_ctx *c, double *evolve_ms, int64_t *evolve_launches, double *select_ms,
+static int profile_read_impl(ones_ctx *c, double *evolve_ms, int64_t *evolve_launches, double *select_ms,
                       int64_t *select_launches) {
   if (!c) return ONES_E_INVALID_ARG;
   HIP_TRY(hipStreamSynchronize(c->stream));
@@ -581,7 +617,7 @@ int ones_profile_read(ones_ctx *c, double *evolve_ms, int64_t *evolve_launches, 
   return ONES_OK;
 }
 
-int ones_update_limits(int32_t n_slots, const ones_limit_inputs *in, double sigma, int32_t *limit) {
+static int update_limits_impl(int32_t n_slots, const ones_limit_inputs *in, double sigma, int32_t *limit) {
   if (n_slots < 0 || n_slots > ONES_MAX_SLOTS) return ONES_E_INVALID_ARG;
   if (n_slots > 0 && (!in || !limit || !in->state || !in->bmin || !in->bcap || !in->gpu_max_batch ||
                       !in->last_batch || !in->finished_epoch || !in->elapsed))
@@ -622,10 +658,70 @@ int ones_update_limits(int32_t n_slots, const ones_limit_inputs *in, double sigm
   return ONES_OK;
 }
 
+// The entry points proper: nothing is thrown across the C boundary (the staging vectors may run out of host
+// memory).
+
+int ones_init(ones_ctx **out, const ones_config *cfg, const ones_jobs *jobs, void *d_workspace, size_t workspace_bytes, void *hip_stream) {
+  return guarded([&] { return init_impl(out, cfg, jobs, d_workspace, workspace_bytes, hip_stream); });
+}
+
+int ones_set_jobs(ones_ctx *c, const ones_jobs *jobs) {
+  return guarded([&] { return set_jobs_impl(c, jobs); });
+}
+
+int ones_set_crossover(ones_ctx *c, int32_t mode) {
+  return guarded([&] { return set_crossover_impl(c, mode); });
+}
+
+int ones_set_processed_time(ones_ctx *c, const double *t_processed) {
+  return guarded([&] { return set_processed_time_impl(c, t_processed); });
+}
+
+int ones_set_progress(ones_ctx *c, const double *alpha, const double *beta, const double *processed) {
+  return guarded([&] { return set_progress_impl(c, alpha, beta, processed); });
+}
+
+int ones_set_new_jobs_first(ones_ctx *c, int32_t on) {
+  return guarded([&] { return set_new_jobs_first_impl(c, on); });
+}
+
+int ones_export_remaining(ones_ctx *c, double *remaining_out) {
+  return guarded([&] { return export_remaining_impl(c, remaining_out); });
+}
+
+int ones_generation(ones_ctx *c, int32_t n_generations) {
+  return guarded([&] { return generation_impl(c, n_generations); });
+}
+
+int ones_best(ones_ctx *c, int32_t *batch_out, int32_t *gpus_out, double *fitness_out) {
+  return guarded([&] { return best_impl(c, batch_out, gpus_out, fitness_out); });
+}
+
+int ones_placement(ones_ctx *c, int32_t *slot_of_gpu, int32_t *batch_of_gpu) {
+  return guarded([&] { return placement_impl(c, slot_of_gpu, batch_of_gpu); });
+}
+
+int ones_export(ones_ctx *c, int32_t *genes, double *fit, int32_t *sel, int64_t *generation) {
+  return guarded([&] { return export_impl(c, genes, fit, sel, generation); });
+}
+
+int ones_profile_enable(ones_ctx *c, int32_t on) {
+  return guarded([&] { return profile_enable_impl(c, on); });
+}
+
+int ones_profile_read(ones_ctx *c, double *evolve_ms, int64_t *evolve_launches, double *select_ms, int64_t *select_launches) {
+  return guarded([&] { return profile_read_impl(c, evolve_ms, evolve_launches, select_ms, select_launches); });
+}
+
+int ones_update_limits(int32_t n_slots, const ones_limit_inputs *in, double sigma, int32_t *limit) {
+  return guarded([&] { return update_limits_impl(n_slots, in, sigma, limit); });
+}
+
 void ones_destroy(ones_ctx *c) {
   if (!c) return;
   for (auto &e : c->evolve_ev) { (void)hipEventDestroy(e.start); (void)hipEventDestroy(e.stop); }
   for (auto &e : c->select_ev) { (void)hipEventDestroy(e.start); (void)hipEventDestroy(e.stop); }
+  if (c->stage) (void)hipHostFree(c->stage);
   delete c;
 }
 
