@@ -52,3 +52,44 @@ def test_host_side_argument_checks_need_no_gpu():
     assert L.ones_generation(None, 1) == -1 and L.ones_best(None, None, None, None) == -1
     assert b"power" in L.ones_strerror(-2)
     L.ones_destroy(None)
+
+
+def test_job_table_validation_needs_no_gpu():
+    """ones_init checks the job table and the workspace before it touches the device."""
+    from paper_2108_03645_amd import ones
+    from pyref import make_jobs
+    if not os.path.exists(ones.library_path()):
+        pytest.skip("libones.so not built here")
+    L = ones.load()
+    cfg = ones.ones_config(16, 8, 64, 0, 0.1, 0.5)
+    h = ctypes.c_void_p()
+
+    def init(jobs, workspace=0x1000, nbytes=1):
+        js, keep = ones.make_jobs(jobs)
+        return L.ones_init(ctypes.byref(h), ctypes.byref(cfg), ctypes.byref(js), ctypes.c_void_p(workspace), nbytes, None)
+
+    good = make_jobs(8)
+    assert init(good) == -5                                    # valid table, workspace of one byte
+    assert init(good, workspace=0x1001, nbytes=1 << 30) == -5  # misaligned workspace
+    assert init(good, workspace=0) == -1
+    for field, value, code in [("bmin", 48, -2), ("bmax", None, -3), ("gpu_max_batch", 0, -2),
+                               ("a", float("nan"), -4), ("remaining", float("inf"), -4), ("d", -1.0, -1),
+                               ("c", 1e101, -3)]:
+        bad = make_jobs(8)
+        arr = getattr(bad, field)
+        if field == "bmax":
+            arr[3] = 1 << 30
+            bad.gpu_max_batch[3] = 1                           # 2^30 GPUs: beyond the 2^20 a job may hold
+        else:
+            arr[3] = value
+        assert init(bad) == code, field
+        bad.active[3] = 0                                      # an empty slot's values are ignored
+        assert init(bad) == -5, field
+    lo_above_hi = make_jobs(8, bmin=512, bmax=256)
+    assert init(lo_above_hi) == -3
+    assert h.value is None
+    for call in (lambda: L.ones_set_jobs(None, None), lambda: L.ones_set_progress(None, None, None, None),
+                 lambda: L.ones_set_crossover(None, 0), lambda: L.ones_set_processed_time(None, None),
+                 lambda: L.ones_set_new_jobs_first(None, 1), lambda: L.ones_placement(None, None, None),
+                 lambda: L.ones_export(None, None, None, None, None), lambda: L.ones_export_remaining(None, None)):
+        assert call() == -1
