@@ -616,3 +616,20 @@ def test_full_size_stress_with_the_crossover_over_gpus(ones, ref):
         gpu.close(); cpu.close()
     finally:
         ref.set_threads(1)
+
+
+def test_crossover_over_gpus_on_degenerate_clusters(ones, ref):
+    for cl, jobs, label in [(cluster(8, 0, 16), make_jobs(0), "no slots"),
+                            (cluster(8, 10, 16), make_jobs(10, active=0), "all inactive"),
+                            (cluster(0, 10, 16), make_jobs(10), "no GPUs"),
+                            (cluster(1, 1, 4), make_jobs(1), "one job, one GPU, K=1"),
+                            (cluster(8192, 70, 8), make_jobs(70, bmin=1, bmax=1 << 28, gpu_max_batch=256), "huge jobs"),
+                            (cluster(40, 90, 8), make_jobs(90, bmin=2048, bmax=4096, gpu_max_batch=64),
+                             "window above the per-GPU batch")]:
+        say(f"[crossover over GPUs] {label}")
+        gpu, cpu = ones.Search(cl, jobs), ref.RefSearch(cl, jobs)
+        gpu.set_crossover(per_gpu=True); cpu.set_crossover(per_gpu=True)
+        for gen in range(3):
+            gpu.generation(1); cpu.generation(1)
+            assert_same_state(gpu, cpu, f"{label} generation {gen + 1}")
+        gpu.close(); cpu.close()
