@@ -144,3 +144,48 @@ def test_mode_validation(ref):
     ok.set_crossover(per_gpu=True)
     ok.generation(1)
     s.close(); t.close(); ok.close()
+
+
+def test_parents_are_read_under_the_current_table(ref):
+    """After a table change the parents' genes were written under the old table: a parent's job
+    holds the GPUs that clamp and lift of the repair would give it under the new one (batch pulled
+    into the new window and raised for free to the new per-GPU batch), an emptied slot none, and
+    what does not fit the cluster lies beyond its last GPU."""
+    rng = np.random.default_rng(8)
+    n = 70
+    jobs = random_jobs(rng, n)
+    cl = cluster(60, n, 64, seed=5)
+    s = ref.RefSearch(cl, jobs)
+    s.set_crossover(per_gpu=True)
+    s.generation(2)
+    j2 = random_jobs(np.random.default_rng(9), n)             # other windows, per-GPU batches, empty slots
+    j2.job_id[:] = jobs.job_id                                # same jobs: no slot is reset
+    s.set_jobs(j2)
+    genes, _, sel, t = s.export()
+    K = cl.population // 4
+
+    def gpus_under_new_table(b, j):
+        if not j2.active[j] or b == 0:
+            return 0
+        b = min(max(int(b), int(j2.bmin[j])), int(j2.bmax[j]))
+        b = max(b, min(int(j2.gpu_max_batch[j]), int(j2.bmax[j])))
+        return pyref.gpus(b, j2.gpu_max_batch[j])
+
+    lifted = 0
+    for p0 in range(K, 3 * K, 2):
+        first, _, pa, pb = s.compose_slot(p0)
+        second = s.compose_slot(p0 + 1)[0]
+        c_a = [gpus_under_new_table(genes[pa][j], j) for j in range(n)]
+        c_b = [gpus_under_new_table(genes[pb][j], j) for j in range(n)]
+        lifted += sum(1 for j in range(n) if genes[pa][j] and j2.active[j] and genes[pa][j] < min(j2.gpu_max_batch[j], j2.bmax[j]))
+        n1, n2 = pyref.gpu_crossover(cl.seed, p0, t + 1, cl.n_gpus, c_a, c_b)
+        for child, counts in ((first, n1), (second, n2)):
+            for j in range(n):
+                want = 0 if counts[j] == 0 else (1 << (counts[j].bit_length() - 1)) * min(int(j2.gpu_max_batch[j]), int(j2.bmax[j]))
+                assert child[j] == want
+    assert lifted > 0                                          # the case the lift matters for did occur
+    s.generation(1)
+    genes = s.export()[0]
+    for p in range(cl.population):
+        check_invariants(cl.n_gpus, j2, genes[p, :n])
+    s.close()
