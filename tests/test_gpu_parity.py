@@ -181,17 +181,20 @@ def test_online_sequence(ones, ref):
     gpu.close(); cpu.close()
 
 
-def test_online_sequence_with_limit_policies(ones, ref):
+@pytest.mark.parametrize("per_gpu", [False, True])
+def test_online_sequence_with_limit_policies(ones, ref, per_gpu):
     """The online sequence with the batch-size limits of Section 3.3.2 (each side computes them
     with its own update_limits) and newly arrived jobs served first after every table change
-    (refresh (3) of Section 3.2.2)."""
+    (refresh (3) of Section 3.2.2), the room for them taken from the longest runners; with the
+    crossover over the jobs and over the GPUs."""
     sims = [W.OnlineSequence(epochs=40, limits=ones.update_limits), W.OnlineSequence(epochs=40, limits=ref.update_limits)]
     cl = sims[0].cluster
     cl.population = 512
-    say(f"[parity] online with limit policies: P={cl.population} epochs=40 gens/epoch=5")
+    say(f"[parity] online with limit policies: P={cl.population} epochs=40 gens/epoch=5 per_gpu={per_gpu}")
     gpu = ones.Search(cl, sims[0].jobs)
     cpu = ref.RefSearch(cl, sims[1].jobs)
     gpu.set_new_jobs_first(True); cpu.set_new_jobs_first(True)
+    gpu.set_crossover(per_gpu=per_gpu); cpu.set_crossover(per_gpu=per_gpu)
     limits_seen = set()
     for epoch in range(40):
         gpu.generation(5); cpu.generation(5)
