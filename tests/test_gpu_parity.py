@@ -495,17 +495,19 @@ def test_placement_matches_the_oracle(ones, ref, n_slots, n_gpus, pop, seed):
                                                            (2048, 4096, 256, 3, 300), (2048, 100, 64, 4, 500),
                                                            (200, 300, 8192, 5, 17)])
 @pytest.mark.parametrize("times", ["none", "ties", "distinct"])
-def test_new_jobs_first_matches_the_oracle(ones, ref, n_slots, n_gpus, pop, seed, n_new, times):
+@pytest.mark.parametrize("per_gpu", [False, True])
+def test_new_jobs_first_matches_the_oracle(ones, ref, n_slots, n_gpus, pop, seed, n_new, times, per_gpu):
     """The option of serving arrived jobs first: the generation after the table change and the
     ordinary ones that follow, with more and with fewer new jobs than GPUs; the others admitted
     in visiting order or by executed time (many equal times, or all distinct)."""
     rng = np.random.default_rng(seed)
     cl = cluster(n_gpus, n_slots, pop, seed=seed)
     jobs = random_jobs(rng, n_slots)
-    say(f"[new first] G={n_gpus} slots={n_slots} P={pop} seed={seed} new={n_new} times={times}")
+    say(f"[new first] G={n_gpus} slots={n_slots} P={pop} seed={seed} new={n_new} times={times} per_gpu={per_gpu}")
     gpu, cpu = ones.Search(cl, jobs), ref.RefSearch(cl, jobs)
     for s in (gpu, cpu):
         s.set_new_jobs_first(True)
+        s.set_crossover(per_gpu=per_gpu)
         s.generation(3)
     assert_same_state(gpu, cpu, "before the arrivals")
     j2 = make_jobs(n_slots, **{k: np.array(getattr(jobs, k)) for k in
