@@ -305,10 +305,10 @@ __global__ __launch_bounds__(kSampleThreads) void sample_splitters_kernel(const 
   if (t < kLanes) {
     const uint32_t r = rank[t];
     if ((r & 1u) && r / 2 + 1 < sample / 2) split[r / 2] = key;
-    // the splitters beyond the sample are +inf: nothing lands in those buckets
-    if (mine == 0)
-      for (uint32_t c = sample / 2 - 1; c < static_cast<uint32_t>(kMaxBuckets); ++c) split[c] = ~0ull;
   }
+  // the splitters beyond the sample are +inf: nothing lands in those buckets
+  if (blockIdx.x == 0)
+    for (uint32_t c = sample / 2 - 1 + t; c < static_cast<uint32_t>(kMaxBuckets); c += kSampleThreads) split[c] = ~0ull;
 }
 
 // Bucket of a score = number of splitters <= it (equal scores share a bucket).  A workgroup
