@@ -79,6 +79,9 @@ def online(args, torch, ones, W) -> int:
     torch.cuda.set_device(0)
     search = ones.Search(cl, sim.jobs, device="cuda:0")
     search.set_new_jobs_first(args.policies)
+    search.set_crossover(per_gpu=args.crossover == "gpus")
+    if args.sampled:
+        search.set_progress(*sim.progress())
     gens = cl.generations
     t_set = t_gen = t_best = 0.0
     evals = 0
@@ -96,6 +99,8 @@ def online(args, torch, ones, W) -> int:
         search.set_jobs(sim.jobs)
         if args.policies:
             search.set_processed_time(sim.elapsed)
+        if args.sampled:
+            search.set_progress(*sim.progress())
         t4 = time.perf_counter()
         if timed:
             t_gen += t1 - t0; t_best += t2 - t1; t_set += t4 - t3
@@ -107,7 +112,9 @@ def online(args, torch, ones, W) -> int:
            "dtype": "i32 genes, f64 fitness", "data": "synthetic",
            "config": {"workload": "online", "n_gpus_cluster": cl.n_gpus, "slots": cl.n_slots,
                       "population": cl.population, "generations_per_epoch": gens, "seed": cl.seed,
-                      "limit_policies": bool(args.policies), "jobs_completed": sim.completed},
+                      "limit_policies": bool(args.policies), "crossover": "over " + args.crossover,
+                      "remaining_work": "sampled per generation" if args.sampled else "fixed",
+                      "jobs_completed": sim.completed},
            "generations_per_s": gens * args.steps / dt,
            "per_epoch_ms": {"generations": t_gen * 1e3 / args.steps, "ones_best": t_best * 1e3 / args.steps,
                             "ones_set_jobs": t_set * 1e3 / args.steps,

@@ -173,6 +173,11 @@ class OnlineSequence:
     the job's own maximum: a job starts on one GPU's batch, doubles its limit after every
     epoch it ran (penalised by its executed time, sigma = the arrival rate), is capped at its
     last batch when it gets pre-empted and halved for every further epoch it waits.
+
+    ``progress()`` gives the inputs of the probability sampling (Alg. 1) the way a progress
+    predictor would, without its training logs: a job has processed the fraction rho of its
+    work; the predictor's Be(alpha, beta) is centred there and gets sharper with every epoch it
+    has observed: alpha = 1 + k rho, beta = 1 + k (1 - rho), k = 8 (1 + epochs run).
     """
     EPOCH_S = 60.0
     MAX_BUSY = 60
@@ -187,6 +192,8 @@ class OnlineSequence:
         self.elapsed = np.zeros(n_slots)                # executed seconds
         self.prev_batch = np.zeros(n_slots, np.int32)   # batch in the epoch before
         self.arrived = np.zeros(n_slots, np.uint8)      # arrived since the last limit update
+        self.total = np.zeros(n_slots)                  # samples the job had to process when it arrived
+        self.epochs_run = np.zeros(n_slots, np.int64)
         self.next_id = 1
         self.backlog = 0
         self.completed = 0
@@ -204,6 +211,7 @@ class OnlineSequence:
             j.a[s], j.c[s], j.d[s], j.remaining[s] = a[0], c[0], d[0], y[0]
             j.bmin[s], j.bmax[s], j.gpu_max_batch[s] = bmin[0], bmax[0], 256
             self.cap[s], self.elapsed[s], self.prev_batch[s], self.arrived[s] = bmax[0], 0.0, 0, 1
+            self.total[s], self.epochs_run[s] = y[0], 0
             self.next_id += 1
             self.backlog -= 1
         if self.limits is not None:
@@ -225,11 +233,22 @@ class OnlineSequence:
                 j.active[s] = 0
                 j.remaining[s] = 0.0
                 self.completed += 1
-            if self.limits is not None:
-                self.elapsed[s] += self.EPOCH_S
+            self.elapsed[s] += self.EPOCH_S
+            self.epochs_run[s] += 1
         self._arrive(int(self.rng.poisson(0.5)))
         if self.limits is not None:
             self._update_limits(np.asarray(batch, np.int32))
+
+    def progress(self):
+        """(alpha, beta, processed) per slot for ``set_progress``; empty slots get Be(1, 1) and 0."""
+        j = self.jobs
+        live = j.active != 0
+        processed = np.where(live, np.maximum(self.total - j.remaining, 0.0), 0.0)
+        rho = np.where(live & (self.total > 0), processed / np.maximum(self.total, 1e-300), 0.0)
+        k = 8.0 * (1.0 + self.epochs_run)
+        alpha = np.where(live, 1.0 + k * rho, 1.0)
+        beta = np.where(live, 1.0 + k * (1.0 - rho), 1.0)
+        return alpha, beta, processed
 
     def _update_limits(self, batch):
         """Section 3.3.2: the limits the scheduler sees in the next epoch."""

@@ -211,6 +211,37 @@ def test_online_sequence_with_limit_policies(ones, ref, per_gpu):
     gpu.close(); cpu.close()
 
 
+def test_online_sequence_with_everything_on(ones, ref):
+    """The whole loop at once: limit policies, new jobs first with executed times, the crossover
+    over the GPUs, and the remaining work drawn per generation from the progress the simulated
+    predictor reports (Alg. 1)."""
+    sims = [W.OnlineSequence(epochs=30, limits=ones.update_limits), W.OnlineSequence(epochs=30, limits=ref.update_limits)]
+    cl = sims[0].cluster
+    cl.population = 1024
+    say(f"[parity] online, everything on: P={cl.population} epochs=30 gens/epoch=4")
+    gpu = ones.Search(cl, sims[0].jobs)
+    cpu = ref.RefSearch(cl, sims[1].jobs)
+    for s, sim in ((gpu, sims[0]), (cpu, sims[1])):
+        s.set_new_jobs_first(True)
+        s.set_crossover(per_gpu=True)
+        s.set_progress(*sim.progress())
+    for epoch in range(30):
+        gpu.generation(4); cpu.generation(4)
+        assert_same_state(gpu, cpu, f"online/all epoch {epoch}")
+        assert np.array_equal(gpu.export_remaining(), cpu.export_remaining())
+        gb, gg, gf = gpu.best(); cb, cg, cf = cpu.best()
+        assert gb.tolist() == cb.tolist() and gg.tolist() == cg.tolist() and gf == cf
+        sims[0].advance(gb); sims[1].advance(cb)
+        assert sims[0].jobs.sha256() == sims[1].jobs.sha256()
+        for s, sim in ((gpu, sims[0]), (cpu, sims[1])):
+            s.set_jobs(sim.jobs)
+            s.set_processed_time(sim.elapsed)
+            s.set_progress(*sim.progress())
+        assert_same_state(gpu, cpu, f"online/all epoch {epoch} after the updates")
+    assert sims[0].completed > 0
+    gpu.close(); cpu.close()
+
+
 def test_set_jobs_rejects_bad_tables_and_keeps_state(ones, ref):
     rng = np.random.default_rng(31)
     jobs = random_jobs(rng, 64)
