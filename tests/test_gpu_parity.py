@@ -669,3 +669,53 @@ def test_crossover_over_gpus_on_degenerate_clusters(ones, ref):
             gpu.generation(1); cpu.generation(1)
             assert_same_state(gpu, cpu, f"{label} generation {gen + 1}")
         gpu.close(); cpu.close()
+
+
+@pytest.mark.parametrize("block", range(4))
+def test_random_configurations(ones, ref, block):
+    """Seeded random shapes, rates and modes (crossover over jobs or GPUs, sampled remaining
+    work, new jobs first, executed times), each with two table changes and a placement."""
+    ref.set_threads(8)
+    try:
+        for case in range(20 * block, 20 * block + 20):
+            rng = np.random.default_rng(10_000 + case)
+            n_slots = int(rng.choice([rng.integers(1, 65), rng.integers(1, 400), rng.integers(1, 2049)]))
+            n_gpus = int(rng.choice([rng.integers(0, 20), rng.integers(0, 300), rng.integers(0, 8193),
+                                     rng.integers(0, 3 * n_slots + 1)]))
+            pop = 4 * int(rng.choice([rng.integers(1, 17), rng.integers(1, 300), rng.integers(1, 1200),
+                                      rng.integers(1000, 3000), rng.integers(1000, 6000)]))
+            pop = min(pop, 2048) if n_slots > 512 else min(pop, 8192) if n_slots > 128 else pop
+            cl = cluster(n_gpus, n_slots, pop, seed=int(rng.integers(0, 2**62)),
+                         theta=float(rng.choice([0.0, 0.02, 0.1, 0.5, 1.0])), chi=float(rng.choice([0.0, 0.3, 0.5, 1.0])))
+            per_gpu, sampled, new_first, times = (bool(rng.integers(0, 2)) for _ in range(4))
+            jobs = random_jobs(rng, n_slots)
+            tag = (f"random {case}: slots={n_slots} G={n_gpus} P={pop} theta={cl.mutation_rate} chi={cl.crossover_rate} "
+                   f"per_gpu={per_gpu} sampled={sampled} new_first={new_first} times={times}")
+            say(f"[parity] {tag}")
+            gpu, cpu = ones.Search(cl, jobs), ref.RefSearch(cl, jobs)
+            assert_same_state(gpu, cpu, tag + " initial population")
+            for s in (gpu, cpu):
+                s.set_crossover(per_gpu=per_gpu)
+                s.set_new_jobs_first(new_first)
+                if sampled:
+                    s.set_progress(*W.progress(n_slots, seed=case))
+            for step in range(3):
+                n = int(rng.integers(1, 4))
+                gpu.generation(n); cpu.generation(n)
+                assert_same_state(gpu, cpu, tag + f" step {step}")
+                assert gpu.best()[0].tolist() == cpu.best()[0].tolist()
+                if step == 2:
+                    assert all(np.array_equal(x, y) for x, y in zip(gpu.placement(), cpu.placement())), tag
+                    break
+                j2 = random_jobs(rng, n_slots) if rng.random() < 0.5 else jobs
+                j2.job_id = np.where(rng.random(n_slots) < 0.7, jobs.job_id, jobs.job_id + 5000 * (step + 1))
+                t_processed = rng.integers(0, 6, n_slots) * 60.0
+                for s in (gpu, cpu):
+                    s.set_jobs(j2)
+                    if times:
+                        s.set_processed_time(t_processed)
+                assert_same_state(gpu, cpu, tag + f" table change {step}")
+                jobs = j2
+            gpu.close(); cpu.close()
+    finally:
+        ref.set_threads(1)
