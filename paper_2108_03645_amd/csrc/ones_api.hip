@@ -225,7 +225,9 @@ int upload_table(ones_ctx *c, const HostJobs &h, const std::vector<uint32_t> *ch
   const Layout &L = c->L;
   auto staged = [&](size_t off) { return c->stage + (off - L.rawinfo); };   // laid out as in the workspace
   memcpy(staged(L.rawinfo), h.rawinfo.data(), n4);
-  if (changed) memcpy(staged(L.changed), changed->data(), n4); else memset(staged(L.changed), 0, n4);
+  const size_t n_changed = changed ? changed->size() : 0;          // the slots that changed hands, as a list
+  if (n_changed) memcpy(staged(L.changed), changed->data(), n_changed * 4);
+  memset(staged(L.changed) + n_changed * 4, 0, n4 - n_changed * 4);
   memcpy(staged(L.ra), h.a.data(), n8);
   memcpy(staged(L.rc), h.c.data(), n8);
   memcpy(staged(L.rd), h.d.data(), n8);
@@ -236,11 +238,9 @@ int upload_table(ones_ctx *c, const HostJobs &h, const std::vector<uint32_t> *ch
   c->term_E = h.term_E;
   HIP_TRY(launch_prepare_table(raw, c->table(), c->Jp, c->stream));
   HIP_TRY(launch_build_terms(c->table(), c->Jp, c->stream));
-  if (changed) {
-    // every physical row, whether a candidate lives in it or not
-    HIP_TRY(launch_reset_slots(c->at<int32_t>(c->L.genes), c->at<uint32_t>(c->L.changed), c->P + c->K, c->Jp,
-                               c->stream));
-  }
+  if (n_changed)   // every physical row, whether a candidate lives in it or not
+    HIP_TRY(launch_reset_slots(c->at<int32_t>(c->L.genes), c->at<uint32_t>(c->L.changed),
+                               static_cast<uint32_t>(n_changed), c->P + c->K, c->Jp, c->stream));
   HIP_TRY(hipStreamSynchronize(c->stream));     // the staging buffer is free again
   return ONES_OK;
 }
@@ -424,15 +424,13 @@ static int set_jobs_impl(ones_ctx *c, const ones_jobs *jobs) {
   HostJobs h;
   int rc = stage_jobs(static_cast<int>(c->Jn), static_cast<int>(c->Jp), jobs, h);
   if (rc) return rc;
-  std::vector<uint32_t> changed(c->Jp, 0u);
-  bool any = false;
+  std::vector<uint32_t> changed;                                  // the slots that changed hands
   for (uint32_t j = 0; j < c->Jn; ++j)
     if (h.id[j] != c->ids[j]) {
-      changed[j] = 1u;
-      any = true;
+      changed.push_back(j);
       if ((h.rawinfo[j] >> 15) & 1u) h.rawinfo[j] |= 1u << 16;   // an active job arrived in this slot
     }
-  if ((rc = upload_table(c, h, any ? &changed : nullptr))) return rc;
+  if ((rc = upload_table(c, h, changed.empty() ? nullptr : &changed))) return rc;
   c->ids = h.id;
   c->table_changed = true;
   c->no_schedule = true;

@@ -152,7 +152,9 @@ struct Progress {
 };
 hipError_t launch_sample_remaining(const Progress &pr, const JobTable &tab, uint32_t Jn, uint32_t Jp,
                                    uint32_t key0, uint32_t key1, uint32_t t, hipStream_t s);
-hipError_t launch_reset_slots(int32_t *genes, const uint32_t *changed, uint32_t P, uint32_t Jp, hipStream_t s);
+// slots: the n_changed slots whose genes are set to "waiting" in every one of the rows
+hipError_t launch_reset_slots(int32_t *genes, const uint32_t *slots, uint32_t n_changed, uint32_t rows, uint32_t Jp,
+                              hipStream_t s);
 // same_table: the job table is the one the previous generation was repaired and scored with
 hipError_t launch_evolve_group0(const EvolveArgs &a, int rows, bool same_table, int n_cus, hipStream_t s);
 hipError_t launch_evolve_group1(const EvolveArgs &a, int rows, bool same_table, int n_cus, hipStream_t s);

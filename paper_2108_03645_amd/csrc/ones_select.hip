@@ -473,11 +473,15 @@ __global__ void build_terms_kernel(JobTable tab, uint32_t Jp) {
   tab.terms[q] = term_of(tab.abl[j], tab.cc[j], tab.d[j], tab.Y[j], info_blexp(tab.info[j]), e);
 }
 
-__global__ void reset_slots_kernel(int32_t *genes, const uint32_t *changed, uint32_t P, uint32_t Jp) {
-  const size_t n = static_cast<size_t>(P) * Jp;
-  for (size_t e = blockIdx.x * static_cast<size_t>(blockDim.x) + threadIdx.x; e < n;
-       e += static_cast<size_t>(gridDim.x) * blockDim.x)
-    if (changed[e % Jp]) genes[e] = 0;
+// slots: the n_changed slots that changed hands; they start from "waiting" in every row.
+// One thread per (row, changed slot), the slots of a row next to each other.
+__global__ void reset_slots_kernel(int32_t *genes, const uint32_t *slots, uint32_t n_changed, uint32_t rows,
+                                   uint32_t Jp) {
+  const uint32_t n = rows * n_changed;               // at most 1.25 * 2^20 * 2048 < 2^32
+  for (uint32_t e = blockIdx.x * blockDim.x + threadIdx.x; e < n; e += gridDim.x * blockDim.x) {
+    const uint32_t row = e / n_changed, k = e - row * n_changed;
+    genes[static_cast<size_t>(row) * Jp + slots[k]] = 0;
+  }
 }
 
 __global__ void best_kernel(const int32_t *genes, const double *fit_row, const uint32_t *row_of, const int32_t *sel,
@@ -561,10 +565,13 @@ hipError_t launch_build_terms(const JobTable &tab, uint32_t Jp, hipStream_t s) {
   return hipGetLastError();
 }
 
-hipError_t launch_reset_slots(int32_t *genes, const uint32_t *changed, uint32_t P, uint32_t Jp, hipStream_t s) {
-  const size_t n = static_cast<size_t>(P) * Jp;
-  const uint32_t blocks = static_cast<uint32_t>(std::min<size_t>((n + 255) / 256, 65536));
-  hipLaunchKernelGGL(reset_slots_kernel, dim3(blocks), dim3(256), 0, s, genes, changed, P, Jp);
+hipError_t launch_reset_slots(int32_t *genes, const uint32_t *slots, uint32_t n_changed, uint32_t rows, uint32_t Jp,
+                              hipStream_t s) {
+  if (n_changed == 0 || rows == 0) return hipSuccess;
+  const uint64_t n = static_cast<uint64_t>(rows) * n_changed;
+  if (n > 0xFFFFFFFFull) return hipErrorInvalidValue;
+  const uint32_t blocks = static_cast<uint32_t>(std::min<uint64_t>((n + 255) / 256, 16384));
+  hipLaunchKernelGGL(reset_slots_kernel, dim3(blocks), dim3(256), 0, s, genes, slots, n_changed, rows, Jp);
   return hipGetLastError();
 }
 
