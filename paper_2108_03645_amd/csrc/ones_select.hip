@@ -16,12 +16,37 @@ __device__ __forceinline__ bool key_less(uint64_t ka, uint32_t ia, uint64_t kb, 
   return ka < kb || (ka == kb && ia < ib);
 }
 
-// Slot id takes rank g < K: it survives in its row.
-__device__ __forceinline__ void keep_row(const RowPlan &rp, uint32_t g, uint32_t id) {
-  const uint32_t row = rp.row_of_cur[id];
-  rp.parent_next[g] = row;
-  rp.row_of_next[g] = row;
-  atomicOr(&rp.occupied[row / 32], 1u << (row % 32));
+// Value of lane + n within the lane's row of 16 (DPP row_shl:n), or fallback where that row ends.
+template <int N>
+__device__ __forceinline__ uint32_t from_lane_above(uint32_t fallback, uint32_t v) {
+  return static_cast<uint32_t>(__builtin_amdgcn_update_dpp(static_cast<int>(fallback), static_cast<int>(v), 0x100 + N,
+                                                           0xF, 0xF, false));
+}
+
+// Slot id takes rank g < K (lanes with valid set): it survives in its row.  Called by whole
+// waves.  Neighbouring lanes whose rows share a word of the bitmap hand their bits to the first
+// lane of their run (within a row of 16 lanes), which issues one atomic for all of them: the
+// rows of a pool that has stopped changing are neighbours, and one atomic per row would queue
+// up on the same few words.  Lanes that share a word without being neighbours simply issue
+// their own atomics.
+__device__ __forceinline__ void keep_rows(const RowPlan &rp, bool valid, uint32_t g, uint32_t id) {
+  uint32_t row = 0;
+  if (valid) {
+    row = rp.row_of_cur[id];
+    rp.parent_next[g] = row;
+    rp.row_of_next[g] = row;
+  }
+  const uint32_t word = valid ? row / 32 : 0xFFFFFFFFu;        // no bitmap has that many words
+  uint32_t bits = valid ? 1u << (row % 32) : 0u;
+  // after the steps 1, 2, 4, 8 a lane holds the bits of the lanes above it up to the end of its run
+  { const uint32_t w = from_lane_above<1>(~word, word), b = from_lane_above<1>(0u, bits); bits |= w == word ? b : 0u; }
+  { const uint32_t w = from_lane_above<2>(~word, word), b = from_lane_above<2>(0u, bits); bits |= w == word ? b : 0u; }
+  { const uint32_t w = from_lane_above<4>(~word, word), b = from_lane_above<4>(0u, bits); bits |= w == word ? b : 0u; }
+  { const uint32_t w = from_lane_above<8>(~word, word), b = from_lane_above<8>(0u, bits); bits |= w == word ? b : 0u; }
+  // the lane below (DPP row_shr:1) has another word, or there is none: this lane starts a run
+  const uint32_t below = static_cast<uint32_t>(
+      __builtin_amdgcn_update_dpp(static_cast<int>(~word), static_cast<int>(word), 0x111, 0xF, 0xF, false));
+  if (valid && below != word) atomicOr(&rp.occupied[word], bits);
 }
 
 // Bitonic sorting network over n (a power of two) keys by one workgroup, ascending
@@ -88,9 +113,10 @@ __global__ __launch_bounds__(kSortThreads) void rank_pool_kernel(const double *f
     if (n != 0) atomicAdd(&below[t % kRankPoolPer], n);
   }
   __syncthreads();
-  if (t < kRankPoolPer && mine < P && below[t] < K) {
-    sel[below[t]] = static_cast<int32_t>(mine);
-    keep_row(rp, below[t], mine);
+  if (t < kRankPoolPer) {                              // one whole wave
+    const bool in = mine < P && below[t] < K;
+    if (in) sel[below[t]] = static_cast<int32_t>(mine);
+    keep_rows(rp, in, below[t], mine);
   }
 }
 
@@ -137,51 +163,59 @@ __device__ __forceinline__ void rank_bucket(K64 *sk, I32 *si, const uint64_t *ek
   const uint32_t tid = threadIdx.x, nb = bk.nb;
   // offspring i: rank = offspring before it + survivors with score <= its score (a survivor
   // wins a tie: smaller slot)
-  for (uint32_t i = tid; i < n; i += kBucketThreads) {
-    const uint64_t key = sk[i];
-    const uint32_t id = si[i];
-    uint32_t below = i;
-    if (!sorted) {
-      below = 0;                                     // padding keys are never below a real one
-      for (uint32_t q = 0; q < npad; q += 8) {
+  for (uint32_t base = 0; base < n; base += kBucketThreads) {   // whole waves go round together
+    const uint32_t i = base + tid;
+    uint32_t g = K, id = 0;
+    if (i < n) {
+      const uint64_t key = sk[i];
+      id = si[i];
+      uint32_t below = i;
+      if (!sorted) {
+        below = 0;                                   // padding keys are never below a real one
+        for (uint32_t q = 0; q < npad; q += 8) {
 #pragma unroll
-        for (int u = 0; u < 8; ++u) below += key_less(sk[q + u], si[q + u], key, id) ? 1u : 0u;
+          for (int u = 0; u < 8; ++u) below += key_less(sk[q + u], si[q + u], key, id) ? 1u : 0u;
+        }
       }
-    }
-    uint32_t lo = 0, hi = ne;
-    while (lo < hi) {
-      const uint32_t mid = (lo + hi) >> 1;
-      if (ek[mid] <= key) lo = mid + 1; else hi = mid;
-    }
-    const uint32_t g = off + below + lo;
-    if (g < K) {
-      sel[g] = static_cast<int32_t>(id);
-      keep_row(rp, g, id);
-      note_rank(g, key, K, nb, bk.split_next, bk.thresh_next);
-    }
-  }
-  // survivor e: rank = e + offspring with a strictly smaller score
-  for (uint32_t e = tid; e < ne; e += kBucketThreads) {
-    const uint64_t key = ek[e];
-    uint32_t lo = 0;
-    if (!sorted) {
-      for (uint32_t q = 0; q < npad; q += 8) {
-#pragma unroll
-        for (int u = 0; u < 8; ++u) lo += sk[q + u] < key ? 1u : 0u;
-      }
-    } else {
-      uint32_t hi = n;
+      uint32_t lo = 0, hi = ne;
       while (lo < hi) {
         const uint32_t mid = (lo + hi) >> 1;
-        if (sk[mid] < key) lo = mid + 1; else hi = mid;
+        if (ek[mid] <= key) lo = mid + 1; else hi = mid;
+      }
+      g = off + below + lo;
+      if (g < K) {
+        sel[g] = static_cast<int32_t>(id);
+        note_rank(g, key, K, nb, bk.split_next, bk.thresh_next);
       }
     }
-    const uint32_t g = off + e + lo;
-    if (g < K) {
-      sel[g] = static_cast<int32_t>(e0 + e);
-      keep_row(rp, g, e0 + e);
-      note_rank(g, key, K, nb, bk.split_next, bk.thresh_next);
+    keep_rows(rp, g < K, g, id);
+  }
+  // survivor e: rank = e + offspring with a strictly smaller score
+  for (uint32_t base = 0; base < ne; base += kBucketThreads) {
+    const uint32_t e = base + tid;
+    uint32_t g = K;
+    if (e < ne) {
+      const uint64_t key = ek[e];
+      uint32_t lo = 0;
+      if (!sorted) {
+        for (uint32_t q = 0; q < npad; q += 8) {
+#pragma unroll
+          for (int u = 0; u < 8; ++u) lo += sk[q + u] < key ? 1u : 0u;
+        }
+      } else {
+        uint32_t hi = n;
+        while (lo < hi) {
+          const uint32_t mid = (lo + hi) >> 1;
+          if (sk[mid] < key) lo = mid + 1; else hi = mid;
+        }
+      }
+      g = off + e + lo;
+      if (g < K) {
+        sel[g] = static_cast<int32_t>(e0 + e);
+        note_rank(g, key, K, nb, bk.split_next, bk.thresh_next);
+      }
     }
+    keep_rows(rp, g < K, g, e0 + e);
   }
 }
 
@@ -399,25 +433,33 @@ __global__ __launch_bounds__(kSortBucketThreads) void bucket_sort_kernel(BucketA
     }
     if (e < n && cnt != 0) atomicAdd(&below[e], cnt);
     __syncthreads();
-    if (tid < n && off + below[tid] < K) {
-      sel[off + below[tid]] = static_cast<int32_t>(si[tid]);
-      keep_row(rp, off + below[tid], si[tid]);
+    {
+      const bool in = tid < n && off + below[tid < n ? tid : 0] < K;   // n <= kCountSort < the threads
+      const uint32_t g = in ? off + below[tid] : K, id = in ? si[tid] : 0u;
+      if (in) sel[g] = static_cast<int32_t>(id);
+      keep_rows(rp, in, g, id);
     }
   } else if (in_lds) {
     gather_bucket(sk, si, bk, b, n, npad, &spill_cursor);
     bitonic_sort(sk, si, npad);
-    for (uint32_t e = tid; e < n && off + e < K; e += kSortBucketThreads) {
-      sel[off + e] = static_cast<int32_t>(si[e]);
-      keep_row(rp, off + e, si[e]);
+    for (uint32_t base = 0; base < n && off + base < K; base += kSortBucketThreads) {
+      const uint32_t e = base + tid;
+      const bool in = e < n && off + e < K;
+      const uint32_t id = in ? si[e] : 0u;
+      if (in) sel[off + e] = static_cast<int32_t>(id);
+      keep_rows(rp, in, off + e, id);
     }
   } else {                                           // oversized bucket: same network in global memory
     uint64_t *pk = bk.pool_keys + pool_base;
     uint32_t *pi = bk.pool_idx + pool_base;
     gather_bucket(pk, pi, bk, b, n, npad, &spill_cursor);
     bitonic_sort(pk, pi, npad);
-    for (uint32_t e = tid; e < n && off + e < K; e += kSortBucketThreads) {
-      sel[off + e] = static_cast<int32_t>(pi[e]);
-      keep_row(rp, off + e, pi[e]);
+    for (uint32_t base = 0; base < n && off + base < K; base += kSortBucketThreads) {
+      const uint32_t e = base + tid;
+      const bool in = e < n && off + e < K;
+      const uint32_t id = in ? pi[e] : 0u;
+      if (in) sel[off + e] = static_cast<int32_t>(id);
+      keep_rows(rp, in, off + e, id);
     }
   }
 }
