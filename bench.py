@@ -24,7 +24,7 @@ HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published peak
 
 # HBM bytes per evolve launch on the stress workload from rocprofv3 --pmc FETCH_SIZE and
 # WRITE_SIZE (see profiles/), valid only for the kernel source with this hash.
-MEASURED_TRAFFIC = {"source_sha256": "bb4b30601c43893001dcba0ee01e2e80794e7a57f1bd2312fe2f7ebdae936aed", "bytes_per_launch": 802793926}
+MEASURED_TRAFFIC = {"source_sha256": "e9d81364773f1cf0cc269181a542b992b7978dba02948547dbb9499219ac3215", "bytes_per_launch": 802786829}
 
 
 def evolve_source_hash() -> str:

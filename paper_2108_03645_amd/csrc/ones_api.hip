@@ -42,7 +42,7 @@ int guarded(F &&body) noexcept {
 size_t align_up(size_t v) { return (v + 255) & ~static_cast<size_t>(255); }
 
 struct Layout {
-  size_t genes, fit_row, row_of[2], parent_row[2], occupied[2], sel, split, thresh, bcount[2], bkeys, bidx, skeys, sidx, sbucket, pkeys, pidx, cstart, cmax, info, abl, cc, d, Y, terms;
+  size_t genes, fit_row, row_of[2], parent_row[2], occupied[2], sel, split, thresh, bcount[2], bkeys, bidx, skeys, sidx, sbucket, pkeys, pidx, cstart, cmax, info, abl, cc, d, Y[2], terms[2];
   size_t rawinfo, changed, ra, rc, rd, rY, alpha, beta, processed, time_rank, best_batch, best_gpus, best_fit, place_slot, place_batch, total;
 };
 
@@ -92,8 +92,10 @@ Layout make_layout(uint32_t P, uint32_t Jp, uint32_t G) {
   L.pkeys = take(static_cast<size_t>(bp.pool) * 8);
   L.pidx = take(static_cast<size_t>(bp.pool) * 4);
   L.cstart = take(Jp * 4); L.cmax = take(Jp * 4); L.info = take(Jp * 4);
-  L.abl = take(Jp * 8); L.cc = take(Jp * 8); L.d = take(Jp * 8); L.Y = take(Jp * 8);
-  L.terms = take(static_cast<size_t>(Jp) * kMaxTermEntries * 8);
+  L.abl = take(Jp * 8); L.cc = take(Jp * 8); L.d = take(Jp * 8);
+  // remaining work and the term table built from it, twice: under probability sampling the draw
+  // of the coming generation is made while the last one is still being ranked
+  for (int k = 0; k < 2; ++k) { L.Y[k] = take(Jp * 8); L.terms[k] = take(static_cast<size_t>(Jp) * kMaxTermEntries * 8); }
   L.rawinfo = take(Jp * 4); L.changed = take(Jp * 4);
   L.ra = take(Jp * 8); L.rc = take(Jp * 8); L.rd = take(Jp * 8); L.rY = take(Jp * 8);
   L.alpha = take(Jp * 8); L.beta = take(Jp * 8); L.processed = take(Jp * 8);
@@ -195,6 +197,8 @@ struct ones_ctx {
   bool no_schedule;           // ... by ones_set_jobs: the winner is not a schedule under the new table
   bool new_jobs_first;        // option: the generation after ones_set_jobs serves the arrived jobs first
   bool sampling;              // remaining work drawn per generation (Alg. 1) instead of the table's
+  int y_cur;                  // which remaining-work array and term table the last generation was scored with
+  int64_t drawn_for;          // the other pair already holds the draw of this generation (0: it does not)
   bool per_gpu;               // uniform crossover over the GPUs instead of the jobs (ones_set_crossover)
   bool has_times;             // executed times known (ones_set_processed_time): their ranks are on the device
   BucketPlan bp;              // nb == 0: pool small enough for the single-chunk sort
@@ -211,11 +215,12 @@ struct ones_ctx {
   size_t evolve_used, select_used;
 
   template <typename T> T *at(size_t off) const { return reinterpret_cast<T *>(ws + off); }
-  JobTable table() const {
+  JobTable table(int which) const {     // with the remaining work and term table number `which`
     return JobTable{at<uint32_t>(L.cstart), at<uint32_t>(L.cmax), at<uint32_t>(L.info),
-                    at<double>(L.abl), at<double>(L.cc), at<double>(L.d), at<double>(L.Y),
-                    at<double>(L.terms), term_E};
+                    at<double>(L.abl), at<double>(L.cc), at<double>(L.d), at<double>(L.Y[which]),
+                    at<double>(L.terms[which]), term_E};
   }
+  JobTable table() const { return table(y_cur); }
 };
 
 namespace {
@@ -273,7 +278,12 @@ int run_generation(ones_ctx *c, uint32_t t) {
   a.row_of = c->at<uint32_t>(c->L.row_of[next]);
   a.occupied = c->at<uint32_t>(c->L.occupied[c->cur]);          // set by the last selection
   a.occupied_other = c->at<uint32_t>(c->L.occupied[c->cur ^ 1]);
-  a.tab = c->table();
+  // Under probability sampling this generation is scored with the other remaining-work array
+  // and term table: the previous generation's selection has filled them already, or the draw
+  // is made now (first sampled generation, or the inputs changed since).
+  const bool sampled = t != 0 && c->sampling;
+  const int y_this = sampled ? c->y_cur ^ 1 : c->y_cur;
+  a.tab = c->table(y_this);
   a.G = c->G; a.P = c->P; a.K = c->K; a.Jp = c->Jp;
   a.key0 = static_cast<uint32_t>(c->cfg.seed);
   a.key1 = static_cast<uint32_t>(c->cfg.seed >> 32);
@@ -281,7 +291,6 @@ int run_generation(ones_ctx *c, uint32_t t) {
   // same table: the survivors are fixed points of the repair.  Under probability sampling their
   // scores still change with every draw of the remaining work, so they are scored again.
   const bool same_table = t != 0 && !c->table_changed;
-  const bool sampled = t != 0 && c->sampling;
   a.rescore = same_table && sampled ? 1u : 0u;
   a.new_first = c->new_jobs_first && c->no_schedule ? 1u : 0u;   // the table's "arrived" marks are fresh
   a.per_gpu = c->per_gpu ? 1u : 0u;
@@ -309,10 +318,9 @@ int run_generation(ones_ctx *c, uint32_t t) {
   rp.occupied = c->at<uint32_t>(c->L.occupied[next]);
   int rc;
   if ((rc = timed(c, c->evolve_ev, c->evolve_used, true))) return rc;
-  if (sampled) {
-    const Progress pr{c->at<double>(c->L.alpha), c->at<double>(c->L.beta), c->at<double>(c->L.processed)};
+  const Progress pr{c->at<double>(c->L.alpha), c->at<double>(c->L.beta), c->at<double>(c->L.processed)};
+  if (sampled && c->drawn_for != static_cast<int64_t>(t))
     HIP_TRY(launch_sample_remaining(pr, a.tab, c->Jn, c->Jp, a.key0, a.key1, t, c->stream));
-  }
   HIP_TRY(launch_evolve(a, static_cast<int>(c->R), same_table, c->n_cus, c->stream));
   if ((rc = timed(c, c->evolve_ev, c->evolve_used, false))) return rc;
   if ((rc = timed(c, c->select_ev, c->select_used, true))) return rc;
@@ -325,7 +333,12 @@ int run_generation(ones_ctx *c, uint32_t t) {
     BucketArgs store = a.bk;                       // same storage; always the first counter set
     store.nb = c->bp.nb;
     store.count = c->at<uint32_t>(c->L.bcount[0]);
-    HIP_TRY(launch_select(a.fit_row, rp, c->P, c->K, store, c->at<int32_t>(c->L.sel), c->stream));
+    // the workgroups behind the ranking ones draw the remaining work of generation t + 1 into the
+    // pair of arrays this generation did not use
+    SampleNext draw{pr, c->table(y_this ^ 1), c->Jn, c->Jp, a.key0, a.key1, t + 1, 0u};
+    draw.on = sampled && t != 0xFFFFFFFFu ? 1u : 0u;
+    HIP_TRY(launch_select(a.fit_row, rp, c->P, c->K, store, c->at<int32_t>(c->L.sel), draw, c->stream));
+    if (draw.on) c->drawn_for = static_cast<int64_t>(t) + 1;
     if (c->bp.nb != 0 && !sampled)   // splitters for the bucketed generations that follow; clears both
                                      // counter sets.  Under sampling no bucketed generation can follow.
       HIP_TRY(launch_splitters(a.fit_row, a.row_of, c->at<int32_t>(c->L.sel), c->K, c->bp.nb,
@@ -335,6 +348,7 @@ int run_generation(ones_ctx *c, uint32_t t) {
   }
   if ((rc = timed(c, c->select_ev, c->select_used, false))) return rc;
   c->cur = next;
+  c->y_cur = y_this;
   c->table_changed = false;
   c->no_schedule = false;
   c->profile_tick += 1;
@@ -392,6 +406,8 @@ static int init_impl(ones_ctx **out, const ones_config *cfg, const ones_jobs *jo
   c->no_schedule = false;
   c->new_jobs_first = false;
   c->sampling = false;
+  c->y_cur = 0;
+  c->drawn_for = 0;
   c->has_times = false;
   c->per_gpu = false;
   c->bp = bucket_plan(c->P);
@@ -434,6 +450,7 @@ static int set_jobs_impl(ones_ctx *c, const ones_jobs *jobs) {
   c->ids = h.id;
   c->table_changed = true;
   c->no_schedule = true;
+  c->drawn_for = 0;            // a draw made ahead built its term table from the old job table
   return ONES_OK;
 }
 
@@ -442,11 +459,12 @@ static int set_progress_impl(ones_ctx *c, const double *alpha, const double *bet
   if (!alpha && !beta && !processed) {
     if (c->sampling) {
       // back to the table's remaining work (still staged on the device); every score is stale
-      HIP_TRY(hipMemcpyAsync(c->ws + c->L.Y, c->ws + c->L.rY, static_cast<size_t>(c->Jp) * 8,
+      HIP_TRY(hipMemcpyAsync(c->ws + c->L.Y[c->y_cur], c->ws + c->L.rY, static_cast<size_t>(c->Jp) * 8,
                              hipMemcpyDeviceToDevice, c->stream));
       HIP_TRY(launch_build_terms(c->table(), c->Jp, c->stream));
       HIP_TRY(hipStreamSynchronize(c->stream));
       c->sampling = false;
+      c->drawn_for = 0;
       c->table_changed = true;
     }
     return ONES_OK;
@@ -468,6 +486,7 @@ static int set_progress_impl(ones_ctx *c, const double *alpha, const double *bet
                          hipMemcpyHostToDevice, c->stream));
   HIP_TRY(hipStreamSynchronize(c->stream));     // the staging buffer is free again
   c->sampling = true;
+  c->drawn_for = 0;            // a draw made ahead used the old parameters
   return ONES_OK;
 }
 
@@ -508,7 +527,7 @@ static int set_processed_time_impl(ones_ctx *c, const double *t_processed) {
 static int export_remaining_impl(ones_ctx *c, double *remaining_out) {
   if (!c || !remaining_out) return ONES_E_INVALID_ARG;
   HIP_TRY(hipStreamSynchronize(c->stream));
-  if (c->Jn) HIP_TRY(hipMemcpy(remaining_out, c->ws + c->L.Y, static_cast<size_t>(c->Jn) * 8, hipMemcpyDeviceToHost));
+  if (c->Jn) HIP_TRY(hipMemcpy(remaining_out, c->ws + c->L.Y[c->y_cur], static_cast<size_t>(c->Jn) * 8, hipMemcpyDeviceToHost));
   return ONES_OK;
 }
 

@@ -152,6 +152,14 @@ struct Progress {
 };
 hipError_t launch_sample_remaining(const Progress &pr, const JobTable &tab, uint32_t Jn, uint32_t Jp,
                                    uint32_t key0, uint32_t key1, uint32_t t, hipStream_t s);
+// The same draw for the coming generation t, made by extra workgroups of the general selection's
+// first kernel (into tab.Y and tab.terms, which must not be the arrays the finished generation
+// was scored with).  on == 0: no draw.
+struct SampleNext {
+  Progress pr;
+  JobTable tab;
+  uint32_t Jn, Jp, key0, key1, t, on;
+};
 // slots: the n_changed slots whose genes are set to "waiting" in every one of the rows
 hipError_t launch_reset_slots(int32_t *genes, const uint32_t *slots, uint32_t n_changed, uint32_t rows, uint32_t Jp,
                               hipStream_t s);
@@ -173,7 +181,7 @@ inline hipError_t launch_evolve(const EvolveArgs &a, int rows, bool same_table, 
 // arrays, split as scratch for the splitters, nb * seg entries of bucket space); used for pools
 // above kSortChunk slots.
 hipError_t launch_select(const double *fit_row, const RowPlan &rp, uint32_t P, uint32_t K, const BucketArgs &store,
-                         int32_t *sel, hipStream_t s);
+                         int32_t *sel, const SampleNext &next, hipStream_t s);
 hipError_t launch_zero_words(uint32_t *words, uint32_t n, hipStream_t s);
 hipError_t launch_bucket_select(const double *fit_row, const uint32_t *parent_row, const BucketArgs &bk,
                                 const RowPlan &rp, uint32_t K, uint32_t *count_next, int32_t *sel, hipStream_t s);

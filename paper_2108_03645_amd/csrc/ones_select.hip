@@ -4,6 +4,7 @@
 // Order: ascending (score, pool slot).  A score is a non-negative fp64, so its bit pattern
 // read as an unsigned 64-bit integer orders the same way; ties fall to the smaller slot.
 #include "ones_device.h"
+#include "ones_sample.h"
 
 #pragma clang fp contract(off)
 
@@ -83,7 +84,13 @@ __device__ __forceinline__ uint32_t pow2_at_least(uint32_t v) {
 // wave reads one LDS address at a time, a broadcast); ranks below K are survivors.
 constexpr int kRankPoolPer = 64;
 __global__ __launch_bounds__(kSortThreads) void rank_pool_kernel(const double *fit_row, RowPlan rp, uint32_t P,
-                                                                uint32_t K, int32_t *sel) {
+                                                                uint32_t K, int32_t *sel, SampleNext next,
+                                                                uint32_t rank_blocks) {
+  if (blockIdx.x >= rank_blocks) {                     // the workgroups behind the ranking ones draw the next remaining work
+    sample_remaining_slot(next.pr, next.tab, next.Jn, next.key0, next.key1, next.t,
+                          (blockIdx.x - rank_blocks) * kSortThreads + threadIdx.x);
+    return;
+  }
   const uint32_t *row_of = rp.row_of_cur;
   __shared__ uint64_t sk[kSortChunk];
   __shared__ uint32_t below[kRankPoolPer];
@@ -307,7 +314,12 @@ constexpr int kSampleThreads = 1024;
 constexpr int kSampleMax = 2 * kMaxBuckets;
 __global__ __launch_bounds__(kSampleThreads) void sample_splitters_kernel(const double *fit_row, const uint32_t *row_of,
                                                                          uint32_t P, uint32_t sample,
-                                                                         uint64_t *split, uint32_t *count) {
+                                                                         uint64_t *split, uint32_t *count, SampleNext next) {
+  if (blockIdx.x >= sample / kLanes) {                 // the workgroups behind the ranking ones draw the next remaining work
+    sample_remaining_slot(next.pr, next.tab, next.Jn, next.key0, next.key1, next.t,
+                          (blockIdx.x - sample / kLanes) * kSampleThreads + threadIdx.x);
+    return;
+  }
   __shared__ uint64_t sk[kSampleMax];
   __shared__ uint32_t rank[kLanes];
   const uint32_t t = threadIdx.x;
@@ -326,7 +338,7 @@ __global__ __launch_bounds__(kSampleThreads) void sample_splitters_kernel(const 
   if (t < kLanes) rank[t] = 0;
   __syncthreads();
   constexpr uint32_t kWaves = kSampleThreads / kLanes;
-  const uint32_t mine = blockIdx.x * kLanes + t % kLanes;              // sample = 64 * gridDim.x
+  const uint32_t mine = blockIdx.x * kLanes + t % kLanes;              // sample = 64 * the ranking workgroups
   const uint32_t part = sample / kWaves, from = (t / kLanes) * part;   // sample is a multiple of 128
   const uint64_t key = sk[mine];
   uint32_t below = 0;
@@ -623,10 +635,14 @@ hipError_t launch_zero_words(uint32_t *words, uint32_t n, hipStream_t s) {
 }
 
 hipError_t launch_select(const double *fit, const RowPlan &rp, uint32_t P, uint32_t K, const BucketArgs &store,
-                         int32_t *sel, hipStream_t s) {
+                         int32_t *sel, const SampleNext &next, hipStream_t s) {
+  // workgroups of 1024 threads behind the ranking ones, 64 slots each, for the next draw
+  const uint32_t draw_blocks = next.on ? next.Jp * kLanesPerSlot / kSortThreads : 0u;
+  static_assert(kSortThreads == kSampleThreads && kSortThreads % (kLanes * kLanesPerSlot) == 0, "64 slots per workgroup");
   if (P <= static_cast<uint32_t>(kSortChunk)) {
-    hipLaunchKernelGGL(rank_pool_kernel, dim3((P + kRankPoolPer - 1) / kRankPoolPer), dim3(kSortThreads), 0, s, fit, rp,
-                       P, K, sel);
+    const uint32_t rank_blocks = (P + kRankPoolPer - 1) / kRankPoolPer;
+    hipLaunchKernelGGL(rank_pool_kernel, dim3(rank_blocks + draw_blocks), dim3(kSortThreads), 0, s, fit, rp, P, K, sel,
+                       next, rank_blocks);
     return hipGetLastError();
   }
   // about 64 candidates per bucket, two sample points per bucket
@@ -636,8 +652,8 @@ hipError_t launch_select(const double *fit, const RowPlan &rp, uint32_t P, uint3
   const uint32_t sample = 2 * nb;
   bk.seg = static_cast<uint32_t>(static_cast<size_t>(store.nb) * store.seg / nb);   // the same storage, re-divided
   bk.nb = nb;
-  hipLaunchKernelGGL(sample_splitters_kernel, dim3(sample / kLanes), dim3(kSampleThreads), 0, s, fit, rp.row_of_cur,
-                     P, sample, const_cast<uint64_t *>(bk.split), bk.count);
+  hipLaunchKernelGGL(sample_splitters_kernel, dim3(sample / kLanes + draw_blocks), dim3(kSampleThreads), 0, s, fit,
+                     rp.row_of_cur, P, sample, const_cast<uint64_t *>(bk.split), bk.count, next);
   hipError_t rc = hipGetLastError();
   if (rc != hipSuccess) return rc;
   hipLaunchKernelGGL(drop_all_kernel, dim3((P + kDropThreads - 1) / kDropThreads), dim3(kDropThreads), 0, s, fit,
