@@ -295,13 +295,14 @@ class RefSearch:
         _check(lib().ones_ref_placement(self._h, slot.ctypes.data, batch.ctypes.data))
         return slot[:self.n_gpus], batch[:self.n_gpus]
 
-    def export(self):
-        genes = np.zeros((self.population, self.jp), np.int32)
+    def export(self, genes=True):
+        g = np.zeros((self.population, self.jp), np.int32) if genes else None
         fit = np.zeros(self.population, np.float64)
         sel = np.zeros(self.population // 4, np.int32)
         t = C.c_int64(0)
-        _check(lib().ones_ref_export(self._h, genes.ctypes.data, fit.ctypes.data, sel.ctypes.data, C.byref(t)))
-        return genes, fit, sel, t.value
+        _check(lib().ones_ref_export(self._h, g.ctypes.data if genes else None, fit.ctypes.data, sel.ctypes.data,
+                                     C.byref(t)))
+        return g, fit, sel, t.value
 
     def compose_slot(self, p):
         g = np.zeros(self.jp, np.int32)

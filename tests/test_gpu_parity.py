@@ -30,12 +30,14 @@ def say(msg):
     sys.stdout.flush()
 
 
-def assert_same_state(gpu, cpu, where):
-    g_genes, g_fit, g_sel, g_t = gpu.export()
-    c_genes, c_fit, c_sel, c_t = cpu.export()
+def assert_same_state(gpu, cpu, where, genes=True):
+    """genes=False leaves the genomes out (the scores and the survivor list still cover every candidate)."""
+    g_genes, g_fit, g_sel, g_t = gpu.export(genes=genes)
+    c_genes, c_fit, c_sel, c_t = cpu.export(genes=genes)
     assert g_t == c_t, where
-    bad = np.flatnonzero((g_genes != c_genes).any(axis=1))
-    assert bad.size == 0, f"{where}: genomes differ in {bad.size} slots, first {bad[:5]}"
+    if genes:
+        bad = np.flatnonzero((g_genes != c_genes).any(axis=1))
+        assert bad.size == 0, f"{where}: genomes differ in {bad.size} slots, first {bad[:5]}"
     rel = np.abs(g_fit - c_fit) / np.maximum(np.abs(c_fit), 1e-300)
     assert rel.max() <= 1e-12 if rel.size else True, f"{where}: fitness off by {rel.max()}"
     assert np.array_equal(g_sel, c_sel), f"{where}: survivor lists differ"
@@ -300,24 +302,87 @@ def test_two_contexts_and_a_side_stream(ones, ref):
     assert_same_state(b, cb, "context b (side stream)")
 
 
-def test_full_size_stress_matches_oracle(ones, ref):
-    """The benchmark's own launch configuration: 2048 jobs, pool 65536.  The oracle runs the
-    same three steps on all host threads (about 2 s per generation on 8 cores)."""
+# ---- the five configurations at their stated size and length ----
+
+def host_threads():
     import os
-    cl, jobs = W.stress()
-    ref.set_threads(min(16, os.cpu_count() or 1))
+    return min(16, os.cpu_count() or 1)
+
+
+def test_online_config_at_full_size(ones, ref):
+    """64 GPUs, 64 slots, pool 2048, 200 scheduling epochs of 20 warm-started generations each;
+    every epoch the winner drives the simulated cluster and the job table is replaced.  The
+    first epoch in which the two sides differ fails the test and is named."""
+    sims = [W.OnlineSequence(), W.OnlineSequence()]
+    cl = sims[0].cluster
+    assert (cl.population, cl.n_slots, cl.n_gpus, cl.epochs, cl.generations) == (2048, 64, 64, 200, 20)
+    say(f"[parity] online at full size: P={cl.population} epochs={cl.epochs} gens/epoch={cl.generations} seed={cl.seed}")
+    ref.set_threads(host_threads())
     try:
-        run_pair(ones, ref, cl, jobs, 2, 1, "stress full size")
+        gpu = ones.Search(cl, sims[0].jobs)
+        cpu = ref.RefSearch(cl, sims[1].jobs)
+        busy = []
+        for epoch in range(cl.epochs):
+            gpu.generation(cl.generations); cpu.generation(cl.generations)
+            assert_same_state(gpu, cpu, f"online, first divergent epoch {epoch} (after its generations)")
+            gb, gg, gf = gpu.best(); cb, cg, cf = cpu.best()
+            assert gb.tolist() == cb.tolist() and gg.tolist() == cg.tolist() and gf == cf, f"winner differs in epoch {epoch}"
+            sims[0].advance(gb); sims[1].advance(cb)
+            assert sims[0].jobs.sha256() == sims[1].jobs.sha256()
+            busy.append(int(sims[0].jobs.active.sum()))
+            gpu.set_jobs(sims[0].jobs); cpu.set_jobs(sims[1].jobs)
+            assert_same_state(gpu, cpu, f"online, first divergent epoch {epoch} (after the table change)")
+            if epoch % 50 == 49:
+                say(f"[parity] online at full size: epoch {epoch + 1} done, {sims[0].completed} jobs completed")
+        assert gpu.export(genes=False)[3] == cl.epochs * cl.generations
+        assert sims[0].completed > 20 and min(busy) < max(busy)          # jobs came and went
+        gpu.close(); cpu.close()
     finally:
         ref.set_threads(1)
 
 
-def test_full_size_large_matches_oracle(ones, ref):
-    import os
+@pytest.mark.parametrize("mode", ["plain", "sampled", "crossover over gpus"])
+def test_large_config_at_full_length(ones, ref, mode):
+    """1024 GPUs, 512 jobs, pool 16384: all 50 generations, every one compared in full."""
     cl, jobs = W.large()
-    ref.set_threads(min(16, os.cpu_count() or 1))
+    assert (cl.population, cl.n_slots, cl.n_gpus, cl.generations) == (16384, 512, 1024, 50)
+    say(f"[parity] large at full length ({mode}): P={cl.population} gens={cl.generations} seed={cl.seed}")
+    ref.set_threads(host_threads())
     try:
-        run_pair(ones, ref, cl, jobs, 3, 1, "large full size")
+        gpu, cpu = ones.Search(cl, jobs), ref.RefSearch(cl, jobs)
+        for s in (gpu, cpu):
+            if mode == "sampled":
+                s.set_progress(*W.progress(cl.n_slots, seed=cl.seed))
+            s.set_crossover(per_gpu=mode == "crossover over gpus")
+        assert_same_state(gpu, cpu, "large generation 0")
+        for gen in range(1, cl.generations + 1):
+            gpu.generation(1); cpu.generation(1)
+            assert_same_state(gpu, cpu, f"large ({mode}) generation {gen}")
+        gb, cb = gpu.best(), cpu.best()
+        assert gb[0].tolist() == cb[0].tolist() and gb[1].tolist() == cb[1].tolist() and gb[2] == cb[2]
+        gpu.close(); cpu.close()
+    finally:
+        ref.set_threads(1)
+
+
+def test_stress_config_at_full_length(ones, ref):
+    """4096 GPUs, 2048 jobs, pool 65536, the benchmark's launch configuration: all 20 generations.
+    Scores (bit for bit) and survivor lists of every generation; the 512 MiB of genomes at
+    generations 0, 1, 5, 10, 15 and 20."""
+    cl, jobs = W.stress()
+    assert (cl.population, cl.n_slots, cl.n_gpus, cl.generations) == (65536, 2048, 4096, 20)
+    say(f"[parity] stress at full length: P={cl.population} gens={cl.generations} seed={cl.seed}")
+    ref.set_threads(host_threads())
+    try:
+        gpu, cpu = ones.Search(cl, jobs), ref.RefSearch(cl, jobs)
+        assert_same_state(gpu, cpu, "stress generation 0")
+        for gen in range(1, cl.generations + 1):
+            gpu.generation(1); cpu.generation(1)
+            assert_same_state(gpu, cpu, f"stress generation {gen}", genes=gen in (1, 5, 10, 15, 20))
+            say(f"[parity] stress at full length: generation {gen} matches")
+        gb, cb = gpu.best(), cpu.best()
+        assert gb[0].tolist() == cb[0].tolist() and gb[1].tolist() == cb[1].tolist() and gb[2] == cb[2]
+        gpu.close(); cpu.close()
     finally:
         ref.set_threads(1)
 
