@@ -21,17 +21,24 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=o
          *os.environ.get("ONES_EXTRA_FLAGS", "").split()]
 
 
-def _compile(unit) -> str:
+HEADERS = [os.path.join(CSRC, "ones_device.h"), os.path.join(CSRC, "ones_sample.h"), os.path.join(INCLUDE, "ones.h"),
+           os.path.abspath(__file__)]
+
+
+def _compile(unit, force: bool = True) -> str:
     src, obj, extra = unit
-    obj = os.path.join(CSRC, obj)
-    subprocess.check_call([HIPCC, *FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", obj])
+    obj, src = os.path.join(CSRC, obj), os.path.join(CSRC, src)
+    fresh = os.path.exists(obj) and all(os.path.getmtime(f) <= os.path.getmtime(obj) for f in [src, *HEADERS])
+    if force or not fresh:
+        subprocess.check_call([HIPCC, *FLAGS, *extra, "-c", src, "-o", obj])
     return obj
 
 
-def build(verbose: bool = True) -> str:
-    """Compile every source and link the shared library; returns its path."""
+def build(verbose: bool = True, force: bool = True) -> str:
+    """Compile every source (force=False: only those older than their inputs) and link the
+    shared library; returns its path."""
     with ThreadPoolExecutor(max_workers=min(8, len(UNITS))) as ex:
-        objs = list(ex.map(_compile, UNITS))
+        objs = list(ex.map(lambda u: _compile(u, force), UNITS))
     subprocess.check_call([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", LIB])
     if verbose:
         print(f"built {LIB}", file=sys.stderr)
@@ -39,4 +46,4 @@ def build(verbose: bool = True) -> str:
 
 
 if __name__ == "__main__":
-    build()
+    build(force="--changed" not in sys.argv)
