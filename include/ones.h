@@ -39,6 +39,7 @@ extern "C" {
 #define ONES_MAX_GPUS       1048576   /* cluster size |C|                              */
 #define ONES_MAX_POPULATION 1048576   /* pool size P                                   */
 #define ONES_MAX_PARAM      1e100     /* upper bound of a, c, d, remaining             */
+#define ONES_STATIC_SCRATCH_BYTES (16u << 20)  /* scratch of ones_generation_static, per GPU */
 
 enum {
   ONES_OK = 0,
@@ -49,8 +50,13 @@ enum {
   ONES_E_NONFINITE = -4,           /* NaN or infinity in a, c, d or remaining            */
   ONES_E_WORKSPACE_TOO_SMALL = -5, /* workspace_bytes < ones_workspace_bytes(cfg), or
                                       the workspace pointer is not 256-byte aligned      */
-  ONES_E_HIP = -6                  /* a HIP call failed, or host memory ran out;
-                                      ones_strerror says which (per thread)               */
+  ONES_E_HIP = -6,                 /* a HIP call failed, or host memory ran out;
+                                      ones_strerror says which (per thread).  After a launch
+                                      that failed in the middle of a generation the context is
+                                      inconsistent: ones_generation and ones_generation_static
+                                      keep returning this code until ones_destroy            */
+  ONES_E_STATIC_LIMIT = -7         /* ones_generation_static: the population needs more
+                                      scratch than ONES_STATIC_SCRATCH_BYTES                 */
 };
 
 typedef struct ones_ctx ones_ctx;  /* opaque, host side; owns no device memory */
@@ -158,8 +164,28 @@ int ones_export_remaining(ones_ctx *ctx, double *remaining_out);
  * on the stream. */
 int ones_generation(ones_ctx *ctx, int32_t n_generations);
 
+/* For callers that cannot allocate (code under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc): ones_generation with the selection's scratch (splitters, counters,
+ * bucket storage, spill list, sort pool) in a static device array of ONES_STATIC_SCRATCH_BYTES
+ * that the library's code object holds on every GPU it runs on until the process ends, instead of
+ * the caller's workspace.  The population, scores and survivor list stay in the workspace as
+ * always, and the results are those of ones_generation bit for bit; the two calls may be mixed
+ * freely on one context.  Calls no hipMalloc, hipFree, hipHostMalloc, event or other allocating
+ * routine and takes no HIP events (the measurement hook does not see these generations).
+ * Every context on a GPU shares that GPU's array, which keeps the last call's contents: each call
+ * sets up by itself what it reads (its first generation ranks the pool without relying on
+ * anything left there), so calls may follow each other in any order, but two calls that overlap
+ * in time on one GPU (different streams or threads) race.  Must be called with the context's
+ * device current.  Errors: ONES_E_STATIC_LIMIT when the population's scratch exceeds the array
+ * (populations up to 65536 fit; nothing is launched), ONES_E_INVALID_ARG (null context, negative
+ * count, another device current), ONES_E_HIP. */
+int ones_generation_static(ones_ctx *ctx, int32_t n_generations);
+
 /* The winner S* (Alg. 1: smallest score): global batch and GPU count per slot (HOST
- * arrays of n_slots entries, either may be NULL) and its score.  Synchronises. */
+ * arrays of n_slots entries, either may be NULL) and its score.  Between ones_set_jobs and the
+ * next generation no schedule exists under the new table: the call then returns the last
+ * winner as it is stored (slots that changed hands already set to waiting) with the score it had
+ * under the old table; run a generation first.  Synchronises. */
 int ones_best(ones_ctx *ctx, int32_t *batch_out, int32_t *gpus_out, double *fitness_out);
 
 /* The winner as the paper's mapping from (job, GPU) to a local batch (Eq. 1), packed the way

@@ -8,8 +8,14 @@
 #include <cstdio>
 #include <cstring>
 #include <memory>
+#include <mutex>
 #include <new>
 #include <vector>
+
+// Scratch of ones_generation_static: one copy per GPU, held by every device that runs the
+// library until the process ends.  Host code must not use this name as an address: the
+// per-device address comes from hipGetSymbolAddress (static_scratch_of below).
+static __device__ __align__(256) unsigned char scratch[ONES_STATIC_SCRATCH_BYTES];
 
 namespace {
 
@@ -41,9 +47,38 @@ int guarded(F &&body) noexcept {
 
 size_t align_up(size_t v) { return (v + 255) & ~static_cast<size_t>(255); }
 
+// Device address of the static scratch array on the current device, resolved once per device.
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+char *g_scratch_ptr[kMaxDevices];
+
+int static_scratch_of(int device, char **out) {
+  if (device < 0 || device >= kMaxDevices) {
+    snprintf(g_hip_msg, sizeof(g_hip_msg), "device ordinal %d outside 0..%d", device, kMaxDevices - 1);
+    return ONES_E_HIP;
+  }
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[device]) {
+    void *ptr = nullptr;
+    HIP_TRY(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));   // for the device that is current
+    g_scratch_ptr[device] = static_cast<char *>(ptr);
+  }
+  *out = g_scratch_ptr[device];
+  return ONES_OK;
+}
+
+// Scratch of the selection: nothing in it outlives the generations of one ones_generation call
+// except the splitters, the threshold and the cleared counter sets, which the next call may use
+// (ctx->splitters_valid).  Offsets from the block's base, which lies in the caller's workspace
+// or, for ones_generation_static, in the library's static array.
+struct ScratchLayout {
+  size_t split, thresh, bcount[2], bkeys, bidx, skeys, sidx, sbucket, pkeys, pidx, total;
+};
+
 struct Layout {
-  size_t genes, fit_row, row_of[2], parent_row[2], occupied[2], sel, split, thresh, bcount[2], bkeys, bidx, skeys, sidx, sbucket, pkeys, pidx, cstart, cmax, info, abl, cc, d, Y[2], terms[2];
+  size_t genes, fit_row, row_of[2], parent_row[2], occupied[2], sel, scratch, cstart, cmax, info, abl, cc, d, Y[2], terms[2];
   size_t rawinfo, changed, ra, rc, rd, rY, alpha, beta, processed, time_rank, best_batch, best_gpus, best_fit, place_slot, place_batch, total;
+  ScratchLayout S;
 };
 
 // Buckets of the selection: about 16 survivors each, at most kMaxBuckets.  A bucket stores eight
@@ -66,6 +101,24 @@ BucketPlan bucket_plan(uint32_t P) {
   return bp;
 }
 
+ScratchLayout make_scratch_layout(uint32_t P) {
+  ScratchLayout S;
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t at = off; off = align_up(off + bytes); return at; };
+  const BucketPlan bp = bucket_plan(P);
+  S.split = take(kMaxBuckets * 8); S.thresh = take(8);
+  S.bcount[0] = take(kBucketCounters * 4); S.bcount[1] = take(kBucketCounters * 4);
+  S.bkeys = take(static_cast<size_t>(bp.nb) * bp.seg * 8);
+  S.bidx = take(static_cast<size_t>(bp.nb) * bp.seg * 4);
+  S.skeys = take(static_cast<size_t>(bp.spill) * 8);
+  S.sidx = take(static_cast<size_t>(bp.spill) * 4);
+  S.sbucket = take(static_cast<size_t>(bp.spill) * 4);
+  S.pkeys = take(static_cast<size_t>(bp.pool) * 8);
+  S.pidx = take(static_cast<size_t>(bp.pool) * 4);
+  S.total = off;
+  return S;
+}
+
 Layout make_layout(uint32_t P, uint32_t Jp, uint32_t G) {
   Layout L;
   size_t off = 0;
@@ -80,17 +133,9 @@ Layout make_layout(uint32_t P, uint32_t Jp, uint32_t G) {
   L.occupied[0] = take((rows + 31) / 32 * 4);     // bitmaps of the rows the survivors keep
   L.occupied[1] = take((rows + 31) / 32 * 4);
   L.sel = take(static_cast<size_t>(P / 4) * 4);
-  // quantile buckets of the selection (pools larger than one sort chunk)
-  const BucketPlan bp = bucket_plan(P);
-  L.split = take(kMaxBuckets * 8); L.thresh = take(8);
-  L.bcount[0] = take(kBucketCounters * 4); L.bcount[1] = take(kBucketCounters * 4);
-  L.bkeys = take(static_cast<size_t>(bp.nb) * bp.seg * 8);
-  L.bidx = take(static_cast<size_t>(bp.nb) * bp.seg * 4);
-  L.skeys = take(static_cast<size_t>(bp.spill) * 8);
-  L.sidx = take(static_cast<size_t>(bp.spill) * 4);
-  L.sbucket = take(static_cast<size_t>(bp.spill) * 4);
-  L.pkeys = take(static_cast<size_t>(bp.pool) * 8);
-  L.pidx = take(static_cast<size_t>(bp.pool) * 4);
+  // the selection's scratch: splitters, counters, bucket storage, spill list, scratch pool
+  L.S = make_scratch_layout(P);
+  L.scratch = take(L.S.total);
   L.cstart = take(Jp * 4); L.cmax = take(Jp * 4); L.info = take(Jp * 4);
   L.abl = take(Jp * 8); L.cc = take(Jp * 8); L.d = take(Jp * 8);
   // remaining work and the term table built from it, twice: under probability sampling the draw
@@ -203,6 +248,11 @@ struct ones_ctx {
   bool has_times;             // executed times known (ones_set_processed_time): their ranks are on the device
   BucketPlan bp;              // nb == 0: pool small enough for the single-chunk sort
   int bucket_phase;           // which counter set the next bucketed generation fills
+  bool splitters_valid;       // the workspace's selection scratch holds the splitters of the current survivors
+                              // and cleared counter sets: a bucketed generation may follow
+  bool poisoned;              // a launch failed in the middle of a generation: the state is inconsistent
+  int device;                 // the device the context was created on
+  char *static_scratch;       // this device's copy of the library's static scratch array
   int n_cus;
   uint32_t term_E;            // entries per job of the term table
   int64_t t;                  // generation counter
@@ -267,8 +317,12 @@ int timed(ones_ctx *c, std::vector<EventPair> &pool, size_t &used, bool begin) {
   return ONES_OK;
 }
 
-int run_generation(ones_ctx *c, uint32_t t) {
+// scratch: base of the selection's scratch block (the workspace's, or the static array);
+// splitters_valid: that block holds the current survivors' splitters and cleared counters.
+int run_generation(ones_ctx *c, uint32_t t, char *scratch, bool &splitters_valid, bool events) {
   EvolveArgs a;
+  const ScratchLayout &S = c->L.S;
+  auto sc = [&](size_t off) { return scratch + off; };
   // generation 0 fills row_of[cur]; later generations complete the array whose first K entries
   // the last selection wrote
   const int next = t == 0 ? c->cur : c->cur ^ 1;
@@ -297,19 +351,19 @@ int run_generation(ones_ctx *c, uint32_t t) {
   a.stash_stride = 0;                                            // the launcher sets it
   a.time_rank = c->has_times ? c->at<uint32_t>(c->L.time_rank) : nullptr;
   // quantile buckets: only when the survivors reappear with the scores they had
-  const bool buckets = same_table && !sampled && c->bp.nb != 0;
+  const bool buckets = same_table && !sampled && c->bp.nb != 0 && splitters_valid;
   a.bk.nb = buckets ? c->bp.nb : 0;
   a.bk.seg = c->bp.seg;
-  a.bk.split = a.bk.split_next = c->at<uint64_t>(c->L.split);
-  a.bk.thresh = a.bk.thresh_next = c->at<uint64_t>(c->L.thresh);
-  a.bk.count = c->at<uint32_t>(c->L.bcount[c->bucket_phase]);
-  a.bk.keys = c->at<uint64_t>(c->L.bkeys);
-  a.bk.idx = c->at<uint32_t>(c->L.bidx);
-  a.bk.spill_keys = c->at<uint64_t>(c->L.skeys);
-  a.bk.spill_idx = c->at<uint32_t>(c->L.sidx);
-  a.bk.spill_bucket = c->at<uint32_t>(c->L.sbucket);
-  a.bk.pool_keys = c->at<uint64_t>(c->L.pkeys);
-  a.bk.pool_idx = c->at<uint32_t>(c->L.pidx);
+  a.bk.split = a.bk.split_next = reinterpret_cast<uint64_t *>(sc(S.split));
+  a.bk.thresh = a.bk.thresh_next = reinterpret_cast<uint64_t *>(sc(S.thresh));
+  a.bk.count = reinterpret_cast<uint32_t *>(sc(S.bcount[c->bucket_phase]));
+  a.bk.keys = reinterpret_cast<uint64_t *>(sc(S.bkeys));
+  a.bk.idx = reinterpret_cast<uint32_t *>(sc(S.bidx));
+  a.bk.spill_keys = reinterpret_cast<uint64_t *>(sc(S.skeys));
+  a.bk.spill_idx = reinterpret_cast<uint32_t *>(sc(S.sidx));
+  a.bk.spill_bucket = reinterpret_cast<uint32_t *>(sc(S.sbucket));
+  a.bk.pool_keys = reinterpret_cast<uint64_t *>(sc(S.pkeys));
+  a.bk.pool_idx = reinterpret_cast<uint32_t *>(sc(S.pidx));
   // the selection notes the rows the survivors keep: parents and first K slots of the next pool
   RowPlan rp;
   rp.row_of_cur = a.row_of;
@@ -317,36 +371,39 @@ int run_generation(ones_ctx *c, uint32_t t) {
   rp.row_of_next = c->at<uint32_t>(c->L.row_of[next ^ 1]);
   rp.occupied = c->at<uint32_t>(c->L.occupied[next]);
   int rc;
-  if ((rc = timed(c, c->evolve_ev, c->evolve_used, true))) return rc;
   const Progress pr{c->at<double>(c->L.alpha), c->at<double>(c->L.beta), c->at<double>(c->L.processed)};
   if (sampled && c->drawn_for != static_cast<int64_t>(t))
     HIP_TRY(launch_sample_remaining(pr, a.tab, c->Jn, c->Jp, a.key0, a.key1, t, c->stream));
+  if (events && (rc = timed(c, c->evolve_ev, c->evolve_used, true))) return rc;
   HIP_TRY(launch_evolve(a, static_cast<int>(c->R), same_table, c->n_cus, c->stream));
-  if ((rc = timed(c, c->evolve_ev, c->evolve_used, false))) return rc;
-  if ((rc = timed(c, c->select_ev, c->select_used, true))) return rc;
+  if (events && (rc = timed(c, c->evolve_ev, c->evolve_used, false))) return rc;
+  if (events && (rc = timed(c, c->select_ev, c->select_used, true))) return rc;
   if (buckets) {
     HIP_TRY(launch_bucket_select(a.fit_row, a.parent_row, a.bk, rp, c->K,
-                                 c->at<uint32_t>(c->L.bcount[c->bucket_phase ^ 1]), c->at<int32_t>(c->L.sel),
-                                 c->stream));
+                                 reinterpret_cast<uint32_t *>(sc(S.bcount[c->bucket_phase ^ 1])),
+                                 c->at<int32_t>(c->L.sel), c->stream));
     c->bucket_phase ^= 1;
   } else {
     BucketArgs store = a.bk;                       // same storage; always the first counter set
     store.nb = c->bp.nb;
-    store.count = c->at<uint32_t>(c->L.bcount[0]);
+    store.count = reinterpret_cast<uint32_t *>(sc(S.bcount[0]));
     // the workgroups behind the ranking ones draw the remaining work of generation t + 1 into the
     // pair of arrays this generation did not use
     SampleNext draw{pr, c->table(y_this ^ 1), c->Jn, c->Jp, a.key0, a.key1, t + 1, 0u};
     draw.on = sampled && t != 0xFFFFFFFFu ? 1u : 0u;
     HIP_TRY(launch_select(a.fit_row, rp, c->P, c->K, store, c->at<int32_t>(c->L.sel), draw, c->stream));
     if (draw.on) c->drawn_for = static_cast<int64_t>(t) + 1;
-    if (c->bp.nb != 0 && !sampled)   // splitters for the bucketed generations that follow; clears both
+    splitters_valid = false;
+    if (c->bp.nb != 0 && !sampled) { // splitters for the bucketed generations that follow; clears both
                                      // counter sets.  Under sampling no bucketed generation can follow.
       HIP_TRY(launch_splitters(a.fit_row, a.row_of, c->at<int32_t>(c->L.sel), c->K, c->bp.nb,
-                               c->at<uint64_t>(c->L.split),
-                               c->at<uint64_t>(c->L.thresh), c->at<uint32_t>(c->L.bcount[0]),
-                               c->at<uint32_t>(c->L.bcount[1]), c->stream));
+                               reinterpret_cast<uint64_t *>(sc(S.split)), reinterpret_cast<uint64_t *>(sc(S.thresh)),
+                               reinterpret_cast<uint32_t *>(sc(S.bcount[0])),
+                               reinterpret_cast<uint32_t *>(sc(S.bcount[1])), c->stream));
+      splitters_valid = true;
+    }
   }
-  if ((rc = timed(c, c->select_ev, c->select_used, false))) return rc;
+  if (events && (rc = timed(c, c->select_ev, c->select_used, false))) return rc;
   c->cur = next;
   c->y_cur = y_this;
   c->table_changed = false;
@@ -412,6 +469,8 @@ static int init_impl(ones_ctx **out, const ones_config *cfg, const ones_jobs *jo
   c->per_gpu = false;
   c->bp = bucket_plan(c->P);
   c->bucket_phase = 0;
+  c->splitters_valid = false;
+  c->poisoned = false;
   c->ids = h.id;
   {
     int dev = 0;
@@ -420,6 +479,9 @@ static int init_impl(ones_ctx **out, const ones_config *cfg, const ones_jobs *jo
     if (e == hipSuccess) e = hipGetDeviceProperties(&prop, dev);
     if (e != hipSuccess) return hip_fail(e, "hipGetDeviceProperties");
     c->n_cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+    c->device = dev;
+    c->static_scratch = nullptr;
+    if ((rc = static_scratch_of(dev, &c->static_scratch))) return rc;
   }
   c->profiling = false; c->profile_every = 1; c->profile_tick = 0; c->evolve_used = c->select_used = 0;
   {
@@ -428,7 +490,9 @@ static int init_impl(ones_ctx **out, const ones_config *cfg, const ones_jobs *jo
     if (e == hipSuccess) e = launch_zero_words(c->at<uint32_t>(c->L.occupied[1]), words, c->stream);
     if (e != hipSuccess) return hip_fail(e, "launch_zero_words");
   }
-  if ((rc = upload_table(c, h, nullptr)) || (rc = run_generation(c, 0))) return rc;
+  if ((rc = upload_table(c, h, nullptr)) ||
+      (rc = run_generation(c, 0, c->ws + c->L.scratch, c->splitters_valid, false)))
+    return rc;
   hipError_t e = hipStreamSynchronize(c->stream);
   if (e != hipSuccess) return hip_fail(e, "hipStreamSynchronize");
   *out = owner.release();
@@ -531,12 +595,29 @@ static int export_remaining_impl(ones_ctx *c, double *remaining_out) {
   return ONES_OK;
 }
 
-static int generation_impl(ones_ctx *c, int32_t n_generations) {
+static int poisoned_error() {
+  snprintf(g_hip_msg, sizeof(g_hip_msg), "an earlier launch failed in the middle of a generation; destroy the context");
+  return ONES_E_HIP;
+}
+
+static int generation_impl(ones_ctx *c, int32_t n_generations, bool in_static_scratch) {
   if (!c || n_generations < 0) return ONES_E_INVALID_ARG;
   if (c->t + n_generations > 0xFFFFFFFFll) return ONES_E_INVALID_ARG;
+  if (c->poisoned) return poisoned_error();
+  char *block = c->ws + c->L.scratch;
+  bool static_valid = false;      // the static array holds whatever the last call on this GPU left
+  if (in_static_scratch) {
+    if (c->L.S.total > ONES_STATIC_SCRATCH_BYTES) return ONES_E_STATIC_LIMIT;
+    int dev = -1;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev != c->device) return ONES_E_INVALID_ARG;
+    block = c->static_scratch;
+    if (n_generations > 0) c->splitters_valid = false;   // the workspace's splitters fall behind
+  }
   for (int32_t i = 0; i < n_generations; ++i) {
-    int rc = run_generation(c, static_cast<uint32_t>(c->t + 1));
-    if (rc) return rc;
+    int rc = run_generation(c, static_cast<uint32_t>(c->t + 1), block,
+                            in_static_scratch ? static_valid : c->splitters_valid, !in_static_scratch);
+    if (rc) { c->poisoned = true; return rc; }
     c->t += 1;
   }
   return ONES_OK;
@@ -707,7 +788,11 @@ int ones_export_remaining(ones_ctx *c, double *remaining_out) {
 }
 
 int ones_generation(ones_ctx *c, int32_t n_generations) {
-  return guarded([&] { return generation_impl(c, n_generations); });
+  return guarded([&] { return generation_impl(c, n_generations, false); });
+}
+
+int ones_generation_static(ones_ctx *c, int32_t n_generations) {
+  return guarded([&] { return generation_impl(c, n_generations, true); });
 }
 
 int ones_best(ones_ctx *c, int32_t *batch_out, int32_t *gpus_out, double *fitness_out) {
@@ -751,6 +836,7 @@ const char *ones_strerror(int code) {
     case ONES_E_NONFINITE: return "NaN or infinity in a job parameter";
     case ONES_E_WORKSPACE_TOO_SMALL: return "workspace too small or not 256-byte aligned";
     case ONES_E_HIP: return g_hip_msg;
+    case ONES_E_STATIC_LIMIT: return "population too large for the static scratch of ones_generation_static";
     default: return "unknown error code";
   }
 }
