@@ -208,6 +208,9 @@ int32_t ones_padded_jobs(int32_t n_slots);
 /* Measurement hook.  With every = n > 0 the evolve and the select kernels of every n-th
  * generation are bracketed by HIP events on the context's stream (n = 1: every generation;
  * an event costs a few microseconds of stream time); every <= 0 switches it off.
+ * A small pool (at most 64 job slots and 2048 candidates, fixed remaining work) runs all
+ * generations of a ones_generation call in one launch: that launch counts as one evolve launch
+ * (every n-th call is bracketed) and there is no select launch.
  * ones_profile_read synchronises and returns the accumulated kernel time in milliseconds
  * and the number of bracketed launches since the last ones_profile_enable call (any output
  * may be NULL). */

@@ -12,7 +12,7 @@ INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB = os.path.join(HERE, "libones.so")
 # (source, object, extra flags); the evolve kernel is built once per group of eight row counts
 UNITS = [("ones_api.hip", "ones_api.o", []), ("ones_select.hip", "ones_select.o", []),
-         ("ones_sample.hip", "ones_sample.o", [])] + [
+         ("ones_sample.hip", "ones_sample.o", []), ("ones_fused.hip", "ones_fused.o", [])] + [
     ("ones_evolve.hip", f"ones_evolve_{g}.o", [f"-DONES_ROW_GROUP={g}"]) for g in range(4)]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
@@ -21,7 +21,8 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=o
          *os.environ.get("ONES_EXTRA_FLAGS", "").split()]
 
 
-HEADERS = [os.path.join(CSRC, "ones_device.h"), os.path.join(CSRC, "ones_sample.h"), os.path.join(INCLUDE, "ones.h"),
+HEADERS = [os.path.join(CSRC, h) for h in ("ones_device.h", "ones_sample.h", "ones_candidate.h", "ones_sort.h")] + [
+           os.path.join(INCLUDE, "ones.h"),
            os.path.abspath(__file__)]
 
 

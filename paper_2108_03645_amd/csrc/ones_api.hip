@@ -76,8 +76,8 @@ struct ScratchLayout {
 };
 
 struct Layout {
-  size_t genes, fit_row, row_of[2], parent_row[2], occupied[2], sel, scratch, cstart, cmax, info, abl, cc, d, Y[2], terms[2];
-  size_t rawinfo, changed, ra, rc, rd, rY, alpha, beta, processed, time_rank, best_batch, best_gpus, best_fit, place_slot, place_batch, total;
+  size_t genes, fit_row, row_of[2], parent_row[2], occupied[2], sel, fsync, xkeys, scratch, cstart, cmax, info, abl, cc, d, Y[2], terms[2];
+  size_t rawinfo, changed, ra, rc, rd, rY, alpha, beta, processed, time_rank, best_batch, best_gpus, best_fit, best_err, place_slot, place_batch, total;
   ScratchLayout S;
 };
 
@@ -100,6 +100,9 @@ BucketPlan bucket_plan(uint32_t P) {
   bp.seg = std::min(pow2_at_least(std::max<uint32_t>(256, 8 * ((3 * K + bp.nb - 1) / bp.nb))), bp.pool / 4);
   return bp;
 }
+
+// Pools whose generations run in one launch per ones_generation call (ones_fused.hip).
+bool fused_pool(uint32_t P, uint32_t Jp) { return Jp == static_cast<uint32_t>(kLanes) && P <= kFusedMaxPool; }
 
 ScratchLayout make_scratch_layout(uint32_t P) {
   ScratchLayout S;
@@ -133,6 +136,9 @@ Layout make_layout(uint32_t P, uint32_t Jp, uint32_t G) {
   L.occupied[0] = take((rows + 31) / 32 * 4);     // bitmaps of the rows the survivors keep
   L.occupied[1] = take((rows + 31) / 32 * 4);
   L.sel = take(static_cast<size_t>(P / 4) * 4);
+  // single-launch generations of small pools: arrival counter + error word, scores exchanged by slot
+  L.fsync = take(256);
+  L.xkeys = take(fused_pool(P, Jp) ? static_cast<size_t>(2) * P * 8 : 0);
   // the selection's scratch: splitters, counters, bucket storage, spill list, scratch pool
   L.S = make_scratch_layout(P);
   L.scratch = take(L.S.total);
@@ -145,7 +151,7 @@ Layout make_layout(uint32_t P, uint32_t Jp, uint32_t G) {
   L.ra = take(Jp * 8); L.rc = take(Jp * 8); L.rd = take(Jp * 8); L.rY = take(Jp * 8);
   L.alpha = take(Jp * 8); L.beta = take(Jp * 8); L.processed = take(Jp * 8);
   L.time_rank = take(Jp * 4);
-  L.best_batch = take(Jp * 4); L.best_gpus = take(Jp * 4); L.best_fit = take(8);
+  L.best_batch = take(Jp * 4); L.best_gpus = take(Jp * 4); L.best_fit = take(8); L.best_err = take(4);
   L.place_slot = take(static_cast<size_t>(G) * 4); L.place_batch = take(static_cast<size_t>(G) * 4);
   L.total = off;
   return L;
@@ -157,7 +163,7 @@ Layout make_layout(uint32_t P, uint32_t Jp, uint32_t G) {
 size_t stage_bytes(const Layout &L, uint32_t Jp, uint32_t G) {
   const size_t table = L.rY + static_cast<size_t>(Jp) * 8 - L.rawinfo;        // rawinfo, changed, a, c, d, Y
   const size_t progress = L.processed + static_cast<size_t>(Jp) * 8 - L.alpha; // alpha, beta, processed
-  const size_t best = L.best_fit + 8 - L.best_batch;                           // batch, gpus, fitness
+  const size_t best = L.best_err + 4 - L.best_batch;                           // batch, gpus, fitness, error word
   const size_t place = L.place_batch + static_cast<size_t>(G) * 4 - L.place_slot;
   return std::max({table, progress, best, place, static_cast<size_t>(Jp) * 4});
 }
@@ -251,6 +257,9 @@ struct ones_ctx {
   bool splitters_valid;       // the workspace's selection scratch holds the splitters of the current survivors
                               // and cleared counter sets: a bucketed generation may follow
   bool poisoned;              // a launch failed in the middle of a generation: the state is inconsistent
+  bool fused;                 // small pool: all generations of a call in one cooperative launch
+  uint32_t arrivals;          // what the arrival counter of those launches reads once they have all finished
+  uint32_t spin_limit;        // polls before a device-wide wait gives up
   int device;                 // the device the context was created on
   char *static_scratch;       // this device's copy of the library's static scratch array
   int n_cus;
@@ -471,6 +480,9 @@ static int init_impl(ones_ctx **out, const ones_config *cfg, const ones_jobs *jo
   c->bucket_phase = 0;
   c->splitters_valid = false;
   c->poisoned = false;
+  c->fused = false;
+  c->arrivals = 0;
+  c->spin_limit = 1u << 22;   // a few seconds of polling
   c->ids = h.id;
   {
     int dev = 0;
@@ -482,12 +494,16 @@ static int init_impl(ones_ctx **out, const ones_config *cfg, const ones_jobs *jo
     c->device = dev;
     c->static_scratch = nullptr;
     if ((rc = static_scratch_of(dev, &c->static_scratch))) return rc;
+    // the single-launch path needs a launch whose workgroups are all resident at once
+    c->fused = fused_pool(c->P, c->Jp) && prop.cooperativeLaunch != 0 &&
+               fused_workgroups(c->P) <= static_cast<uint32_t>(c->n_cus);
   }
   c->profiling = false; c->profile_every = 1; c->profile_tick = 0; c->evolve_used = c->select_used = 0;
   {
     const uint32_t words = (c->P + c->K + 31) / 32;
     hipError_t e = launch_zero_words(c->at<uint32_t>(c->L.occupied[0]), words, c->stream);
     if (e == hipSuccess) e = launch_zero_words(c->at<uint32_t>(c->L.occupied[1]), words, c->stream);
+    if (e == hipSuccess) e = launch_zero_words(c->at<uint32_t>(c->L.fsync), 64, c->stream);
     if (e != hipSuccess) return hip_fail(e, "launch_zero_words");
   }
   if ((rc = upload_table(c, h, nullptr)) ||
@@ -595,6 +611,49 @@ static int export_remaining_impl(ones_ctx *c, double *remaining_out) {
   return ONES_OK;
 }
 
+// All n generations in one cooperative launch (small pools, fixed remaining work).
+static int run_fused(ones_ctx *c, uint32_t n, bool events) {
+  FusedArgs fa;
+  EvolveArgs &a = fa.ev;
+  a.genes = c->at<int32_t>(c->L.genes);
+  a.fit_row = c->at<double>(c->L.fit_row);
+  a.parent_row = nullptr; a.row_of = nullptr; a.occupied = nullptr; a.occupied_other = nullptr;
+  a.tab = c->table();
+  a.G = c->G; a.P = c->P; a.K = c->K; a.Jp = c->Jp;
+  a.key0 = static_cast<uint32_t>(c->cfg.seed);
+  a.key1 = static_cast<uint32_t>(c->cfg.seed >> 32);
+  a.t = static_cast<uint32_t>(c->t);
+  a.T_mut = c->T_mut; a.T_x = c->T_x;
+  a.new_first = c->new_jobs_first && c->no_schedule ? 1u : 0u;
+  a.time_rank = c->has_times ? c->at<uint32_t>(c->L.time_rank) : nullptr;
+  a.rescore = 0;
+  a.per_gpu = c->per_gpu ? 1u : 0u;
+  a.stash_stride = 0; a.term_lds = 0;
+  a.bk = BucketArgs{};
+  const int next = c->cur ^ 1;
+  fa.parent_rows = c->at<uint32_t>(c->L.parent_row[next]);
+  fa.row_of_next = c->at<uint32_t>(c->L.row_of[next]);
+  fa.row_of_cur = c->at<uint32_t>(c->L.row_of[c->cur]);
+  fa.occupied = c->at<uint32_t>(c->L.occupied[c->cur]);
+  fa.sel = c->at<int32_t>(c->L.sel);
+  fa.xkeys = c->at<uint64_t>(c->L.xkeys);
+  fa.sync = c->at<uint32_t>(c->L.fsync);
+  fa.arrivals_before = c->arrivals;
+  fa.n_generations = n;
+  fa.first_changed = c->table_changed ? 1u : 0u;
+  fa.spin_limit = c->spin_limit;
+  int rc;
+  if (events && (rc = timed(c, c->evolve_ev, c->evolve_used, true))) return rc;
+  HIP_TRY(launch_fused(fa, c->stream));
+  if (events && (rc = timed(c, c->evolve_ev, c->evolve_used, false))) return rc;
+  c->arrivals += fused_workgroups(c->P) * n;
+  c->table_changed = false;
+  c->no_schedule = false;
+  c->splitters_valid = false;       // the two-launch path ranks the pool in full before it uses buckets again
+  c->profile_tick += 1;
+  return ONES_OK;
+}
+
 static int poisoned_error() {
   snprintf(g_hip_msg, sizeof(g_hip_msg), "an earlier launch failed in the middle of a generation; destroy the context");
   return ONES_E_HIP;
@@ -614,6 +673,13 @@ static int generation_impl(ones_ctx *c, int32_t n_generations, bool in_static_sc
     block = c->static_scratch;
     if (n_generations > 0) c->splitters_valid = false;   // the workspace's splitters fall behind
   }
+  if (c->fused && !c->sampling && n_generations > 0) {
+    // uses no scratch at all: every workgroup ranks the pool in its LDS
+    int rc = run_fused(c, static_cast<uint32_t>(n_generations), !in_static_scratch);
+    if (rc) { c->poisoned = true; return rc; }
+    c->t += n_generations;
+    return ONES_OK;
+  }
   for (int32_t i = 0; i < n_generations; ++i) {
     int rc = run_generation(c, static_cast<uint32_t>(c->t + 1), block,
                             in_static_scratch ? static_valid : c->splitters_valid, !in_static_scratch);
@@ -623,17 +689,40 @@ static int generation_impl(ones_ctx *c, int32_t n_generations, bool in_static_sc
   return ONES_OK;
 }
 
+// A device-wide wait of a single-launch generation gave up (it never does on a healthy device):
+// the population is inconsistent from then on.
+static int wait_gave_up(ones_ctx *c) {
+  c->poisoned = true;
+  snprintf(g_hip_msg, sizeof(g_hip_msg), "a device-wide wait inside the generation kernel gave up; destroy the context");
+  return ONES_E_HIP;
+}
+
+// For the calls that synchronise without reading the winner: fetches the error word of the
+// single-launch generations.  The stream must be idle.
+static int check_waits(ones_ctx *c) {
+  if (c->poisoned) return poisoned_error();
+  if (!c->fused) return ONES_OK;
+  uint32_t gave_up = 0;
+  HIP_TRY(hipMemcpy(&gave_up, c->ws + c->L.fsync + 4, 4, hipMemcpyDeviceToHost));
+  return gave_up ? wait_gave_up(c) : ONES_OK;
+}
+
 static int best_impl(ones_ctx *c, int32_t *batch_out, int32_t *gpus_out, double *fitness_out) {
   if (!c) return ONES_E_INVALID_ARG;
+  if (c->poisoned) return poisoned_error();
   HIP_TRY(launch_best(c->at<int32_t>(c->L.genes), c->at<double>(c->L.fit_row), c->at<uint32_t>(c->L.row_of[c->cur]),
                       c->at<int32_t>(c->L.sel),
                       c->at<uint32_t>(c->L.info), c->Jn, c->Jp, c->at<int32_t>(c->L.best_batch),
-                      c->at<int32_t>(c->L.best_gpus), c->at<double>(c->L.best_fit), c->stream));
+                      c->at<int32_t>(c->L.best_gpus), c->at<double>(c->L.best_fit),
+                      c->at<uint32_t>(c->L.fsync) + 1, c->at<uint32_t>(c->L.best_err), c->stream));
   const Layout &L = c->L;
-  HIP_TRY(hipMemcpyAsync(c->stage, c->ws + L.best_batch, L.best_fit + 8 - L.best_batch, hipMemcpyDeviceToHost,
+  HIP_TRY(hipMemcpyAsync(c->stage, c->ws + L.best_batch, L.best_err + 4 - L.best_batch, hipMemcpyDeviceToHost,
                          c->stream));
   HIP_TRY(hipStreamSynchronize(c->stream));
   auto staged = [&](size_t off) { return c->stage + (off - L.best_batch); };   // laid out as in the workspace
+  uint32_t gave_up = 0;
+  memcpy(&gave_up, staged(L.best_err), 4);
+  if (gave_up) return wait_gave_up(c);
   if (batch_out && c->Jn) memcpy(batch_out, staged(L.best_batch), c->Jn * 4);
   if (gpus_out && c->Jn) memcpy(gpus_out, staged(L.best_gpus), c->Jn * 4);
   if (fitness_out) memcpy(fitness_out, staged(L.best_fit), 8);
@@ -642,6 +731,7 @@ static int best_impl(ones_ctx *c, int32_t *batch_out, int32_t *gpus_out, double 
 
 static int placement_impl(ones_ctx *c, int32_t *slot_of_gpu, int32_t *batch_of_gpu) {
   if (!c || c->no_schedule) return ONES_E_INVALID_ARG;
+  if (c->poisoned) return poisoned_error();
   const size_t n4 = static_cast<size_t>(c->G) * 4;
   HIP_TRY(launch_placement(c->at<int32_t>(c->L.genes), c->at<uint32_t>(c->L.row_of[c->cur]), c->at<int32_t>(c->L.sel),
                            c->at<uint32_t>(c->L.info), c->Jn, c->Jp, c->G, c->at<int32_t>(c->L.place_slot),
@@ -651,6 +741,7 @@ static int placement_impl(ones_ctx *c, int32_t *slot_of_gpu, int32_t *batch_of_g
     HIP_TRY(hipMemcpyAsync(c->stage, c->ws + L.place_slot, L.place_batch + n4 - L.place_slot, hipMemcpyDeviceToHost,
                            c->stream));
   HIP_TRY(hipStreamSynchronize(c->stream));
+  if (int rc = check_waits(c)) return rc;
   auto staged = [&](size_t off) { return c->stage + (off - L.place_slot); };   // laid out as in the workspace
   if (slot_of_gpu && c->G) memcpy(slot_of_gpu, staged(L.place_slot), n4);
   if (batch_of_gpu && c->G) memcpy(batch_of_gpu, staged(L.place_batch), n4);
@@ -660,6 +751,7 @@ static int placement_impl(ones_ctx *c, int32_t *slot_of_gpu, int32_t *batch_of_g
 static int export_impl(ones_ctx *c, int32_t *genes, double *fit, int32_t *sel, int64_t *generation) {
   if (!c) return ONES_E_INVALID_ARG;
   HIP_TRY(hipStreamSynchronize(c->stream));
+  if (int rc = check_waits(c)) return rc;
   // candidates live in physical rows: fetch the rows and put them in slot order on the host
   const size_t rows = static_cast<size_t>(c->P) + c->K, Jp = c->Jp;
   std::vector<uint32_t> row_of(c->P);

@@ -117,6 +117,33 @@ struct EvolveArgs {
   BucketArgs     bk;
 };
 
+// All generations of one ones_generation call in a single launch, for pools that are small
+// enough to be ranked inside every workgroup's LDS (one row of 64 job columns, at most
+// kFusedMaxPool candidates).  ev describes the problem as for the evolve kernel; of its row
+// bookkeeping only genes, fit_row and tab are used, and ev.t is the generation counter BEFORE
+// the call (the launch runs generations ev.t + 1 .. ev.t + n_generations).
+constexpr uint32_t kFusedMaxPool = 2048;
+constexpr int kFusedWaves = 8;               // waves per workgroup
+struct FusedArgs {
+  EvolveArgs ev;
+  uint32_t *parent_rows;    // [K] in: rows of the survivors, best first; out: of the new survivors
+  uint32_t *row_of_next;    // [P] out, entries [0,K): the same rows (the next pool's first K slots)
+  uint32_t *row_of_cur;     // [P] out: row of every slot of the last generation's pool
+  uint32_t *occupied;       // bitmap over the P + K rows, in: the survivors' rows; out likewise
+  int32_t  *sel;            // [K] out: survivor slots of the last generation's pool, best first
+  uint64_t *xkeys;          // [2][P] score bits by pool slot, exchanged between the workgroups (by generation parity)
+  uint32_t *sync;           // [0] arrivals at the device-wide waits since the context was created (never reset),
+                            // [1] set when a wait gave up
+  uint32_t arrivals_before; // value of sync[0] when every earlier launch has finished
+  uint32_t n_generations;   // > 0
+  uint32_t first_changed;   // the job table changed since the survivors were scored: the first generation refreshes them
+  uint32_t spin_limit;      // polls before a wait gives up (0: gives up at once; for tests of that path)
+  uint32_t table_lds;       // set by the launcher: bytes of LDS the staged job table takes
+};
+// Workgroups to launch for a pool of P (the launch must be co-resident: cooperative).
+uint32_t fused_workgroups(uint32_t P);
+hipError_t launch_fused(const FusedArgs &fa, hipStream_t s);
+
 // What a selection records besides the survivor list: the survivors keep their rows.
 struct RowPlan {
   const uint32_t *row_of_cur;   // [P] row of every slot of the pool being ranked
@@ -196,6 +223,6 @@ hipError_t launch_placement(const int32_t *genes, const uint32_t *row_of, const 
 hipError_t launch_best(const int32_t *genes, const double *fit_row, const uint32_t *row_of, const int32_t *sel,
                        const uint32_t *info,
                        uint32_t Jn, uint32_t Jp, int32_t *batch_out, int32_t *gpus_out, double *fit_out,
-                       hipStream_t s);
+                       const uint32_t *err_in, uint32_t *err_out, hipStream_t s);
 
 }  // namespace ones

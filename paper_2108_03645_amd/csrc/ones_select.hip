@@ -5,6 +5,7 @@
 // read as an unsigned 64-bit integer orders the same way; ties fall to the smaller slot.
 #include "ones_device.h"
 #include "ones_sample.h"
+#include "ones_sort.h"
 
 #pragma clang fp contract(off)
 
@@ -12,10 +13,6 @@ namespace ones {
 namespace {
 
 constexpr int kSortThreads = kSortChunk / 2 > 1024 ? 1024 : kSortChunk / 2;
-
-__device__ __forceinline__ bool key_less(uint64_t ka, uint32_t ia, uint64_t kb, uint32_t ib) {
-  return ka < kb || (ka == kb && ia < ib);
-}
 
 // Value of lane + n within the lane's row of 16 (DPP row_shl:n), or fallback where that row ends.
 template <int N>
@@ -48,33 +45,6 @@ __device__ __forceinline__ void keep_rows(const RowPlan &rp, bool valid, uint32_
   const uint32_t below = static_cast<uint32_t>(
       __builtin_amdgcn_update_dpp(static_cast<int>(~word), static_cast<int>(word), 0x111, 0xF, 0xF, false));
   if (valid && below != word) atomicOr(&rp.occupied[word], bits);
-}
-
-// Bitonic sorting network over n (a power of two) keys by one workgroup, ascending
-// (score bits, slot).  Works on LDS or, for oversized inputs, on global memory.
-template <typename K64, typename I32>
-__device__ __forceinline__ void bitonic_sort(K64 *sk, I32 *si, uint32_t n) {
-  for (uint32_t k = 2; k <= n; k <<= 1) {
-    for (uint32_t j = k >> 1; j > 0; j >>= 1) {
-      for (uint32_t e = threadIdx.x; e < n / 2; e += blockDim.x) {
-        const uint32_t lo = ((e & ~(j - 1)) << 1) | (e & (j - 1));
-        const uint32_t hi = lo | j;
-        const bool up = (lo & k) == 0;
-        const uint64_t ka = sk[lo], kb = sk[hi];
-        const uint32_t ia = si[lo], ib = si[hi];
-        if (key_less(kb, ib, ka, ia) == up) {
-          sk[lo] = kb; si[lo] = ib;
-          sk[hi] = ka; si[hi] = ia;
-        }
-      }
-      __threadfence_block();
-      __syncthreads();
-    }
-  }
-}
-
-__device__ __forceinline__ uint32_t pow2_at_least(uint32_t v) {
-  return v <= 1 ? 1u : 1u << (32 - __clz(static_cast<int>(v - 1)));
 }
 
 // ---------------------------------------------------------------- general path -----
@@ -540,7 +510,7 @@ __global__ void reset_slots_kernel(int32_t *genes, const uint32_t *slots, uint32
 
 __global__ void best_kernel(const int32_t *genes, const double *fit_row, const uint32_t *row_of, const int32_t *sel,
                             const uint32_t *info, uint32_t Jn, uint32_t Jp, int32_t *batch_out, int32_t *gpus_out,
-                            double *fit_out) {
+                            double *fit_out, const uint32_t *err_in, uint32_t *err_out) {
   const uint32_t best = row_of[sel[0]];
   const int32_t *row = genes + static_cast<size_t>(best) * Jp;
   for (uint32_t j = threadIdx.x; j < Jn; j += blockDim.x) {
@@ -548,7 +518,10 @@ __global__ void best_kernel(const int32_t *genes, const double *fit_row, const u
     batch_out[j] = static_cast<int32_t>(B);
     gpus_out[j] = static_cast<int32_t>(B ? max(1u, B >> info_mu(info[j])) : 0u);
   }
-  if (threadIdx.x == 0) *fit_out = fit_row[best];
+  if (threadIdx.x == 0) {
+    *fit_out = fit_row[best];
+    *err_out = *err_in;                              // travels to the host with the winner
+  }
 }
 
 // The winner unrolled over the GPUs (Eq. 1, reorder): every workgroup scans the jobs' GPU
@@ -690,9 +663,9 @@ hipError_t launch_placement(const int32_t *genes, const uint32_t *row_of, const 
 
 hipError_t launch_best(const int32_t *genes, const double *fit_row, const uint32_t *row_of, const int32_t *sel,
                        const uint32_t *info, uint32_t Jn, uint32_t Jp, int32_t *batch_out, int32_t *gpus_out,
-                       double *fit_out, hipStream_t s) {
+                       double *fit_out, const uint32_t *err_in, uint32_t *err_out, hipStream_t s) {
   hipLaunchKernelGGL(best_kernel, dim3(1), dim3(256), 0, s, genes, fit_row, row_of, sel, info, Jn, Jp, batch_out,
-                     gpus_out, fit_out);
+                     gpus_out, fit_out, err_in, err_out);
   return hipGetLastError();
 }
 

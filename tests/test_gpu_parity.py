@@ -388,7 +388,8 @@ def test_stress_config_at_full_length(ones, ref):
 
 
 def test_profile_hook_counts_launches(ones):
-    cl, jobs = W.paper_scale()
+    cl = cluster(200, 130, 1024, seed=1)                 # two job rows: one evolve and one selection launch per generation
+    jobs = random_jobs(np.random.default_rng(1), 130)
     s = ones.Search(cl, jobs)
     s.profile_enable(1)
     s.generation(7)
@@ -401,6 +402,16 @@ def test_profile_hook_counts_launches(ones):
     s.profile_enable(0)
     s.generation(1)
     assert s.profile_read()["evolve_launches"] == 0
+    s.close()
+    # a pool of at most 64 job slots and 2048 candidates runs a whole call in one launch
+    cl, jobs = W.paper_scale()
+    s = ones.Search(cl, jobs)
+    s.profile_enable(1)
+    s.generation(7)
+    s.generation(1)
+    prof = s.profile_read()
+    assert prof["evolve_launches"] == 2 and prof["select_launches"] == 0 and prof["evolve_ms"] > 0
+    s.close()
 
 
 # ------------------------------------------------ probability sampling (Alg. 1, Eq. 7) ----
