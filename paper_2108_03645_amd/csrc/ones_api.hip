@@ -138,7 +138,7 @@ Layout make_layout(uint32_t P, uint32_t Jp, uint32_t G) {
   L.sel = take(static_cast<size_t>(P / 4) * 4);
   // single-launch generations of small pools: arrival counter + error word, scores exchanged by slot
   L.fsync = take(256);
-  L.xkeys = take(fused_pool(P, Jp) ? static_cast<size_t>(2) * P * 8 : 0);
+  L.xkeys = take(fused_pool(P, Jp) ? fused_exchange_bytes(P) : 0);
   // the selection's scratch: splitters, counters, bucket storage, spill list, scratch pool
   L.S = make_scratch_layout(P);
   L.scratch = take(L.S.total);
@@ -258,7 +258,8 @@ struct ones_ctx {
                               // and cleared counter sets: a bucketed generation may follow
   bool poisoned;              // a launch failed in the middle of a generation: the state is inconsistent
   bool fused;                 // small pool: all generations of a call in one cooperative launch
-  uint32_t arrivals;          // what the arrival counter of those launches reads once they have all finished
+  uint32_t fused_generations; // generations those launches have run so far
+  uint32_t fused_changes;     // ... of them first generations after a table change
   uint32_t spin_limit;        // polls before a device-wide wait gives up
   int device;                 // the device the context was created on
   char *static_scratch;       // this device's copy of the library's static scratch array
@@ -481,7 +482,8 @@ static int init_impl(ones_ctx **out, const ones_config *cfg, const ones_jobs *jo
   c->splitters_valid = false;
   c->poisoned = false;
   c->fused = false;
-  c->arrivals = 0;
+  c->fused_generations = 0;
+  c->fused_changes = 0;
   c->spin_limit = 1u << 22;   // a few seconds of polling
   c->ids = h.id;
   {
@@ -504,6 +506,8 @@ static int init_impl(ones_ctx **out, const ones_config *cfg, const ones_jobs *jo
     hipError_t e = launch_zero_words(c->at<uint32_t>(c->L.occupied[0]), words, c->stream);
     if (e == hipSuccess) e = launch_zero_words(c->at<uint32_t>(c->L.occupied[1]), words, c->stream);
     if (e == hipSuccess) e = launch_zero_words(c->at<uint32_t>(c->L.fsync), 64, c->stream);
+    if (e == hipSuccess && fused_pool(c->P, c->Jp))   // the exchange buffers of the single-launch path: every tag starts at 0
+      e = launch_zero_words(c->at<uint32_t>(c->L.xkeys), static_cast<uint32_t>(fused_exchange_bytes(c->P) / 4), c->stream);
     if (e != hipSuccess) return hip_fail(e, "launch_zero_words");
   }
   if ((rc = upload_table(c, h, nullptr)) ||
@@ -637,8 +641,11 @@ static int run_fused(ones_ctx *c, uint32_t n, bool events) {
   fa.occupied = c->at<uint32_t>(c->L.occupied[c->cur]);
   fa.sel = c->at<int32_t>(c->L.sel);
   fa.xkeys = c->at<uint64_t>(c->L.xkeys);
+  fa.xsurv = fa.xkeys + static_cast<size_t>(2) * c->P;
+  fa.xrank = fa.xsurv + static_cast<size_t>(2) * c->K;
   fa.sync = c->at<uint32_t>(c->L.fsync);
-  fa.arrivals_before = c->arrivals;
+  fa.generations_before = c->fused_generations;
+  fa.changes_before = c->fused_changes;
   fa.n_generations = n;
   fa.first_changed = c->table_changed ? 1u : 0u;
   fa.spin_limit = c->spin_limit;
@@ -646,7 +653,8 @@ static int run_fused(ones_ctx *c, uint32_t n, bool events) {
   if (events && (rc = timed(c, c->evolve_ev, c->evolve_used, true))) return rc;
   HIP_TRY(launch_fused(fa, c->stream));
   if (events && (rc = timed(c, c->evolve_ev, c->evolve_used, false))) return rc;
-  c->arrivals += fused_workgroups(c->P) * n;
+  c->fused_generations += n;
+  c->fused_changes += fa.first_changed;
   c->table_changed = false;
   c->no_schedule = false;
   c->splitters_valid = false;       // the two-launch path ranks the pool in full before it uses buckets again

@@ -131,10 +131,13 @@ struct FusedArgs {
   uint32_t *row_of_cur;     // [P] out: row of every slot of the last generation's pool
   uint32_t *occupied;       // bitmap over the P + K rows, in: the survivors' rows; out likewise
   int32_t  *sel;            // [K] out: survivor slots of the last generation's pool, best first
-  uint64_t *xkeys;          // [2][P] score bits by pool slot, exchanged between the workgroups (by generation parity)
-  uint32_t *sync;           // [0] arrivals at the device-wide waits since the context was created (never reset),
-                            // [1] set when a wait gave up
-  uint32_t arrivals_before; // value of sync[0] when every earlier launch has finished
+  // exchange between the workgroups, zeroed when the context is created, then only written by these launches:
+  uint64_t *xkeys;          // [2][P] tagged score bits of the children by pool slot, a buffer per generation parity
+  uint64_t *xsurv;          // [2][K] the same for survivors refreshed after a table change
+  uint64_t *xrank;          // [P] ranks from a ranking by counting, stamped with the generation
+  uint32_t *sync;           // [1] set when a poll ran out
+  uint32_t generations_before;  // generations these launches have run for the context so far
+  uint32_t changes_before;      // ... of them first generations after a table change
   uint32_t n_generations;   // > 0
   uint32_t first_changed;   // the job table changed since the survivors were scored: the first generation refreshes them
   uint32_t spin_limit;      // polls before a wait gives up (0: gives up at once; for tests of that path)
@@ -142,6 +145,7 @@ struct FusedArgs {
 };
 // Workgroups to launch for a pool of P (the launch must be co-resident: cooperative).
 uint32_t fused_workgroups(uint32_t P);
+size_t fused_exchange_bytes(uint32_t P);    // xkeys, xsurv and xrank, consecutive
 hipError_t launch_fused(const FusedArgs &fa, hipStream_t s);
 
 // What a selection records besides the survivor list: the survivors keep their rows.

@@ -6,19 +6,24 @@
 // Two launches per generation cost more than the generation itself at this size, so here a
 // co-resident grid stays on the chip for the whole call.  Per generation every wave composes,
 // repairs and scores its share of the 3K children (4K candidates after a table change) and
-// publishes genome and score; then all workgroups meet at a device-wide wait, and each of them
-// ranks the pool by itself in its LDS: the survivors' scores, rows and the list of free rows are
-// kept there redundantly, so the only data that cross workgroups are the genomes and one score
-// per candidate.  While the job table stays the same the K survivors reappear with the scores
-// they had, already in order, so the ranking is a merge of the few children that beat the K-th
-// survivor into that order; otherwise the pool is sorted.
+// publishes genome and score; every workgroup then collects all scores and ranks the pool by
+// itself in its LDS: the survivors' scores, rows and the list of free rows are kept there
+// redundantly, so the only data that cross workgroups are the genomes and one score per
+// candidate.  While the job table stays the same the K survivors reappear with the scores they
+// had, already in order, so the ranking is a merge of the few children that beat the K-th
+// survivor into that order; when there are many of them, or after a table change, every
+// workgroup ranks a share of the pool by counting and the ranks are exchanged like the scores.
 //
-// Data written by one workgroup and read by another inside the launch (genomes, scores, the
-// arrival counter) go through relaxed atomic stores and loads at device scope, which the
-// hardware performs at the device's point of coherence instead of in the caches of one XCD;
-// every wave waits for its stores to be acknowledged before its workgroup arrives, and reads
-// others' data only after the wait.  The wait is bounded: a workgroup that gives up sets an
-// error word and leaves, and so do all others.
+// Exchange.  Data written by one workgroup and read by another inside the launch (genomes,
+// scores, ranks) go through relaxed atomic stores and loads at device scope, which the hardware
+// performs at the device's point of coherence instead of in the caches of one XCD.  There is no
+// barrier: a published score carries a tag (its sign bit, which a score never uses, alternating
+// with every reuse of the exchange buffer; ranks carry the generation number), a reader polls
+// until every entry shows the tag of the current generation, and a wave publishes its score only
+// after its genome stores have been acknowledged.  Seeing all scores of a generation therefore
+// means that every wave has finished reading that generation's parents and writing its
+// children, which is all the ordering the rows need.  Every poll is bounded: a workgroup that
+// gives up sets an error word and leaves, and so, in time, do all others.
 #include "ones_candidate.h"
 #include "ones_sort.h"
 
@@ -27,7 +32,9 @@ namespace {
 
 constexpr int kFusedThreads = kFusedWaves * kLanes;
 constexpr uint32_t kFusedMaxWorkgroups = 96;
-constexpr uint32_t kMergeMax = 256;          // children beating the K-th survivor that are still ranked by counting
+constexpr uint32_t kFusedUnits = 4;          // most units (candidates) one wave computes per generation
+constexpr uint32_t kMergeMax = 256;          // children beating the K-th survivor that are still merged locally
+constexpr int kGatherPer = kFusedMaxPool / kFusedThreads;   // entries per thread when a workgroup collects P values
 
 template <typename T>
 __device__ __forceinline__ T shared_load(const T *p) {
@@ -37,6 +44,11 @@ template <typename T>
 __device__ __forceinline__ void shared_store(T *p, T v) {
   __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
+
+// Tag of the n-th use (n = 0, 1, ..) of a pair of exchange buffers that start out zeroed: use n
+// goes to buffer n & 1 and flips the tag that buffer's entries carried before.
+__device__ __forceinline__ uint64_t use_tag(uint32_t n) { return static_cast<uint64_t>(((n >> 1) & 1u) ^ 1u) << 63; }
+constexpr uint64_t kTagBit = 1ull << 63;
 
 // Per-workgroup copy of the search state between two generations, plus scratch of the ranking.
 struct Ranks {
@@ -49,45 +61,49 @@ struct Ranks {
   __device__ __forceinline__ uint16_t *srow(int which) const { return srows + static_cast<uint32_t>(which) * K; }
   uint16_t *nsel;      // [K] pool slot each new survivor had in the generation just ranked
   uint16_t *frow;      // [P] the free rows in ascending order: unit u of a generation writes row frow[u]
-  uint64_t *ckey;      // [pow2(P)] score bits by pool slot; sorted in place when the pool is sorted
-  uint32_t *cidx;      // [pow2(P)] payload of that sort: the slot
-  uint64_t *mkey;      // [3K] children that beat the K-th survivor, then the same in order
+  uint64_t *ckey;      // [P] score bits by pool slot
+  uint64_t *mkey;      // [3K] children that beat the K-th survivor
   uint32_t *mslot;     // [3K]
-  uint64_t *okey;      // [kMergeMax] ... ordered
+  uint64_t *okey;      // [kMergeMax] ... in order
   uint32_t *oslot;     // [kMergeMax]
-  uint32_t *below;     // [kMergeMax] rank of such a child among them
+  uint32_t *below;     // [kMergeMax] counters of the rankings by counting
   uint32_t *occ;       // bitmap over the P + K rows: the survivors' rows
-  uint32_t *misc;      // [0] outcome of the wait, [1] number of such children
+  uint32_t *misc;      // [0] number of children that beat the K-th survivor
+  uint32_t *draws;     // [waves][kFusedUnits][4] per unit: ranks of the parents, rotation (drawn ahead)
+  uint32_t *words;     // [waves][kFusedUnits][64] per unit: the gene words (drawn ahead)
+  uint64_t *ukeys;     // [waves][kFusedUnits] per unit: the score, until the wave publishes it
 };
 
 inline size_t ranks_bytes(uint32_t P) {
-  const size_t K = P / 4, Ppad = 1u << (32 - __builtin_clz(std::max(P, 2u) - 1));
-  return 2 * K * 8 + 2 * K * 2 + K * 2 + P * 2 + Ppad * 8 + Ppad * 4 + 3 * K * 8 + 3 * K * 4 +
-         kMergeMax * (8 + 4 + 4) + ((P + K + 31) / 32) * 4 + 16 + 64;
+  const size_t K = P / 4;
+  return 2 * K * 8 + 2 * K * 2 + K * 2 + P * 2 + P * 8 + 3 * K * 8 + 3 * K * 4 + kMergeMax * (8 + 4 + 4) +
+         ((P + K + 31) / 32) * 4 + 16 + kFusedWaves * kFusedUnits * ((4 + kLanes) * 4 + 8) + 64;
 }
 
 __device__ __forceinline__ Ranks carve_ranks(unsigned char *base, uint32_t P) {
-  const uint32_t K = P / 4, Ppad = pow2_at_least(P);
+  const uint32_t K = P / 4;
   Ranks r;
   r.K = K;
-  r.skeys = reinterpret_cast<uint64_t *>(base);
+  r.ukeys = reinterpret_cast<uint64_t *>(base);
+  r.skeys = r.ukeys + kFusedWaves * kFusedUnits;
   r.ckey = r.skeys + 2 * K;
-  r.mkey = r.ckey + Ppad;
+  r.mkey = r.ckey + P;
   r.okey = r.mkey + 3 * K;
-  r.cidx = reinterpret_cast<uint32_t *>(r.okey + kMergeMax);
-  r.mslot = r.cidx + Ppad;
+  r.mslot = reinterpret_cast<uint32_t *>(r.okey + kMergeMax);
   r.oslot = r.mslot + 3 * K;
   r.below = r.oslot + kMergeMax;
   r.occ = r.below + kMergeMax;
   r.misc = r.occ + (P + K + 31) / 32;
-  r.srows = reinterpret_cast<uint16_t *>(r.misc + 4);
+  r.draws = r.misc + 4;
+  r.words = r.draws + kFusedWaves * kFusedUnits * 4;
+  r.srows = reinterpret_cast<uint16_t *>(r.words + kFusedWaves * kFusedUnits * kLanes);
   r.nsel = r.srows + 2 * K;
   r.frow = r.nsel + K;
   return r;
 }
 
 // The survivors' rows (rows[0..K)) as a bitmap, and from it the free rows in ascending order.
-// Whole workgroup; ends with a barrier.
+// from_bitmap: the bitmap is there already.  Whole workgroup; ends with a barrier.
 __device__ __forceinline__ void list_free_rows(const Ranks &rk, const uint16_t *rows, uint32_t P, bool from_bitmap) {
   const uint32_t K = P / 4, n_rows = P + K, words = (n_rows + 31) / 32;
   if (!from_bitmap) {
@@ -126,66 +142,90 @@ __device__ __forceinline__ uint32_t row_of_slot(const Ranks &rk, int cur, uint32
   return changed ? rk.frow[3 * K + p] : rk.srow(cur)[p];
 }
 
-// Ranks the whole pool: ckey[0..P) holds every slot's score bits.  Writes the new survivors
-// into the buffers number nxt.  Whole workgroup; ends with a barrier.
-__device__ __forceinline__ void rank_by_sorting(const Ranks &rk, int cur, uint32_t P, bool changed) {
-  const uint32_t K = P / 4, Ppad = pow2_at_least(P);
-  for (uint32_t i = threadIdx.x; i < Ppad; i += blockDim.x) {
-    rk.cidx[i] = i < P ? i : 0xFFFFFFFFu;
-    if (i >= P) rk.ckey[i] = ~0ull;
+// Collects n published 64-bit entries: thread t takes entries t, t + threads, ..., polls until
+// each one is ready and hands it to take.  False when the polls ran out.
+template <typename Ready, typename Take>
+__device__ __forceinline__ bool gather(const uint64_t *src, uint32_t n, uint32_t spin_limit, Ready ready, Take take) {
+  uint32_t pending = 0;
+#pragma unroll
+  for (int k = 0; k < kGatherPer; ++k)
+    if (threadIdx.x + k * kFusedThreads < n) pending |= 1u << k;
+  for (uint32_t spins = 0; pending != 0; ++spins) {
+    if (spins >= spin_limit) return false;
+    uint64_t v[kGatherPer];
+#pragma unroll
+    for (int k = 0; k < kGatherPer; ++k)
+      if ((pending >> k) & 1u) v[k] = shared_load(src + threadIdx.x + k * kFusedThreads);
+#pragma unroll
+    for (int k = 0; k < kGatherPer; ++k)
+      if (((pending >> k) & 1u) && ready(v[k])) {
+        take(threadIdx.x + k * kFusedThreads, v[k]);
+        pending &= ~(1u << k);
+      }
+    if (pending != 0) __builtin_amdgcn_s_sleep(1);
   }
-  __syncthreads();
-  bitonic_sort(rk.ckey, rk.cidx, Ppad);
-  const int nxt = cur ^ 1;
-  for (uint32_t g = threadIdx.x; g < K; g += blockDim.x) {
-    const uint32_t slot = rk.cidx[g];
-    rk.skey(nxt)[g] = rk.ckey[g];
-    rk.srow(nxt)[g] = static_cast<uint16_t>(row_of_slot(rk, cur, slot, K, changed));
-    rk.nsel[g] = static_cast<uint16_t>(slot);
+  return true;
+}
+
+// What a child or mutant draws before it needs anything of its parents: the parents' ranks, the
+// rotation of its repair, its word per gene.  Depends on (seed, generation, slot) only, so a
+// wave draws for the coming generation while the scores of the current one are still arriving.
+template <bool kOverGpus>
+__device__ __forceinline__ void draw_ahead(const EvolveArgs &a, uint32_t t, uint32_t u, int lane, uint32_t *draws,
+                                           uint32_t *words) {
+  const uint32_t K = a.K;
+  Draw d;
+  uint32_t w[1] = {0u};
+  if (u < 2 * K) {                                   // child of a pair: both share the pair's parents and words
+    const uint32_t p0 = K + (u & ~1u);
+    d = candidate_draw(a, t, p0);
+    if (u & 1u) d.r = candidate_draw(a, t, p0 + 1).r;
+    if (!kOverGpus) gene_words<1>(a, t, p0, lane, w);
+  } else {
+    d = candidate_draw(a, t, K + u);
+    gene_words<1>(a, t, K + u, lane, w);
   }
-  __syncthreads();
+  if (lane == 0) { draws[0] = d.ra; draws[1] = d.rb; draws[2] = d.r; }
+  words[lane] = w[0];
 }
 
 // One candidate of generation t: unit u < 2K is a child of pair u / 2, u < 3K a mutant, u >= 3K
 // (only after a table change) the survivor of rank u - 3K to refresh.  srow: rows of the
 // survivors by rank.  Returns the score; the repaired GPU counts are left in c.
 template <bool kSameTable, bool kOverGpus>
-__device__ __forceinline__ double compose_unit(const EvolveArgs &a, uint32_t t, const Smem &s, const uint16_t *srow, uint32_t u,
-                                               bool new_first, uint8_t *stash, int lane, uint32_t (&c)[1]) {
+__device__ __forceinline__ double compose_unit(const EvolveArgs &a, uint32_t t, const Smem &s, const uint16_t *srow,
+                                               uint32_t u, bool new_first, uint8_t *stash, const uint32_t *draws,
+                                               const uint32_t *words, int lane, uint32_t (&c)[1]) {
   const uint32_t K = a.K;
   uint32_t r;
   auto gene_of = [&](uint32_t row) {
     return static_cast<uint32_t>(shared_load(a.genes + static_cast<size_t>(row) * kLanes + lane));
   };
-  if (u < 2 * K) {
-    const uint32_t p0 = K + (u & ~1u), side = u & 1u;
-    const Draw d0 = candidate_draw(a, t, p0);
-    r = side ? candidate_draw(a, t, p0 + 1).r : d0.r;
-    uint32_t B[1];
-    c[0] = gene_of(srow[d0.ra]);
-    B[0] = gene_of(srow[d0.rb]);
-    gpus_from_batches<1, kSameTable>(s, lane, c);
-    gpus_from_batches<1, kSameTable>(s, lane, B);
-    if (kOverGpus) {
-      crossover_over_gpus<1>(a, t, s, reinterpret_cast<uint64_t *>(stash), p0, lane, c, B);
-      c[0] = side ? B[0] : c[0];
+  if (u < 3 * K) {
+    const uint32_t ra = __builtin_amdgcn_readfirstlane(draws[0]), rb = __builtin_amdgcn_readfirstlane(draws[1]);
+    r = __builtin_amdgcn_readfirstlane(draws[2]);
+    const uint32_t w = words[lane];
+    if (u < 2 * K) {
+      const uint32_t side = u & 1u;
+      uint32_t B[1];
+      c[0] = gene_of(srow[ra]);
+      B[0] = gene_of(srow[rb]);
+      gpus_from_batches<1, kSameTable>(s, lane, c);
+      gpus_from_batches<1, kSameTable>(s, lane, B);
+      if (kOverGpus) {
+        crossover_over_gpus<1>(a, t, s, reinterpret_cast<uint64_t *>(stash), K + (u & ~1u), lane, c, B);
+        c[0] = side ? B[0] : c[0];
+      } else {
+        const bool swap = w < a.T_x;                 // the first child takes the second parent's gene
+        c[0] = (swap != (side != 0)) ? B[0] : c[0];
+      }
     } else {
-      uint32_t w[1];
-      gene_words<1>(a, t, p0, lane, w);
-      const bool swap = w[0] < a.T_x;                      // the first child takes the second parent's gene
-      c[0] = (swap != (side != 0)) ? B[0] : c[0];
+      c[0] = gene_of(srow[ra]);
+      const uint32_t word = s.info[lane];
+      const uint32_t k = ((w & 0xFFFFu) * info_n(word)) >> 16;
+      c[0] = w < a.T_mut ? batch_from_draw(k, word) : c[0];
+      gpus_from_batches<1, false>(s, lane, c);
     }
-  } else if (u < 3 * K) {
-    const uint32_t p = K + u;
-    const Draw d = candidate_draw(a, t, p);
-    r = d.r;
-    uint32_t w[1];
-    gene_words<1>(a, t, p, lane, w);
-    c[0] = gene_of(srow[d.ra]);
-    const uint32_t word = s.info[lane];
-    const uint32_t k = ((w[0] & 0xFFFFu) * info_n(word)) >> 16;
-    c[0] = w[0] < a.T_mut ? batch_from_draw(k, word) : c[0];
-    gpus_from_batches<1, false>(s, lane, c);
   } else {
     const uint32_t p = u - 3 * K;
     r = candidate_draw(a, t, p).r;
@@ -199,95 +239,111 @@ __device__ __forceinline__ double compose_unit(const EvolveArgs &a, uint32_t t, 
 template <bool kOverGpus>
 __global__ __launch_bounds__(kFusedThreads) void fused_kernel(FusedArgs fa) {
   extern __shared__ __align__(16) unsigned char smem_raw[];
-  const uint32_t P = fa.ev.P, K = fa.ev.K, tid = threadIdx.x;
-  const Smem s = carve(smem_raw, kLanes, fa.ev.term_lds, kFusedWaves, fa.ev.stash_stride);
+  const EvolveArgs &a = fa.ev;
+  const uint32_t P = a.P, K = a.K, tid = threadIdx.x;
+  const Smem s = carve(smem_raw, kLanes, a.term_lds, kFusedWaves, a.stash_stride);
   const Ranks rk = carve_ranks(smem_raw + fa.table_lds, P);
-  stage_table<1>(fa.ev.tab, fa.ev.bk, s, kLanes, fa.ev.term_lds);
+  const int lane0 = tid & (kLanes - 1);
+  const uint32_t wave_in_block = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const uint32_t wave = blockIdx.x * kFusedWaves + wave_in_block, n_waves = gridDim.x * kFusedWaves;
+  uint8_t *stash = s.stash + static_cast<size_t>(wave_in_block) * a.stash_stride;
+  uint32_t *my_draws = rk.draws + wave_in_block * kFusedUnits * 4;
+  uint32_t *my_words = rk.words + wave_in_block * kFusedUnits * kLanes;
+  uint64_t *my_keys = rk.ukeys + wave_in_block * kFusedUnits;
+  auto draw_units = [&](uint32_t t) {                // this wave's children and mutants of generation t
+    for (uint32_t k = 0, u = wave; k < kFusedUnits && u < 3 * K; ++k, u += n_waves)
+      draw_ahead<kOverGpus>(a, t, u, opaque(lane0), my_draws + 4 * k, my_words + kLanes * k);
+  };
+  draw_units(a.t + 1);
+  stage_table<1>(a.tab, a.bk, s, kLanes, a.term_lds);
   // the state the last selection left: the survivors' rows and scores, the bitmap of their rows
   for (uint32_t e = tid; e < K; e += kFusedThreads) {
     const uint32_t row = fa.parent_rows[e];
     rk.srow(0)[e] = static_cast<uint16_t>(row);
-    rk.skey(0)[e] = static_cast<uint64_t>(__double_as_longlong(fa.ev.fit_row[row]));
+    rk.skey(0)[e] = static_cast<uint64_t>(__double_as_longlong(a.fit_row[row]));
   }
   for (uint32_t w = tid; w < (P + K + 31) / 32; w += kFusedThreads) rk.occ[w] = fa.occupied[w];
+  if (tid == 0) rk.misc[0] = 0;
   __syncthreads();
   list_free_rows(rk, nullptr, P, true);
 
-  const int lane0 = tid & (kLanes - 1);
-  const uint32_t wave_in_block = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const uint32_t wave = blockIdx.x * kFusedWaves + wave_in_block, n_waves = gridDim.x * kFusedWaves;
-  uint8_t *stash = s.stash + static_cast<size_t>(wave_in_block) * fa.ev.stash_stride;
   int cur = 0;
   for (uint32_t g = 0; g < fa.n_generations; ++g) {
-    const EvolveArgs &a = fa.ev;
-    const uint32_t t = fa.ev.t + g + 1;
+    const uint32_t t = a.t + g + 1;
+    const uint32_t use = fa.generations_before + g;            // how often the children's exchange buffers have been used
     const bool changed = g == 0 && fa.first_changed != 0;
-    const bool new_first = changed && fa.ev.new_first != 0;
+    const bool new_first = changed && a.new_first != 0;
     const bool last = g + 1 == fa.n_generations;
     const uint32_t units = changed ? 4 * K : 3 * K;
-    uint64_t *xk = fa.xkeys + static_cast<size_t>(g & 1u) * P;
-    for (uint32_t u = wave; u < units; u += n_waves) {
+    uint64_t *xk = fa.xkeys + static_cast<size_t>(use & 1u) * P;
+    uint64_t *xs = fa.xsurv + static_cast<size_t>(fa.changes_before & 1u) * K;
+    // ---- compose, repair, score and store this wave's candidates (at most kFusedUnits of them)
+    for (uint32_t k = 0, u = wave; u < units; ++k, u += n_waves) {
       const int lane = opaque(lane0);
       uint32_t c[1];
-      const double f = changed ? compose_unit<false, kOverGpus>(a, t, s, rk.srow(cur), u, new_first, stash, lane, c)
-                               : compose_unit<true, kOverGpus>(a, t, s, rk.srow(cur), u, false, stash, lane, c);
-      const uint32_t row = rk.frow[u], slot = u < 3 * K ? K + u : u - 3 * K;
-      shared_store(a.genes + static_cast<size_t>(row) * kLanes + lane, static_cast<int32_t>(c[0] << info_blexp(s.info[lane])));
+      const double f = changed ? compose_unit<false, kOverGpus>(a, t, s, rk.srow(cur), u, new_first, stash,
+                                                                my_draws + 4 * k, my_words + kLanes * k, lane, c)
+                               : compose_unit<true, kOverGpus>(a, t, s, rk.srow(cur), u, false, stash,
+                                                               my_draws + 4 * k, my_words + kLanes * k, lane, c);
+      const uint32_t row = rk.frow[u];
+      shared_store(a.genes + static_cast<size_t>(row) * kLanes + lane,
+                   static_cast<int32_t>(c[0] << info_blexp(s.info[lane])));
       if (lane == 0) {
-        // (also the score kept with the row goes to the point of coherence: a row is written by
+        // (the score kept with the row goes to the point of coherence too: a row is written by
         // different workgroups in different generations, and a plain store could linger in one
         // XCD's cache and be written back over a later one)
         const uint64_t bits = static_cast<uint64_t>(__double_as_longlong(f));
         shared_store(reinterpret_cast<uint64_t *>(a.fit_row) + row, bits);
-        shared_store(xk + slot, bits);
+        my_keys[k] = bits;
       }
     }
-    // every store of this wave has been acknowledged before its workgroup arrives
+    // the genomes have arrived before their scores are published
     __builtin_amdgcn_s_waitcnt(0);
-    __syncthreads();
-    if (tid == 0) __hip_atomic_fetch_add(fa.sync, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    if (last && blockIdx.x != 0) return;             // only the first workgroup writes the final state
-    if (tid == 0) {
-      const uint32_t target = fa.arrivals_before + gridDim.x * (g + 1);
-      uint32_t ok = 0;
-      for (uint32_t spins = 0; spins < fa.spin_limit; ++spins) {
-        if (static_cast<int32_t>(shared_load(fa.sync) - target) >= 0) { ok = 1; break; }
-        __builtin_amdgcn_s_sleep(1);
+    if (lane0 == 0)
+      for (uint32_t k = 0, u = wave; u < units; ++k, u += n_waves) {
+        if (u < 3 * K) shared_store(xk + K + u, my_keys[k] | use_tag(use));
+        else shared_store(xs + (u - 3 * K), my_keys[k] | use_tag(fa.changes_before));
       }
-      if (!ok) shared_store(fa.sync + 1, 1u);
-      rk.misc[0] = ok;
-      rk.misc[1] = 0;
+    if (!last) draw_units(t + 1);                    // while the others' scores are on their way
+
+    // ---- collect the scores
+    bool ok = gather(xk + K, 3 * K, fa.spin_limit, [&](uint64_t v) { return (v & kTagBit) == use_tag(use); },
+                     [&](uint32_t i, uint64_t v) { rk.ckey[K + i] = v & ~kTagBit; });
+    if (changed)
+      ok = gather(xs, K, fa.spin_limit, [&](uint64_t v) { return (v & kTagBit) == use_tag(fa.changes_before); },
+                  [&](uint32_t i, uint64_t v) { rk.ckey[i] = v & ~kTagBit; }) && ok;
+    if (__syncthreads_or(ok ? 0 : 1)) {              // a poll ran out
+      if (tid == 0) shared_store(fa.sync + 1, 1u);
+      return;
     }
-    __syncthreads();
-    if (rk.misc[0] == 0) return;                     // the wait gave up: the error word is set
 
     // ---- rank the pool
-    bool moved = true;                               // the set of survivors (hence the free rows) changed
-    if (changed) {
-      for (uint32_t i = tid; i < P; i += kFusedThreads) rk.ckey[i] = shared_load(xk + i);
-      rank_by_sorting(rk, cur, P, true);
-    } else {
+    bool moved = true;                               // the set of survivors (hence the free rows) changes
+    bool by_counting = changed;                      // rank the whole pool, a share per workgroup
+    if (!changed) {
       // children that beat the K-th survivor (an equal score loses to the survivor's smaller slot)
       const uint64_t thresh = rk.skey(cur)[K - 1];
       for (uint32_t base = 0; base < 3 * K; base += kFusedThreads) {   // whole waves go round together
         const uint32_t i = base + tid;
-        const uint64_t key = i < 3 * K ? shared_load(xk + K + i) : ~0ull;
-        if (i < 3 * K) rk.ckey[K + i] = key;
+        const uint64_t key = i < 3 * K ? rk.ckey[K + i] : ~0ull;
         const bool beats = key < thresh;
         const uint64_t mask = __ballot(beats);
         uint32_t at = 0;
-        if (lane0 == 0 && mask != 0) at = atomicAdd(&rk.misc[1], static_cast<uint32_t>(__popcll(mask)));
+        if (lane0 == 0 && mask != 0) at = atomicAdd(&rk.misc[0], static_cast<uint32_t>(__popcll(mask)));
         at = __builtin_amdgcn_readfirstlane(at) + static_cast<uint32_t>(__popcll(mask & ((1ull << lane0) - 1ull)));
         if (beats) { rk.mkey[at] = key; rk.mslot[at] = K + i; }
       }
       __syncthreads();
-      const uint32_t M = rk.misc[1];
+      const uint32_t M = rk.misc[0];
+      // in the last generation only the first workgroup needs the ranking (it writes the state the
+      // call leaves); the others stay for their share of a ranking by counting, if there is one
+      if (last && blockIdx.x != 0 && M <= kMergeMax) return;
       if (M == 0) {
         moved = false;                               // same survivors, same order, same free rows
         if (last) for (uint32_t e = tid; e < K; e += kFusedThreads) rk.nsel[e] = static_cast<uint16_t>(e);
       } else if (M > kMergeMax) {
+        by_counting = true;
         for (uint32_t e = tid; e < K; e += kFusedThreads) rk.ckey[e] = rk.skey(cur)[e];
-        rank_by_sorting(rk, cur, P, false);
       } else {
         // rank of each such child among them, the comparisons dealt to all threads
         const uint32_t Mp = pow2_at_least(M), parts = kFusedThreads / Mp, per = (M + parts - 1) / parts;
@@ -337,7 +393,45 @@ __global__ __launch_bounds__(kFusedThreads) void fused_kernel(FusedArgs fa) {
             rk.nsel[rank] = static_cast<uint16_t>(e);
           }
         }
-        __syncthreads();
+      }
+      __syncthreads();
+      if (tid == 0) rk.misc[0] = 0;                  // for the next generation (read again only after further barriers)
+    }
+    if (by_counting) {
+      // ckey holds the whole pool's scores by slot.  This workgroup ranks its share of the slots
+      // (rank = candidates below in (score, slot) order), publishes the ranks, collects all.
+      const uint32_t lo = static_cast<uint32_t>(static_cast<uint64_t>(P) * blockIdx.x / gridDim.x);
+      const uint32_t hi = static_cast<uint32_t>(static_cast<uint64_t>(P) * (blockIdx.x + 1) / gridDim.x);
+      const uint32_t ns = hi - lo, nsp = pow2_at_least(max(ns, 1u)), parts = kFusedThreads / nsp;   // ns <= kMergeMax
+      if (tid < kMergeMax) rk.below[tid] = 0;
+      __syncthreads();
+      {
+        const uint32_t i = tid % nsp, part = tid / nsp;
+        if (i < ns) {
+          const uint32_t slot = lo + i;
+          const uint64_t key = rk.ckey[slot];
+          uint32_t n = 0;
+          for (uint32_t j = part; j < P; j += parts) n += key_less(rk.ckey[j], j, key, slot) ? 1u : 0u;
+          if (n) atomicAdd(&rk.below[i], n);
+        }
+      }
+      __syncthreads();
+      const uint64_t stamp = static_cast<uint64_t>(use + 1u) << 32;     // no generation has number 0
+      if (tid < ns) shared_store(fa.xrank + lo + tid, stamp | rk.below[tid]);
+      if (last && blockIdx.x != 0) return;
+      const int nxt = cur ^ 1;
+      ok = gather(fa.xrank, P, fa.spin_limit, [&](uint64_t v) { return (v >> 32) == (stamp >> 32); },
+                  [&](uint32_t p, uint64_t v) {
+                    const uint32_t rank = static_cast<uint32_t>(v);
+                    if (rank < K) {
+                      rk.skey(nxt)[rank] = rk.ckey[p];
+                      rk.srow(nxt)[rank] = static_cast<uint16_t>(row_of_slot(rk, cur, p, K, changed));
+                      rk.nsel[rank] = static_cast<uint16_t>(p);
+                    }
+                  });
+      if (__syncthreads_or(ok ? 0 : 1)) {
+        if (tid == 0) shared_store(fa.sync + 1, 1u);
+        return;
       }
     }
     const int nxt = moved ? cur ^ 1 : cur;
@@ -375,9 +469,17 @@ uint32_t fused_workgroups(uint32_t P) {
   return std::max(1u, std::min(kFusedMaxWorkgroups, (units + kFusedWaves - 1) / kFusedWaves));
 }
 
+size_t fused_exchange_bytes(uint32_t P) {             // xkeys [2][P], xsurv [2][K], xrank [P]; zeroed once
+  return (static_cast<size_t>(2) * P + 2 * (P / 4) + P) * 8;
+}
+
 hipError_t launch_fused(const FusedArgs &args, hipStream_t stream) {
   FusedArgs fa = args;
   if (fa.ev.Jp != static_cast<uint32_t>(kLanes) || fa.ev.P > kFusedMaxPool || fa.ev.P < 4 || fa.n_generations == 0)
+    return hipErrorInvalidValue;
+  const uint32_t n_wg = fused_workgroups(fa.ev.P);
+  // every wave keeps its units of a generation in registers, and a workgroup's share of a ranking by counting fits its counters
+  if ((fa.ev.P + n_wg * kFusedWaves - 1) / (n_wg * kFusedWaves) > kFusedUnits || (fa.ev.P + n_wg - 1) / n_wg > kMergeMax)
     return hipErrorInvalidValue;
   fa.ev.bk.nb = 0;
   fa.ev.stash_stride = stash_stride(kLanes, fa.ev.per_gpu != 0);
@@ -391,8 +493,7 @@ hipError_t launch_fused(const FusedArgs &args, hipStream_t stream) {
   if (rc != hipSuccess) return rc;
   void *params[] = {&fa};
   // cooperative: the runtime refuses the launch unless all workgroups can be resident at once
-  return hipLaunchCooperativeKernel(fn, dim3(fused_workgroups(fa.ev.P)), dim3(kFusedThreads), params,
-                                    static_cast<unsigned int>(lds), stream);
+  return hipLaunchCooperativeKernel(fn, dim3(n_wg), dim3(kFusedThreads), params, static_cast<unsigned int>(lds), stream);
 }
 
 }  // namespace ones
