@@ -181,6 +181,15 @@ int ones_generation(ones_ctx *ctx, int32_t n_generations);
  * count, another device current), ONES_E_HIP. */
 int ones_generation_static(ones_ctx *ctx, int32_t n_generations);
 
+/* Pools of at most 64 job slots and 2048 candidates with a fixed remaining work run all
+ * generations of a ones_generation call of three or more generations in ONE launch whose
+ * workgroups exchange results while it runs; a workgroup polls for the others' results at most
+ * `polls` times (at first 2^22, a few seconds) and then gives up: the launch ends, the next call
+ * that synchronises (ones_best, ones_export, ones_placement) returns ONES_E_HIP, and the context
+ * only accepts ones_destroy from then on.  This never happens on a healthy device; polls = 0
+ * makes every wait give up at once, which is how the error path is tested. */
+int ones_set_wait_limit(ones_ctx *ctx, uint32_t polls);
+
 /* The winner S* (Alg. 1: smallest score): global batch and GPU count per slot (HOST
  * arrays of n_slots entries, either may be NULL) and its score.  Between ones_set_jobs and the
  * next generation no schedule exists under the new table: the call then returns the last
@@ -209,8 +218,9 @@ int32_t ones_padded_jobs(int32_t n_slots);
  * generation are bracketed by HIP events on the context's stream (n = 1: every generation;
  * an event costs a few microseconds of stream time); every <= 0 switches it off.
  * A small pool (at most 64 job slots and 2048 candidates, fixed remaining work) runs all
- * generations of a ones_generation call in one launch: that launch counts as one evolve launch
- * (every n-th call is bracketed) and there is no select launch.
+ * generations of a ones_generation call of three or more generations in one launch: that
+ * launch counts as one evolve launch (every n-th call is bracketed) and there is no select
+ * launch.
  * ones_profile_read synchronises and returns the accumulated kernel time in milliseconds
  * and the number of bracketed launches since the last ones_profile_enable call (any output
  * may be NULL). */

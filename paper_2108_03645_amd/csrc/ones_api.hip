@@ -101,7 +101,10 @@ BucketPlan bucket_plan(uint32_t P) {
   return bp;
 }
 
-// Pools whose generations run in one launch per ones_generation call (ones_fused.hip).
+// Pools whose generations run in one launch per ones_generation call (ones_fused.hip).  The
+// launch is a cooperative one, which costs about 20 us where an ordinary launch costs 2.5, so
+// calls of one or two generations are cheaper as two ordinary launches per generation.
+constexpr int32_t kFusedMinGenerations = 3;
 bool fused_pool(uint32_t P, uint32_t Jp) { return Jp == static_cast<uint32_t>(kLanes) && P <= kFusedMaxPool; }
 
 ScratchLayout make_scratch_layout(uint32_t P) {
@@ -681,7 +684,7 @@ static int generation_impl(ones_ctx *c, int32_t n_generations, bool in_static_sc
     block = c->static_scratch;
     if (n_generations > 0) c->splitters_valid = false;   // the workspace's splitters fall behind
   }
-  if (c->fused && !c->sampling && n_generations > 0) {
+  if (c->fused && !c->sampling && n_generations >= kFusedMinGenerations) {
     // uses no scratch at all: every workgroup ranks the pool in its LDS
     int rc = run_fused(c, static_cast<uint32_t>(n_generations), !in_static_scratch);
     if (rc) { c->poisoned = true; return rc; }
@@ -889,6 +892,12 @@ int ones_export_remaining(ones_ctx *c, double *remaining_out) {
 
 int ones_generation(ones_ctx *c, int32_t n_generations) {
   return guarded([&] { return generation_impl(c, n_generations, false); });
+}
+
+int ones_set_wait_limit(ones_ctx *c, uint32_t polls) {
+  if (!c) return ONES_E_INVALID_ARG;
+  c->spin_limit = polls;
+  return ONES_OK;
 }
 
 int ones_generation_static(ones_ctx *c, int32_t n_generations) {

@@ -123,7 +123,6 @@ struct EvolveArgs {
 // bookkeeping only genes, fit_row and tab are used, and ev.t is the generation counter BEFORE
 // the call (the launch runs generations ev.t + 1 .. ev.t + n_generations).
 constexpr uint32_t kFusedMaxPool = 2048;
-constexpr int kFusedWaves = 8;               // waves per workgroup
 struct FusedArgs {
   EvolveArgs ev;
   uint32_t *parent_rows;    // [K] in: rows of the survivors, best first; out: of the new survivors

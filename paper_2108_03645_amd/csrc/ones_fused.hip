@@ -30,11 +30,18 @@
 namespace ones {
 namespace {
 
+#ifndef ONES_FUSED_WAVES
+#define ONES_FUSED_WAVES 8
+#endif
+#ifndef ONES_FUSED_WORKGROUPS
+#define ONES_FUSED_WORKGROUPS 192
+#endif
+constexpr int kFusedWaves = ONES_FUSED_WAVES;          // waves per workgroup
 constexpr int kFusedThreads = kFusedWaves * kLanes;
-constexpr uint32_t kFusedMaxWorkgroups = 96;
+constexpr uint32_t kFusedMaxWorkgroups = ONES_FUSED_WORKGROUPS;
 constexpr uint32_t kFusedUnits = 4;          // most units (candidates) one wave computes per generation
-constexpr uint32_t kMergeMax = 256;          // children beating the K-th survivor that are still merged locally
-constexpr int kGatherPer = kFusedMaxPool / kFusedThreads;   // entries per thread when a workgroup collects P values
+constexpr uint32_t kMergeMax = 128;          // children beating the K-th survivor that are still merged locally
+constexpr int kGatherPer = (kFusedMaxPool + kFusedThreads - 1) / kFusedThreads;   // entries per thread when a workgroup collects P values
 
 template <typename T>
 __device__ __forceinline__ T shared_load(const T *p) {
@@ -68,7 +75,8 @@ struct Ranks {
   uint32_t *oslot;     // [kMergeMax]
   uint32_t *below;     // [kMergeMax] counters of the rankings by counting
   uint32_t *occ;       // bitmap over the P + K rows: the survivors' rows
-  uint32_t *misc;      // [0] number of children that beat the K-th survivor
+  uint32_t *wfree;     // free rows before each word of the bitmap
+  uint32_t *misc;      // [0] number of children that beat the K-th survivor, [1] whether there is one
   uint32_t *draws;     // [waves][kFusedUnits][4] per unit: ranks of the parents, rotation (drawn ahead)
   uint32_t *words;     // [waves][kFusedUnits][64] per unit: the gene words (drawn ahead)
   uint64_t *ukeys;     // [waves][kFusedUnits] per unit: the score, until the wave publishes it
@@ -77,7 +85,7 @@ struct Ranks {
 inline size_t ranks_bytes(uint32_t P) {
   const size_t K = P / 4;
   return 2 * K * 8 + 2 * K * 2 + K * 2 + P * 2 + P * 8 + 3 * K * 8 + 3 * K * 4 + kMergeMax * (8 + 4 + 4) +
-         ((P + K + 31) / 32) * 4 + 16 + kFusedWaves * kFusedUnits * ((4 + kLanes) * 4 + 8) + 64;
+         ((P + K + 31) / 32) * 8 + 16 + kFusedWaves * kFusedUnits * ((4 + kLanes) * 4 + 8) + 64;
 }
 
 __device__ __forceinline__ Ranks carve_ranks(unsigned char *base, uint32_t P) {
@@ -93,7 +101,8 @@ __device__ __forceinline__ Ranks carve_ranks(unsigned char *base, uint32_t P) {
   r.oslot = r.mslot + 3 * K;
   r.below = r.oslot + kMergeMax;
   r.occ = r.below + kMergeMax;
-  r.misc = r.occ + (P + K + 31) / 32;
+  r.wfree = r.occ + (P + K + 31) / 32;
+  r.misc = r.wfree + (P + K + 31) / 32;
   r.draws = r.misc + 4;
   r.words = r.draws + kFusedWaves * kFusedUnits * 4;
   r.srows = reinterpret_cast<uint16_t *>(r.words + kFusedWaves * kFusedUnits * kLanes);
@@ -105,32 +114,31 @@ __device__ __forceinline__ Ranks carve_ranks(unsigned char *base, uint32_t P) {
 // The survivors' rows (rows[0..K)) as a bitmap, and from it the free rows in ascending order.
 // from_bitmap: the bitmap is there already.  Whole workgroup; ends with a barrier.
 __device__ __forceinline__ void list_free_rows(const Ranks &rk, const uint16_t *rows, uint32_t P, bool from_bitmap) {
-  const uint32_t K = P / 4, n_rows = P + K, words = (n_rows + 31) / 32;
+  const uint32_t K = P / 4, n_rows = P + K, words = (n_rows + 31) / 32;   // at most 80 words
   if (!from_bitmap) {
     for (uint32_t w = threadIdx.x; w < words; w += blockDim.x) rk.occ[w] = 0;
     __syncthreads();
     for (uint32_t g = threadIdx.x; g < K; g += blockDim.x) atomicOr(&rk.occ[rows[g] >> 5], 1u << (rows[g] & 31u));
     __syncthreads();
   }
+  // free rows before each bitmap word (one wave scans the words' counts), ...
   if (threadIdx.x < kLanes) {
-    const uint32_t lane = threadIdx.x;
     uint32_t carry = 0;
     for (uint32_t base = 0; base < words; base += kLanes) {
-      const uint32_t w = base + lane;
-      uint32_t bits = 0;
-      if (w < words) {
-        bits = ~rk.occ[w];
-        if (w == words - 1 && n_rows % 32 != 0) bits &= (1u << (n_rows % 32)) - 1u;
-      }
-      const uint32_t n = __popc(bits);
+      const uint32_t w = base + threadIdx.x;
+      const uint32_t n = w < words ? __popc(~rk.occ[w]) : 0u;   // bits beyond the last row are never looked at
       const uint32_t incl = wave_inclusive_scan(n);
-      uint32_t pos = carry + incl - n;
-      while (bits) {
-        if (pos < P) rk.frow[pos] = static_cast<uint16_t>(w * 32 + (__ffs(static_cast<int>(bits)) - 1));
-        bits &= bits - 1;
-        ++pos;
-      }
+      if (w < words) rk.wfree[w] = carry + incl - n;
       carry += __builtin_amdgcn_readlane(incl, kLanes - 1);
+    }
+  }
+  __syncthreads();
+  // ... then every row finds its own place in the list
+  for (uint32_t row = threadIdx.x; row < n_rows; row += blockDim.x) {
+    const uint32_t free_bits = ~rk.occ[row >> 5], bit = row & 31u;
+    if ((free_bits >> bit) & 1u) {
+      const uint32_t pos = rk.wfree[row >> 5] + __popc(free_bits & ((1u << bit) - 1u));
+      if (pos < P) rk.frow[pos] = static_cast<uint16_t>(row);
     }
   }
   __syncthreads();
@@ -162,30 +170,33 @@ __device__ __forceinline__ bool gather(const uint64_t *src, uint32_t n, uint32_t
         take(threadIdx.x + k * kFusedThreads, v[k]);
         pending &= ~(1u << k);
       }
-    if (pending != 0) __builtin_amdgcn_s_sleep(1);
   }
   return true;
 }
 
-// What a child or mutant draws before it needs anything of its parents: the parents' ranks, the
-// rotation of its repair, its word per gene.  Depends on (seed, generation, slot) only, so a
-// wave draws for the coming generation while the scores of the current one are still arriving.
-template <bool kOverGpus>
-__device__ __forceinline__ void draw_ahead(const EvolveArgs &a, uint32_t t, uint32_t u, int lane, uint32_t *draws,
-                                           uint32_t *words) {
+// What a child or mutant draws before it needs anything of its parents: the parents' ranks and
+// the rotation of its repair (draw_parents), its word per gene (draw_words).  Both depend on
+// (seed, generation, slot) only, so a wave draws for the coming generation while the scores of
+// the current generation are still arriving.
+__device__ __forceinline__ void draw_parents(const EvolveArgs &a, uint32_t t, uint32_t u, int lane, uint32_t *draws) {
   const uint32_t K = a.K;
   Draw d;
-  uint32_t w[1] = {0u};
-  if (u < 2 * K) {                                   // child of a pair: both share the pair's parents and words
+  if (u < 2 * K) {                                   // child of a pair: both share the pair's parents
     const uint32_t p0 = K + (u & ~1u);
     d = candidate_draw(a, t, p0);
     if (u & 1u) d.r = candidate_draw(a, t, p0 + 1).r;
-    if (!kOverGpus) gene_words<1>(a, t, p0, lane, w);
   } else {
     d = candidate_draw(a, t, K + u);
-    gene_words<1>(a, t, K + u, lane, w);
   }
   if (lane == 0) { draws[0] = d.ra; draws[1] = d.rb; draws[2] = d.r; }
+}
+
+template <bool kOverGpus>
+__device__ __forceinline__ void draw_words(const EvolveArgs &a, uint32_t t, uint32_t u, int lane, uint32_t *words) {
+  const uint32_t K = a.K;
+  uint32_t w[1] = {0u};
+  if (u >= 2 * K) gene_words<1>(a, t, K + u, lane, w);
+  else if (!kOverGpus) gene_words<1>(a, t, K + (u & ~1u), lane, w);   // both children share the pair's words
   words[lane] = w[0];
 }
 
@@ -250,11 +261,16 @@ __global__ __launch_bounds__(kFusedThreads) void fused_kernel(FusedArgs fa) {
   uint32_t *my_draws = rk.draws + wave_in_block * kFusedUnits * 4;
   uint32_t *my_words = rk.words + wave_in_block * kFusedUnits * kLanes;
   uint64_t *my_keys = rk.ukeys + wave_in_block * kFusedUnits;
-  auto draw_units = [&](uint32_t t) {                // this wave's children and mutants of generation t
+  auto draw_unit_parents = [&](uint32_t t) {         // for this wave's children and mutants of generation t
     for (uint32_t k = 0, u = wave; k < kFusedUnits && u < 3 * K; ++k, u += n_waves)
-      draw_ahead<kOverGpus>(a, t, u, opaque(lane0), my_draws + 4 * k, my_words + kLanes * k);
+      draw_parents(a, t, u, opaque(lane0), my_draws + 4 * k);
   };
-  draw_units(a.t + 1);
+  auto draw_unit_words = [&](uint32_t t) {
+    for (uint32_t k = 0, u = wave; k < kFusedUnits && u < 3 * K; ++k, u += n_waves)
+      draw_words<kOverGpus>(a, t, u, opaque(lane0), my_words + kLanes * k);
+  };
+  draw_unit_parents(a.t + 1);
+  draw_unit_words(a.t + 1);
   stage_table<1>(a.tab, a.bk, s, kLanes, a.term_lds);
   // the state the last selection left: the survivors' rows and scores, the bitmap of their rows
   for (uint32_t e = tid; e < K; e += kFusedThreads) {
@@ -263,7 +279,7 @@ __global__ __launch_bounds__(kFusedThreads) void fused_kernel(FusedArgs fa) {
     rk.skey(0)[e] = static_cast<uint64_t>(__double_as_longlong(a.fit_row[row]));
   }
   for (uint32_t w = tid; w < (P + K + 31) / 32; w += kFusedThreads) rk.occ[w] = fa.occupied[w];
-  if (tid == 0) rk.misc[0] = 0;
+  if (tid == 0) rk.misc[0] = rk.misc[1] = 0;
   __syncthreads();
   list_free_rows(rk, nullptr, P, true);
 
@@ -304,11 +320,19 @@ __global__ __launch_bounds__(kFusedThreads) void fused_kernel(FusedArgs fa) {
         if (u < 3 * K) shared_store(xk + K + u, my_keys[k] | use_tag(use));
         else shared_store(xs + (u - 3 * K), my_keys[k] | use_tag(fa.changes_before));
       }
-    if (!last) draw_units(t + 1);                    // while the others' scores are on their way
+    if (!last) {                                     // while the others' scores are on their way
+      draw_unit_parents(t + 1);
+      draw_unit_words(t + 1);
+    }
 
-    // ---- collect the scores
+    // ---- collect the scores; a child that beats the K-th survivor raises a flag (an equal score
+    // loses to the survivor's smaller slot)
+    const uint64_t thresh = changed ? 0ull : rk.skey(cur)[K - 1];
     bool ok = gather(xk + K, 3 * K, fa.spin_limit, [&](uint64_t v) { return (v & kTagBit) == use_tag(use); },
-                     [&](uint32_t i, uint64_t v) { rk.ckey[K + i] = v & ~kTagBit; });
+                     [&](uint32_t i, uint64_t v) {
+                       rk.ckey[K + i] = v & ~kTagBit;
+                       if ((v & ~kTagBit) < thresh) rk.misc[1] = 1;
+                     });
     if (changed)
       ok = gather(xs, K, fa.spin_limit, [&](uint64_t v) { return (v & kTagBit) == use_tag(fa.changes_before); },
                   [&](uint32_t i, uint64_t v) { rk.ckey[i] = v & ~kTagBit; }) && ok;
@@ -320,9 +344,13 @@ __global__ __launch_bounds__(kFusedThreads) void fused_kernel(FusedArgs fa) {
     // ---- rank the pool
     bool moved = true;                               // the set of survivors (hence the free rows) changes
     bool by_counting = changed;                      // rank the whole pool, a share per workgroup
-    if (!changed) {
-      // children that beat the K-th survivor (an equal score loses to the survivor's smaller slot)
-      const uint64_t thresh = rk.skey(cur)[K - 1];
+    if (!changed && rk.misc[1] == 0) {
+      // no child beats the K-th survivor: same survivors, same order, same free rows
+      if (last && blockIdx.x != 0) return;
+      moved = false;
+      if (last) for (uint32_t e = tid; e < K; e += kFusedThreads) rk.nsel[e] = static_cast<uint16_t>(e);
+    } else if (!changed) {
+      // list the children that beat the K-th survivor
       for (uint32_t base = 0; base < 3 * K; base += kFusedThreads) {   // whole waves go round together
         const uint32_t i = base + tid;
         const uint64_t key = i < 3 * K ? rk.ckey[K + i] : ~0ull;
@@ -338,10 +366,7 @@ __global__ __launch_bounds__(kFusedThreads) void fused_kernel(FusedArgs fa) {
       // in the last generation only the first workgroup needs the ranking (it writes the state the
       // call leaves); the others stay for their share of a ranking by counting, if there is one
       if (last && blockIdx.x != 0 && M <= kMergeMax) return;
-      if (M == 0) {
-        moved = false;                               // same survivors, same order, same free rows
-        if (last) for (uint32_t e = tid; e < K; e += kFusedThreads) rk.nsel[e] = static_cast<uint16_t>(e);
-      } else if (M > kMergeMax) {
+      if (M > kMergeMax) {
         by_counting = true;
         for (uint32_t e = tid; e < K; e += kFusedThreads) rk.ckey[e] = rk.skey(cur)[e];
       } else {
@@ -395,7 +420,7 @@ __global__ __launch_bounds__(kFusedThreads) void fused_kernel(FusedArgs fa) {
         }
       }
       __syncthreads();
-      if (tid == 0) rk.misc[0] = 0;                  // for the next generation (read again only after further barriers)
+      if (tid == 0) rk.misc[0] = rk.misc[1] = 0;     // for the next generation (read again only after further barriers)
     }
     if (by_counting) {
       // ckey holds the whole pool's scores by slot.  This workgroup ranks its share of the slots

@@ -34,7 +34,7 @@ _JOB_DTYPES = {"job_id": np.int64, "active": np.uint8, "bmin": np.int32, "bmax":
                "gpu_max_batch": np.int32, "a": np.float64, "c": np.float64, "d": np.float64,
                "remaining": np.float64}
 
-EXPORTS = ["ones_workspace_bytes", "ones_init", "ones_set_jobs", "ones_generation", "ones_generation_static", "ones_best",
+EXPORTS = ["ones_workspace_bytes", "ones_init", "ones_set_jobs", "ones_generation", "ones_generation_static", "ones_set_wait_limit", "ones_best",
            "ones_export", "ones_placement", "ones_update_limits", "ones_set_new_jobs_first", "ones_set_processed_time", "ones_set_crossover",
            "ones_set_progress", "ones_export_remaining", "ones_padded_jobs",
            "ones_profile_enable", "ones_profile_read",
@@ -85,6 +85,7 @@ def load():
     L.ones_set_jobs.argtypes = [C.c_void_p, C.POINTER(ones_jobs)]
     L.ones_generation.argtypes = [C.c_void_p, C.c_int32]
     L.ones_generation_static.argtypes = [C.c_void_p, C.c_int32]
+    L.ones_set_wait_limit.argtypes = [C.c_void_p, C.c_uint32]
     L.ones_best.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(C.c_double)]
     L.ones_export.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(C.c_int64)]
     L.ones_placement.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
@@ -176,6 +177,9 @@ class Search:
         static device array (for callers that cannot allocate)."""
         with self._torch.cuda.device(self.device):
             _check(load().ones_generation_static(self._h, int(n)))
+
+    def set_wait_limit(self, polls: int):
+        _check(load().ones_set_wait_limit(self._h, int(polls)))
 
     def set_progress(self, alpha=None, beta=None, processed=None):
         """ones_set_progress: one entry per slot each; all None switches the sampling off."""

@@ -302,6 +302,76 @@ def test_two_contexts_and_a_side_stream(ones, ref):
     assert_same_state(b, cb, "context b (side stream)")
 
 
+# ---- pools of one job row: all generations of a call in one launch ----
+
+@pytest.mark.parametrize("n_slots,n_gpus,pop,seed,per_gpu,new_first", [
+    (8, 16, 64, 0, False, False), (40, 64, 1024, 1, False, False), (64, 64, 2048, 2, False, True),
+    (64, 200, 2048, 3, True, True), (33, 20, 68, 4, False, False), (5, 3, 4, 5, True, False), (17, 9, 8, 6, False, True),
+    (60, 64, 1500, 7, True, False), (1, 1, 12, 8, False, False), (64, 4000, 600, 9, False, True)])
+def test_single_launch_generations_with_mixed_call_lengths(ones, ref, n_slots, n_gpus, pop, seed, per_gpu, new_first):
+    """Calls of 1 and 2 generations take two launches per generation, longer ones a single launch
+    for the whole call; the state one path leaves is the state the other starts from.  With table
+    changes (the first generation of the next call refreshes the survivors), arrivals served first
+    by executed time, and both crossovers."""
+    rng = np.random.default_rng(seed)
+    cl = cluster(n_gpus, n_slots, pop, seed=seed + 77)
+    jobs = random_jobs(rng, n_slots)
+    say(f"[single launch] G={n_gpus} slots={n_slots} P={pop} seed={cl.seed} per_gpu={per_gpu} new_first={new_first}")
+    gpu, cpu = ones.Search(cl, jobs), ref.RefSearch(cl, jobs)
+    for s in (gpu, cpu):
+        s.set_crossover(per_gpu=per_gpu)
+        s.set_new_jobs_first(new_first)
+    assert_same_state(gpu, cpu, "initial population")
+    for step, n in enumerate([5, 1, 3, 2, 20, 4, 1, 7, 3, 40]):
+        gpu.generation(n); cpu.generation(n)
+        assert_same_state(gpu, cpu, f"call {step} of {n} generations")
+        gb, cb = gpu.best(), cpu.best()
+        assert gb[0].tolist() == cb[0].tolist() and gb[1].tolist() == cb[1].tolist() and gb[2] == cb[2]
+        if step in (1, 3, 4, 6, 8):                                   # a new table before calls of 3, 20, 4, 7 and 40
+            j2 = random_jobs(rng, n_slots) if step != 4 else jobs
+            j2.job_id = np.where(rng.random(n_slots) < 0.6, jobs.job_id, jobs.job_id + 1000 * (step + 1))
+            j2.remaining = j2.remaining * 0.9
+            for s in (gpu, cpu):
+                s.set_jobs(j2)
+                if new_first and step != 6:
+                    s.set_processed_time(rng_times(seed, step, n_slots))
+            assert_same_state(gpu, cpu, f"table change after call {step}")
+            jobs = j2
+    assert all(np.array_equal(x, y) for x, y in zip(gpu.placement(), cpu.placement()))
+    gpu.close(); cpu.close()
+
+
+def rng_times(seed, step, n_slots):
+    return np.random.default_rng([seed, step]).integers(0, 5, n_slots) * 60.0
+
+
+def test_single_launch_waits_are_bounded(ones):
+    """With a wait limit of 0 every workgroup gives up at its first wait for the others' results:
+    the launch ends by itself, the next synchronising call reports the error and the context
+    refuses further work."""
+    cl, jobs = W.paper_scale()
+    s = ones.Search(cl, jobs)
+    s.generation(5)
+    before = s.export(genes=False)
+    assert before[3] == 5
+    s.set_wait_limit(0)
+    say("[single launch] wait limit 0")
+    s.generation(5)                                  # asynchronous: the launch itself succeeds
+    with pytest.raises(ones.OnesError) as e:
+        s.best()
+    assert e.value.code == -6 and b"gave up" in ones.load().ones_strerror(-6)
+    for call in (lambda: s.generation(1), lambda: s.generation(5), s.best, s.export, s.placement):
+        with pytest.raises(ones.OnesError) as e:
+            call()
+        assert e.value.code == -6
+    s.close()
+    # an untouched context is not affected
+    s = ones.Search(cl, jobs)
+    s.generation(5)
+    assert np.array_equal(s.export(genes=False)[2], before[2])
+    s.close()
+
+
 # ---- the five configurations at their stated size and length ----
 
 def host_threads():
@@ -408,9 +478,12 @@ def test_profile_hook_counts_launches(ones):
     s = ones.Search(cl, jobs)
     s.profile_enable(1)
     s.generation(7)
-    s.generation(1)
+    s.generation(3)
     prof = s.profile_read()
     assert prof["evolve_launches"] == 2 and prof["select_launches"] == 0 and prof["evolve_ms"] > 0
+    s.generation(1)                           # a call of one or two generations takes two launches per generation
+    prof = s.profile_read()
+    assert prof["evolve_launches"] == 3 and prof["select_launches"] == 1
     s.close()
 
 
