@@ -5,7 +5,12 @@ A step is one generation of the whole hot path (compose the pool from the surviv
 every candidate to the cluster capacity, score it, select the best quarter) on the stress
 cluster: 4096 GPUs, 2048 jobs, pool of 65536 candidates.  Prints one JSON line.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload stress|large|paper_scale|tiny]
+Protocol: the search is created from the same seed --reps + 1 times (initial population and
+W warm-up generations untimed, then exactly K timed generations between two synchronisations);
+the first repetition is a warm-up run, the reported figures are those of the repetition with
+the median time of the others.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--reps 3] [--workload stress|large|paper_scale|tiny|online]
 """
 from __future__ import annotations
 
@@ -14,6 +19,9 @@ import hashlib
 import json
 import os
 import sys
+import platform
+import statistics
+import subprocess
 import time
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
@@ -34,31 +42,79 @@ def evolve_source_hash() -> str:
     return h.hexdigest()
 
 
+def device_copy_gbps(torch) -> float:
+    """Read + write rate of a plain 1 GiB device-to-device copy (best of 5), HIP events on the current stream."""
+    src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda:0").fill_(1)
+    dst = torch.empty_like(src)
+    dst.copy_(src)
+    best = float("inf")
+    for _ in range(5):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(); dst.copy_(src); e1.record()
+        e1.synchronize()
+        best = min(best, e0.elapsed_time(e1))
+    del src, dst
+    return 2 * (1 << 30) / (best * 1e-3) / 1e9
+
+
+def host_info():
+    model = ""
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.lower().startswith("model name"):
+                model = line.split(":", 1)[1].strip()
+                break
+    except OSError:
+        pass
+    try:
+        gcc = subprocess.run(["gcc", "--version"], capture_output=True, text=True).stdout.splitlines()[0]
+    except (OSError, IndexError):
+        gcc = ""
+    try:
+        usable = len(os.sched_getaffinity(0))
+    except AttributeError:
+        usable = os.cpu_count() or 1
+    return {"cpu_model": model or platform.processor(), "nproc": os.cpu_count() or 1, "usable_cpus": usable,
+            "compiler": gcc}
+
+
 def cpu_baseline(workload: str, sampled: bool = False):
-    """The CPU oracle, as it stands, on a bounded sample of the same workload."""
+    """The CPU oracle, as it stands, on a bounded sample of the same workload: a leg on the
+    host's share of cores (at most 16 threads, the share of a one-GPU machine) and a single-thread
+    leg, both from the same initial population."""
     from oracle import ones_ref
     from paper_2108_03645_amd import workloads as W
-    threads = max(1, min(16, os.cpu_count() or 1))
+    info = host_info()
+    threads = max(1, min(16, info["usable_cpus"]))
     if workload == "stress":
         cl, jobs = W.stress()
-        gens, sample = 3, "stress cluster at full size (pool 65536), 3 generations after the initial population"
+        gens_all, gens_one = 10, 2
     else:
         cl, jobs = W.CONFIGS[workload]()
-        gens = max(1, min(cl.generations, int(2e8 / (cl.population * max(cl.n_slots, 1)))))
-        sample = f"{workload}, {gens} generations"
-    ones_ref.set_threads(threads)
-    s = ones_ref.RefSearch(cl, jobs)
-    if sampled:
-        s.set_progress(*W.progress(cl.n_slots, seed=cl.seed))
-    t0 = time.perf_counter()
-    s.generation(gens)
-    dt = time.perf_counter() - t0
-    s.close()
-    ones_ref.set_threads(1)
+        gens_all = max(10, min(cl.generations, int(1.5e9 / (cl.population * max(cl.n_slots, 1)))))
+        gens_one = max(2, gens_all // 8)
     active = int(jobs.active.sum())
-    return {"value": cl.population * active * gens / dt, "unit": "evals/s", "cores": threads,
-            "kind": "oracle", "sample": sample,
-            "generations_per_s": gens / dt, "seconds": dt}
+    legs = {}
+    for name, n_threads, gens in (("all", threads, gens_all), ("one", 1, gens_one)):
+        ones_ref.set_threads(n_threads)
+        s = ones_ref.RefSearch(cl, jobs)              # initial population, not timed
+        if sampled:
+            s.set_progress(*W.progress(cl.n_slots, seed=cl.seed))
+        t0 = time.perf_counter()
+        s.generation(gens)
+        dt = time.perf_counter() - t0
+        s.close()
+        legs[name] = {"value": cl.population * active * gens / dt, "generations_per_s": gens / dt, "seconds": dt,
+                      "generations": gens, "threads": n_threads}
+    ones_ref.set_threads(1)
+    out = {"value": legs["all"]["value"], "unit": "evals/s", "cores": threads, "kind": "oracle",
+           "sample": f"{workload} at full size (pool {cl.population}, {active} jobs): {gens_all} generations after the initial "
+                     f"population on {threads} threads; single-thread leg: {gens_one} generations",
+           "generations_per_s": legs["all"]["generations_per_s"], "seconds": legs["all"]["seconds"],
+           "single_thread": {k: legs["one"][k] for k in ("value", "generations_per_s", "seconds", "generations")},
+           "flags": "gcc -O2 -ffp-contract=off -fopenmp"}
+    out.update(info)
+    return out
 
 
 def online(args, torch, ones, W) -> int:
@@ -129,6 +185,9 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=40)
     ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--reps", type=int, default=3,
+                    help="timed repetitions from the same seed after one warm-up repetition; the median is reported "
+                         "(0: a single run, for profilers)")
     ap.add_argument("--workload", default="stress", choices=["stress", "large", "paper_scale", "tiny", "online"])
     ap.add_argument("--sampled", action="store_true",
                     help="probability sampling of the remaining work (Alg. 1): every generation draws it anew "
@@ -159,37 +218,53 @@ def main() -> int:
     active = int(jobs.active.sum())
     jp = ones.padded_jobs(cl.n_slots)
     torch.cuda.set_device(0)
-    search = ones.Search(cl, jobs, device="cuda:0")       # initial population, not timed
-    if args.sampled:
-        search.set_progress(*W.progress(cl.n_slots, seed=cl.seed))
-    search.set_crossover(per_gpu=args.crossover == "gpus")
-    search.generation(args.warmup)
-    search.synchronize()
-    torch.cuda.synchronize()
 
-    search.profile_enable(0 if args.no_events else 4)     # events on every 4th generation
-    t0 = time.perf_counter()
-    search.generation(args.steps)
-    search.synchronize()
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    prof = search.profile_read()
-    _, _, best_fit = search.best()
+    def one_run():
+        search = ones.Search(cl, jobs, device="cuda:0")       # initial population, not timed
+        if args.sampled:
+            search.set_progress(*W.progress(cl.n_slots, seed=cl.seed))
+        search.set_crossover(per_gpu=args.crossover == "gpus")
+        search.generation(args.warmup)
+        search.synchronize()
+        torch.cuda.synchronize()
+        search.profile_enable(0 if args.no_events else 4)     # events on every 4th generation
+        t0 = time.perf_counter()
+        search.generation(args.steps)
+        search.synchronize()
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        prof = search.profile_read()
+        _, _, best_fit = search.best()
+        search.close()
+        return {"dt": dt, "prof": prof, "best_fit": best_fit}
 
+    runs = [one_run() for _ in range(args.reps + 1)][1:] if args.reps > 0 else [one_run()]
+    times = sorted(r["dt"] for r in runs)
+    median = next(r for r in runs if r["dt"] == times[(len(times) - 1) // 2])
+    dt, prof, best_fit = median["dt"], median["prof"], median["best_fit"]
+    assert all(r["best_fit"] == best_fit for r in runs), "repetitions from one seed must end in one state"
+
+    single_launch = prof["select_launches"] == 0 and prof["evolve_launches"] > 0   # small pool: one launch per call
     if args.no_events:
         prof = {"evolve_ms": float("nan"), "evolve_launches": 1, "select_ms": float("nan"), "select_launches": 1}
     evolve_ms = prof["evolve_ms"] / max(1, prof["evolve_launches"])
     select_ms = prof["select_ms"] / max(1, prof["select_launches"])
-    # algorithmic bytes of one evolve launch: every gene read once and written once (int32),
-    # one fp64 score per candidate
-    alg_bytes = cl.population * cl.n_slots * 8 + cl.population * 8
-    if args.sampled:      # the survivors are kept in place (no read, no write) but read once more to be scored
-        alg_bytes = (cl.population * 3 // 4) * cl.n_slots * 8 + (cl.population // 4) * cl.n_slots * 4 + cl.population * 8
+    if single_launch:
+        evolve_ms, select_ms = evolve_ms / args.steps, 0.0    # the launch runs all timed generations
+    # Bytes one evolve launch has to move for what it computes: it composes the 3P/4 children and
+    # mutants (the P/4 survivors stay where they are), each gene of them read once from a parent
+    # row and written once (int32), plus one fp64 score per candidate composed.
+    composed = cl.population * 3 // 4
+    alg_bytes = composed * cl.n_slots * 8 + composed * 8
+    if args.sampled:      # the survivors are read once more to be scored again
+        alg_bytes += (cl.population // 4) * (cl.n_slots * 4 + 8)
+    pool_bytes = cl.population * cl.n_slots * 8 + cl.population * 8   # every candidate of the pool counted as read and written
     achieved = alg_bytes / (evolve_ms * 1e-3) / 1e9
     traffic = None
     if MEASURED_TRAFFIC["source_sha256"] == evolve_source_hash() and args.workload == "stress" and not args.sampled \
             and args.crossover == "jobs":
         traffic = MEASURED_TRAFFIC["bytes_per_launch"]
+    copy_gbps = device_copy_gbps(torch)
 
     out = {
         "metric": "candidate-job fitness evals/sec",
@@ -205,14 +280,25 @@ def main() -> int:
                    "seed": cl.seed, "jobs_sha256": jobs.sha256()[:16],
                    "remaining_work": "sampled per generation" if args.sampled else "fixed",
                    "crossover": "over " + args.crossover},
+        "repetitions": {"timed": len(runs), "warmup_runs": 1 if args.reps > 0 else 0, "reported": "median",
+                        "ms_per_step_all": [r["dt"] * 1e3 / args.steps for r in runs]},
         "generations_per_s": args.steps / dt,
         "best_fitness": best_fit,
-        "kernels": {"evolve_ms": evolve_ms, "select_ms": select_ms},
-        "roofline": {"bound": "hbm", "kernel": "evolve_kernel", "achieved": achieved, "peak": HBM_PEAK_GBPS,
+        "kernels": {"evolve_ms": evolve_ms, "select_ms": select_ms,
+                    "launches_per_generation": "one launch for all timed generations" if single_launch else "evolve + select"},
+        "roofline": {"bound": "hbm", "kernel": "fused_kernel" if single_launch else "evolve_kernel",
+                     "achieved": achieved, "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
-                     "algorithmic_bytes_per_launch": alg_bytes},
+                     "algorithmic_bytes_per_launch": alg_bytes,
+                     "units_per_launch": f"{composed} candidates composed x {cl.n_slots} job slots, 8 B each, + 8 B per candidate",
+                     # measured traffic over the same duration (None once the kernel has changed since the counters were read)
+                     "physical_gbps": None if traffic is None else traffic / (evolve_ms * 1e-3) / 1e9,
+                     "physical_frac": None if traffic is None else traffic / (evolve_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+                     # a plain device-to-device copy of 1 GiB on this machine, read + write: the practical ceiling
+                     "device_copy_gbps": copy_gbps, "frac_of_device_copy": achieved / copy_gbps,
+                     # the survey's per-pool figure (every candidate counted as read and written, survivors included)
+                     "pool_equivalent_gbps": pool_bytes / (evolve_ms * 1e-3) / 1e9},
     }
-    search.close()
     if args.copy_reference:
         src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda:0").fill_(1)
         dst = torch.empty_like(src)
