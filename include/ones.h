@@ -208,7 +208,9 @@ int ones_placement(ones_ctx *ctx, int32_t *slot_of_gpu, int32_t *batch_of_gpu);
 
 /* Copies the whole state to HOST arrays (any may be NULL): genes[P][Jp] batch sizes with
  * Jp = ones_padded_jobs(n_slots), fit[P], sel[K] (survivor slots by ascending
- * (fitness, slot)), generation counter.  For parity checks and checkpoints.  Synchronises. */
+ * (fitness, slot)), generation counter.  For parity checks and checkpoints.  Synchronises.
+ * Also reports, as ONES_E_HIP, a defect of the library's own row bookkeeping that its kernels
+ * detected (a genome row index outside the array, which they pull back inside before use). */
 int ones_export(ones_ctx *ctx, int32_t *genes, double *fit, int32_t *sel, int64_t *generation);
 
 /* Job slots padded to whole rows of 64 columns: 64 * ceil(max(n_slots,1) / 64). */

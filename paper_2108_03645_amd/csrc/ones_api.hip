@@ -154,7 +154,7 @@ Layout make_layout(uint32_t P, uint32_t Jp, uint32_t G) {
   L.ra = take(Jp * 8); L.rc = take(Jp * 8); L.rd = take(Jp * 8); L.rY = take(Jp * 8);
   L.alpha = take(Jp * 8); L.beta = take(Jp * 8); L.processed = take(Jp * 8);
   L.time_rank = take(Jp * 4);
-  L.best_batch = take(Jp * 4); L.best_gpus = take(Jp * 4); L.best_fit = take(8); L.best_err = take(4);
+  L.best_batch = take(Jp * 4); L.best_gpus = take(Jp * 4); L.best_fit = take(8); L.best_err = take(8);
   L.place_slot = take(static_cast<size_t>(G) * 4); L.place_batch = take(static_cast<size_t>(G) * 4);
   L.total = off;
   return L;
@@ -166,7 +166,7 @@ Layout make_layout(uint32_t P, uint32_t Jp, uint32_t G) {
 size_t stage_bytes(const Layout &L, uint32_t Jp, uint32_t G) {
   const size_t table = L.rY + static_cast<size_t>(Jp) * 8 - L.rawinfo;        // rawinfo, changed, a, c, d, Y
   const size_t progress = L.processed + static_cast<size_t>(Jp) * 8 - L.alpha; // alpha, beta, processed
-  const size_t best = L.best_err + 4 - L.best_batch;                           // batch, gpus, fitness, error word
+  const size_t best = L.best_err + 8 - L.best_batch;                           // batch, gpus, fitness, error words
   const size_t place = L.place_batch + static_cast<size_t>(G) * 4 - L.place_slot;
   return std::max({table, progress, best, place, static_cast<size_t>(Jp) * 4});
 }
@@ -362,6 +362,7 @@ int run_generation(ones_ctx *c, uint32_t t, char *scratch, bool &splitters_valid
   a.new_first = c->new_jobs_first && c->no_schedule ? 1u : 0u;   // the table's "arrived" marks are fresh
   a.per_gpu = c->per_gpu ? 1u : 0u;
   a.stash_stride = 0;                                            // the launcher sets it
+  a.fault = c->at<uint32_t>(c->L.fsync) + 2;
   a.time_rank = c->has_times ? c->at<uint32_t>(c->L.time_rank) : nullptr;
   // quantile buckets: only when the survivors reappear with the scores they had
   const bool buckets = same_table && !sampled && c->bp.nb != 0 && splitters_valid;
@@ -407,8 +408,13 @@ int run_generation(ones_ctx *c, uint32_t t, char *scratch, bool &splitters_valid
     HIP_TRY(launch_select(a.fit_row, rp, c->P, c->K, store, c->at<int32_t>(c->L.sel), draw, c->stream));
     if (draw.on) c->drawn_for = static_cast<int64_t>(t) + 1;
     splitters_valid = false;
-    if (c->bp.nb != 0 && !sampled) { // splitters for the bucketed generations that follow; clears both
-                                     // counter sets.  Under sampling no bucketed generation can follow.
+    if (c->bp.nb != 0 && !sampled && same_table) {
+      // Splitters for the bucketed generations that follow; clears both counter sets.  Under sampling
+      // no bucketed generation can follow.  Nor after an initial population or a refresh under a new
+      // table: the scores of such survivors say little about where their children will fall (nearly
+      // all children of a random population beat its best members and would crowd into the first
+      // bucket, more than a workgroup sorts in LDS), so the generation after it is ranked in full
+      // once more and the buckets start from survivors that the search itself produced.
       HIP_TRY(launch_splitters(a.fit_row, a.row_of, c->at<int32_t>(c->L.sel), c->K, c->bp.nb,
                                reinterpret_cast<uint64_t *>(sc(S.split)), reinterpret_cast<uint64_t *>(sc(S.thresh)),
                                reinterpret_cast<uint32_t *>(sc(S.bcount[0])),
@@ -636,6 +642,7 @@ static int run_fused(ones_ctx *c, uint32_t n, bool events) {
   a.rescore = 0;
   a.per_gpu = c->per_gpu ? 1u : 0u;
   a.stash_stride = 0; a.term_lds = 0;
+  a.fault = c->at<uint32_t>(c->L.fsync) + 2;
   a.bk = BucketArgs{};
   const int next = c->cur ^ 1;
   fa.parent_rows = c->at<uint32_t>(c->L.parent_row[next]);
@@ -708,14 +715,23 @@ static int wait_gave_up(ones_ctx *c) {
   return ONES_E_HIP;
 }
 
-// For the calls that synchronise without reading the winner: fetches the error word of the
-// single-launch generations.  The stream must be idle.
+// A kernel had to pull a row index back into the genome array: the row bookkeeping is wrong
+// (a defect of the library, never of the caller's input).
+static int row_fault(ones_ctx *c) {
+  c->poisoned = true;
+  snprintf(g_hip_msg, sizeof(g_hip_msg), "internal error: a genome row index was out of range; destroy the context");
+  return ONES_E_HIP;
+}
+
+// For the calls that synchronise without reading the winner: fetches the error words the
+// kernels leave (a wait of a single-launch generation gave up; a row index was out of range).
+// The stream must be idle.
 static int check_waits(ones_ctx *c) {
   if (c->poisoned) return poisoned_error();
-  if (!c->fused) return ONES_OK;
-  uint32_t gave_up = 0;
-  HIP_TRY(hipMemcpy(&gave_up, c->ws + c->L.fsync + 4, 4, hipMemcpyDeviceToHost));
-  return gave_up ? wait_gave_up(c) : ONES_OK;
+  uint32_t words[2] = {0, 0};
+  HIP_TRY(hipMemcpy(words, c->ws + c->L.fsync + 4, 8, hipMemcpyDeviceToHost));
+  if (words[0]) return wait_gave_up(c);
+  return words[1] ? row_fault(c) : ONES_OK;
 }
 
 static int best_impl(ones_ctx *c, int32_t *batch_out, int32_t *gpus_out, double *fitness_out) {
@@ -727,13 +743,14 @@ static int best_impl(ones_ctx *c, int32_t *batch_out, int32_t *gpus_out, double 
                       c->at<int32_t>(c->L.best_gpus), c->at<double>(c->L.best_fit),
                       c->at<uint32_t>(c->L.fsync) + 1, c->at<uint32_t>(c->L.best_err), c->stream));
   const Layout &L = c->L;
-  HIP_TRY(hipMemcpyAsync(c->stage, c->ws + L.best_batch, L.best_err + 4 - L.best_batch, hipMemcpyDeviceToHost,
+  HIP_TRY(hipMemcpyAsync(c->stage, c->ws + L.best_batch, L.best_err + 8 - L.best_batch, hipMemcpyDeviceToHost,
                          c->stream));
   HIP_TRY(hipStreamSynchronize(c->stream));
   auto staged = [&](size_t off) { return c->stage + (off - L.best_batch); };   // laid out as in the workspace
-  uint32_t gave_up = 0;
-  memcpy(&gave_up, staged(L.best_err), 4);
-  if (gave_up) return wait_gave_up(c);
+  uint32_t words[2] = {0, 0};
+  memcpy(words, staged(L.best_err), 8);
+  if (words[0]) return wait_gave_up(c);
+  if (words[1]) return row_fault(c);
   if (batch_out && c->Jn) memcpy(batch_out, staged(L.best_batch), c->Jn * 4);
   if (gpus_out && c->Jn) memcpy(gpus_out, staged(L.best_gpus), c->Jn * 4);
   if (fitness_out) memcpy(fitness_out, staged(L.best_fit), 8);

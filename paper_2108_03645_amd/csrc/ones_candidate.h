@@ -242,7 +242,30 @@ __device__ __forceinline__ void list_free_rows(const EvolveArgs &a, const Smem &
   }
 }
 
+// The kernel's own argument block, for values that only a rare path needs: read there, at the
+// point of use, they are not carried (and spilled) through every work item.  Valid in kernels
+// whose argument block starts with one EvolveArgs passed by value, which every kernel that
+// includes this header must take (each of them says so at its signature).
+using KernelArgs = const __attribute__((address_space(4))) EvolveArgs;
+__device__ __forceinline__ KernelArgs *kernel_args() {
+  KernelArgs *ka = (KernelArgs *)__builtin_amdgcn_kernarg_segment_ptr();
+  asm volatile("" : "+s"(ka));
+  return ka;
+}
+
+// A row index is kept inside the genome array whatever the free-row list holds, so that a mistake
+// in it cannot turn into a stray access; but such a mistake must not pass unnoticed either.
+// Every entry of a round's list passes through checked_row once, when the kernel records the
+// rows of the round's slots: a clamp that changes a value is noted in LDS (s.next_item[1]) and
+// the workgroup raises the context's fault word, which ones_export reports, when it ends.
+__device__ __forceinline__ uint32_t checked_row(const Smem &s, uint32_t row, uint32_t n_rows) {
+  if (row >= n_rows) s.next_item[1] = 1;
+  return min(row, n_rows - 1);
+}
+
 // Row listed at position i of the current round (wave-uniform); never outside the genome array.
+// (No note here: this sits in the work-item loop, whose register allocation has no room to spare,
+// and reads the entries that checked_row has seen.)
 __device__ __forceinline__ uint32_t row_at(const Smem &s, uint32_t i, const EvolveArgs &a) {
   return min(static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(s.rows[i])), a.P + a.K - 1);
 }
@@ -447,11 +470,8 @@ __device__ __forceinline__ void drop_in_bucket(const EvolveArgs &a, const Smem &
   if (lane == 0) {
     // The pointers of the bucket storage are read from the kernel's argument block here, where
     // the few candidates that get this far need them, instead of being carried (and spilled)
-    // through every work item.  The kernels of this file take one EvolveArgs by value, so the
-    // argument block is that struct.
-    using KernelArgs = const __attribute__((address_space(4))) EvolveArgs;
-    KernelArgs *ka = (KernelArgs *)__builtin_amdgcn_kernarg_segment_ptr();
-    asm volatile("" : "+s"(ka));
+    // through every work item.
+    KernelArgs *ka = kernel_args();
     uint32_t *count = ka->bk.count;
     const uint32_t seg = ka->bk.seg;
     const uint32_t slot = atomicAdd(&count[b], 1u);
@@ -524,7 +544,11 @@ __device__ __forceinline__ void crossover_over_gpus(const EvolveArgs &a, uint32_
     const uint32_t mask = bits >= 32u ? 0xFFFFFFFFu : (1u << bits) - 1u;
     return static_cast<uint32_t>(e >> 32) + static_cast<uint32_t>(__popc(static_cast<uint32_t>(e) & mask));
   };
+  // A job's first GPU is the GPU after its predecessor's last one (slot order: the lane to the left,
+  // or the last lane of the row above), so the heads below a job's range are looked up once, at
+  // its end, and its start takes the predecessor's value.
   uint32_t carry_a = 0, carry_b = 0;                             // GPUs of the rows above (wave-uniform)
+  uint32_t above_a = 0, above_b = 0;                             // heads below the first GPU of the row (wave-uniform)
 #pragma unroll
   for (int i = 0; i < R; ++i) {
     const uint32_t incl_a = wave_inclusive_scan(cA[i]), incl_b = wave_inclusive_scan(cB[i]);
@@ -532,8 +556,12 @@ __device__ __forceinline__ void crossover_over_gpus(const EvolveArgs &a, uint32_
     const uint32_t end_b = min(carry_b + incl_b, a.G), start_b = min(carry_b + incl_b - cB[i], a.G);
     carry_a += __builtin_amdgcn_readlane(incl_a, kLanes - 1);
     carry_b += __builtin_amdgcn_readlane(incl_b, kLanes - 1);
-    const uint32_t heads_a = heads_below(end_a) - heads_below(start_a);
-    const uint32_t heads_b = heads_below(end_b) - heads_below(start_b);
+    const uint32_t at_end_a = heads_below(end_a), at_end_b = heads_below(end_b);
+    const uint32_t left_a = __shfl_up(at_end_a, 1, kLanes), left_b = __shfl_up(at_end_b, 1, kLanes);
+    const uint32_t heads_a = at_end_a - (lane == 0 ? above_a : left_a);
+    const uint32_t heads_b = at_end_b - (lane == 0 ? above_b : left_b);
+    above_a = __builtin_amdgcn_readlane(at_end_a, kLanes - 1);
+    above_b = __builtin_amdgcn_readlane(at_end_b, kLanes - 1);
     const uint32_t n1 = heads_a + ((end_b - start_b) - heads_b);
     const uint32_t n2 = ((end_a - start_a) - heads_a) + heads_b;
     const uint2 k = s.cc2[lane + kLanes * i];

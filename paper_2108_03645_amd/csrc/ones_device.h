@@ -114,6 +114,7 @@ struct EvolveArgs {
   uint32_t       per_gpu;     // the uniform crossover scans the GPUs (Eq. 1) instead of the jobs; needs G <= kMaxCoinGpus
   uint32_t       stash_stride; // set by the launcher: bytes of LDS scratch per wave
   uint32_t       term_lds;    // set by the launcher: entries per job of the term table in LDS, 0 = none
+  uint32_t       *fault;      // [1] raised when a row index had to be pulled back into the genome array
   BucketArgs     bk;
 };
 

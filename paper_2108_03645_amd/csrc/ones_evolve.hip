@@ -29,6 +29,7 @@ constexpr int kGroupFirst = 8 * ONES_ROW_GROUP + 1;   // row counts kGroupFirst 
 template <int R> struct Shape { static constexpr int kWaves = R > 16 ? ONES_WAVES_BIG : (R > 4 ? 8 : 4); };
 
 // Initial population G_0: every gene uniform over {waiting, bmin..bmax}.
+// (Argument block: one EvolveArgs by value, see kernel_args.)
 template <int R>
 __global__ __launch_bounds__(Shape<R>::kWaves *kLanes) void init_kernel(EvolveArgs a) {
   extern __shared__ __align__(16) unsigned char smem_raw[];
@@ -59,12 +60,14 @@ __global__ __launch_bounds__(Shape<R>::kWaves *kLanes) void init_kernel(EvolveAr
 // generation was repaired and scored, so a survivor is a fixed point of the repair with the
 // same score: it stays in its row untouched, and stored genes need no clamp.
 // kOverGpus: the uniform crossover scans the GPUs instead of the jobs.
+// (Argument block: one EvolveArgs by value, see kernel_args.)
 template <int R, bool kSameTable, bool kOverGpus>
 __global__ __launch_bounds__(Shape<R>::kWaves *kLanes) void evolve_kernel(EvolveArgs a) {
   extern __shared__ __align__(16) unsigned char smem_raw[];
   const Smem s = carve(smem_raw, a.Jp, a.term_lds, Shape<R>::kWaves, a.stash_stride);
   const int lane0 = threadIdx.x & (kLanes - 1);
   const IndexLoads index_loads = index_free_rows_begin(a, lane0);
+  if (threadIdx.x == 0) s.next_item[1] = 0;          // no row index has been out of range (checked_row)
   stage_table<R>(a.tab, a.bk, s, a.Jp, a.term_lds);
   index_free_rows_end(a, s, index_loads, lane0);
   const uint32_t wave_in_block = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -86,7 +89,7 @@ __global__ __launch_bounds__(Shape<R>::kWaves *kLanes) void evolve_kernel(Evolve
   __syncthreads();
   for (uint32_t i = threadIdx.x; i < (kSameTable ? 3 : 4) * n; i += blockDim.x) {
     const uint32_t p = i < 2 * n ? K + 2 * ra + i : i < 3 * n ? 3 * K + ra + (i - 2 * n) : ra + (i - 3 * n);
-    a.row_of[p] = min(s.rows[i], a.P + a.K - 1);
+    a.row_of[p] = checked_row(s, s.rows[i], a.P + a.K);
   }
   const uint32_t kinds = (!kSameTable || a.rescore) ? 3u : 2u;
   const bool new_first = !kSameTable && a.new_first != 0;       // never under an unchanged table
@@ -192,6 +195,8 @@ __global__ __launch_bounds__(Shape<R>::kWaves *kLanes) void evolve_kernel(Evolve
     }
   }
   }
+  __syncthreads();
+  if (threadIdx.x == 0 && s.next_item[1] != 0) atomicOr(kernel_args()->fault, 1u);
 }
 
 template <typename Kernel>

@@ -27,6 +27,8 @@
 #include "ones_candidate.h"
 #include "ones_sort.h"
 
+#include <cstddef>
+
 namespace ones {
 namespace {
 
@@ -247,6 +249,8 @@ __device__ __forceinline__ double compose_unit(const EvolveArgs &a, uint32_t t, 
   return score<1>(c, s, a.term_lds, lane);
 }
 
+// (Argument block: FusedArgs by value, which starts with its EvolveArgs, see kernel_args.)
+static_assert(offsetof(FusedArgs, ev) == 0, "kernel_args() reads the EvolveArgs at the start of the argument block");
 template <bool kOverGpus>
 __global__ __launch_bounds__(kFusedThreads) void fused_kernel(FusedArgs fa) {
   extern __shared__ __align__(16) unsigned char smem_raw[];

@@ -520,7 +520,8 @@ __global__ void best_kernel(const int32_t *genes, const double *fit_row, const u
   }
   if (threadIdx.x == 0) {
     *fit_out = fit_row[best];
-    *err_out = *err_in;                              // travels to the host with the winner
+    err_out[0] = err_in[0];                          // the two error words travel to the host with the winner
+    err_out[1] = err_in[1];
   }
 }
 
