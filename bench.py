@@ -198,6 +198,10 @@ def main() -> int:
     ap.add_argument("--policies", action="store_true",
                     help="online workload only: batch-size limits from the policies of Section 3.3.2 "
                          "(ones_update_limits, timed as a leg of its own) and new jobs served first")
+    ap.add_argument("--table-changes", type=int, default=0,
+                    help="replace the job table (remaining work shrunk by 1 %%) this many times, evenly spread over the "
+                         "timed generations: exercises the refresh of the survivors under a new table and the "
+                         "selection that follows it; not the headline configuration")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-events", action="store_true", help="do not bracket kernels with HIP events")
     ap.add_argument("--copy-reference", action="store_true",
@@ -229,7 +233,18 @@ def main() -> int:
         torch.cuda.synchronize()
         search.profile_enable(0 if args.no_events else 4)     # events on every 4th generation
         t0 = time.perf_counter()
-        search.generation(args.steps)
+        if args.table_changes > 0:
+            table = jobs.copy()
+            done = 0
+            for k in range(args.table_changes + 1):
+                upto = args.steps * (k + 1) // (args.table_changes + 1)
+                search.generation(upto - done)
+                done = upto
+                if k < args.table_changes:
+                    table.remaining = table.remaining * 0.99
+                    search.set_jobs(table)
+        else:
+            search.generation(args.steps)
         search.synchronize()
         torch.cuda.synchronize()
         dt = time.perf_counter() - t0
@@ -279,7 +294,7 @@ def main() -> int:
                    "mutation_rate": cl.mutation_rate, "crossover_rate": cl.crossover_rate,
                    "seed": cl.seed, "jobs_sha256": jobs.sha256()[:16],
                    "remaining_work": "sampled per generation" if args.sampled else "fixed",
-                   "crossover": "over " + args.crossover},
+                   "crossover": "over " + args.crossover, "table_changes": args.table_changes},
         "repetitions": {"timed": len(runs), "warmup_runs": 1 if args.reps > 0 else 0, "reported": "median",
                         "ms_per_step_all": [r["dt"] * 1e3 / args.steps for r in runs]},
         "generations_per_s": args.steps / dt,

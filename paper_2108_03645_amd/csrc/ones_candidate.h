@@ -520,7 +520,9 @@ __device__ __forceinline__ void load_genes(const int32_t *row, int lane, uint32_
 // Coin of GPU i: bit i mod 32 of word (i mod 128) div 32 of Philox block (i div 128, p0, t, 3);
 // lane l draws the coins of GPUs 128 l .. 128 l + 127.  coins: this wave's kMaxCoinGpus / 32
 // entries of LDS, each a coin word and, above it, the number of heads on the GPUs before it.
-template <int R>
+// kFeasible: both parents are known to fit the cluster (they were repaired under the current
+// job table), so no GPU position needs to be cut off at the cluster's size.
+template <int R, bool kFeasible>
 __device__ __forceinline__ void crossover_over_gpus(const EvolveArgs &a, uint32_t t, const Smem &s, uint64_t *coins, uint32_t p0,
                                                     int lane, uint32_t (&cA)[R], uint32_t (&cB)[R]) {
   {
@@ -552,8 +554,12 @@ __device__ __forceinline__ void crossover_over_gpus(const EvolveArgs &a, uint32_
 #pragma unroll
   for (int i = 0; i < R; ++i) {
     const uint32_t incl_a = wave_inclusive_scan(cA[i]), incl_b = wave_inclusive_scan(cB[i]);
-    const uint32_t end_a = min(carry_a + incl_a, a.G), start_a = min(carry_a + incl_a - cA[i], a.G);
-    const uint32_t end_b = min(carry_b + incl_b, a.G), start_b = min(carry_b + incl_b - cB[i], a.G);
+    uint32_t end_a = carry_a + incl_a, start_a = end_a - cA[i];
+    uint32_t end_b = carry_b + incl_b, start_b = end_b - cB[i];
+    if (!kFeasible) {
+      end_a = min(end_a, a.G); start_a = min(start_a, a.G);
+      end_b = min(end_b, a.G); start_b = min(start_b, a.G);
+    }
     carry_a += __builtin_amdgcn_readlane(incl_a, kLanes - 1);
     carry_b += __builtin_amdgcn_readlane(incl_b, kLanes - 1);
     const uint32_t at_end_a = heads_below(end_a), at_end_b = heads_below(end_b);

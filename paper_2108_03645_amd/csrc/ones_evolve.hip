@@ -35,12 +35,19 @@ __global__ __launch_bounds__(Shape<R>::kWaves *kLanes) void init_kernel(EvolveAr
   extern __shared__ __align__(16) unsigned char smem_raw[];
   const Smem s = carve(smem_raw, a.Jp, a.term_lds, Shape<R>::kWaves, a.stash_stride);
   stage_table<R>(a.tab, a.bk, s, a.Jp, a.term_lds);
+  if (threadIdx.x == 0) *s.next_item = 0;
   __syncthreads();
   const int lane0 = threadIdx.x & (kLanes - 1);
-  const uint32_t wave = __builtin_amdgcn_readfirstlane(blockIdx.x * Shape<R>::kWaves + (threadIdx.x >> 6));
-  const uint32_t stride = gridDim.x * Shape<R>::kWaves;
-  for (uint32_t p = wave; p < a.P; p += stride) {
+  // The workgroup owns a contiguous share of the slots; its waves take them one by one from an
+  // LDS counter (random genomes differ widely in the fill rounds their repair needs).
+  const uint32_t first = static_cast<uint32_t>(static_cast<uint64_t>(a.P) * blockIdx.x / gridDim.x);
+  const uint32_t last = static_cast<uint32_t>(static_cast<uint64_t>(a.P) * (blockIdx.x + 1) / gridDim.x);
+  for (;;) {
     const int lane = opaque(lane0);
+    uint32_t taken = 0;
+    if (lane == 0) taken = atomicAdd(s.next_item, 1u);
+    const uint32_t p = first + static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(taken));
+    if (p >= last) break;
     const Draw dr = candidate_draw(a, a.t, p);
     uint32_t c[R];
     gene_words<R>(a, a.t, p, lane, c);
@@ -116,7 +123,7 @@ __global__ __launch_bounds__(Shape<R>::kWaves *kLanes) void evolve_kernel(Evolve
         gpus_from_batches<R, kSameTable>(s, lane, c);
         gpus_from_batches<R, kSameTable>(s, lane, B);
         phase_fence();
-        crossover_over_gpus<R>(a, a.t, s, reinterpret_cast<uint64_t *>(stash), p0, lane, c, B);
+        crossover_over_gpus<R, kSameTable>(a, a.t, s, reinterpret_cast<uint64_t *>(stash), p0, lane, c, B);
         phase_fence();                                   // the coins are no longer needed: their place holds the second child
 #pragma unroll
         for (int i = 0; i < R; ++i) stash[lane + kLanes * i] = static_cast<uint8_t>(32 - __clz(static_cast<int>(B[i])));

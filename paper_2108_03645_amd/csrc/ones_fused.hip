@@ -226,7 +226,7 @@ __device__ __forceinline__ double compose_unit(const EvolveArgs &a, uint32_t t, 
       gpus_from_batches<1, kSameTable>(s, lane, c);
       gpus_from_batches<1, kSameTable>(s, lane, B);
       if (kOverGpus) {
-        crossover_over_gpus<1>(a, t, s, reinterpret_cast<uint64_t *>(stash), K + (u & ~1u), lane, c, B);
+        crossover_over_gpus<1, kSameTable>(a, t, s, reinterpret_cast<uint64_t *>(stash), K + (u & ~1u), lane, c, B);
         c[0] = side ? B[0] : c[0];
       } else {
         const bool swap = w < a.T_x;                 // the first child takes the second parent's gene
