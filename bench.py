@@ -32,12 +32,12 @@ HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published peak
 
 # HBM bytes per evolve launch on the stress workload from rocprofv3 --pmc FETCH_SIZE and
 # WRITE_SIZE (see profiles/), valid only for the kernel source with this hash.
-MEASURED_TRAFFIC = {"source_sha256": "e9d81364773f1cf0cc269181a542b992b7978dba02948547dbb9499219ac3215", "bytes_per_launch": 802786829}
+MEASURED_TRAFFIC = {"source_sha256": "1579c037114a092e839ce058b7b53ac52fb8f72901d27261c534f0f12af5a31d", "bytes_per_launch": 802600137}
 
 
 def evolve_source_hash() -> str:
     h = hashlib.sha256()
-    for f in ("ones_evolve.hip", "ones_device.h"):
+    for f in ("ones_evolve.hip", "ones_candidate.h", "ones_device.h"):
         h.update(open(os.path.join(ROOT, "paper_2108_03645_amd", "csrc", f), "rb").read())
     return h.hexdigest()
 

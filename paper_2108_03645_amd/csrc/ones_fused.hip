@@ -28,6 +28,7 @@
 #include "ones_sort.h"
 
 #include <cstddef>
+#include <cstdlib>
 
 namespace ones {
 namespace {
@@ -521,6 +522,11 @@ hipError_t launch_fused(const FusedArgs &args, hipStream_t stream) {
   hipError_t rc = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
   if (rc != hipSuccess) return rc;
   void *params[] = {&fa};
+  // For tools that cannot follow a cooperative launch (rocprofv3's kernel trace ends in a fault when
+  // the process exits after one): the same kernel as an ordinary launch.  Its waits stay bounded,
+  // but nothing then guarantees that all workgroups are resident at once, so this is not for production.
+  static const bool plain = getenv("ONES_FUSED_PLAIN_LAUNCH") != nullptr;
+  if (plain) return hipLaunchKernel(fn, dim3(n_wg), dim3(kFusedThreads), params, lds, stream);
   // cooperative: the runtime refuses the launch unless all workgroups can be resident at once
   return hipLaunchCooperativeKernel(fn, dim3(n_wg), dim3(kFusedThreads), params, static_cast<unsigned int>(lds), stream);
 }
