@@ -262,7 +262,8 @@ struct ones_ctx {
   bool poisoned;              // a launch failed in the middle of a generation: the state is inconsistent
   bool fused;                 // small pool: all generations of a call in one cooperative launch
   uint32_t fused_generations; // generations those launches have run so far
-  uint32_t fused_changes;     // ... of them first generations after a table change
+  uint32_t fused_changes;     // ... of them generations that also exchanged the survivors' scores
+  uint32_t fused_draws;       // ... of them generations with a drawn remaining work
   uint32_t spin_limit;        // polls before a device-wide wait gives up
   int device;                 // the device the context was created on
   char *static_scratch;       // this device's copy of the library's static scratch array
@@ -304,11 +305,9 @@ int upload_table(ones_ctx *c, const HostJobs &h, const std::vector<uint32_t> *ch
   RawJobs raw{c->at<uint32_t>(c->L.rawinfo), c->at<double>(c->L.ra), c->at<double>(c->L.rc),
               c->at<double>(c->L.rd), c->at<double>(c->L.rY)};
   c->term_E = h.term_E;
-  HIP_TRY(launch_prepare_table(raw, c->table(), c->Jp, c->stream));
-  HIP_TRY(launch_build_terms(c->table(), c->Jp, c->stream));
-  if (n_changed)   // every physical row, whether a candidate lives in it or not
-    HIP_TRY(launch_reset_slots(c->at<int32_t>(c->L.genes), c->at<uint32_t>(c->L.changed),
-                               static_cast<uint32_t>(n_changed), c->P + c->K, c->Jp, c->stream));
+  // every physical row, whether a candidate lives in it or not
+  HIP_TRY(launch_table_change(raw, c->table(), c->Jp, c->at<int32_t>(c->L.genes), c->at<uint32_t>(c->L.changed),
+                              static_cast<uint32_t>(n_changed), c->P + c->K, c->stream));
   HIP_TRY(hipStreamSynchronize(c->stream));     // the staging buffer is free again
   return ONES_OK;
 }
@@ -493,6 +492,7 @@ static int init_impl(ones_ctx **out, const ones_config *cfg, const ones_jobs *jo
   c->fused = false;
   c->fused_generations = 0;
   c->fused_changes = 0;
+  c->fused_draws = 0;
   c->spin_limit = 1u << 22;   // a few seconds of polling
   c->ids = h.id;
   {
@@ -507,7 +507,7 @@ static int init_impl(ones_ctx **out, const ones_config *cfg, const ones_jobs *jo
     if ((rc = static_scratch_of(dev, &c->static_scratch))) return rc;
     // the single-launch path needs a launch whose workgroups are all resident at once
     c->fused = fused_pool(c->P, c->Jp) && prop.cooperativeLaunch != 0 &&
-               fused_workgroups(c->P) <= static_cast<uint32_t>(c->n_cus);
+               fused_grid_limit(c->P) <= static_cast<uint32_t>(c->n_cus);
   }
   c->profiling = false; c->profile_every = 1; c->profile_tick = 0; c->evolve_used = c->select_used = 0;
   {
@@ -624,7 +624,7 @@ static int export_remaining_impl(ones_ctx *c, double *remaining_out) {
   return ONES_OK;
 }
 
-// All n generations in one cooperative launch (small pools, fixed remaining work).
+// All n generations in one cooperative launch (small pools).
 static int run_fused(ones_ctx *c, uint32_t n, bool events) {
   FusedArgs fa;
   EvolveArgs &a = fa.ev;
@@ -653,6 +653,12 @@ static int run_fused(ones_ctx *c, uint32_t n, bool events) {
   fa.xkeys = c->at<uint64_t>(c->L.xkeys);
   fa.xsurv = fa.xkeys + static_cast<size_t>(2) * c->P;
   fa.xrank = fa.xsurv + static_cast<size_t>(2) * c->K;
+  fa.xdraw = fa.xrank + c->P;
+  fa.draws_before = c->fused_draws;
+  fa.sampled = c->sampling ? 1u : 0u;
+  fa.pr = Progress{c->at<double>(c->L.alpha), c->at<double>(c->L.beta), c->at<double>(c->L.processed)};
+  fa.n_slots = c->Jn;
+  fa.y_out = c->at<double>(c->L.Y[c->y_cur]);      // what ones_export_remaining reads
   fa.sync = c->at<uint32_t>(c->L.fsync);
   fa.generations_before = c->fused_generations;
   fa.changes_before = c->fused_changes;
@@ -664,7 +670,11 @@ static int run_fused(ones_ctx *c, uint32_t n, bool events) {
   HIP_TRY(launch_fused(fa, c->stream));
   if (events && (rc = timed(c, c->evolve_ev, c->evolve_used, false))) return rc;
   c->fused_generations += n;
-  c->fused_changes += fa.first_changed;
+  c->fused_changes += c->sampling ? n : fa.first_changed;
+  if (c->sampling) {
+    c->fused_draws += n;
+    c->drawn_for = 0;               // the two-launch path makes its own draw for the generation it runs next
+  }
   c->table_changed = false;
   c->no_schedule = false;
   c->splitters_valid = false;       // the two-launch path ranks the pool in full before it uses buckets again
@@ -691,7 +701,7 @@ static int generation_impl(ones_ctx *c, int32_t n_generations, bool in_static_sc
     block = c->static_scratch;
     if (n_generations > 0) c->splitters_valid = false;   // the workspace's splitters fall behind
   }
-  if (c->fused && !c->sampling && n_generations >= kFusedMinGenerations) {
+  if (c->fused && n_generations >= kFusedMinGenerations) {
     // uses no scratch at all: every workgroup ranks the pool in its LDS
     int rc = run_fused(c, static_cast<uint32_t>(n_generations), !in_static_scratch);
     if (rc) { c->poisoned = true; return rc; }

@@ -118,6 +118,12 @@ struct EvolveArgs {
   BucketArgs     bk;
 };
 
+// Remaining work of slot j under probability sampling (Alg. 1, Eq. 7) for generation t:
+// tab.Y[j] = processed[j] * (1/rho - 1), rho ~ Be(alpha[j], beta[j]), for j < Jn; then the
+// slot's entries of the term table.
+struct Progress {
+  const double *alpha, *beta, *processed;   // [Jp]
+};
 // All generations of one ones_generation call in a single launch, for pools that are small
 // enough to be ranked inside every workgroup's LDS (one row of 64 job columns, at most
 // kFusedMaxPool candidates).  ev describes the problem as for the evolve kernel; of its row
@@ -135,16 +141,24 @@ struct FusedArgs {
   uint64_t *xkeys;          // [2][P] tagged score bits of the children by pool slot, a buffer per generation parity
   uint64_t *xsurv;          // [2][K] the same for survivors refreshed after a table change
   uint64_t *xrank;          // [P] ranks from a ranking by counting, stamped with the generation
+  uint64_t *xdraw;          // [4][64] tagged draws of the remaining work (probability sampling), four generations rotating
   uint32_t *sync;           // [1] set when a poll ran out
   uint32_t generations_before;  // generations these launches have run for the context so far
-  uint32_t changes_before;      // ... of them first generations after a table change
+  uint32_t changes_before;      // ... of them generations that also exchanged the survivors' scores
+  uint32_t draws_before;        // ... of them generations with a drawn remaining work
+  uint32_t sampled;             // probability sampling (Alg. 1): every generation draws the remaining work anew
+  Progress pr;                  // its inputs
+  uint32_t n_slots;             // Jn: slots at or beyond it have no remaining work
+  double  *y_out;               // [64] out: the remaining work the last generation was scored with
   uint32_t n_generations;   // > 0
   uint32_t first_changed;   // the job table changed since the survivors were scored: the first generation refreshes them
   uint32_t spin_limit;      // polls before a wait gives up (0: gives up at once; for tests of that path)
   uint32_t table_lds;       // set by the launcher: bytes of LDS the staged job table takes
+  uint32_t work_groups;     // set by the launcher: workgroups that compute candidates (the grid's first ones)
 };
 // Workgroups to launch for a pool of P (the launch must be co-resident: cooperative).
-uint32_t fused_workgroups(uint32_t P);
+uint32_t fused_workgroups(uint32_t P, bool sampled);
+uint32_t fused_grid_limit(uint32_t P);      // the largest grid a launch for a pool of P uses
 size_t fused_exchange_bytes(uint32_t P);    // xkeys, xsurv and xrank, consecutive
 hipError_t launch_fused(const FusedArgs &fa, hipStream_t s);
 
@@ -173,14 +187,11 @@ struct RawJobs {              // uploaded by the host after validation, [Jp] eac
 };
 
 // launchers (each returns the hipGetLastError of its launch)
-hipError_t launch_prepare_table(const RawJobs &raw, const JobTable &tab, uint32_t Jp, hipStream_t s);
+// The per-slot values and the term table from the raw table, and the n_changed slots (may be 0)
+// that changed hands set to "waiting" in every one of the genome rows; one launch.
+hipError_t launch_table_change(const RawJobs &raw, const JobTable &tab, uint32_t Jp, int32_t *genes, const uint32_t *slots,
+                               uint32_t n_changed, uint32_t rows, hipStream_t s);
 hipError_t launch_build_terms(const JobTable &tab, uint32_t Jp, hipStream_t s);
-// Remaining work of slot j under probability sampling (Alg. 1, Eq. 7) for generation t:
-// tab.Y[j] = processed[j] * (1/rho - 1), rho ~ Be(alpha[j], beta[j]), for j < Jn; then the
-// slot's entries of the term table.
-struct Progress {
-  const double *alpha, *beta, *processed;   // [Jp]
-};
 hipError_t launch_sample_remaining(const Progress &pr, const JobTable &tab, uint32_t Jn, uint32_t Jp,
                                    uint32_t key0, uint32_t key1, uint32_t t, hipStream_t s);
 // The same draw for the coming generation t, made by extra workgroups of the general selection's
@@ -191,9 +202,6 @@ struct SampleNext {
   JobTable tab;
   uint32_t Jn, Jp, key0, key1, t, on;
 };
-// slots: the n_changed slots whose genes are set to "waiting" in every one of the rows
-hipError_t launch_reset_slots(int32_t *genes, const uint32_t *slots, uint32_t n_changed, uint32_t rows, uint32_t Jp,
-                              hipStream_t s);
 // same_table: the job table is the one the previous generation was repaired and scored with
 hipError_t launch_evolve_group0(const EvolveArgs &a, int rows, bool same_table, int n_cus, hipStream_t s);
 hipError_t launch_evolve_group1(const EvolveArgs &a, int rows, bool same_table, int n_cus, hipStream_t s);

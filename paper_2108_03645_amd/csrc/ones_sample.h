@@ -72,11 +72,12 @@ __device__ inline bool gamma_candidate(uint32_t key0, uint32_t key1, uint32_t n,
 constexpr int kTeam = 8;
 constexpr int kLanesPerSlot = 2 * kTeam;
 
-// thread: position among the Jp * kLanesPerSlot threads that serve the Jp slots (whole waves,
-// all lanes active).  Writes tab.Y[j] and the slot's entries of tab.terms for generation t.
-__device__ inline void sample_remaining_slot(const Progress &pr, const JobTable &tab, uint32_t Jn, uint32_t key0,
-                                             uint32_t key1, uint32_t t, uint32_t thread) {
-  const uint32_t j = thread / kLanesPerSlot;                 // grid covers Jp slots exactly
+// The draw of slot j for generation t: Y_j = processed_j (1/rho_j - 1), rho_j ~ Be(alpha_j, beta_j)
+// (0 for a slot at or beyond Jn).  Called by whole waves with all lanes active, the kLanesPerSlot
+// lanes of a slot next to each other and aligned (lane % kLanesPerSlot = position in the slot's
+// team); every lane of the slot gets the value.
+__device__ inline double draw_remaining(const Progress &pr, uint32_t Jn, uint32_t key0, uint32_t key1, uint32_t t,
+                                        uint32_t j) {
   const uint32_t lane = threadIdx.x & (kLanes - 1);
   const uint32_t in_slot = lane % kLanesPerSlot, which = in_slot / kTeam + 1, member = in_slot % kTeam;
   const bool real = j < Jn;
@@ -111,6 +112,16 @@ __device__ inline void sample_remaining_slot(const Progress &pr, const JobTable 
     Y = pr.processed[j] * ratio;
     if (Y > kMaxParam) Y = kMaxParam;
   }
+  return Y;
+}
+
+// thread: position among the Jp * kLanesPerSlot threads that serve the Jp slots (whole waves,
+// all lanes active).  Writes tab.Y[j] and the slot's entries of tab.terms for generation t.
+__device__ inline void sample_remaining_slot(const Progress &pr, const JobTable &tab, uint32_t Jn, uint32_t key0,
+                                             uint32_t key1, uint32_t t, uint32_t thread) {
+  const uint32_t j = thread / kLanesPerSlot;                 // grid covers Jp slots exactly
+  const uint32_t in_slot = (threadIdx.x & (kLanes - 1)) % kLanesPerSlot;
+  const double Y = draw_remaining(pr, Jn, key0, key1, t, j);
   if (in_slot == 0) tab.Y[j] = Y;
   // the slot's column of the term table, its entries dealt to the slot's lanes
   const uint32_t E = tab.term_E, col = j % kLanes, row = j / kLanes;

@@ -463,27 +463,57 @@ __global__ void splitters_kernel(const double *fit_row, const uint32_t *row_of, 
   if (c == 0) *thresh = static_cast<uint64_t>(__double_as_longlong(fit_row[row_of[sel[K - 1]]]));
 }
 
-__global__ void prepare_table_kernel(RawJobs raw, JobTable tab, uint32_t Jp) {
-  const uint32_t j = blockIdx.x * blockDim.x + threadIdx.x;
-  if (j >= Jp) return;
+// What the kernels need of one job slot, derived from the validated raw table.
+struct SlotValues { uint32_t cstart, cmax, info; double abl, cc, d, Y; };
+
+__device__ __forceinline__ SlotValues derive_slot(const RawJobs &raw, uint32_t j) {
   const uint32_t w = raw.rawinfo[j];
   const int lo = w & 31, hi = (w >> 5) & 31, mu = (w >> 10) & 31;
-  if (!((w >> 15) & 1u)) {
-    tab.cstart[j] = 0; tab.cmax[j] = 0; tab.info[j] = 0;
-    tab.abl[j] = 0.0; tab.cc[j] = 0.0; tab.d[j] = 0.0; tab.Y[j] = 0.0;
-    return;
-  }
+  if (!((w >> 15) & 1u)) return SlotValues{0u, 0u, 0u, 0.0, 0.0, 0.0, 0.0};
   const int bl = min(mu, hi);                       // log2 of the local batch of a running job
   const int gstart = max(lo, bl);                   // batch a waiting job resumes with
-  tab.cstart[j] = 1u << max(0, gstart - mu);
-  tab.cmax[j] = 1u << max(0, hi - mu);
-  tab.info[j] = static_cast<uint32_t>(lo) | (static_cast<uint32_t>(hi - lo + 2) << 5) |
-                (static_cast<uint32_t>(mu) << 11) | (static_cast<uint32_t>(bl) << 16) | (1u << 21) |
-                (((w >> 16) & 1u) << 22);
-  tab.abl[j] = raw.a[j] * static_cast<double>(1u << bl);
-  tab.cc[j] = raw.c[j];
-  tab.d[j] = raw.d[j];
-  tab.Y[j] = raw.Y[j];
+  SlotValues v;
+  v.cstart = 1u << max(0, gstart - mu);
+  v.cmax = 1u << max(0, hi - mu);
+  v.info = static_cast<uint32_t>(lo) | (static_cast<uint32_t>(hi - lo + 2) << 5) | (static_cast<uint32_t>(mu) << 11) |
+           (static_cast<uint32_t>(bl) << 16) | (1u << 21) | (((w >> 16) & 1u) << 22);
+  v.abl = raw.a[j] * static_cast<double>(1u << bl);
+  v.cc = raw.c[j];
+  v.d = raw.d[j];
+  v.Y = raw.Y[j];
+  return v;
+}
+
+// A new job table in one launch.  The first table_blocks workgroups derive the per-slot values
+// and the term table (thread q: entry q of the term table; the thread of a slot's code 0 also
+// writes the slot's values); the workgroups behind them set the n_changed slots that changed
+// hands to "waiting" in every genome row (one thread per (row, changed slot), the slots of a
+// row next to each other).
+constexpr int kTableThreads = 256;
+__global__ __launch_bounds__(kTableThreads) void table_change_kernel(RawJobs raw, JobTable tab, uint32_t Jp,
+                                                                     uint32_t table_blocks, int32_t *genes,
+                                                                     const uint32_t *slots, uint32_t n_changed,
+                                                                     uint32_t rows) {
+  if (blockIdx.x < table_blocks) {
+    const uint32_t q = blockIdx.x * kTableThreads + threadIdx.x;
+    const uint32_t E = tab.term_E;
+    if (q >= Jp * E) return;
+    const uint32_t lane = q % kLanes, e = (q / kLanes) % E, row = q / (kLanes * E);
+    const uint32_t j = row * kLanes + lane;
+    const SlotValues v = derive_slot(raw, j);
+    tab.terms[q] = term_of(v.abl, v.cc, v.d, v.Y, info_blexp(v.info), e);
+    if (e == 0) {
+      tab.cstart[j] = v.cstart; tab.cmax[j] = v.cmax; tab.info[j] = v.info;
+      tab.abl[j] = v.abl; tab.cc[j] = v.cc; tab.d[j] = v.d; tab.Y[j] = v.Y;
+    }
+    return;
+  }
+  const uint32_t n = rows * n_changed;               // at most 1.25 * 2^20 * 2048 < 2^32
+  const uint32_t reset_blocks = gridDim.x - table_blocks;
+  for (uint32_t e = (blockIdx.x - table_blocks) * kTableThreads + threadIdx.x; e < n; e += reset_blocks * kTableThreads) {
+    const uint32_t row = e / n_changed, k = e - row * n_changed;
+    genes[static_cast<size_t>(row) * Jp + slots[k]] = 0;
+  }
 }
 
 // Term table: the score formula evaluated once per (slot, GPU-count code), same operations in
@@ -495,17 +525,6 @@ __global__ void build_terms_kernel(JobTable tab, uint32_t Jp) {
   const uint32_t lane = q % kLanes, e = (q / kLanes) % E, row = q / (kLanes * E);
   const uint32_t j = row * kLanes + lane;
   tab.terms[q] = term_of(tab.abl[j], tab.cc[j], tab.d[j], tab.Y[j], info_blexp(tab.info[j]), e);
-}
-
-// slots: the n_changed slots that changed hands; they start from "waiting" in every row.
-// One thread per (row, changed slot), the slots of a row next to each other.
-__global__ void reset_slots_kernel(int32_t *genes, const uint32_t *slots, uint32_t n_changed, uint32_t rows,
-                                   uint32_t Jp) {
-  const uint32_t n = rows * n_changed;               // at most 1.25 * 2^20 * 2048 < 2^32
-  for (uint32_t e = blockIdx.x * blockDim.x + threadIdx.x; e < n; e += gridDim.x * blockDim.x) {
-    const uint32_t row = e / n_changed, k = e - row * n_changed;
-    genes[static_cast<size_t>(row) * Jp + slots[k]] = 0;
-  }
 }
 
 __global__ void best_kernel(const int32_t *genes, const double *fit_row, const uint32_t *row_of, const int32_t *sel,
@@ -582,24 +601,20 @@ __global__ __launch_bounds__(kPlaceThreads) void placement_kernel(const int32_t 
 
 }  // namespace
 
-hipError_t launch_prepare_table(const RawJobs &raw, const JobTable &tab, uint32_t Jp, hipStream_t s) {
-  hipLaunchKernelGGL(prepare_table_kernel, dim3((Jp + 255) / 256), dim3(256), 0, s, raw, tab, Jp);
-  return hipGetLastError();
-}
-
 hipError_t launch_build_terms(const JobTable &tab, uint32_t Jp, hipStream_t s) {
   const uint32_t n = Jp * tab.term_E;
   hipLaunchKernelGGL(build_terms_kernel, dim3((n + 255) / 256), dim3(256), 0, s, tab, Jp);
   return hipGetLastError();
 }
 
-hipError_t launch_reset_slots(int32_t *genes, const uint32_t *slots, uint32_t n_changed, uint32_t rows, uint32_t Jp,
-                              hipStream_t s) {
-  if (n_changed == 0 || rows == 0) return hipSuccess;
+hipError_t launch_table_change(const RawJobs &raw, const JobTable &tab, uint32_t Jp, int32_t *genes, const uint32_t *slots,
+                               uint32_t n_changed, uint32_t rows, hipStream_t s) {
+  const uint32_t table_blocks = (Jp * tab.term_E + kTableThreads - 1) / kTableThreads;
   const uint64_t n = static_cast<uint64_t>(rows) * n_changed;
   if (n > 0xFFFFFFFFull) return hipErrorInvalidValue;
-  const uint32_t blocks = static_cast<uint32_t>(std::min<uint64_t>((n + 255) / 256, 16384));
-  hipLaunchKernelGGL(reset_slots_kernel, dim3(blocks), dim3(256), 0, s, genes, slots, n_changed, rows, Jp);
+  const uint32_t reset_blocks = static_cast<uint32_t>(std::min<uint64_t>((n + kTableThreads - 1) / kTableThreads, 16384));
+  hipLaunchKernelGGL(table_change_kernel, dim3(table_blocks + reset_blocks), dim3(kTableThreads), 0, s, raw, tab, Jp,
+                     table_blocks, genes, slots, n_changed, rows);
   return hipGetLastError();
 }
 

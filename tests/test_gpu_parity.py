@@ -304,27 +304,38 @@ def test_two_contexts_and_a_side_stream(ones, ref):
 
 # ---- pools of one job row: all generations of a call in one launch ----
 
+@pytest.mark.parametrize("sampled", [False, True])
 @pytest.mark.parametrize("n_slots,n_gpus,pop,seed,per_gpu,new_first", [
     (8, 16, 64, 0, False, False), (40, 64, 1024, 1, False, False), (64, 64, 2048, 2, False, True),
     (64, 200, 2048, 3, True, True), (33, 20, 68, 4, False, False), (5, 3, 4, 5, True, False), (17, 9, 8, 6, False, True),
     (60, 64, 1500, 7, True, False), (1, 1, 12, 8, False, False), (64, 4000, 600, 9, False, True)])
-def test_single_launch_generations_with_mixed_call_lengths(ones, ref, n_slots, n_gpus, pop, seed, per_gpu, new_first):
+def test_single_launch_generations_with_mixed_call_lengths(ones, ref, n_slots, n_gpus, pop, seed, per_gpu, new_first,
+                                                           sampled):
     """Calls of 1 and 2 generations take two launches per generation, longer ones a single launch
     for the whole call; the state one path leaves is the state the other starts from.  With table
     changes (the first generation of the next call refreshes the survivors), arrivals served first
-    by executed time, and both crossovers."""
+    by executed time, both crossovers, and the remaining work fixed or drawn per generation (the
+    draw of the last generation is what ones_export_remaining returns; switched off and on again
+    half way)."""
     rng = np.random.default_rng(seed)
     cl = cluster(n_gpus, n_slots, pop, seed=seed + 77)
     jobs = random_jobs(rng, n_slots)
-    say(f"[single launch] G={n_gpus} slots={n_slots} P={pop} seed={cl.seed} per_gpu={per_gpu} new_first={new_first}")
+    say(f"[single launch] G={n_gpus} slots={n_slots} P={pop} seed={cl.seed} per_gpu={per_gpu} new_first={new_first} sampled={sampled}")
     gpu, cpu = ones.Search(cl, jobs), ref.RefSearch(cl, jobs)
+    progress = W.progress(n_slots, seed=seed)
     for s in (gpu, cpu):
         s.set_crossover(per_gpu=per_gpu)
         s.set_new_jobs_first(new_first)
+        if sampled:
+            s.set_progress(*progress)
     assert_same_state(gpu, cpu, "initial population")
     for step, n in enumerate([5, 1, 3, 2, 20, 4, 1, 7, 3, 40]):
         gpu.generation(n); cpu.generation(n)
         assert_same_state(gpu, cpu, f"call {step} of {n} generations")
+        assert np.array_equal(gpu.export_remaining().view(np.uint64), cpu.export_remaining().view(np.uint64)), f"call {step}"
+        if sampled and step in (4, 6):                                # off before the call of 4, on again before the call of 7
+            for s in (gpu, cpu):
+                s.set_progress(*(progress if step == 6 else (None, None, None)))
         gb, cb = gpu.best(), cpu.best()
         assert gb[0].tolist() == cb[0].tolist() and gb[1].tolist() == cb[1].tolist() and gb[2] == cb[2]
         if step in (1, 3, 4, 6, 8):                                   # a new table before calls of 3, 20, 4, 7 and 40
