@@ -41,16 +41,18 @@ def same(a, b, where):
 
 def test_static_scratch_matches_the_workspace_scratch_on_two_calls_in_a_row(ones, ref):
     """A pool that selects through the buckets (P = 8192, 200 slots), then a smaller one
-    (P = 1024, 40 slots), then the first one again: the second call finds the first one's
-    leftovers in the array and the third the second one's."""
+    (P = 1024, 130 slots), then the first one again: the second call finds the first one's
+    leftovers in the array and the third the second one's.  (Both have more than one row of job
+    slots: a pool of one row runs its generations in a single launch that uses no scratch at all,
+    whichever entry point is called; the third shape checks that.)"""
     lib = ones.load()
-    shapes = [(300, 200, 8192, 11), (64, 40, 1024, 12)]
+    shapes = [(300, 200, 8192, 11), (200, 130, 1024, 12), (64, 40, 512, 13)]
     pairs = []
     for n_gpus, n_slots, pop, seed in shapes:
         cl = cluster(n_gpus, n_slots, pop, seed)
         jobs = random_jobs(np.random.default_rng(seed), n_slots)
         pairs.append((ones.Search(cl, jobs), ones.Search(cl, jobs), ref.RefSearch(cl, jobs), cl, jobs))
-    for rnd, which in enumerate([0, 1, 0, 1]):
+    for rnd, which in enumerate([0, 1, 0, 1, 2, 0]):
         static, plain, cpu, cl, jobs = pairs[which]
         say(f"[no alloc] call {rnd}: P={cl.population} slots={cl.n_slots} seed={cl.seed}")
         assert lib.ones_generation_static(static._h, 3) == 0          # straight through the C ABI
