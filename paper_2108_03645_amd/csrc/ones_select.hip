@@ -48,10 +48,16 @@ __device__ __forceinline__ void keep_rows(const RowPlan &rp, bool valid, uint32_
 }
 
 // ---------------------------------------------------------------- general path -----
-// Pools of at most kSortChunk slots: the rank of a candidate is the number of candidates below
+// Pools of at most kRankPoolMax slots: the rank of a candidate is the number of candidates below
 // it in (score, slot) order.  Every workgroup loads all scores into LDS and ranks 64 of them:
 // lane l of every wave works on element l, each wave over its own sixteenth of the pool (so a
-// wave reads one LDS address at a time, a broadcast); ranks below K are survivors.
+// wave reads one LDS address at a time, a broadcast); ranks below K are survivors.  One launch,
+// where the sample sort below takes three; but the comparisons per thread grow with the pool
+// (P / 16), and at P = 16384 this takes 75 us where the three launches take 21.
+#ifndef ONES_RANK_POOL_MAX
+#define ONES_RANK_POOL_MAX 4096
+#endif
+constexpr uint32_t kRankPoolMax = ONES_RANK_POOL_MAX;
 constexpr int kRankPoolPer = 64;
 __global__ __launch_bounds__(kSortThreads) void rank_pool_kernel(const double *fit_row, RowPlan rp, uint32_t P,
                                                                 uint32_t K, int32_t *sel, SampleNext next,
@@ -62,20 +68,23 @@ __global__ __launch_bounds__(kSortThreads) void rank_pool_kernel(const double *f
     return;
   }
   const uint32_t *row_of = rp.row_of_cur;
-  __shared__ uint64_t sk[kSortChunk];
-  __shared__ uint32_t below[kRankPoolPer];
+  extern __shared__ __align__(16) uint64_t sk[];       // [padded] scores, then [kRankPoolPer] counters
   constexpr uint32_t kTeam = kSortThreads / kRankPoolPer;
   const uint32_t t = threadIdx.x;
   const uint32_t padded = (P + 8 * kTeam - 1) / (8 * kTeam) * (8 * kTeam);     // eight comparisons per step
-  uint64_t loaded[kSortChunk / kSortThreads];
+  uint32_t *below = reinterpret_cast<uint32_t *>(sk + padded);
+  constexpr int kAhead = 4;                            // loads in flight per thread
+  for (uint32_t base = 0; base < padded; base += kAhead * kSortThreads) {
+    uint64_t loaded[kAhead];
 #pragma unroll
-  for (int u = 0; u < kSortChunk / kSortThreads; ++u) {                         // all loads first
-    const uint32_t e = t + u * kSortThreads;
-    loaded[u] = e < P ? static_cast<uint64_t>(__double_as_longlong(fit_row[row_of[e]])) : ~0ull;
+    for (int u = 0; u < kAhead; ++u) {                 // all loads first
+      const uint32_t e = base + t + u * kSortThreads;
+      loaded[u] = e < P ? static_cast<uint64_t>(__double_as_longlong(fit_row[row_of[e]])) : ~0ull;
+    }
+#pragma unroll
+    for (int u = 0; u < kAhead; ++u)
+      if (base + t + u * kSortThreads < padded) sk[base + t + u * kSortThreads] = loaded[u];
   }
-#pragma unroll
-  for (int u = 0; u < kSortChunk / kSortThreads; ++u)
-    if (t + u * kSortThreads < padded) sk[t + u * kSortThreads] = loaded[u];
   if (t < kRankPoolPer) below[t] = 0;
   __syncthreads();
   const uint32_t mine = blockIdx.x * kRankPoolPer + t % kRankPoolPer;
@@ -628,9 +637,14 @@ hipError_t launch_select(const double *fit, const RowPlan &rp, uint32_t P, uint3
   // workgroups of 1024 threads behind the ranking ones, 64 slots each, for the next draw
   const uint32_t draw_blocks = next.on ? next.Jp * kLanesPerSlot / kSortThreads : 0u;
   static_assert(kSortThreads == kSampleThreads && kSortThreads % (kLanes * kLanesPerSlot) == 0, "64 slots per workgroup");
-  if (P <= static_cast<uint32_t>(kSortChunk)) {
+  if (P <= kRankPoolMax) {
     const uint32_t rank_blocks = (P + kRankPoolPer - 1) / kRankPoolPer;
-    hipLaunchKernelGGL(rank_pool_kernel, dim3(rank_blocks + draw_blocks), dim3(kSortThreads), 0, s, fit, rp, P, K, sel,
+    constexpr uint32_t kStep = 8 * (kSortThreads / kRankPoolPer);
+    const size_t lds = static_cast<size_t>((P + kStep - 1) / kStep * kStep) * 8 + kRankPoolPer * 4;
+    hipError_t rc = hipFuncSetAttribute(reinterpret_cast<const void *>(rank_pool_kernel),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
+    if (rc != hipSuccess) return rc;
+    hipLaunchKernelGGL(rank_pool_kernel, dim3(rank_blocks + draw_blocks), dim3(kSortThreads), lds, s, fit, rp, P, K, sel,
                        next, rank_blocks);
     return hipGetLastError();
   }

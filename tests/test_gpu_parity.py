@@ -265,6 +265,33 @@ def test_set_jobs_rejects_bad_tables_and_keeps_state(ones, ref):
     assert_same_state(gpu, cpu, "generation after rejected set_jobs")
 
 
+def test_best_between_a_table_change_and_the_next_generation(ones, ref):
+    """ones_best right after ones_set_jobs: no schedule exists under the new table yet; the call returns the
+    last winner as stored (slots that changed hands already waiting) with the score it had under the old
+    table, on both sides alike; ones_placement refuses in that state."""
+    rng = np.random.default_rng(77)
+    jobs = random_jobs(rng, 100, inactive_frac=0.0)
+    cl = cluster(150, 100, 256, seed=9)
+    gpu, cpu = ones.Search(cl, jobs), ref.RefSearch(cl, jobs)
+    gpu.generation(4); cpu.generation(4)
+    before = gpu.best()
+    running = np.flatnonzero(before[0] > 0)
+    assert running.size > 2
+    jobs.job_id[running[:2]] += 500                                # two running jobs are replaced
+    jobs.remaining = jobs.remaining * 0.5
+    gpu.set_jobs(jobs); cpu.set_jobs(jobs)
+    gb, cb = gpu.best(), cpu.best()
+    assert gb[0].tolist() == cb[0].tolist() and gb[1].tolist() == cb[1].tolist() and gb[2] == cb[2]
+    assert gb[2] == before[2] and (gb[0][running[:2]] == 0).all() and (gb[0][running[2:]] == before[0][running[2:]]).all()
+    with pytest.raises(ones.OnesError) as e:
+        gpu.placement()
+    assert e.value.code == -1
+    gpu.generation(1); cpu.generation(1)
+    assert_same_state(gpu, cpu, "the generation after")
+    assert gpu.best()[2] == cpu.best()[2] != before[2]
+    gpu.close(); cpu.close()
+
+
 def test_init_rejects_bad_arguments(ones):
     import torch
     jobs = make_jobs(4)
@@ -350,6 +377,28 @@ def test_single_launch_generations_with_mixed_call_lengths(ones, ref, n_slots, n
             jobs = j2
     assert all(np.array_equal(x, y) for x, y in zip(gpu.placement(), cpu.placement()))
     gpu.close(); cpu.close()
+
+
+@pytest.mark.parametrize("name,calls,per_call", [("tiny", 10, 500), ("paper_scale", 8, 250)])
+def test_single_launch_long_calls(ones, ref, name, calls, per_call):
+    """Thousands of generations inside few launches: every exchange between the workgroups of a launch
+    (scores, ranks) happens hundreds of times per call, and a single stale or early read would change the
+    state the oracle reaches."""
+    cl, jobs = W.CONFIGS[name]()
+    say(f"[single launch] long calls: {name}, {calls} calls of {per_call} generations")
+    ref.set_threads(host_threads())
+    try:
+        gpu, cpu = ones.Search(cl, jobs), ref.RefSearch(cl, jobs)
+        for call in range(calls):
+            if call == calls // 2:                   # a new table half way, so that the second half starts from a changed pool
+                jobs.remaining = jobs.remaining * 0.7
+                jobs.job_id[1] += 100
+                gpu.set_jobs(jobs); cpu.set_jobs(jobs)
+            gpu.generation(per_call); cpu.generation(per_call)
+            assert_same_state(gpu, cpu, f"{name} after call {call}")
+        gpu.close(); cpu.close()
+    finally:
+        ref.set_threads(1)
 
 
 def rng_times(seed, step, n_slots):
