@@ -32,7 +32,7 @@ HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published peak
 
 # HBM bytes per evolve launch on the stress workload from rocprofv3 --pmc FETCH_SIZE and
 # WRITE_SIZE (see profiles/), valid only for the kernel source with this hash.
-MEASURED_TRAFFIC = {"source_sha256": "1579c037114a092e839ce058b7b53ac52fb8f72901d27261c534f0f12af5a31d", "bytes_per_launch": 802600137}
+MEASURED_TRAFFIC = {"source_sha256": "f384ee9604890d68ac7ebeadad024fa29cc9bf1f115169e7912b2c3c48c3dca5", "bytes_per_launch": 802583865}
 
 
 def evolve_source_hash() -> str:
