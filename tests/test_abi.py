@@ -91,5 +91,7 @@ def test_job_table_validation_needs_no_gpu():
     for call in (lambda: L.ones_set_jobs(None, None), lambda: L.ones_set_progress(None, None, None, None),
                  lambda: L.ones_set_crossover(None, 0), lambda: L.ones_set_processed_time(None, None),
                  lambda: L.ones_set_new_jobs_first(None, 1), lambda: L.ones_placement(None, None, None),
-                 lambda: L.ones_export(None, None, None, None, None), lambda: L.ones_export_remaining(None, None)):
+                 lambda: L.ones_export(None, None, None, None, None), lambda: L.ones_export_remaining(None, None),
+                 lambda: L.ones_generation_static(None, 1), lambda: L.ones_set_wait_limit(None, 5)):
         assert call() == -1
+    assert b"static scratch" in L.ones_strerror(-7)
