@@ -117,23 +117,10 @@ def cpu_baseline(workload: str, sampled: bool = False):
     return out
 
 
-def online(args, torch, ones, W) -> int:
-    """The online sequence: every scheduling epoch replaces the job table (ones_set_jobs), runs
-    20 warm-started generations and reads the winner (ones_best), which drives the simulated
-    cluster.  A step is one epoch; --steps counts epochs."""
-    t_lim = [0.0, False]
-
-    def timed_limits(*a, **k):
-        t = time.perf_counter()
-        out = ones.update_limits(*a, **k)
-        if t_lim[1]:
-            t_lim[0] += time.perf_counter() - t
-        return out
-
-    sim = W.OnlineSequence(epochs=args.steps + args.warmup, limits=timed_limits if args.policies else None)
+def online_loop(make_search, sim, args, limits_clock, synchronize):
+    """One run of the online sequence with any implementation of the search; returns the per-leg times."""
     cl = sim.cluster
-    torch.cuda.set_device(0)
-    search = ones.Search(cl, sim.jobs, device="cuda:0")
+    search = make_search(cl, sim.jobs)
     search.set_new_jobs_first(args.policies)
     search.set_crossover(per_gpu=args.crossover == "gpus")
     if args.sampled:
@@ -145,11 +132,11 @@ def online(args, torch, ones, W) -> int:
         timed = epoch >= args.warmup
         t0 = time.perf_counter()
         search.generation(gens)
-        search.synchronize()
+        synchronize(search)
         t1 = time.perf_counter()
         batch, _, _ = search.best()
         t2 = time.perf_counter()
-        t_lim[1] = timed
+        limits_clock[1] = timed
         sim.advance(batch)
         t3 = time.perf_counter()
         search.set_jobs(sim.jobs)
@@ -161,8 +148,43 @@ def online(args, torch, ones, W) -> int:
         if timed:
             t_gen += t1 - t0; t_best += t2 - t1; t_set += t4 - t3
             evals += cl.population * int(sim.jobs.active.sum()) * gens
-    dt = t_gen + t_best + t_set + t_lim[0]
-    out = {"metric": "candidate-job fitness evals/sec", "value": evals / dt, "unit": "evals/s", "n_gpus": 1,
+    search.close()
+    return {"generations": t_gen, "ones_best": t_best, "ones_set_jobs": t_set, "ones_update_limits": limits_clock[0],
+            "evals": evals, "completed": sim.completed, "last_batch": batch.tolist()}
+
+
+def online(args, torch, ones, W) -> int:
+    """The online sequence: every scheduling epoch replaces the job table (ones_set_jobs), runs
+    20 warm-started generations and reads the winner (ones_best), which drives the simulated
+    cluster.  A step is one epoch; --steps counts epochs.  Median of --reps repetitions of the
+    whole sequence from the same seed after a warm-up repetition."""
+    torch.cuda.set_device(0)
+
+    def one_run(update_limits, make_search, synchronize):
+        clock = [0.0, False]
+
+        def timed_limits(*a, **k):
+            t = time.perf_counter()
+            out = update_limits(*a, **k)
+            if clock[1]:
+                clock[0] += time.perf_counter() - t
+            return out
+
+        sim = W.OnlineSequence(epochs=args.steps + args.warmup, limits=timed_limits if args.policies else None)
+        return sim.cluster, online_loop(make_search, sim, args, clock, synchronize)
+
+    def gpu_run():
+        return one_run(ones.update_limits, lambda cl, jobs: ones.Search(cl, jobs, device="cuda:0"), lambda s: s.synchronize())
+
+    legs = ("generations", "ones_best", "ones_set_jobs", "ones_update_limits")
+    runs = [gpu_run() for _ in range(args.reps + 1)][1:] if args.reps > 0 else [gpu_run()]
+    cl = runs[0][0]
+    totals = sorted(sum(r[1][k] for k in legs) for r in runs)
+    res = next(r[1] for r in runs if sum(r[1][k] for k in legs) == totals[(len(totals) - 1) // 2])
+    assert all(r[1]["last_batch"] == res["last_batch"] for r in runs), "repetitions from one seed must end in one state"
+    dt = sum(res[k] for k in legs)
+    gens = cl.generations
+    out = {"metric": "candidate-job fitness evals/sec", "value": res["evals"] / dt, "unit": "evals/s", "n_gpus": 1,
            "steps": args.steps, "warmup": args.warmup, "ms_per_step": dt * 1e3 / args.steps,
            "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
            "dtype": "i32 genes, f64 fitness", "data": "synthetic",
@@ -170,12 +192,28 @@ def online(args, torch, ones, W) -> int:
                       "population": cl.population, "generations_per_epoch": gens, "seed": cl.seed,
                       "limit_policies": bool(args.policies), "crossover": "over " + args.crossover,
                       "remaining_work": "sampled per generation" if args.sampled else "fixed",
-                      "jobs_completed": sim.completed},
+                      "jobs_completed": res["completed"]},
+           "repetitions": {"timed": len(runs), "warmup_runs": 1 if args.reps > 0 else 0, "reported": "median",
+                           "ms_per_step_all": [sum(r[1][k] for k in legs) * 1e3 / args.steps for r in runs]},
            "generations_per_s": gens * args.steps / dt,
-           "per_epoch_ms": {"generations": t_gen * 1e3 / args.steps, "ones_best": t_best * 1e3 / args.steps,
-                            "ones_set_jobs": t_set * 1e3 / args.steps,
-                            "ones_update_limits": t_lim[0] * 1e3 / args.steps}}
-    search.close()
+           "per_epoch_ms": {k: res[k] * 1e3 / args.steps for k in legs}}
+    if not args.no_cpu_baseline:
+        # the oracle through the same loop, on the host's share of cores and on one
+        from oracle import ones_ref
+        info = host_info()
+        threads = max(1, min(16, info["usable_cpus"]))
+        cpu = {}
+        for name, n_threads in (("all", threads), ("one", 1)):
+            ones_ref.set_threads(n_threads)
+            _, r = one_run(ones_ref.update_limits, lambda c, jobs: ones_ref.RefSearch(c, jobs), lambda s: None)
+            t = sum(r[k] for k in legs)
+            cpu[name] = {"value": r["evals"] / t, "ms_per_epoch": t * 1e3 / args.steps, "threads": n_threads}
+            assert r["last_batch"] == res["last_batch"], "the oracle's sequence must end where the library's does"
+        ones_ref.set_threads(1)
+        out["cpu_baseline"] = {"value": cpu["all"]["value"], "unit": "evals/s", "cores": threads, "kind": "oracle",
+                               "sample": f"the same {args.warmup} + {args.steps} epochs", "ms_per_epoch": cpu["all"]["ms_per_epoch"],
+                               "single_thread": {"value": cpu["one"]["value"], "ms_per_epoch": cpu["one"]["ms_per_epoch"]},
+                               "flags": "gcc -O2 -ffp-contract=off -fopenmp", **info}
     print(json.dumps(out))
     return 0
 
