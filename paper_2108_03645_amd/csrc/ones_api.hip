@@ -76,7 +76,7 @@ struct ScratchLayout {
 };
 
 struct Layout {
-  size_t genes, fit_row, row_of[2], parent_row[2], occupied[2], sel, fsync, xkeys, scratch, cstart, cmax, info, abl, cc, d, Y[2], terms[2];
+  size_t genes, fit_row, row_of[2], parent_row[2], occupied[2], sel, fsync, xkeys, scratch, cstart, cmax, info, abl, cc, d, Y[kDrawRing], terms[kDrawRing];
   size_t rawinfo, changed, ra, rc, rd, rY, alpha, beta, processed, time_rank, best_batch, best_gpus, best_fit, best_err, place_slot, place_batch, total;
   ScratchLayout S;
 };
@@ -147,9 +147,10 @@ Layout make_layout(uint32_t P, uint32_t Jp, uint32_t G) {
   L.scratch = take(L.S.total);
   L.cstart = take(Jp * 4); L.cmax = take(Jp * 4); L.info = take(Jp * 4);
   L.abl = take(Jp * 8); L.cc = take(Jp * 8); L.d = take(Jp * 8);
-  // remaining work and the term table built from it, twice: under probability sampling the draw
-  // of the coming generation is made while the last one is still being ranked
-  for (int k = 0; k < 2; ++k) { L.Y[k] = take(Jp * 8); L.terms[k] = take(static_cast<size_t>(Jp) * kMaxTermEntries * 8); }
+  // remaining work and the term table built from it, a ring of kDrawRing pairs at equal distances:
+  // under probability sampling the draws of that many generations are made in one launch, and
+  // generation g is scored with pair g mod kDrawRing
+  for (int k = 0; k < kDrawRing; ++k) { L.Y[k] = take(Jp * 8); L.terms[k] = take(static_cast<size_t>(Jp) * kMaxTermEntries * 8); }
   L.rawinfo = take(Jp * 4); L.changed = take(Jp * 4);
   L.ra = take(Jp * 8); L.rc = take(Jp * 8); L.rd = take(Jp * 8); L.rY = take(Jp * 8);
   L.alpha = take(Jp * 8); L.beta = take(Jp * 8); L.processed = take(Jp * 8);
@@ -252,7 +253,7 @@ struct ones_ctx {
   bool new_jobs_first;        // option: the generation after ones_set_jobs serves the arrived jobs first
   bool sampling;              // remaining work drawn per generation (Alg. 1) instead of the table's
   int y_cur;                  // which remaining-work array and term table the last generation was scored with
-  int64_t drawn_for;          // the other pair already holds the draw of this generation (0: it does not)
+  int64_t drawn_from, drawn_to;  // the ring holds the draws of generations [drawn_from, drawn_to) (equal: none)
   bool per_gpu;               // uniform crossover over the GPUs instead of the jobs (ones_set_crossover)
   bool has_times;             // executed times known (ones_set_processed_time): their ranks are on the device
   BucketPlan bp;              // nb == 0: pool small enough for the single-chunk sort
@@ -344,11 +345,11 @@ int run_generation(ones_ctx *c, uint32_t t, char *scratch, bool &splitters_valid
   a.row_of = c->at<uint32_t>(c->L.row_of[next]);
   a.occupied = c->at<uint32_t>(c->L.occupied[c->cur]);          // set by the last selection
   a.occupied_other = c->at<uint32_t>(c->L.occupied[c->cur ^ 1]);
-  // Under probability sampling this generation is scored with the other remaining-work array
-  // and term table: the previous generation's selection has filled them already, or the draw
-  // is made now (first sampled generation, or the inputs changed since).
+  // Under probability sampling this generation is scored with its own place of the ring of
+  // remaining-work arrays and term tables: a launch of an earlier generation has filled it
+  // already, or the draws of this and the next generations are made now.
   const bool sampled = t != 0 && c->sampling;
-  const int y_this = sampled ? c->y_cur ^ 1 : c->y_cur;
+  const int y_this = sampled ? static_cast<int>(t % kDrawRing) : c->y_cur;
   a.tab = c->table(y_this);
   a.G = c->G; a.P = c->P; a.K = c->K; a.Jp = c->Jp;
   a.key0 = static_cast<uint32_t>(c->cfg.seed);
@@ -385,8 +386,14 @@ int run_generation(ones_ctx *c, uint32_t t, char *scratch, bool &splitters_valid
   rp.occupied = c->at<uint32_t>(c->L.occupied[next]);
   int rc;
   const Progress pr{c->at<double>(c->L.alpha), c->at<double>(c->L.beta), c->at<double>(c->L.processed)};
-  if (sampled && c->drawn_for != static_cast<int64_t>(t))
-    HIP_TRY(launch_sample_remaining(pr, a.tab, c->Jn, c->Jp, a.key0, a.key1, t, c->stream));
+  if (sampled && !(c->drawn_from <= static_cast<int64_t>(t) && static_cast<int64_t>(t) < c->drawn_to)) {
+    const uint32_t count = static_cast<uint32_t>(std::min<int64_t>(kDrawRing, 0x100000000ll - static_cast<int64_t>(t)));
+    // places lie at equal distances (make_layout); counted in doubles
+    const uint32_t ring_stride = static_cast<uint32_t>((c->L.Y[1] - c->L.Y[0]) / 8);
+    HIP_TRY(launch_sample_remaining(pr, c->table(0), ring_stride, c->Jn, c->Jp, a.key0, a.key1, t, count, c->stream));
+    c->drawn_from = t;
+    c->drawn_to = static_cast<int64_t>(t) + count;
+  }
   if (events && (rc = timed(c, c->evolve_ev, c->evolve_used, true))) return rc;
   HIP_TRY(launch_evolve(a, static_cast<int>(c->R), same_table, c->n_cus, c->stream));
   if (events && (rc = timed(c, c->evolve_ev, c->evolve_used, false))) return rc;
@@ -400,12 +407,7 @@ int run_generation(ones_ctx *c, uint32_t t, char *scratch, bool &splitters_valid
     BucketArgs store = a.bk;                       // same storage; always the first counter set
     store.nb = c->bp.nb;
     store.count = reinterpret_cast<uint32_t *>(sc(S.bcount[0]));
-    // the workgroups behind the ranking ones draw the remaining work of generation t + 1 into the
-    // pair of arrays this generation did not use
-    SampleNext draw{pr, c->table(y_this ^ 1), c->Jn, c->Jp, a.key0, a.key1, t + 1, 0u};
-    draw.on = sampled && t != 0xFFFFFFFFu ? 1u : 0u;
-    HIP_TRY(launch_select(a.fit_row, rp, c->P, c->K, store, c->at<int32_t>(c->L.sel), draw, c->stream));
-    if (draw.on) c->drawn_for = static_cast<int64_t>(t) + 1;
+    HIP_TRY(launch_select(a.fit_row, rp, c->P, c->K, store, c->at<int32_t>(c->L.sel), c->stream));
     splitters_valid = false;
     if (c->bp.nb != 0 && !sampled && same_table) {
       // Splitters for the bucketed generations that follow; clears both counter sets.  Under sampling
@@ -482,7 +484,7 @@ static int init_impl(ones_ctx **out, const ones_config *cfg, const ones_jobs *jo
   c->new_jobs_first = false;
   c->sampling = false;
   c->y_cur = 0;
-  c->drawn_for = 0;
+  c->drawn_from = c->drawn_to = 0;
   c->has_times = false;
   c->per_gpu = false;
   c->bp = bucket_plan(c->P);
@@ -543,7 +545,7 @@ static int set_jobs_impl(ones_ctx *c, const ones_jobs *jobs) {
   c->ids = h.id;
   c->table_changed = true;
   c->no_schedule = true;
-  c->drawn_for = 0;            // a draw made ahead built its term table from the old job table
+  c->drawn_from = c->drawn_to = 0;   // the draws made ahead built their term tables from the old job table
   return ONES_OK;
 }
 
@@ -557,7 +559,7 @@ static int set_progress_impl(ones_ctx *c, const double *alpha, const double *bet
       HIP_TRY(launch_build_terms(c->table(), c->Jp, c->stream));
       HIP_TRY(hipStreamSynchronize(c->stream));
       c->sampling = false;
-      c->drawn_for = 0;
+      c->drawn_from = c->drawn_to = 0;
       c->table_changed = true;
     }
     return ONES_OK;
@@ -579,7 +581,7 @@ static int set_progress_impl(ones_ctx *c, const double *alpha, const double *bet
                          hipMemcpyHostToDevice, c->stream));
   HIP_TRY(hipStreamSynchronize(c->stream));     // the staging buffer is free again
   c->sampling = true;
-  c->drawn_for = 0;            // a draw made ahead used the old parameters
+  c->drawn_from = c->drawn_to = 0;   // the draws made ahead used the old parameters
   return ONES_OK;
 }
 
@@ -673,7 +675,7 @@ static int run_fused(ones_ctx *c, uint32_t n, bool events) {
   c->fused_changes += c->sampling ? n : fa.first_changed;
   if (c->sampling) {
     c->fused_draws += n;
-    c->drawn_for = 0;               // the two-launch path makes its own draw for the generation it runs next
+    c->drawn_from = c->drawn_to = 0;   // the ring may hold tables this launch wrote over (y_out); the two-launch path draws again
   }
   c->table_changed = false;
   c->no_schedule = false;

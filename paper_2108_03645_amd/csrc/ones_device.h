@@ -89,6 +89,17 @@ struct BucketArgs {
   uint32_t        nb, seg;
 };
 
+// Remaining work of slot j under probability sampling (Alg. 1, Eq. 7) for generation t:
+// tab.Y[j] = processed[j] * (1/rho - 1), rho ~ Be(alpha[j], beta[j]), for j < Jn; then the
+// slot's entries of the term table.
+struct Progress {
+  const double *alpha, *beta, *processed;   // [Jp]
+};
+// The draws depend on nothing but (seed, slot, generation), so they are made ahead, kDrawRing
+// generations in one launch: generation g's remaining work and term table sit at place
+// g mod kDrawRing of a ring of (Y, terms) pairs.
+constexpr int kDrawRing = 8;
+
 // Genomes live in physical rows; a candidate keeps its row for as long as it survives, so a
 // survivor is never copied.  The pool of P slots uses P + K rows, K of them held by the
 // survivors (the selection marks them in a bitmap).  Of the P free rows in ascending order,
@@ -118,12 +129,6 @@ struct EvolveArgs {
   BucketArgs     bk;
 };
 
-// Remaining work of slot j under probability sampling (Alg. 1, Eq. 7) for generation t:
-// tab.Y[j] = processed[j] * (1/rho - 1), rho ~ Be(alpha[j], beta[j]), for j < Jn; then the
-// slot's entries of the term table.
-struct Progress {
-  const double *alpha, *beta, *processed;   // [Jp]
-};
 // All generations of one ones_generation call in a single launch, for pools that are small
 // enough to be ranked inside every workgroup's LDS (one row of 64 job columns, at most
 // kFusedMaxPool candidates).  ev describes the problem as for the evolve kernel; of its row
@@ -192,16 +197,11 @@ struct RawJobs {              // uploaded by the host after validation, [Jp] eac
 hipError_t launch_table_change(const RawJobs &raw, const JobTable &tab, uint32_t Jp, int32_t *genes, const uint32_t *slots,
                                uint32_t n_changed, uint32_t rows, hipStream_t s);
 hipError_t launch_build_terms(const JobTable &tab, uint32_t Jp, hipStream_t s);
-hipError_t launch_sample_remaining(const Progress &pr, const JobTable &tab, uint32_t Jn, uint32_t Jp,
-                                   uint32_t key0, uint32_t key1, uint32_t t, hipStream_t s);
-// The same draw for the coming generation t, made by extra workgroups of the general selection's
-// first kernel (into tab.Y and tab.terms, which must not be the arrays the finished generation
-// was scored with).  on == 0: no draw.
-struct SampleNext {
-  Progress pr;
-  JobTable tab;
-  uint32_t Jn, Jp, key0, key1, t, on;
-};
+// ring: the job table with Y and terms pointing at place 0 of the ring, whose places lie
+// ring_stride doubles apart; draws generations t .. t + count - 1 (count <= kDrawRing).
+hipError_t launch_sample_remaining(const Progress &pr, const JobTable &ring, uint32_t ring_stride, uint32_t Jn,
+                                   uint32_t Jp, uint32_t key0, uint32_t key1, uint32_t t, uint32_t count,
+                                   hipStream_t s);
 // same_table: the job table is the one the previous generation was repaired and scored with
 hipError_t launch_evolve_group0(const EvolveArgs &a, int rows, bool same_table, int n_cus, hipStream_t s);
 hipError_t launch_evolve_group1(const EvolveArgs &a, int rows, bool same_table, int n_cus, hipStream_t s);
@@ -217,10 +217,10 @@ inline hipError_t launch_evolve(const EvolveArgs &a, int rows, bool same_table, 
   }
 }
 // General selection (any scores).  store: the bucket storage (count, keys, idx, spill and pool
-// arrays, split as scratch for the splitters, nb * seg entries of bucket space); used for pools
-// above kSortChunk slots.
+// arrays, split as scratch for the splitters, nb * seg entries of bucket space); used by pools
+// too large for the single launch that ranks a whole pool.
 hipError_t launch_select(const double *fit_row, const RowPlan &rp, uint32_t P, uint32_t K, const BucketArgs &store,
-                         int32_t *sel, const SampleNext &next, hipStream_t s);
+                         int32_t *sel, hipStream_t s);
 hipError_t launch_zero_words(uint32_t *words, uint32_t n, hipStream_t s);
 hipError_t launch_bucket_select(const double *fit_row, const uint32_t *parent_row, const BucketArgs &bk,
                                 const RowPlan &rp, uint32_t K, uint32_t *count_next, int32_t *sel, hipStream_t s);

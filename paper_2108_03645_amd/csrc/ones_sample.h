@@ -8,8 +8,9 @@
 // ones, and the logarithm is spelled out, so the draw is a function of (seed, slot, generation)
 // that any implementation of the same steps reproduces bit for bit.
 //
-// Device code shared by the kernel of ones_sample.hip and by the selection kernels, which make
-// the next generation's draw on workgroups of their own (ones_select.hip).
+// Device code shared by the kernel of ones_sample.hip, which draws a run of generations ahead,
+// and by the single-launch kernel, whose drawing workgroups keep ahead of its generations
+// (ones_fused.hip).
 #pragma once
 
 #include "ones_device.h"

@@ -4,7 +4,6 @@
 // Order: ascending (score, pool slot).  A score is a non-negative fp64, so its bit pattern
 // read as an unsigned 64-bit integer orders the same way; ties fall to the smaller slot.
 #include "ones_device.h"
-#include "ones_sample.h"
 #include "ones_sort.h"
 
 #pragma clang fp contract(off)
@@ -60,13 +59,7 @@ __device__ __forceinline__ void keep_rows(const RowPlan &rp, bool valid, uint32_
 constexpr uint32_t kRankPoolMax = ONES_RANK_POOL_MAX;
 constexpr int kRankPoolPer = 64;
 __global__ __launch_bounds__(kSortThreads) void rank_pool_kernel(const double *fit_row, RowPlan rp, uint32_t P,
-                                                                uint32_t K, int32_t *sel, SampleNext next,
-                                                                uint32_t rank_blocks) {
-  if (blockIdx.x >= rank_blocks) {                     // the workgroups behind the ranking ones draw the next remaining work
-    sample_remaining_slot(next.pr, next.tab, next.Jn, next.key0, next.key1, next.t,
-                          (blockIdx.x - rank_blocks) * kSortThreads + threadIdx.x);
-    return;
-  }
+                                                                uint32_t K, int32_t *sel) {
   const uint32_t *row_of = rp.row_of_cur;
   extern __shared__ __align__(16) uint64_t sk[];       // [padded] scores, then [kRankPoolPer] counters
   constexpr uint32_t kTeam = kSortThreads / kRankPoolPer;
@@ -286,21 +279,18 @@ __global__ __launch_bounds__(kBucketThreads) void bucket_select_kernel(const dou
 // rank K do any work.  The sample only decides how even the buckets are, never the result.
 
 // Splitters: `sample` = 2 nb scores taken at a fixed stride from the pool; those of odd rank
-// 2c + 1 among them become splitter c.  Ranks by counting, laid out like rank_pool_kernel: every
-// workgroup loads the whole sample and ranks 64 of its elements, one per lane, each wave over
-// its own share of the sample.
+// 2c + 1 among them become splitter c.  A splitter may be any value, so the low bits of a sample
+// score give way to its position in the sample: all sample values differ and one 64-bit
+// comparison orders them.  Ranks by counting: every workgroup loads the whole sample into LDS
+// and each of its waves ranks one element, the lanes striding over the sample.
 constexpr int kSampleThreads = 1024;
 constexpr int kSampleMax = 2 * kMaxBuckets;
+constexpr int kSamplePer = kSampleThreads / kLanes;    // elements ranked by one workgroup
 __global__ __launch_bounds__(kSampleThreads) void sample_splitters_kernel(const double *fit_row, const uint32_t *row_of,
                                                                          uint32_t P, uint32_t sample,
-                                                                         uint64_t *split, uint32_t *count, SampleNext next) {
-  if (blockIdx.x >= sample / kLanes) {                 // the workgroups behind the ranking ones draw the next remaining work
-    sample_remaining_slot(next.pr, next.tab, next.Jn, next.key0, next.key1, next.t,
-                          (blockIdx.x - sample / kLanes) * kSampleThreads + threadIdx.x);
-    return;
-  }
+                                                                         uint64_t *split, uint32_t *count) {
   __shared__ uint64_t sk[kSampleMax];
-  __shared__ uint32_t rank[kLanes];
+  static_assert(kSampleMax <= 2048, "the position in the sample takes the low 11 bits of a score");
   const uint32_t t = threadIdx.x;
   if (blockIdx.x == 0)
     for (uint32_t c = t; c < static_cast<uint32_t>(kBucketCounters); c += kSampleThreads) count[c] = 0;
@@ -309,28 +299,24 @@ __global__ __launch_bounds__(kSampleThreads) void sample_splitters_kernel(const 
   for (int u = 0; u < kSampleMax / kSampleThreads; ++u) {          // all loads first, then the stores
     const uint32_t e = t + u * kSampleThreads;
     mine_of[u] = e < sample ? static_cast<uint64_t>(__double_as_longlong(
-                                  fit_row[row_of[static_cast<uint64_t>(e) * P / sample]])) : ~0ull;
+                                  fit_row[row_of[static_cast<uint64_t>(e) * P / sample]])) : 0ull;
   }
 #pragma unroll
-  for (int u = 0; u < kSampleMax / kSampleThreads; ++u)
-    if (t + u * kSampleThreads < sample) sk[t + u * kSampleThreads] = mine_of[u];
-  if (t < kLanes) rank[t] = 0;
+  for (int u = 0; u < kSampleMax / kSampleThreads; ++u) {
+    const uint32_t e = t + u * kSampleThreads;
+    sk[e] = e < sample ? (mine_of[u] & ~0x7FFull) | e : ~0ull;     // the padding is never below an element
+  }
   __syncthreads();
-  constexpr uint32_t kWaves = kSampleThreads / kLanes;
-  const uint32_t mine = blockIdx.x * kLanes + t % kLanes;              // sample = 64 * the ranking workgroups
-  const uint32_t part = sample / kWaves, from = (t / kLanes) * part;   // sample is a multiple of 128
+  const uint32_t lane = t % kLanes;
+  const uint32_t mine = blockIdx.x * kSamplePer + t / kLanes;          // sample = kSamplePer * the workgroups
   const uint64_t key = sk[mine];
   uint32_t below = 0;
-  for (uint32_t q = from; q < from + part; q += 8) {
+  for (uint32_t q = lane; q < sample; q += 4 * kLanes) {               // runs into the padding when sample = 128
 #pragma unroll
-    for (int u = 0; u < 8; ++u) below += key_less(sk[q + u], q + u, key, mine) ? 1u : 0u;
+    for (int u = 0; u < 4; ++u) below += sk[q + u * kLanes] < key ? 1u : 0u;
   }
-  if (below != 0) atomicAdd(&rank[t % kLanes], below);
-  __syncthreads();
-  if (t < kLanes) {
-    const uint32_t r = rank[t];
-    if ((r & 1u) && r / 2 + 1 < sample / 2) split[r / 2] = key;
-  }
+  const uint32_t r = wave_sum_u32(below);
+  if (lane == 0 && (r & 1u) && r / 2 + 1 < sample / 2) split[r / 2] = key;
   // the splitters beyond the sample are +inf: nothing lands in those buckets
   if (blockIdx.x == 0)
     for (uint32_t c = sample / 2 - 1 + t; c < static_cast<uint32_t>(kMaxBuckets); c += kSampleThreads) split[c] = ~0ull;
@@ -633,10 +619,7 @@ hipError_t launch_zero_words(uint32_t *words, uint32_t n, hipStream_t s) {
 }
 
 hipError_t launch_select(const double *fit, const RowPlan &rp, uint32_t P, uint32_t K, const BucketArgs &store,
-                         int32_t *sel, const SampleNext &next, hipStream_t s) {
-  // workgroups of 1024 threads behind the ranking ones, 64 slots each, for the next draw
-  const uint32_t draw_blocks = next.on ? next.Jp * kLanesPerSlot / kSortThreads : 0u;
-  static_assert(kSortThreads == kSampleThreads && kSortThreads % (kLanes * kLanesPerSlot) == 0, "64 slots per workgroup");
+                         int32_t *sel, hipStream_t s) {
   if (P <= kRankPoolMax) {
     const uint32_t rank_blocks = (P + kRankPoolPer - 1) / kRankPoolPer;
     constexpr uint32_t kStep = 8 * (kSortThreads / kRankPoolPer);
@@ -644,8 +627,7 @@ hipError_t launch_select(const double *fit, const RowPlan &rp, uint32_t P, uint3
     hipError_t rc = hipFuncSetAttribute(reinterpret_cast<const void *>(rank_pool_kernel),
                                         hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
     if (rc != hipSuccess) return rc;
-    hipLaunchKernelGGL(rank_pool_kernel, dim3(rank_blocks + draw_blocks), dim3(kSortThreads), lds, s, fit, rp, P, K, sel,
-                       next, rank_blocks);
+    hipLaunchKernelGGL(rank_pool_kernel, dim3(rank_blocks), dim3(kSortThreads), lds, s, fit, rp, P, K, sel);
     return hipGetLastError();
   }
   // about 64 candidates per bucket, two sample points per bucket
@@ -655,8 +637,8 @@ hipError_t launch_select(const double *fit, const RowPlan &rp, uint32_t P, uint3
   const uint32_t sample = 2 * nb;
   bk.seg = static_cast<uint32_t>(static_cast<size_t>(store.nb) * store.seg / nb);   // the same storage, re-divided
   bk.nb = nb;
-  hipLaunchKernelGGL(sample_splitters_kernel, dim3(sample / kLanes + draw_blocks), dim3(kSampleThreads), 0, s, fit,
-                     rp.row_of_cur, P, sample, const_cast<uint64_t *>(bk.split), bk.count, next);
+  hipLaunchKernelGGL(sample_splitters_kernel, dim3(sample / kSamplePer), dim3(kSampleThreads), 0, s, fit, rp.row_of_cur,
+                     P, sample, const_cast<uint64_t *>(bk.split), bk.count);
   hipError_t rc = hipGetLastError();
   if (rc != hipSuccess) return rc;
   hipLaunchKernelGGL(drop_all_kernel, dim3((P + kDropThreads - 1) / kDropThreads), dim3(kDropThreads), 0, s, fit,

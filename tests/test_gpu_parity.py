@@ -600,6 +600,10 @@ def test_sampled_search_matches_the_oracle(ones, ref, name):
     for i in range(4):
         both(lambda s: s.generation(1), f"sampled generation {i}")
     both(lambda s: s.generation(5), "five sampled generations")
+    # the progress moves on while draws made ahead of it are still waiting to be used
+    alpha2, beta2, proc2 = W.progress(cl.n_slots, seed=6)
+    both(lambda s: s.set_progress(alpha2, beta2, proc2), "new progress under sampling")
+    both(lambda s: s.generation(2), "sampled generations with the new progress")
     # a slot changes hands and another job's window shrinks while sampling is on
     j2 = make_jobs(cl.n_slots, **{k: np.array(getattr(jobs, k)) for k in
                                   ("job_id", "active", "bmin", "bmax", "gpu_max_batch", "a", "c", "d", "remaining")})
