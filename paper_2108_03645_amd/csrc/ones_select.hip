@@ -20,16 +20,14 @@ __device__ __forceinline__ uint32_t from_lane_above(uint32_t fallback, uint32_t 
                                                            0xF, 0xF, false));
 }
 
-// Slot id takes rank g < K (lanes with valid set): it survives in its row.  Called by whole
+// The candidate in genome row `row` takes rank g < K (lanes with valid set): it survives in its row.  Called by whole
 // waves.  Neighbouring lanes whose rows share a word of the bitmap hand their bits to the first
 // lane of their run (within a row of 16 lanes), which issues one atomic for all of them: the
 // rows of a pool that has stopped changing are neighbours, and one atomic per row would queue
 // up on the same few words.  Lanes that share a word without being neighbours simply issue
 // their own atomics.
-__device__ __forceinline__ void keep_rows(const RowPlan &rp, bool valid, uint32_t g, uint32_t id) {
-  uint32_t row = 0;
+__device__ __forceinline__ void keep_rows_at(const RowPlan &rp, bool valid, uint32_t g, uint32_t row) {
   if (valid) {
-    row = rp.row_of_cur[id];
     rp.parent_next[g] = row;
     rp.row_of_next[g] = row;
   }
@@ -44,6 +42,13 @@ __device__ __forceinline__ void keep_rows(const RowPlan &rp, bool valid, uint32_
   const uint32_t below = static_cast<uint32_t>(
       __builtin_amdgcn_update_dpp(static_cast<int>(~word), static_cast<int>(word), 0x111, 0xF, 0xF, false));
   if (valid && below != word) atomicOr(&rp.occupied[word], bits);
+}
+
+// The same, the row looked up from the slot.
+__device__ __forceinline__ void keep_rows(const RowPlan &rp, bool valid, uint32_t g, uint32_t id) {
+  uint32_t row = 0;
+  if (valid) row = rp.row_of_cur[id];
+  keep_rows_at(rp, valid, g, row);
 }
 
 // ---------------------------------------------------------------- general path -----
@@ -123,7 +128,7 @@ __device__ __forceinline__ void note_rank(uint32_t g, uint64_t bits, uint32_t K,
 
 constexpr int kBucketThreads = 256;
 constexpr int kBucketLds = 2048;      // offspring of one bucket that are sorted in LDS
-constexpr int kBucketCount = 64;      // up to here offspring are ranked by counting, not sorted
+constexpr int kBucketCount = 512;     // up to here offspring are ranked by counting, not sorted
 constexpr int kBucketElites = 1025;   // survivors of one bucket: at most ceil(2^18 / 256) + 1
 
 __device__ __forceinline__ uint32_t wave_sum_u32(uint32_t v) {
@@ -150,11 +155,20 @@ __device__ __forceinline__ void rank_bucket(K64 *sk, I32 *si, const uint64_t *ek
       id = si[i];
       uint32_t below = i;
       if (!sorted) {
+        // scores alone decide nearly every comparison: count the smaller and the equal ones, and
+        // only an element that shares its score looks at the slots
+        uint32_t equal = 0;
         below = 0;                                   // padding keys are never below a real one
         for (uint32_t q = 0; q < npad; q += 8) {
 #pragma unroll
-          for (int u = 0; u < 8; ++u) below += key_less(sk[q + u], si[q + u], key, id) ? 1u : 0u;
+          for (int u = 0; u < 8; ++u) {
+            const uint64_t other = sk[q + u];
+            below += other < key ? 1u : 0u;
+            equal += other == key ? 1u : 0u;
+          }
         }
+        if (equal > 1)
+          for (uint32_t q = 0; q < n; ++q) below += (sk[q] == key && si[q] < id) ? 1u : 0u;
       }
       uint32_t lo = 0, hi = ne;
       while (lo < hi) {
@@ -169,9 +183,10 @@ __device__ __forceinline__ void rank_bucket(K64 *sk, I32 *si, const uint64_t *ek
     }
     keep_rows(rp, g < K, g, id);
   }
-  // survivor e: rank = e + offspring with a strictly smaller score
+  // survivor e: rank = e + offspring with a strictly smaller score.  The threads are taken from
+  // the top, so that in a small bucket the survivors' waves are not the offspring's.
   for (uint32_t base = 0; base < ne; base += kBucketThreads) {
-    const uint32_t e = base + tid;
+    const uint32_t e = base + (kBucketThreads - 1 - tid);
     uint32_t g = K;
     if (e < ne) {
       const uint64_t key = ek[e];
@@ -240,11 +255,36 @@ __global__ __launch_bounds__(kBucketThreads) void bucket_select_kernel(const dou
   if ((tid & (kLanes - 1)) == 0) red[tid / kLanes] = before;
   const uint32_t e0 = bucket_bound(b, K, nb), e1 = bucket_bound(b + 1, K, nb), ne = e1 - e0;
   const uint32_t n = bk.count[b];
-  const uint32_t n2 = pow2_at_least(n);
-  const uint32_t npad = n2 < 8 ? 8 : n2;             // counting loops run in steps of 8 over padding
+  // Every global load a small bucket needs is issued here, before anything waits for one: an
+  // offspring per thread counted from thread 0 (read before the bucket's count is known: the
+  // places beyond it hold whatever an earlier generation left, which is only used as an index
+  // when it is one), a survivor per thread counted from the last one, and the rows of both.
+  const uint32_t seg = bk.seg;
+  uint64_t my_key = ~0ull, elite_key = 0;
+  uint32_t my_idx = 0xFFFFFFFFu, my_row = 0, elite_row = 0;
+  if (tid < seg) {
+    my_key = bk.keys[static_cast<size_t>(b) * seg + tid];
+    my_idx = bk.idx[static_cast<size_t>(b) * seg + tid];
+  }
+  const uint32_t se = kBucketThreads - 1 - tid;
+  if (se < ne) elite_row = parent_row[e0 + se];
+  if (se < ne) elite_key = static_cast<uint64_t>(__double_as_longlong(fit_row[elite_row]));   // survivors stayed in their rows
+  if (my_idx < 4 * K) my_row = rp.row_of_cur[my_idx];
+  const bool small = n <= static_cast<uint32_t>(kBucketThreads) && n <= seg && ne <= static_cast<uint32_t>(kBucketThreads);
+  // counting loops run in steps of 8 over padding; the sorting network needs a power of two
+  const bool sorted = n > static_cast<uint32_t>(kBucketCount);
+  const uint32_t npad = sorted ? pow2_at_least(n) : (n < 8 ? 8u : (n + 7) & ~7u);
   const bool in_lds = npad <= static_cast<uint32_t>(kBucketLds);
-  for (uint32_t e = tid; e < ne; e += kBucketThreads)
-    ek[e] = static_cast<uint64_t>(__double_as_longlong(fit_row[parent_row[e0 + e]]));   // survivors stayed in their rows
+  if (small) {
+    if (tid < npad) {                                // never sorted: npad <= the threads
+      sk[tid] = tid < n ? my_key : ~0ull;
+      si[tid] = tid < n ? my_idx : 0xFFFFFFFFu;
+    }
+    if (se < ne) ek[se] = elite_key;
+  } else {
+    for (uint32_t e = tid; e < ne; e += kBucketThreads)
+      ek[e] = static_cast<uint64_t>(__double_as_longlong(fit_row[parent_row[e0 + e]]));
+  }
   if (tid == 0) {
     spill_cursor = 0;
     pool_base = in_lds ? 0u : atomicAdd(&bk.count[kPoolCounter], npad);   // a slice of the scratch pool
@@ -254,9 +294,51 @@ __global__ __launch_bounds__(kBucketThreads) void bucket_select_kernel(const dou
 #pragma unroll
   for (int w = 0; w < kBucketThreads / kLanes; ++w) off += red[w];
   if (off < K) {                                     // otherwise nothing of this bucket survives
-    if (in_lds) {
+    if (small) {
+      // offspring tid: rank = offspring below it + survivors with score <= its score (a survivor
+      // wins a tie: smaller slot)
+      uint32_t g = K;
+      if (tid < n) {
+        uint32_t below = 0, equal = 0;               // padding keys are never below a real one
+        for (uint32_t q = 0; q < npad; q += 8) {
+#pragma unroll
+          for (int u = 0; u < 8; ++u) {
+            const uint64_t other = sk[q + u];
+            below += other < my_key ? 1u : 0u;
+            equal += other == my_key ? 1u : 0u;
+          }
+        }
+        if (equal > 1)                               // shares its score: the slots decide
+          for (uint32_t q = 0; q < n; ++q) below += (sk[q] == my_key && si[q] < my_idx) ? 1u : 0u;
+        uint32_t lo = 0, hi = ne;
+        while (lo < hi) {
+          const uint32_t mid = (lo + hi) >> 1;
+          if (ek[mid] <= my_key) lo = mid + 1; else hi = mid;
+        }
+        g = off + below + lo;
+        if (g < K) {
+          sel[g] = static_cast<int32_t>(my_idx);
+          note_rank(g, my_key, K, nb, bk.split_next, bk.thresh_next);
+        }
+      }
+      keep_rows_at(rp, g < K, g, my_row);
+      // survivor se: rank = se + offspring with a strictly smaller score
+      g = K;
+      if (se < ne) {
+        uint32_t lo = 0;
+        for (uint32_t q = 0; q < npad; q += 8) {
+#pragma unroll
+          for (int u = 0; u < 8; ++u) lo += sk[q + u] < elite_key ? 1u : 0u;
+        }
+        g = off + se + lo;
+        if (g < K) {
+          sel[g] = static_cast<int32_t>(e0 + se);
+          note_rank(g, elite_key, K, nb, bk.split_next, bk.thresh_next);
+        }
+      }
+      keep_rows_at(rp, g < K, g, elite_row);
+    } else if (in_lds) {
       gather_bucket(sk, si, bk, b, n, npad, &spill_cursor);
-      const bool sorted = n > static_cast<uint32_t>(kBucketCount);
       if (sorted) bitonic_sort(sk, si, npad);
       rank_bucket(sk, si, ek, n, npad, ne, e0, off, sorted, K, bk, rp, sel);
     } else {                                         // oversized bucket: same network in global memory
