@@ -140,14 +140,14 @@ __device__ __forceinline__ uint32_t wave_sum_u32(uint32_t v) {
 // Ranks one bucket: offspring in (sk, si)[0..n) (padded with never-smaller keys up to npad, a
 // multiple of 8), survivors' score bits in ek[0..ne).  Writes the survivor list entries that
 // fall below K and notes the next generation's splitters.
-template <typename K64, typename I32>
+template <bool kElites, int kThreads, typename K64, typename I32>
 __device__ __forceinline__ void rank_bucket(K64 *sk, I32 *si, const uint64_t *ek, uint32_t n, uint32_t npad,
                                             uint32_t ne, uint32_t e0, uint32_t off, bool sorted, uint32_t K,
                                             const BucketArgs &bk, const RowPlan &rp, int32_t *sel) {
   const uint32_t tid = threadIdx.x, nb = bk.nb;
   // offspring i: rank = offspring before it + survivors with score <= its score (a survivor
   // wins a tie: smaller slot)
-  for (uint32_t base = 0; base < n; base += kBucketThreads) {   // whole waves go round together
+  for (uint32_t base = 0; base < n; base += kThreads) {   // whole waves go round together
     const uint32_t i = base + tid;
     uint32_t g = K, id = 0;
     if (i < n) {
@@ -178,15 +178,16 @@ __device__ __forceinline__ void rank_bucket(K64 *sk, I32 *si, const uint64_t *ek
       g = off + below + lo;
       if (g < K) {
         sel[g] = static_cast<int32_t>(id);
-        note_rank(g, key, K, nb, bk.split_next, bk.thresh_next);
+        if (kElites) note_rank(g, key, K, nb, bk.split_next, bk.thresh_next);
       }
     }
     keep_rows(rp, g < K, g, id);
   }
+  if (!kElites) return;
   // survivor e: rank = e + offspring with a strictly smaller score.  The threads are taken from
   // the top, so that in a small bucket the survivors' waves are not the offspring's.
-  for (uint32_t base = 0; base < ne; base += kBucketThreads) {
-    const uint32_t e = base + (kBucketThreads - 1 - tid);
+  for (uint32_t base = 0; base < ne; base += kThreads) {
+    const uint32_t e = base + (kThreads - 1 - tid);
     uint32_t g = K;
     if (e < ne) {
       const uint64_t key = ek[e];
@@ -238,22 +239,27 @@ __device__ __forceinline__ void gather_bucket(K64 *dk, I32 *di, const BucketArgs
   __syncthreads();
 }
 
-__global__ __launch_bounds__(kBucketThreads) void bucket_select_kernel(const double *fit_row,
+// kElites: the quantile buckets above, each with its share of the survivors.  Without: the last
+// step of the sample sort of the general path below, a bucket holds candidates only (fit_row,
+// parent_row, count_next unused) and its first rank is the number of candidates before it.
+// kThreads: a bucket of at most that many offspring (nearly all) is ranked straight from registers.
+template <bool kElites, int kThreads>
+__global__ __launch_bounds__(kThreads) void bucket_select_kernel(const double *fit_row,
                                                                        const uint32_t *parent_row, BucketArgs bk,
                                                                        RowPlan rp, uint32_t K, uint32_t *count_next,
                                                                        int32_t *sel) {
   __shared__ uint64_t sk[kBucketLds];
   __shared__ uint32_t si[kBucketLds];
   __shared__ uint64_t ek[kBucketElites];
-  __shared__ uint32_t red[kBucketThreads / kLanes];
+  __shared__ uint32_t red[kThreads / kLanes];
   __shared__ uint32_t spill_cursor, pool_base;
   const uint32_t b = blockIdx.x, nb = bk.nb, tid = threadIdx.x;
   // offset of this bucket = its first survivor rank + all offspring of the buckets before it
   uint32_t before = 0;
-  for (uint32_t c = tid; c < b; c += kBucketThreads) before += bk.count[c];
+  for (uint32_t c = tid; c < b; c += kThreads) before += bk.count[c];
   before = wave_sum_u32(before);
   if ((tid & (kLanes - 1)) == 0) red[tid / kLanes] = before;
-  const uint32_t e0 = bucket_bound(b, K, nb), e1 = bucket_bound(b + 1, K, nb), ne = e1 - e0;
+  const uint32_t e0 = kElites ? bucket_bound(b, K, nb) : 0u, ne = kElites ? bucket_bound(b + 1, K, nb) - e0 : 0u;
   const uint32_t n = bk.count[b];
   // Every global load a small bucket needs is issued here, before anything waits for one: an
   // offspring per thread counted from thread 0 (read before the bucket's count is known: the
@@ -266,11 +272,12 @@ __global__ __launch_bounds__(kBucketThreads) void bucket_select_kernel(const dou
     my_key = bk.keys[static_cast<size_t>(b) * seg + tid];
     my_idx = bk.idx[static_cast<size_t>(b) * seg + tid];
   }
-  const uint32_t se = kBucketThreads - 1 - tid;
+  const uint32_t se = kThreads - 1 - tid;
   if (se < ne) elite_row = parent_row[e0 + se];
   if (se < ne) elite_key = static_cast<uint64_t>(__double_as_longlong(fit_row[elite_row]));   // survivors stayed in their rows
   if (my_idx < 4 * K) my_row = rp.row_of_cur[my_idx];
-  const bool small = n <= static_cast<uint32_t>(kBucketThreads) && n <= seg && ne <= static_cast<uint32_t>(kBucketThreads);
+  static_assert(kThreads <= kBucketCount, "a small bucket is ranked by counting");
+  const bool small = n <= static_cast<uint32_t>(kThreads) && n <= seg && ne <= static_cast<uint32_t>(kThreads);
   // counting loops run in steps of 8 over padding; the sorting network needs a power of two
   const bool sorted = n > static_cast<uint32_t>(kBucketCount);
   const uint32_t npad = sorted ? pow2_at_least(n) : (n < 8 ? 8u : (n + 7) & ~7u);
@@ -282,7 +289,7 @@ __global__ __launch_bounds__(kBucketThreads) void bucket_select_kernel(const dou
     }
     if (se < ne) ek[se] = elite_key;
   } else {
-    for (uint32_t e = tid; e < ne; e += kBucketThreads)
+    for (uint32_t e = tid; e < ne; e += kThreads)
       ek[e] = static_cast<uint64_t>(__double_as_longlong(fit_row[parent_row[e0 + e]]));
   }
   if (tid == 0) {
@@ -292,116 +299,136 @@ __global__ __launch_bounds__(kBucketThreads) void bucket_select_kernel(const dou
   __syncthreads();
   uint32_t off = e0;
 #pragma unroll
-  for (int w = 0; w < kBucketThreads / kLanes; ++w) off += red[w];
-  if (off < K) {                                     // otherwise nothing of this bucket survives
+  for (int w = 0; w < kThreads / kLanes; ++w) off += red[w];
+  if (off < K && n + ne != 0) {                      // otherwise nothing of this bucket survives
     if (small) {
       // offspring tid: rank = offspring below it + survivors with score <= its score (a survivor
       // wins a tie: smaller slot)
-      uint32_t g = K;
-      if (tid < n) {
-        uint32_t below = 0, equal = 0;               // padding keys are never below a real one
-        for (uint32_t q = 0; q < npad; q += 8) {
+      {
+        uint32_t g = K;
+        if (tid < n) {
+          uint32_t below = 0, equal = 0;             // padding keys are never below a real one
+          for (uint32_t q = 0; q < npad; q += 8) {
 #pragma unroll
-          for (int u = 0; u < 8; ++u) {
-            const uint64_t other = sk[q + u];
-            below += other < my_key ? 1u : 0u;
-            equal += other == my_key ? 1u : 0u;
+            for (int v = 0; v < 8; ++v) {
+              const uint64_t other = sk[q + v];
+              below += other < my_key ? 1u : 0u;
+              equal += other == my_key ? 1u : 0u;
+            }
+          }
+          if (equal > 1)                             // shares its score: the slots decide
+            for (uint32_t q = 0; q < n; ++q) below += (sk[q] == my_key && si[q] < my_idx) ? 1u : 0u;
+          uint32_t lo = 0, hi = ne;
+          while (lo < hi) {
+            const uint32_t mid = (lo + hi) >> 1;
+            if (ek[mid] <= my_key) lo = mid + 1; else hi = mid;
+          }
+          g = off + below + lo;
+          if (g < K) {
+            sel[g] = static_cast<int32_t>(my_idx);
+            if (kElites) note_rank(g, my_key, K, nb, bk.split_next, bk.thresh_next);
           }
         }
-        if (equal > 1)                               // shares its score: the slots decide
-          for (uint32_t q = 0; q < n; ++q) below += (sk[q] == my_key && si[q] < my_idx) ? 1u : 0u;
-        uint32_t lo = 0, hi = ne;
-        while (lo < hi) {
-          const uint32_t mid = (lo + hi) >> 1;
-          if (ek[mid] <= my_key) lo = mid + 1; else hi = mid;
-        }
-        g = off + below + lo;
-        if (g < K) {
-          sel[g] = static_cast<int32_t>(my_idx);
-          note_rank(g, my_key, K, nb, bk.split_next, bk.thresh_next);
-        }
+        keep_rows_at(rp, g < K, g, my_row);
       }
-      keep_rows_at(rp, g < K, g, my_row);
       // survivor se: rank = se + offspring with a strictly smaller score
-      g = K;
-      if (se < ne) {
-        uint32_t lo = 0;
-        for (uint32_t q = 0; q < npad; q += 8) {
+      if (kElites) {
+        uint32_t g = K;
+        if (se < ne) {
+          uint32_t lo = 0;
+          for (uint32_t q = 0; q < npad; q += 8) {
 #pragma unroll
-          for (int u = 0; u < 8; ++u) lo += sk[q + u] < elite_key ? 1u : 0u;
+            for (int v = 0; v < 8; ++v) lo += sk[q + v] < elite_key ? 1u : 0u;
+          }
+          g = off + se + lo;
+          if (g < K) {
+            sel[g] = static_cast<int32_t>(e0 + se);
+            note_rank(g, elite_key, K, nb, bk.split_next, bk.thresh_next);
+          }
         }
-        g = off + se + lo;
-        if (g < K) {
-          sel[g] = static_cast<int32_t>(e0 + se);
-          note_rank(g, elite_key, K, nb, bk.split_next, bk.thresh_next);
-        }
+        keep_rows_at(rp, g < K, g, elite_row);
       }
-      keep_rows_at(rp, g < K, g, elite_row);
     } else if (in_lds) {
       gather_bucket(sk, si, bk, b, n, npad, &spill_cursor);
       if (sorted) bitonic_sort(sk, si, npad);
-      rank_bucket(sk, si, ek, n, npad, ne, e0, off, sorted, K, bk, rp, sel);
+      rank_bucket<kElites, kThreads>(sk, si, ek, n, npad, ne, e0, off, sorted, K, bk, rp, sel);
     } else {                                         // oversized bucket: same network in global memory
       uint64_t *pk = bk.pool_keys + pool_base;
       uint32_t *pi = bk.pool_idx + pool_base;
       gather_bucket(pk, pi, bk, b, n, npad, &spill_cursor);
       bitonic_sort(pk, pi, npad);
-      rank_bucket(pk, pi, ek, n, npad, ne, e0, off, true, K, bk, rp, sel);
+      rank_bucket<kElites, kThreads>(pk, pi, ek, n, npad, ne, e0, off, true, K, bk, rp, sel);
     }
   }
-  // the other counter set, for the next generation
-  if (tid == 0) count_next[b] = 0;
-  if (b == 0 && tid < 2) count_next[kMaxBuckets + tid] = 0;
+  if (kElites) {                                     // the other counter set, for the next generation
+    if (tid == 0) count_next[b] = 0;
+    if (b == 0 && tid < 2) count_next[kMaxBuckets + tid] = 0;
+  }
 }
 
 // ------------------------------------------------- general path, larger pools -----
-// Sample sort over the same bucket storage: a sorted sample of the pool's scores gives the
-// splitters, every candidate is dropped into its bucket, and one workgroup per bucket sorts its
-// share; buckets concatenate to the global (score, slot) order and only those that reach below
-// rank K do any work.  The sample only decides how even the buckets are, never the result.
+// Sample sort over the same bucket storage: a ranked sample of the pool's scores gives the
+// splitters, every candidate is dropped into its bucket, and one workgroup per bucket ranks its
+// share (bucket_select_kernel<false, .>); buckets concatenate to the global (score, slot) order and
+// only those that reach below rank K do any work.  The sample only decides how even the buckets
+// are, never the result.
 
-// Splitters: `sample` = 2 nb scores taken at a fixed stride from the pool; those of odd rank
-// 2c + 1 among them become splitter c.  A splitter may be any value, so the low bits of a sample
-// score give way to its position in the sample: all sample values differ and one 64-bit
-// comparison orders them.  Ranks by counting: every workgroup loads the whole sample into LDS
-// and each of its waves ranks one element, the lanes striding over the sample.
+// Splitters: `sample` = per * nb scores taken at a fixed stride from the pool; those of rank
+// per * (c + 1) - 1 among them become splitter c (per = kOversample sample points per bucket, two
+// where that would take more than kSampleMax; a bucket of 64 to 127 candidates on average then
+// hardly ever grows beyond the 512 that are ranked straight from registers).  A splitter may be any value, so the low bits of a sample score
+// give way to its position in the sample: all sample values differ and one 64-bit comparison
+// orders them.  Ranks by counting: every workgroup loads the whole sample into LDS and each of
+// its waves ranks four elements, the lanes striding over the sample.
 constexpr int kSampleThreads = 1024;
-constexpr int kSampleMax = 2 * kMaxBuckets;
-constexpr int kSamplePer = kSampleThreads / kLanes;    // elements ranked by one workgroup
+constexpr int kOversample = 4;
+constexpr int kSampleMax = 2048;
+constexpr int kSamplePerWave = 1;
+constexpr int kSamplePer = kSamplePerWave * kSampleThreads / kLanes;    // elements ranked by one workgroup
 __global__ __launch_bounds__(kSampleThreads) void sample_splitters_kernel(const double *fit_row, const uint32_t *row_of,
-                                                                         uint32_t P, uint32_t sample,
+                                                                         uint32_t P, uint32_t sample, uint32_t nb,
                                                                          uint64_t *split, uint32_t *count) {
   __shared__ uint64_t sk[kSampleMax];
-  static_assert(kSampleMax <= 2048, "the position in the sample takes the low 11 bits of a score");
+  static_assert(kSampleMax <= 4096, "the position in the sample takes the low 12 bits of a score");
+  const uint32_t per = sample / nb;                   // sample points per bucket: kOversample, or fewer with kMaxBuckets buckets
   const uint32_t t = threadIdx.x;
+  const uint32_t sample_log2 = 31 - __clz(static_cast<int>(sample));
   if (blockIdx.x == 0)
     for (uint32_t c = t; c < static_cast<uint32_t>(kBucketCounters); c += kSampleThreads) count[c] = 0;
   uint64_t mine_of[kSampleMax / kSampleThreads];
 #pragma unroll
   for (int u = 0; u < kSampleMax / kSampleThreads; ++u) {          // all loads first, then the stores
     const uint32_t e = t + u * kSampleThreads;
+    // slot floor(e P / sample); sample is a power of two
     mine_of[u] = e < sample ? static_cast<uint64_t>(__double_as_longlong(
-                                  fit_row[row_of[static_cast<uint64_t>(e) * P / sample]])) : 0ull;
+                                  fit_row[row_of[(static_cast<uint64_t>(e) * P) >> sample_log2]])) : 0ull;
   }
 #pragma unroll
   for (int u = 0; u < kSampleMax / kSampleThreads; ++u) {
     const uint32_t e = t + u * kSampleThreads;
-    sk[e] = e < sample ? (mine_of[u] & ~0x7FFull) | e : ~0ull;     // the padding is never below an element
+    sk[e] = e < sample ? (mine_of[u] & ~0xFFFull) | e : ~0ull;     // the padding is never below an element
   }
   __syncthreads();
   const uint32_t lane = t % kLanes;
-  const uint32_t mine = blockIdx.x * kSamplePer + t / kLanes;          // sample = kSamplePer * the workgroups
-  const uint64_t key = sk[mine];
-  uint32_t below = 0;
-  for (uint32_t q = lane; q < sample; q += 4 * kLanes) {               // runs into the padding when sample = 128
+  const uint32_t first = blockIdx.x * kSamplePer + (t / kLanes) * kSamplePerWave;   // sample = kSamplePer * the workgroups
+  uint64_t key[kSamplePerWave];
+  uint32_t below[kSamplePerWave];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) below += sk[q + u * kLanes] < key ? 1u : 0u;
+  for (int m = 0; m < kSamplePerWave; ++m) { key[m] = sk[first + m]; below[m] = 0; }
+  for (uint32_t q = lane; q < sample; q += 2 * kLanes) {           // sample is a multiple of 128
+    const uint64_t a = sk[q], b = sk[q + kLanes];
+#pragma unroll
+    for (int m = 0; m < kSamplePerWave; ++m) below[m] += (a < key[m] ? 1u : 0u) + (b < key[m] ? 1u : 0u);
   }
-  const uint32_t r = wave_sum_u32(below);
-  if (lane == 0 && (r & 1u) && r / 2 + 1 < sample / 2) split[r / 2] = key;
-  // the splitters beyond the sample are +inf: nothing lands in those buckets
+#pragma unroll
+  for (int m = 0; m < kSamplePerWave; ++m) {
+    const uint32_t r = wave_sum_u32(below[m]);
+    // rank per * (c + 1) - 1 makes splitter c; the last bucket has none
+    if (lane == 0 && r % per == per - 1 && r / per + 1 < nb) split[r / per] = key[m];
+  }
+  // the splitters beyond are +inf: nothing lands in those buckets
   if (blockIdx.x == 0)
-    for (uint32_t c = sample / 2 - 1 + t; c < static_cast<uint32_t>(kMaxBuckets); c += kSampleThreads) split[c] = ~0ull;
+    for (uint32_t c = nb - 1 + t; c < static_cast<uint32_t>(kMaxBuckets); c += kSampleThreads) split[c] = ~0ull;
 }
 
 // Bucket of a score = number of splitters <= it (equal scores share a bucket).  A workgroup
@@ -442,83 +469,6 @@ __global__ __launch_bounds__(kDropThreads) void drop_all_kernel(const double *fi
       bk.spill_keys[at] = key;
       bk.spill_idx[at] = p;
       bk.spill_bucket[at] = b;
-    }
-  }
-}
-
-// One workgroup per bucket: its first rank is the number of candidates in the buckets before it.
-// Buckets up to kCountSort elements are ranked by counting (an element's place is the number of
-// elements below it; several threads share an element's comparisons), larger ones by the
-// sorting network.
-constexpr int kSortBucketThreads = 1024;
-constexpr int kCountSort = 512;
-__global__ __launch_bounds__(kSortBucketThreads) void bucket_sort_kernel(BucketArgs bk, RowPlan rp, uint32_t K,
-                                                                        int32_t *sel) {
-  __shared__ uint64_t sk[kBucketLds];
-  __shared__ uint32_t si[kBucketLds];
-  __shared__ uint32_t below[kCountSort];
-  __shared__ uint32_t red[kSortBucketThreads / kLanes];
-  __shared__ uint32_t spill_cursor, pool_base;
-  const uint32_t b = blockIdx.x, tid = threadIdx.x;
-  uint32_t before = 0;
-  for (uint32_t c = tid; c < b; c += kSortBucketThreads) before += bk.count[c];
-  before = wave_sum_u32(before);
-  if ((tid & (kLanes - 1)) == 0) red[tid / kLanes] = before;
-  const uint32_t n = bk.count[b];
-  const uint32_t npad = pow2_at_least(n);
-  const bool in_lds = npad <= static_cast<uint32_t>(kBucketLds);
-  if (tid == 0) {
-    spill_cursor = 0;
-    pool_base = in_lds ? 0u : atomicAdd(&bk.count[kPoolCounter], npad);   // a slice of the scratch pool
-  }
-  if (tid < static_cast<uint32_t>(kCountSort)) below[tid] = 0;
-  __syncthreads();
-  uint32_t off = 0;
-#pragma unroll
-  for (int w = 0; w < kSortBucketThreads / kLanes; ++w) off += red[w];
-  if (off >= K || n == 0) return;                    // nothing of this bucket survives (uniform)
-  if (n <= static_cast<uint32_t>(kCountSort)) {
-    // the threads form npad columns (one element each) by kSortBucketThreads / npad rows
-    // (a share of the comparisons each); padding keys are never below a real one
-    const uint32_t cols = npad < 8 ? 8 : npad, rows_of_threads = kSortBucketThreads / cols;
-    gather_bucket(sk, si, bk, b, n, cols, &spill_cursor);
-    const uint32_t e = tid % cols, share = ((cols + rows_of_threads - 1) / rows_of_threads + 7) & ~7u, from = (tid / cols) * share;
-    const uint64_t key = sk[e];
-    const uint32_t id = si[e];
-    uint32_t cnt = 0;
-    for (uint32_t q = from; q < min(from + share, cols); q += 8) {
-#pragma unroll
-      for (int u = 0; u < 8; ++u) cnt += key_less(sk[q + u], si[q + u], key, id) ? 1u : 0u;
-    }
-    if (e < n && cnt != 0) atomicAdd(&below[e], cnt);
-    __syncthreads();
-    {
-      const bool in = tid < n && off + below[tid < n ? tid : 0] < K;   // n <= kCountSort < the threads
-      const uint32_t g = in ? off + below[tid] : K, id = in ? si[tid] : 0u;
-      if (in) sel[g] = static_cast<int32_t>(id);
-      keep_rows(rp, in, g, id);
-    }
-  } else if (in_lds) {
-    gather_bucket(sk, si, bk, b, n, npad, &spill_cursor);
-    bitonic_sort(sk, si, npad);
-    for (uint32_t base = 0; base < n && off + base < K; base += kSortBucketThreads) {
-      const uint32_t e = base + tid;
-      const bool in = e < n && off + e < K;
-      const uint32_t id = in ? si[e] : 0u;
-      if (in) sel[off + e] = static_cast<int32_t>(id);
-      keep_rows(rp, in, off + e, id);
-    }
-  } else {                                           // oversized bucket: same network in global memory
-    uint64_t *pk = bk.pool_keys + pool_base;
-    uint32_t *pi = bk.pool_idx + pool_base;
-    gather_bucket(pk, pi, bk, b, n, npad, &spill_cursor);
-    bitonic_sort(pk, pi, npad);
-    for (uint32_t base = 0; base < n && off + base < K; base += kSortBucketThreads) {
-      const uint32_t e = base + tid;
-      const bool in = e < n && off + e < K;
-      const uint32_t id = in ? pi[e] : 0u;
-      if (in) sel[off + e] = static_cast<int32_t>(id);
-      keep_rows(rp, in, off + e, id);
     }
   }
 }
@@ -712,29 +662,31 @@ hipError_t launch_select(const double *fit, const RowPlan &rp, uint32_t P, uint3
     hipLaunchKernelGGL(rank_pool_kernel, dim3(rank_blocks), dim3(kSortThreads), lds, s, fit, rp, P, K, sel);
     return hipGetLastError();
   }
-  // about 64 candidates per bucket, two sample points per bucket
+  // 64 to 127 candidates per bucket (more in pools beyond 2^17), kOversample sample points per
+  // bucket while the sample stays within kSampleMax
   BucketArgs bk = store;
-  uint32_t nb = 64;
+  uint32_t nb = 32;
   while (nb < static_cast<uint32_t>(kMaxBuckets) && nb * 128 <= P) nb <<= 1;
-  const uint32_t sample = 2 * nb;
+  const uint32_t sample = std::min<uint32_t>(kOversample * nb, kSampleMax);   // a power of two, 256 .. kSampleMax
   bk.seg = static_cast<uint32_t>(static_cast<size_t>(store.nb) * store.seg / nb);   // the same storage, re-divided
   bk.nb = nb;
   hipLaunchKernelGGL(sample_splitters_kernel, dim3(sample / kSamplePer), dim3(kSampleThreads), 0, s, fit, rp.row_of_cur,
-                     P, sample, const_cast<uint64_t *>(bk.split), bk.count);
+                     P, sample, nb, const_cast<uint64_t *>(bk.split), bk.count);
   hipError_t rc = hipGetLastError();
   if (rc != hipSuccess) return rc;
   hipLaunchKernelGGL(drop_all_kernel, dim3((P + kDropThreads - 1) / kDropThreads), dim3(kDropThreads), 0, s, fit,
                      rp.row_of_cur, P, bk);
   rc = hipGetLastError();
   if (rc != hipSuccess) return rc;
-  hipLaunchKernelGGL(bucket_sort_kernel, dim3(nb), dim3(kSortBucketThreads), 0, s, bk, rp, K, sel);
+  hipLaunchKernelGGL((bucket_select_kernel<false, kBucketCount>), dim3(nb), dim3(kBucketCount), 0, s, nullptr, nullptr,
+                     bk, rp, K, nullptr, sel);
   return hipGetLastError();
 }
 
 hipError_t launch_bucket_select(const double *fit_row, const uint32_t *parent_row, const BucketArgs &bk,
                                 const RowPlan &rp, uint32_t K, uint32_t *count_next, int32_t *sel, hipStream_t s) {
-  hipLaunchKernelGGL(bucket_select_kernel, dim3(bk.nb), dim3(kBucketThreads), 0, s, fit_row, parent_row, bk, rp, K,
-                     count_next, sel);
+  hipLaunchKernelGGL((bucket_select_kernel<true, kBucketThreads>), dim3(bk.nb), dim3(kBucketThreads), 0, s, fit_row,
+                     parent_row, bk, rp, K, count_next, sel);
   return hipGetLastError();
 }
 
