@@ -131,15 +131,17 @@ __device__ __forceinline__ Smem carve(unsigned char *base, uint32_t Jp, uint32_t
   return s;
 }
 
-// No barrier at the end: the caller places one before the first use.
+// Stages the job table into LDS, the work dealt to the `threads` threads (whole waves) that call it
+// with tid = 0 .. threads - 1.  No barrier at the end: the caller places one before the first use.
+constexpr int kStageBatch = 3;
 template <int R>
 __device__ __forceinline__ void stage_table(const JobTable &tab, const BucketArgs &bk, const Smem &s, uint32_t Jp,
-                                            uint32_t E) {
+                                            uint32_t E, uint32_t tid, uint32_t threads) {
   if (bk.nb != 0) {
-    for (uint32_t q = threadIdx.x; q <= kMaxBuckets; q += blockDim.x)
+    for (uint32_t q = tid; q <= kMaxBuckets; q += threads)
       s.split[q] = q < kMaxBuckets ? bk.split[q] : *bk.thresh;
   }
-  for (uint32_t j = threadIdx.x; j < Jp; j += blockDim.x) {
+  for (uint32_t j = tid; j < Jp; j += threads) {
     s.cc2[j] = make_uint2(tab.cstart[j], tab.cmax[j]);
     s.info[j] = tab.info[j];
     if (E == 0) {
@@ -153,9 +155,20 @@ __device__ __forceinline__ void stage_table(const JobTable &tab, const BucketArg
     // global memory holds the table row-major ([row][code][lane]); here the code is the slowest
     // index, so that a row's part of the LDS address is a compile-time offset, and the codes
     // run backwards, so that the index follows the count of leading zeros of the GPU count
-    for (uint32_t tile = threadIdx.x / kLanes; tile < E * R; tile += blockDim.x / kLanes) {   // 64 entries each
-      const uint32_t e = tile / R, row = tile % R, l = threadIdx.x % kLanes;
-      s.terms[((E - 1 - e) * R + row) * kLanes + l] = tab.terms[(row * E + e) * kLanes + l];
+    // (tiles of 64 entries; a batch of loads in flight per wave before the first LDS store waits for one)
+    for (uint32_t first = tid / kLanes; first < E * R; first += kStageBatch * (threads / kLanes)) {
+      const uint32_t l = tid % kLanes;
+      double v[kStageBatch];
+#pragma unroll
+      for (int u = 0; u < kStageBatch; ++u) {
+        const uint32_t tile = first + u * (threads / kLanes), e = tile / R, row = tile % R;
+        if (tile < E * R) v[u] = tab.terms[(row * E + e) * kLanes + l];
+      }
+#pragma unroll
+      for (int u = 0; u < kStageBatch; ++u) {
+        const uint32_t tile = first + u * (threads / kLanes), e = tile / R, row = tile % R;
+        if (tile < E * R) s.terms[((E - 1 - e) * R + row) * kLanes + l] = v[u];
+      }
     }
 }
 
@@ -170,8 +183,7 @@ __device__ __forceinline__ uint32_t free_bits(const uint32_t *occupied, uint32_t
 }
 
 // Every workgroup builds the same small index: the number of free rows in each group of
-// kRowGroupWords bitmap words.  The first bitmap loads are issued before the job table is
-// staged and counted after it, so that their latency overlaps the staging.
+// kRowGroupWords bitmap words.  The first bitmap loads are issued ahead of the rest.
 constexpr int kIndexAhead = 4;                       // groups per wave whose words are loaded ahead
 
 struct IndexLoads { uint32_t bits[kIndexAhead]; };
@@ -185,8 +197,7 @@ __device__ __forceinline__ IndexLoads index_free_rows_begin(const EvolveArgs &a,
   return ld;
 }
 
-// Also clears this workgroup's share of the other bitmap.  Ends with a barrier (which also
-// publishes the staged job table).
+// Also clears this workgroup's share of the other bitmap.  Ends with a barrier.
 __device__ __forceinline__ void index_free_rows_end(const EvolveArgs &a, const Smem &s, const IndexLoads &ld, int lane) {
   const uint32_t rows = a.P + a.K, words = (rows + 31) / 32;
   const uint32_t groups = (words + kRowGroupWords - 1) / kRowGroupWords;

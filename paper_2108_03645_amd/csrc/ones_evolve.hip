@@ -6,9 +6,9 @@
 // uniform crossover, uniform mutation), repairs it to the cluster capacity (refresh + fill
 // under Eq. 4), scores it (Eq. 3 with T = Y/X, Eq. 5) and writes genome and score.
 //
-// Workgroups are persistent: each stages the job table in LDS once, owns a contiguous share
-// of the work and lists the free genome rows its share will fill; its waves then take the
-// share's items one by one from an LDS counter and never wait for each other.
+// Workgroups are persistent: each owns a contiguous share of the work; two or three of its waves
+// list the free genome rows the share will fill while the others stage the job table in LDS;
+// then all waves take the share's items one by one from an LDS counter and never wait for each other.
 #include "ones_candidate.h"
 
 #include <utility>
@@ -34,7 +34,7 @@ template <int R>
 __global__ __launch_bounds__(Shape<R>::kWaves *kLanes) void init_kernel(EvolveArgs a) {
   extern __shared__ __align__(16) unsigned char smem_raw[];
   const Smem s = carve(smem_raw, a.Jp, a.term_lds, Shape<R>::kWaves, a.stash_stride);
-  stage_table<R>(a.tab, a.bk, s, a.Jp, a.term_lds);
+  stage_table<R>(a.tab, a.bk, s, a.Jp, a.term_lds, threadIdx.x, blockDim.x);
   if (threadIdx.x == 0) *s.next_item = 0;
   __syncthreads();
   const int lane0 = threadIdx.x & (kLanes - 1);
@@ -75,7 +75,6 @@ __global__ __launch_bounds__(Shape<R>::kWaves *kLanes) void evolve_kernel(Evolve
   const int lane0 = threadIdx.x & (kLanes - 1);
   const IndexLoads index_loads = index_free_rows_begin(a, lane0);
   if (threadIdx.x == 0) s.next_item[1] = 0;          // no row index has been out of range (checked_row)
-  stage_table<R>(a.tab, a.bk, s, a.Jp, a.term_lds);
   index_free_rows_end(a, s, index_loads, lane0);
   const uint32_t wave_in_block = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const uint32_t K = a.K;
@@ -86,12 +85,22 @@ __global__ __launch_bounds__(Shape<R>::kWaves *kLanes) void evolve_kernel(Evolve
   // consecutive free rows, which one wave each lists into LDS, a round of kRound ranks at a time.
   const uint32_t first = static_cast<uint32_t>(static_cast<uint64_t>(K) * blockIdx.x / gridDim.x);
   const uint32_t last = static_cast<uint32_t>(static_cast<uint64_t>(K) * (blockIdx.x + 1) / gridDim.x);
+  // The first round's rows are listed while the other waves stage the job table.
+  constexpr uint32_t kListing = (kSameTable ? 2 : 3) * kLanes;
+  auto list_round = [&](uint32_t ra, uint32_t n) {
+    if (wave_in_block == 0) list_free_rows(a, s, 2 * ra, 2 * n, s.rows, lane0);
+    if (wave_in_block == 1) list_free_rows(a, s, 2 * K + ra, n, s.rows + 2 * n, lane0);
+    if (!kSameTable && wave_in_block == 2) list_free_rows(a, s, 3 * K + ra, n, s.rows + 3 * n, lane0);
+  };
+  if (first < last) list_round(first, min(kRound, last - first));
+  if (threadIdx.x >= kListing)
+    stage_table<R>(a.tab, a.bk, s, a.Jp, a.term_lds, threadIdx.x - kListing, blockDim.x - kListing);
   for (uint32_t ra = first; ra < last; ra += kRound) {
   const uint32_t n = min(kRound, last - ra);
-  if (ra != first) __syncthreads();                  // the previous round's rows have been used
-  if (wave_in_block == 0) list_free_rows(a, s, 2 * ra, 2 * n, s.rows, lane0);
-  if (wave_in_block == 1) list_free_rows(a, s, 2 * K + ra, n, s.rows + 2 * n, lane0);
-  if (!kSameTable && wave_in_block == 2) list_free_rows(a, s, 3 * K + ra, n, s.rows + 3 * n, lane0);
+  if (ra != first) {
+    __syncthreads();                                 // the previous round's rows have been used
+    list_round(ra, n);
+  }
   if (threadIdx.x == blockDim.x - 1) *s.next_item = 0;
   __syncthreads();
   for (uint32_t i = threadIdx.x; i < (kSameTable ? 3 : 4) * n; i += blockDim.x) {

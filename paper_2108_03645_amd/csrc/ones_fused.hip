@@ -356,7 +356,7 @@ __global__ __launch_bounds__(kFusedThreads) void fused_kernel(FusedArgs fa) {
   }
   draw_unit_parents(a.t + 1);
   draw_unit_words(a.t + 1);
-  stage_table<1>(a.tab, a.bk, s, kLanes, a.term_lds);
+  stage_table<1>(a.tab, a.bk, s, kLanes, a.term_lds, threadIdx.x, blockDim.x);
   // the state the last selection left: the survivors' rows and scores, the bitmap of their rows
   for (uint32_t e = tid; e < K; e += kFusedThreads) {
     const uint32_t row = fa.parent_rows[e];
