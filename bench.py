@@ -32,7 +32,7 @@ HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published peak
 
 # HBM bytes per evolve launch on the stress workload from rocprofv3 --pmc FETCH_SIZE and
 # WRITE_SIZE (see profiles/), valid only for the kernel source with this hash.
-MEASURED_TRAFFIC = {"source_sha256": "f384ee9604890d68ac7ebeadad024fa29cc9bf1f115169e7912b2c3c48c3dca5", "bytes_per_launch": 802583865}
+MEASURED_TRAFFIC = {"source_sha256": "a369f62a0de40131a5afbe40c8966fe959ea95a26fcfc1d0fc78ea69e70646d9", "bytes_per_launch": 802695578}
 
 
 def evolve_source_hash() -> str:
