@@ -76,7 +76,7 @@ struct ScratchLayout {
 };
 
 struct Layout {
-  size_t genes, fit_row, row_of[2], parent_row[2], occupied[2], sel, fsync, xkeys, scratch, cstart, cmax, info, abl, cc, d, Y[kDrawRing], terms[kDrawRing];
+  size_t genes, fit_row, slot_score, row_of[2], parent_row[2], occupied[2], sel, fsync, xkeys, scratch, cstart, cmax, info, abl, cc, d, Y[kDrawRing], terms[kDrawRing];
   size_t rawinfo, changed, ra, rc, rd, rY, alpha, beta, processed, time_rank, best_batch, best_gpus, best_fit, best_err, place_slot, place_batch, total;
   ScratchLayout S;
 };
@@ -132,6 +132,7 @@ Layout make_layout(uint32_t P, uint32_t Jp, uint32_t G) {
   const size_t rows = static_cast<size_t>(P) + P / 4;      // a pool of P slots lives in P + K physical rows
   L.genes = take(rows * Jp * 4);
   L.fit_row = take(rows * 8);
+  L.slot_score = take(static_cast<size_t>(P) * 8);
   L.row_of[0] = take(static_cast<size_t>(P) * 4);
   L.row_of[1] = take(static_cast<size_t>(P) * 4);
   L.parent_row[0] = take(static_cast<size_t>(P / 4) * 4);
@@ -363,6 +364,7 @@ int run_generation(ones_ctx *c, uint32_t t, char *scratch, bool &splitters_valid
   a.per_gpu = c->per_gpu ? 1u : 0u;
   a.stash_stride = 0;                                            // the launcher sets it
   a.fault = c->at<uint32_t>(c->L.fsync) + 2;
+  a.slot_score = c->at<double>(c->L.slot_score);
   a.time_rank = c->has_times ? c->at<uint32_t>(c->L.time_rank) : nullptr;
   // quantile buckets: only when the survivors reappear with the scores they had
   const bool buckets = same_table && !sampled && c->bp.nb != 0 && splitters_valid;
@@ -407,7 +409,11 @@ int run_generation(ones_ctx *c, uint32_t t, char *scratch, bool &splitters_valid
     BucketArgs store = a.bk;                       // same storage; always the first counter set
     store.nb = c->bp.nb;
     store.count = reinterpret_cast<uint32_t *>(sc(S.bcount[0]));
-    HIP_TRY(launch_select(a.fit_row, rp, c->P, c->K, store, c->at<int32_t>(c->L.sel), c->stream));
+    // the launch scored the whole pool (initial population, refresh under a new table, survivors
+    // scored again under a new draw): its scores by slot are complete
+    const bool all_scored = t == 0 || !same_table || a.rescore != 0;
+    HIP_TRY(launch_select(a.fit_row, all_scored ? a.slot_score : nullptr, rp, c->P, c->K, store,
+                          c->at<int32_t>(c->L.sel), c->stream));
     splitters_valid = false;
     if (c->bp.nb != 0 && !sampled && same_table) {
       // Splitters for the bucketed generations that follow; clears both counter sets.  Under sampling
@@ -633,6 +639,7 @@ static int run_fused(ones_ctx *c, uint32_t n, bool events) {
   a.genes = c->at<int32_t>(c->L.genes);
   a.fit_row = c->at<double>(c->L.fit_row);
   a.parent_row = nullptr; a.row_of = nullptr; a.occupied = nullptr; a.occupied_other = nullptr;
+  a.slot_score = nullptr;                              // no selection kernel follows
   a.tab = c->table();
   a.G = c->G; a.P = c->P; a.K = c->K; a.Jp = c->Jp;
   a.key0 = static_cast<uint32_t>(c->cfg.seed);

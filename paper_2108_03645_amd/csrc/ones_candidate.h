@@ -464,6 +464,12 @@ __device__ __forceinline__ double score(const uint32_t (&c)[R], const Smem &s, u
   return acc;
 }
 
+// The score of pool slot p, for a general selection that follows (the pointer is read from the
+// kernel's argument block at the point of use, like the bucket storage below).
+__device__ __forceinline__ void note_slot_score(uint32_t p, double f, int lane) {
+  if (lane == 0) kernel_args()->slot_score[p] = f;
+}
+
 // A child or mutant that beats the K-th survivor joins the bucket of the survivors it falls
 // between: bucket = number of splitters <= its score.  Scores at or above the threshold
 // cannot be among the best K (the K survivors themselves are in the pool, in smaller slots).

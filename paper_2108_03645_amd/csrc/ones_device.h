@@ -126,6 +126,9 @@ struct EvolveArgs {
   uint32_t       stash_stride; // set by the launcher: bytes of LDS scratch per wave
   uint32_t       term_lds;    // set by the launcher: entries per job of the term table in LDS, 0 = none
   uint32_t       *fault;      // [1] raised when a row index had to be pulled back into the genome array
+  double         *slot_score; // [P] the score of every candidate this launch scores, by pool slot (written when
+                              //     the buckets are off): what the general selection reads when the launch scored
+                              //     the whole pool, in place of slot -> row -> score
   BucketArgs     bk;
 };
 
@@ -218,9 +221,10 @@ inline hipError_t launch_evolve(const EvolveArgs &a, int rows, bool same_table, 
 }
 // General selection (any scores).  store: the bucket storage (count, keys, idx, spill and pool
 // arrays, split as scratch for the splitters, nb * seg entries of bucket space); used by pools
-// too large for the single launch that ranks a whole pool.
-hipError_t launch_select(const double *fit_row, const RowPlan &rp, uint32_t P, uint32_t K, const BucketArgs &store,
-                         int32_t *sel, hipStream_t s);
+// too large for the single launch that ranks a whole pool.  slot_score: the pool's scores by slot
+// when the evolve launch wrote them all, else null (they are then looked up through the rows).
+hipError_t launch_select(const double *fit_row, const double *slot_score, const RowPlan &rp, uint32_t P, uint32_t K,
+                         const BucketArgs &store, int32_t *sel, hipStream_t s);
 hipError_t launch_zero_words(uint32_t *words, uint32_t n, hipStream_t s);
 hipError_t launch_bucket_select(const double *fit_row, const uint32_t *parent_row, const BucketArgs &bk,
                                 const RowPlan &rp, uint32_t K, uint32_t *count_next, int32_t *sel, hipStream_t s);

@@ -57,7 +57,8 @@ __global__ __launch_bounds__(Shape<R>::kWaves *kLanes) void init_kernel(EvolveAr
       c[i] = batch_from_draw(bounded(c[i], info_n(w)), w);
     }
     gpus_from_batches<R, false>(s, lane, c);
-    finish<R>(a, s, p, dr.r, c, lane);                 // slot p starts in row p
+    const double f = finish<R>(a, s, p, dr.r, c, lane);   // slot p starts in row p
+    note_slot_score(p, f, lane);
     if (lane == 0) a.row_of[p] = p;
   }
 }
@@ -163,12 +164,12 @@ __global__ __launch_bounds__(Shape<R>::kWaves *kLanes) void evolve_kernel(Evolve
       }
       phase_fence();
       const double f0 = finish<R>(a, s, row_at(s, 2 * idx, a), d0.r, c, lane, new_first);
-      if (kSameTable && a.bk.nb != 0) drop_in_bucket(a, s, p0, f0, lane);
+      if (kSameTable && a.bk.nb != 0) drop_in_bucket(a, s, p0, f0, lane); else note_slot_score(p0, f0, lane);
       phase_fence();
 #pragma unroll
       for (int i = 0; i < R; ++i) c[i] = (1u << stash[lane + kLanes * i]) >> 1;
       const double f1 = finish<R>(a, s, row_at(s, 2 * idx + 1, a), d1.r, c, lane, new_first);
-      if (kSameTable && a.bk.nb != 0) drop_in_bucket(a, s, p0 + 1, f1, lane);
+      if (kSameTable && a.bk.nb != 0) drop_in_bucket(a, s, p0 + 1, f1, lane); else note_slot_score(p0 + 1, f1, lane);
     } else if (item < 2 * K) {
       // uniform mutation: each job redrawn with rate theta (k = 0 pre-empts it)
       const uint32_t p = 3 * K + (item - K);
@@ -191,7 +192,7 @@ __global__ __launch_bounds__(Shape<R>::kWaves *kLanes) void evolve_kernel(Evolve
       phase_fence();
       gpus_from_batches<R, false>(s, lane, c);
       const double f = finish<R>(a, s, row_at(s, idx + n, a), d.r, c, lane, new_first);
-      if (kSameTable && a.bk.nb != 0) drop_in_bucket(a, s, p, f, lane);
+      if (kSameTable && a.bk.nb != 0) drop_in_bucket(a, s, p, f, lane); else note_slot_score(p, f, lane);
     } else if (kSameTable) {
       // the remaining work was drawn anew: the survivor of this rank keeps its genome and row
       // and only gets its score under the new draw
@@ -200,6 +201,7 @@ __global__ __launch_bounds__(Shape<R>::kWaves *kLanes) void evolve_kernel(Evolve
       gpus_from_batches<R, true>(s, lane, c);
       const double f = score<R>(c, s, a.term_lds, lane);
       if (lane == 0) a.fit_row[row] = f;
+      note_slot_score(item - 2 * K, f, lane);
     } else {
       // refresh: the survivor of rank p, projected onto the new job table, goes to one of the
       // last K free rows (its old row is still being read as a parent by other waves)
@@ -207,7 +209,8 @@ __global__ __launch_bounds__(Shape<R>::kWaves *kLanes) void evolve_kernel(Evolve
       const Draw d = candidate_draw(a, a.t, p);
       load_genes<R>(a.genes + static_cast<size_t>(a.parent_row[p]) * a.Jp, lane, c);
       gpus_from_batches<R, false>(s, lane, c);
-      finish<R>(a, s, row_at(s, idx + n, a), d.r, c, lane, new_first);
+      const double f = finish<R>(a, s, row_at(s, idx + n, a), d.r, c, lane, new_first);
+      note_slot_score(p, f, lane);
     }
   }
   }

@@ -63,8 +63,8 @@ __device__ __forceinline__ void keep_rows(const RowPlan &rp, bool valid, uint32_
 #endif
 constexpr uint32_t kRankPoolMax = ONES_RANK_POOL_MAX;
 constexpr int kRankPoolPer = 64;
-__global__ __launch_bounds__(kSortThreads) void rank_pool_kernel(const double *fit_row, RowPlan rp, uint32_t P,
-                                                                uint32_t K, int32_t *sel) {
+__global__ __launch_bounds__(kSortThreads) void rank_pool_kernel(const double *fit_row, const double *slot_score,
+                                                                RowPlan rp, uint32_t P, uint32_t K, int32_t *sel) {
   const uint32_t *row_of = rp.row_of_cur;
   extern __shared__ __align__(16) uint64_t sk[];       // [padded] scores, then [kRankPoolPer] counters
   constexpr uint32_t kTeam = kSortThreads / kRankPoolPer;
@@ -77,7 +77,7 @@ __global__ __launch_bounds__(kSortThreads) void rank_pool_kernel(const double *f
 #pragma unroll
     for (int u = 0; u < kAhead; ++u) {                 // all loads first
       const uint32_t e = base + t + u * kSortThreads;
-      loaded[u] = e < P ? static_cast<uint64_t>(__double_as_longlong(fit_row[row_of[e]])) : ~0ull;
+      loaded[u] = e < P ? static_cast<uint64_t>(__double_as_longlong(slot_score ? slot_score[e] : fit_row[row_of[e]])) : ~0ull;
     }
 #pragma unroll
     for (int u = 0; u < kAhead; ++u)
@@ -385,8 +385,9 @@ constexpr int kOversample = 4;
 constexpr int kSampleMax = 2048;
 constexpr int kSamplePerWave = 1;
 constexpr int kSamplePer = kSamplePerWave * kSampleThreads / kLanes;    // elements ranked by one workgroup
-__global__ __launch_bounds__(kSampleThreads) void sample_splitters_kernel(const double *fit_row, const uint32_t *row_of,
-                                                                         uint32_t P, uint32_t sample, uint32_t nb,
+__global__ __launch_bounds__(kSampleThreads) void sample_splitters_kernel(const double *fit_row, const double *slot_score,
+                                                                         const uint32_t *row_of, uint32_t P,
+                                                                         uint32_t sample, uint32_t nb,
                                                                          uint64_t *split, uint32_t *count) {
   __shared__ uint64_t sk[kSampleMax];
   static_assert(kSampleMax <= 4096, "the position in the sample takes the low 12 bits of a score");
@@ -400,8 +401,8 @@ __global__ __launch_bounds__(kSampleThreads) void sample_splitters_kernel(const 
   for (int u = 0; u < kSampleMax / kSampleThreads; ++u) {          // all loads first, then the stores
     const uint32_t e = t + u * kSampleThreads;
     // slot floor(e P / sample); sample is a power of two
-    mine_of[u] = e < sample ? static_cast<uint64_t>(__double_as_longlong(
-                                  fit_row[row_of[(static_cast<uint64_t>(e) * P) >> sample_log2]])) : 0ull;
+    const uint32_t p = static_cast<uint32_t>((static_cast<uint64_t>(e) * P) >> sample_log2);
+    mine_of[u] = e < sample ? static_cast<uint64_t>(__double_as_longlong(slot_score ? slot_score[p] : fit_row[row_of[p]])) : 0ull;
   }
 #pragma unroll
   for (int u = 0; u < kSampleMax / kSampleThreads; ++u) {
@@ -435,8 +436,8 @@ __global__ __launch_bounds__(kSampleThreads) void sample_splitters_kernel(const 
 // first counts its candidates per bucket in LDS and reserves their places with one global
 // atomic per bucket, instead of one per candidate.
 constexpr int kDropThreads = 1024;
-__global__ __launch_bounds__(kDropThreads) void drop_all_kernel(const double *fit_row, const uint32_t *row_of, uint32_t P,
-                                                               BucketArgs bk) {
+__global__ __launch_bounds__(kDropThreads) void drop_all_kernel(const double *fit_row, const double *slot_score,
+                                                               const uint32_t *row_of, uint32_t P, BucketArgs bk) {
   __shared__ uint64_t split[kMaxBuckets];
   __shared__ uint32_t here[kMaxBuckets], base[kMaxBuckets];
   const uint32_t t = threadIdx.x, nb = bk.nb;
@@ -446,7 +447,7 @@ __global__ __launch_bounds__(kDropThreads) void drop_all_kernel(const double *fi
   uint64_t key = 0;
   uint32_t b = 0, r = 0;
   if (p < P) {
-    key = static_cast<uint64_t>(__double_as_longlong(fit_row[row_of[p]]));
+    key = static_cast<uint64_t>(__double_as_longlong(slot_score ? slot_score[p] : fit_row[row_of[p]]));
     uint32_t lo = 0, hi = nb - 1;                    // splitters 0 .. nb-2
     while (lo < hi) {
       const uint32_t mid = (lo + hi) >> 1;
@@ -650,8 +651,8 @@ hipError_t launch_zero_words(uint32_t *words, uint32_t n, hipStream_t s) {
   return hipGetLastError();
 }
 
-hipError_t launch_select(const double *fit, const RowPlan &rp, uint32_t P, uint32_t K, const BucketArgs &store,
-                         int32_t *sel, hipStream_t s) {
+hipError_t launch_select(const double *fit, const double *slot_score, const RowPlan &rp, uint32_t P, uint32_t K,
+                         const BucketArgs &store, int32_t *sel, hipStream_t s) {
   if (P <= kRankPoolMax) {
     const uint32_t rank_blocks = (P + kRankPoolPer - 1) / kRankPoolPer;
     constexpr uint32_t kStep = 8 * (kSortThreads / kRankPoolPer);
@@ -659,7 +660,7 @@ hipError_t launch_select(const double *fit, const RowPlan &rp, uint32_t P, uint3
     hipError_t rc = hipFuncSetAttribute(reinterpret_cast<const void *>(rank_pool_kernel),
                                         hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
     if (rc != hipSuccess) return rc;
-    hipLaunchKernelGGL(rank_pool_kernel, dim3(rank_blocks), dim3(kSortThreads), lds, s, fit, rp, P, K, sel);
+    hipLaunchKernelGGL(rank_pool_kernel, dim3(rank_blocks), dim3(kSortThreads), lds, s, fit, slot_score, rp, P, K, sel);
     return hipGetLastError();
   }
   // 64 to 127 candidates per bucket (more in pools beyond 2^17), kOversample sample points per
@@ -670,12 +671,12 @@ hipError_t launch_select(const double *fit, const RowPlan &rp, uint32_t P, uint3
   const uint32_t sample = std::min<uint32_t>(kOversample * nb, kSampleMax);   // a power of two, 256 .. kSampleMax
   bk.seg = static_cast<uint32_t>(static_cast<size_t>(store.nb) * store.seg / nb);   // the same storage, re-divided
   bk.nb = nb;
-  hipLaunchKernelGGL(sample_splitters_kernel, dim3(sample / kSamplePer), dim3(kSampleThreads), 0, s, fit, rp.row_of_cur,
-                     P, sample, nb, const_cast<uint64_t *>(bk.split), bk.count);
+  hipLaunchKernelGGL(sample_splitters_kernel, dim3(sample / kSamplePer), dim3(kSampleThreads), 0, s, fit, slot_score,
+                     rp.row_of_cur, P, sample, nb, const_cast<uint64_t *>(bk.split), bk.count);
   hipError_t rc = hipGetLastError();
   if (rc != hipSuccess) return rc;
   hipLaunchKernelGGL(drop_all_kernel, dim3((P + kDropThreads - 1) / kDropThreads), dim3(kDropThreads), 0, s, fit,
-                     rp.row_of_cur, P, bk);
+                     slot_score, rp.row_of_cur, P, bk);
   rc = hipGetLastError();
   if (rc != hipSuccess) return rc;
   hipLaunchKernelGGL((bucket_select_kernel<false, kBucketCount>), dim3(nb), dim3(kBucketCount), 0, s, nullptr, nullptr,
