@@ -247,6 +247,7 @@ struct ones_ctx {
   hipStream_t stream;
   char *ws;
   char *stage;                // pinned host staging buffer (stage_bytes), free between calls
+  char *stage_dev;            // the same buffer as the device addresses it (ones_best's kernel writes the winner there)
   Layout L;
   int cur;                    // which row_of array describes the current generation
   bool table_changed;         // job table replaced since the current generation was computed
@@ -478,11 +479,15 @@ static int init_impl(ones_ctx **out, const ones_config *cfg, const ones_jobs *jo
   c->ws = static_cast<char *>(d_workspace);
   c->L = L;
   c->stage = nullptr;
+  c->stage_dev = nullptr;
   {
     void *pinned = nullptr;
     HIP_TRY(hipHostMalloc(&pinned, stage_bytes(L, static_cast<uint32_t>(Jp), static_cast<uint32_t>(cfg->n_gpus)),
                           hipHostMallocDefault));
     c->stage = static_cast<char *>(pinned);
+    void *mapped = nullptr;
+    HIP_TRY(hipHostGetDevicePointer(&mapped, pinned, 0));
+    c->stage_dev = static_cast<char *>(mapped);
   }
   c->cur = 0; c->t = 0;
   c->table_changed = false;
@@ -756,14 +761,16 @@ static int check_waits(ones_ctx *c) {
 static int best_impl(ones_ctx *c, int32_t *batch_out, int32_t *gpus_out, double *fitness_out) {
   if (!c) return ONES_E_INVALID_ARG;
   if (c->poisoned) return poisoned_error();
-  HIP_TRY(launch_best(c->at<int32_t>(c->L.genes), c->at<double>(c->L.fit_row), c->at<uint32_t>(c->L.row_of[c->cur]),
-                      c->at<int32_t>(c->L.sel),
-                      c->at<uint32_t>(c->L.info), c->Jn, c->Jp, c->at<int32_t>(c->L.best_batch),
-                      c->at<int32_t>(c->L.best_gpus), c->at<double>(c->L.best_fit),
-                      c->at<uint32_t>(c->L.fsync) + 1, c->at<uint32_t>(c->L.best_err), c->stream));
+  // The kernel writes the winner and the two error words straight into the pinned host buffer
+  // (a few hundred bytes to a few kilobytes), laid out as the best_* block of the workspace:
+  // one launch and one wait, no copy.
   const Layout &L = c->L;
-  HIP_TRY(hipMemcpyAsync(c->stage, c->ws + L.best_batch, L.best_err + 8 - L.best_batch, hipMemcpyDeviceToHost,
-                         c->stream));
+  auto mapped = [&](size_t off) { return c->stage_dev + (off - L.best_batch); };
+  HIP_TRY(launch_best(c->at<int32_t>(c->L.genes), c->at<double>(c->L.fit_row), c->at<uint32_t>(c->L.row_of[c->cur]),
+                      c->at<int32_t>(c->L.sel), c->at<uint32_t>(c->L.info), c->Jn, c->Jp,
+                      reinterpret_cast<int32_t *>(mapped(L.best_batch)), reinterpret_cast<int32_t *>(mapped(L.best_gpus)),
+                      reinterpret_cast<double *>(mapped(L.best_fit)), c->at<uint32_t>(c->L.fsync) + 1,
+                      reinterpret_cast<uint32_t *>(mapped(L.best_err)), c->stream));
   HIP_TRY(hipStreamSynchronize(c->stream));
   auto staged = [&](size_t off) { return c->stage + (off - L.best_batch); };   // laid out as in the workspace
   uint32_t words[2] = {0, 0};
