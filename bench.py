@@ -32,7 +32,7 @@ HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published peak
 
 # HBM bytes per evolve launch on the stress workload from rocprofv3 --pmc FETCH_SIZE and
 # WRITE_SIZE (see profiles/), valid only for the kernel source with this hash.
-MEASURED_TRAFFIC = {"source_sha256": "a369f62a0de40131a5afbe40c8966fe959ea95a26fcfc1d0fc78ea69e70646d9", "bytes_per_launch": 802695578}
+MEASURED_TRAFFIC = {"source_sha256": "0b6ef20e102acdea716dafa2501ee9f1b0e5340947bc7b4bf13a3ae8b2a30dbe", "bytes_per_launch": 802626465}
 
 
 def evolve_source_hash() -> str:
