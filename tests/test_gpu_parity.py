@@ -932,3 +932,52 @@ def test_random_configurations(ones, ref, block):
             gpu.close(); cpu.close()
     finally:
         ref.set_threads(1)
+
+
+@pytest.mark.parametrize("block", range(2))
+def test_random_selections_of_larger_pools(ones, ref, block):
+    """Seeded random pools above the size one launch ranks (4100 to 72000 candidates), a third of
+    them with a handful of distinct scores (6 to 11 jobs on a few GPUs): the sample sort and the
+    quantile buckets with small, counted, sorted and oversized buckets, with the remaining work
+    fixed or sampled, the scratch in the workspace or in the static array, a table change in
+    between.  Scores and survivor lists are compared after every call."""
+    ref.set_threads(8)
+    try:
+        for case in range(30 * block, 30 * block + 30):
+            rng = np.random.default_rng(77_000 + case)
+            ties = rng.random() < 0.3
+            n_slots = int(rng.integers(3, 12)) if ties else int(rng.integers(1, 200))
+            n_gpus = int(rng.integers(1, 12)) if ties else int(rng.integers(1, 400))
+            pop = 4 * int(rng.choice([rng.integers(1025, 1100), rng.integers(1025, 4000), rng.integers(4000, 18000)]))
+            cl = cluster(n_gpus, n_slots, pop, seed=int(rng.integers(0, 2**62)),
+                         theta=float(rng.choice([0.02, 0.1, 0.5, 1.0])), chi=float(rng.choice([0.0, 0.3, 0.5, 1.0])))
+            sampled, static, per_gpu = (bool(rng.integers(0, 2)) for _ in range(3))
+            jobs = (make_jobs(n_slots, bmin=256, bmax=512, remaining=rng.uniform(1e5, 1e7, n_slots)) if ties
+                    else random_jobs(rng, n_slots))
+            tag = (f"selection {case}: slots={n_slots} G={n_gpus} P={pop} theta={cl.mutation_rate} chi={cl.crossover_rate} "
+                   f"ties={ties} sampled={sampled} static={static} per_gpu={per_gpu}")
+            say(f"[parity] {tag}")
+            gpu, cpu = ones.Search(cl, jobs), ref.RefSearch(cl, jobs)
+            assert_same_state(gpu, cpu, tag + " initial population", genes=False)
+            for s in (gpu, cpu):
+                s.set_crossover(per_gpu=per_gpu)
+                if sampled:
+                    s.set_progress(*W.progress(n_slots, seed=case))
+            for step in range(3):
+                n = int(rng.integers(1, 5))
+                call = gpu.generation_static if static and rng.random() < 0.7 else gpu.generation
+                try:
+                    call(n)
+                except ones.OnesError as e:                  # the pool's scratch does not fit the static array
+                    assert e.code == -7 and call == gpu.generation_static
+                    gpu.generation(n)
+                cpu.generation(n)
+                assert_same_state(gpu, cpu, tag + f" step {step}", genes=step == 2)
+                if step == 1 and rng.random() < 0.5:
+                    jobs.remaining = jobs.remaining * rng.uniform(0.5, 1.0, n_slots)
+                    gpu.set_jobs(jobs); cpu.set_jobs(jobs)
+            gb, cb = gpu.best(), cpu.best()
+            assert gb[0].tolist() == cb[0].tolist() and gb[2] == cb[2], tag
+            gpu.close(); cpu.close()
+    finally:
+        ref.set_threads(1)
