@@ -349,7 +349,7 @@ def main() -> int:
                      "physical_frac": None if traffic is None else traffic / (evolve_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
                      # a plain device-to-device copy of 1 GiB on this machine, read + write: the practical ceiling
                      "device_copy_gbps": copy_gbps, "frac_of_device_copy": achieved / copy_gbps,
-                     # the survey's per-pool figure (every candidate counted as read and written, survivors included)
+                     # the whole pool counted as read and written, survivors included (what a ping-pong layout would move)
                      "pool_equivalent_gbps": pool_bytes / (evolve_ms * 1e-3) / 1e9},
     }
     if args.copy_reference:
